@@ -1,0 +1,242 @@
+"""Pins of the oracle's decoding logic: teacher-forcing equivalence, the greedy-identity
+invariant by brute force, closed-form iteration structure, suffix matching.  CPU only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from ad_inputs import SPECIAL, edit_guide, init_weights, model_dims, positional_draft
+from oracle import ad_oracle as O
+
+BOS, EOS, MASK = SPECIAL["bos"], SPECIAL["eos"], SPECIAL["mask"]
+
+
+def make(name, seed, dtype=np.float64, contract=False, tie=False):
+    dims = model_dims(name)
+    return dims, O.Model(dims, init_weights(dims, seed, tie_output=tie), dtype, contract=contract, max_pos=96)
+
+
+def src_for(dims, seed, n):
+    return np.random.default_rng(seed).integers(5, dims["vocab"], size=n).astype(np.int32)
+
+
+# ------------------------------------------------------------ teacher forcing equivalence (Section 2)
+@pytest.mark.parametrize("contract", [False, True])
+def test_incremental_equals_full_recompute(contract):
+    dims, m = make("micro", 21, contract=contract)
+    src = src_for(dims, 1, 9)
+    memory = m.encode(src)
+    toks = [BOS] + list(src_for(dims, 2, 10))
+    full = m.decode_full(memory, toks, causal=True)
+    st = O.DecoderState(m, memory)
+    got = []
+    for chunk in ([0, 1], [2], [3, 4, 5, 6], [7, 8, 9, 10]):   # ragged blocks, appended one after another
+        got.append(st.forward([toks[i] for i in chunk]))
+        st.keep(st.length + len(chunk))
+    assert np.allclose(np.concatenate(got), full, atol=1e-10)
+
+
+def test_rollback_discards_rejected_rows():
+    dims, m = make("micro", 22)
+    src = src_for(dims, 3, 7)
+    memory = m.encode(src)
+    toks = [BOS] + list(src_for(dims, 4, 6))
+    st = O.DecoderState(m, memory)
+    st.forward(toks[:2]); st.keep(2)
+    st.forward([9, 10, 11, 12])          # a rejected block: nothing kept
+    st.keep(2)
+    again = st.forward(toks[2:5])
+    full = m.decode_full(memory, toks[:5])
+    assert np.allclose(again, full[2:5], atol=1e-10)
+
+
+def test_verify_rows_are_greedy_steps_and_k1_is_an_ar_step():
+    dims, m = make("micro", 23)
+    src = src_for(dims, 5, 8)
+    g, glog = O.greedy(m, src, 12, EOS, BOS, return_logits=True)
+    g2 = O.greedy(m, src, 12, EOS, BOS, incremental=False)
+    assert g == g2
+    st = O.DecoderState(m, m.encode(src))
+    # a fully right draft: row i reproduces greedy step i
+    o_hat, c, lg = O.verify(st, BOS, g[:6], return_logits=True)
+    assert o_hat == g[:6] and c == 6
+    assert np.allclose(lg, glog[:6], atol=1e-10)
+    st.keep(3)
+    # k = 1 with the never-matching id: an ordinary autoregressive step
+    o_hat, c, lg = O.verify(st, g[2], [O.NEVER], return_logits=True)
+    assert c == 1 and o_hat == [g[3]] and np.allclose(lg[0], glog[3], atol=1e-10)
+
+
+# ------------------------------------------------------------ the invariant, by brute force
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_every_draft_yields_greedy_brute_force(seed):
+    """For every prefix of the greedy output and EVERY draft in V^k (k<=3), the accepted
+    block is the greedy continuation: matched draft prefix plus the first corrected token."""
+    dims, m = make("nano", seed)
+    V = dims["vocab"]
+    src = src_for(dims, seed, 5)
+    g = O.greedy(m, src, 6, EOS, BOS)
+    memory = m.encode(src)
+    o = [BOS] + g
+    for j in range(len(g)):
+        for k in (1, 2, 3):
+            for draft in itertools.product(range(V), repeat=k):
+                st = O.DecoderState(m, memory)
+                if j:
+                    st.forward(o[:j]); st.keep(j)
+                o_hat, c = O.verify(st, o[j], list(draft))
+                assert 1 <= c <= k
+                cont = (g + [None] * k)[j:j + c]          # greedy continuation, where it exists
+                for t in range(c):
+                    if cont[t] is None or (t and g[j + t - 1] == EOS):
+                        break                               # beyond the end of the greedy output
+                    assert o_hat[t] == cont[t]
+                # c is the first mismatch of draft vs o_hat, else k
+                mism = [i for i in range(k) if draft[i] != o_hat[i]]
+                assert c == (mism[0] + 1 if mism else k)
+
+
+@pytest.mark.parametrize("seed", [2, 3, 4, 5])
+def test_every_guide_yields_greedy_brute_force(seed):
+    """Algorithm 1 with every guide of length <= 3 over the whole vocabulary."""
+    dims, m = make("nano", seed)
+    V = dims["vocab"]
+    src = src_for(dims, seed + 10, 4)
+    g = O.greedy(m, src, 6, EOS, BOS)
+    n_multi = 0
+    for n in range(0, 4):
+        for guide in itertools.product(range(V), repeat=n):
+            out, st = O.iad(m, src, list(guide), 6, EOS, BOS)
+            assert out == g, (guide, out, g)
+            assert sum(st.accepted) == len(g)
+            n_multi += any(a > 1 for a in st.accepted)
+    assert n_multi > 0 or len(g) < 2  # some guides really were accepted in blocks
+
+
+@pytest.mark.parametrize("contract,tie", [(False, False), (True, False), (False, True)])
+def test_all_right_all_wrong_random_drafts_tiny(contract, tie):
+    dims, m = make("tiny", 1000, contract=contract, tie=tie)
+    V = dims["vocab"]
+    src = src_for(dims, 1000, 24)
+    T, k = 32, 8
+    g = O.greedy(m, src, T, EOS, BOS)
+    assert len(g) == T or g[-1] == EOS
+    T = len(g)
+    # all right: ceil(T/k) verify forwards
+    out, st = O.gad(m, src, k, 32, EOS, BOS, draft_override=g)
+    assert out == g and st.iterations == math.ceil(T / k)
+    # all wrong: T forwards, one token each
+    wrong = [(t + 1 - 5) % (V - 5) + 5 for t in g]
+    out, st = O.gad(m, src, k, 32, EOS, BOS, draft_override=wrong)
+    assert out == g and st.iterations == T and set(st.accepted) == {1}
+    # random substitutions: block boundaries are a function of the mask alone
+    for s in range(3):
+        D, bad = positional_draft(g, 0.1 + 0.2 * s, 50 + s, V)
+        out, st = O.gad(m, src, k, 32, EOS, BOS, draft_override=D)
+        assert out == g
+        expect, j = [], 0
+        while j < T:
+            kk = min(k, T - j)
+            w = [p for p in range(j, j + kk) if bad[p]]
+            c = (w[0] - j + 1) if w else kk
+            expect.append(c); j += c
+        assert st.accepted == expect
+    # guide = greedy output itself: a single verify forward (no edit, nothing to re-decode)
+    out, st = O.iad(m, src, g, 32, EOS, BOS)
+    assert out == g
+    if len(set(g)) == len(g):
+        assert st.iterations == 1
+    # edited guides
+    for s in range(3):
+        out, st = O.iad(m, src, edit_guide(g, 0.1, s, V), 32, EOS, BOS)
+        assert out == g
+    # block size cap
+    out, st = O.iad(m, src, g, 32, EOS, BOS, k_max=5)
+    assert out == g and max(st.accepted) <= 5
+
+
+def test_gad_with_block_drafter_is_greedy():
+    dims, ver = make("micro", 31)
+    _, dr = make("micro", 32)
+    src = src_for(dims, 6, 10)
+    g = O.greedy(ver, src, 14, EOS, BOS)
+    for k in (1, 3, 5):
+        out, st = O.gad(ver, src, k, 14, EOS, BOS, drafter=dr, mask_id=MASK)
+        assert out == g
+        assert st.draft_rows > 0 and st.rows_verified >= len(g)
+    # the drafter's draft is a function of the prefix only: k masks, bidirectional
+    mem = dr.encode(src)
+    d3 = O.draft_nat(dr, mem, [BOS] + g[:4], 3, MASK)
+    lg = dr.decode_full(mem, [BOS] + g[:4] + [MASK] * 3, causal=False)
+    assert d3 == [int(np.argmax(lg[5 + i])) for i in range(3)]
+
+
+def test_a_verifier_that_drafts_for_itself_accepts_everything():
+    """If the drafter's proposal equals the verifier's own greedy continuation, every
+    iteration accepts its whole block: iterations = ceil(T/k)."""
+    dims, ver = make("micro", 33)
+    src = src_for(dims, 7, 9)
+    g = O.greedy(ver, src, 13, EOS, BOS)
+    for k in (2, 4, 13):
+        out, st = O.gad(ver, src, k, 13, EOS, BOS, draft_override=g)
+        assert out == g and st.iterations == math.ceil(len(g) / k)
+
+
+def test_eos_and_max_len_truncate_the_accepted_block():
+    # find a nano model whose greedy output ends with EOS before max_len
+    for seed in range(1, 60):
+        dims, m = make("nano", seed)
+        src = src_for(dims, seed, 4)
+        g = O.greedy(m, src, 8, EOS, BOS)
+        if g[-1] == EOS and 2 <= len(g) < 8:
+            break
+    else:
+        pytest.skip("no EOS-terminated sample")
+    # a draft that is right up to EOS and proposes more afterwards: nothing after EOS is kept
+    D = g + [5, 6, 7, 5, 6, 7, 5, 6]
+    out, st = O.gad(m, src, 8, 8, EOS, BOS, draft_override=D)
+    assert out == g and st.iterations == 1
+    out, st = O.iad(m, src, g[:-1] + [5, 6], 8, EOS, BOS)
+    assert out == g
+    # max_len in the middle of an accepted block
+    out, st = O.gad(m, src, 8, len(g) - 1, EOS, BOS, draft_override=D)
+    assert out == g[:-1]
+
+
+# ------------------------------------------------------------ suffix match (Algorithm 1, the if-test)
+def _occurrence_ends(sub, x):
+    """Independent formulation through strings: end indices of (overlapping) occurrences."""
+    s = "".join(chr(65 + t) for t in sub)
+    xs = "".join(chr(65 + t) for t in x)
+    ends, start = [], xs.find(s)
+    while start != -1:
+        ends.append(start + len(s) - 1)
+        start = xs.find(s, start + 1)
+    return ends
+
+
+def test_suffix_match_brute_force():
+    for n in range(1, 6):
+        for x in itertools.product(range(3), repeat=n):
+            for j in range(0, 4):
+                for o in itertools.product(range(3), repeat=j + 1):
+                    got = O.suffix_match(list(o), list(x))
+                    expect = None
+                    for q in range(j + 1):
+                        ends = _occurrence_ends(o[j - q:], x)
+                        if len(ends) == 1:
+                            expect = ends[0]
+                        if len(ends) <= 1:
+                            break
+                    assert got == expect
+
+
+def test_suffix_match_worked_cases():
+    # o_0 = x_0 = BOS is unique: the initial aggressive decoding is a suffix match at i = 0
+    assert O.suffix_match([0], [0, 7, 8, 9, -1]) == 0
+    # a repeated token needs a longer suffix to become unique
+    assert O.suffix_match([0, 7, 8], [0, 7, 8, 7, 9, -1]) == 2
+    assert O.suffix_match([0, 5, 7], [0, 7, 8, 7, 9, -1]) is None     # "7" twice, "5 7" never
+    assert O.suffix_match([0, 8, 7], [0, 7, 8, 7, 9, -1]) == 3        # "8 7" once
+    assert O.suffix_match([0, 6], [0, 7, 8, -1]) is None
