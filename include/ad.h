@@ -1,0 +1,201 @@
+/*
+ * ad.h — C ABI of the MI355X-native Aggressive Decoding hot path.
+ *
+ * The library evaluates an encoder-decoder Transformer with hand-written gfx950
+ * kernels and runs the draft-then-verify decoding of "Lossless Acceleration for
+ * Seq2seq Generation with Aggressive Decoding": the parallel verification forward
+ * (Section 3.2, verify paragraph), Input-guided Aggressive Decoding (Section 3.1,
+ * Algorithm 1) and Generalized Aggressive Decoding (Section 3.2) with a
+ * non-autoregressive block drafter (Section 3.2.1), plus plain greedy decoding
+ * (Section 2) as the result every one of them must reproduce token for token.
+ *
+ * Conventions
+ *  - Every `int32_t*` token / length buffer is HOST memory owned by the caller.
+ *  - `verifier_w`, `drafter_w`, `workspace` are DEVICE pointers owned by the caller
+ *    (allocate them with any allocator; they must outlive the context).  The library
+ *    allocates no device memory, ever; after ad_create it allocates no memory at all.
+ *  - `hip_stream` is a hipStream_t (NULL = the null stream).  All device work of a
+ *    context is enqueued on it; calls return after that work has completed.
+ *  - Every function returns AD_OK or a negative AD_E* code and, on error, leaves the
+ *    context as it was.  Nothing throws or aborts across this boundary.
+ *    ad_last_error() gives a static or per-context message for the last failure.
+ *  - A context is not thread-safe.
+ *
+ * Token ids: [0, vocab).  AD_NEVER (-1) in a draft is the id that equals no
+ * prediction (Algorithm 1 appends [PAD] to the guide for this purpose); it may
+ * appear only as the LAST token of a sequence's draft because that token is
+ * compared but never fed to the decoder.
+ */
+#ifndef AD_H_
+#define AD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AD_NEVER (-1)
+
+typedef struct ad_ctx ad_ctx;
+
+/* Model and capacity description.  Both models (verifier, drafter) share it. */
+typedef struct {
+  int32_t enc_layers, dec_layers, d_model, n_heads, d_ffn, vocab;
+  int32_t max_batch;   /* sequences decoded together                                  */
+  int32_t max_src;     /* longest source sentence                                     */
+  int32_t max_len;     /* most output tokens per sequence                             */
+  int32_t k_max;       /* most rows verified (or drafted) per sequence in one call    */
+  int32_t bos, pad, eos, mask;
+  int32_t dtype;       /* AD_F32: fp32 weights and arithmetic; AD_BF16: bf16 weights,
+                          bf16 GEMM/attention operands, fp32 accumulation, fp32 residual
+                          stream, LayerNorm, softmax and logits                        */
+  int32_t tie_output;  /* 1: the embedding table is also the output projection        */
+  int32_t debug_logits;/* 1: keep the last forward's full logits for ad_debug_logits  */
+} ad_config;
+
+typedef struct {
+  int64_t iterations;     /* verify forwards (an autoregressive step is one of k=1)   */
+  int64_t rows_verified;  /* decoder rows fed to the verifier                          */
+  int64_t draft_rows;     /* decoder rows fed to the drafter                           */
+  int64_t tokens_out;     /* tokens emitted over the batch                             */
+  double t_encode_us, t_draft_us, t_verify_us, t_host_us; /* wall time by phase       */
+} ad_stats;
+
+enum { AD_OK = 0, AD_EINVAL = -1, AD_ESTATE = -2, AD_ENOMEM = -3, AD_EDEVICE = -4 };
+enum { AD_F32 = 0, AD_BF16 = 1 };
+enum { AD_VERIFIER = 0, AD_DRAFTER = 1 };
+
+/* ---- sizes and weight layout (host only, no GPU needed) ------------------------------- */
+
+/* Validates a configuration.  AD_EINVAL with a message in ad_last_error(NULL) if a
+ * dimension is unsupported (d_model % 32, d_ffn % 32, vocab % 16, head size in
+ * {16,32,64,128}, capacities >= 1). */
+int ad_config_check(const ad_config* cfg);
+
+/* Bytes of device workspace ad_create needs for `cfg`; 0 if cfg is invalid.
+ * `with_drafter` adds the drafter's encoder memory. */
+size_t ad_workspace_bytes(const ad_config* cfg, int with_drafter);
+
+/* A model's weights are one flat device blob.  Entry `index` (0 .. count-1) of its
+ * layout: tensor name ("emb", "out.w", "enc.0.self.wq", "dec.3.ffn.b1", ... — a matrix
+ * is [out_features, in_features] row-major), byte offset, shape, and element size
+ * (2 = bf16, 4 = fp32; vectors are always fp32).  ad_weights_bytes is the blob size.
+ * ad_weights_entry returns AD_EINVAL past the end. */
+int    ad_weights_count(const ad_config* cfg);
+size_t ad_weights_bytes(const ad_config* cfg);
+int    ad_weights_entry(const ad_config* cfg, int index, char* name, size_t name_cap,
+                        size_t* offset, int32_t* rows, int32_t* cols, int32_t* elem_bytes);
+
+/* ---- context --------------------------------------------------------------------------- */
+
+/* Creates a context over caller-owned device memory.  `drafter_w` may be NULL (then
+ * ad_draft_nat and the drafter in ad_decode_gad are unavailable).  `workspace_bytes`
+ * must be >= ad_workspace_bytes().  Needs a GPU: AD_EDEVICE otherwise. */
+int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_w,
+              void* workspace, size_t workspace_bytes, void* hip_stream, ad_ctx** out);
+int ad_destroy(ad_ctx* ctx);
+const char* ad_last_error(const ad_ctx* ctx /* NULL: last error of a context-free call */);
+
+/* ---- the steps of one decoding iteration ------------------------------------------------- */
+
+/* Encoder forward of `model` over B source sentences (x_1..x_n each, no sentinels;
+ * `src` is [B, max_src], row b holds src_len[b] ids) and the cross-attention keys/values
+ * of every decoder layer.  With model = AD_VERIFIER it also starts a new decode:
+ * accepted length 0, pending decoder input [BOS], empty output, per-sequence output
+ * limit max_out[b] (NULL: cfg.max_len).  1 <= src_len[b] <= max_src. */
+int ad_encode(ad_ctx* ctx, int model, const int32_t* src, const int32_t* src_len, int B,
+              const int32_t* max_out);
+
+/* Parallel verification (Section 3.2: the verifier equation, the bifurcation position c
+ * and the accepted block; Section 3.1.1 for the input-guided case).  For each sequence b
+ * with k[b] > 0 the decoder is fed (o_j, draft[b][0..k[b]-2]) at positions j..j+k[b]-1
+ * under a causal mask against its key/value cache; o_hat_i is the arg max (lowest id on
+ * ties) at row i; c = first i with draft[b][i-1] != o_hat_i, else k[b].  The block
+ * o_hat_1..o_hat_c (= matched draft prefix + first corrected token) is appended to the
+ * output, cut after the first [EOS] and at the sequence's output limit; the cache keeps
+ * exactly the rows of accepted tokens (rollback), and o_hat of the last appended token
+ * becomes the pending decoder input.
+ *   draft      [B, k_max] host, row b holds k[b] ids (AD_NEVER allowed last)
+ *   k          [B] host, 0 = sequence sits this call out
+ *   n_accept   [B] out: tokens appended for b (0 if k[b] = 0)
+ *   next_token [B] out: last appended token (undefined if n_accept = 0)
+ *   verified   [B, k_max] out, nullable: all o_hat of the call, for tests
+ * AD_ESTATE before ad_encode(AD_VERIFIER) or if a finished sequence gets k[b] > 0;
+ * AD_EINVAL for k[b] > k_max, ids outside the vocabulary, AD_NEVER not last. */
+int ad_verify(ad_ctx* ctx, const int32_t* draft, const int32_t* k,
+              int32_t* n_accept, int32_t* next_token, int32_t* verified);
+
+/* Block drafter (Section 3.2, draft paragraph; Section 3.2.1): decoder input
+ * (o_0..o_j, [MASK] x k) at positions 0..j+k with bidirectional self-attention and
+ * cross-attention to the drafter's memory; draft_out[b][i] = arg max at mask row i.
+ * All unfinished sequences draft k tokens (k <= k_max; finished rows get AD_NEVER).
+ * Needs ad_encode(AD_DRAFTER) and ad_encode(AD_VERIFIER) for the same batch. */
+int ad_draft_nat(ad_ctx* ctx, int k, int32_t* draft_out /* [B, k_max] host */);
+
+/* Current output of the decode in progress: out [B, max_len], out_len [B]. */
+int ad_output(ad_ctx* ctx, int32_t* out, int32_t* out_len);
+
+/* ---- whole decodes ------------------------------------------------------------------------ */
+/* All three take B sources as ad_encode does and write out [B, max_len] / out_len [B];
+ * `stats` is nullable.  Their outputs are token-identical by construction. */
+
+/* o_{t+1} = arg max P(. | o_{<=t}, x) one token at a time (Section 2): verify with k = 1. */
+int ad_decode_greedy(ad_ctx* ctx, const int32_t* src, const int32_t* src_len, int B,
+                     const int32_t* max_out, int32_t* out, int32_t* out_len, ad_stats* stats);
+
+/* Algorithm 1.  The guide x (NULL: the source itself) is [B, guide_stride] with
+ * guide_len[b] content ids per row; [BOS] is prepended and the never-matching [PAD]
+ * appended internally.  Each iteration looks for the shortest suffix of the output that
+ * occurs exactly once in the guide; on a match the rest of the guide (at most k_max
+ * tokens) is verified in parallel, otherwise one autoregressive step is taken. */
+int ad_decode_iad(ad_ctx* ctx, const int32_t* src, const int32_t* src_len,
+                  const int32_t* guide, const int32_t* guide_len, int guide_stride, int B,
+                  const int32_t* max_out, int32_t* out, int32_t* out_len, ad_stats* stats);
+
+/* Draft k tokens, verify them, accept through the bifurcation, repeat (Section 3.2).
+ * use_drafter != 0 runs the block drafter each iteration (needs drafter weights).
+ * draft_override (nullable, [B, override_stride], override_len[b] entries per row) is a
+ * positional draft D: output position p is proposed D[b][p]; when given it replaces the
+ * drafter's proposal (the drafter, if enabled, still runs). */
+int ad_decode_gad(ad_ctx* ctx, const int32_t* src, const int32_t* src_len, int B, int k,
+                  int use_drafter, const int32_t* draft_override, const int32_t* override_len,
+                  int override_stride, const int32_t* max_out,
+                  int32_t* out, int32_t* out_len, ad_stats* stats);
+
+/* ---- inspection ------------------------------------------------------------------------------ */
+
+/* Full logits [rows, vocab] (fp32, host) of the last ad_verify or ad_draft_nat, rows in
+ * packed order (sequence by sequence).  Needs cfg.debug_logits; AD_ESTATE otherwise. */
+int ad_debug_logits(ad_ctx* ctx, float* logits, int rows_cap, int* rows);
+
+/* Re-launches the kernels of the last ad_verify forward `reps` times on the context's
+ * stream without touching decode state (the appended cache rows are rewritten with the
+ * same values) and reports the mean duration, by HIP events on that stream, of the whole
+ * forward and of its output-projection/arg-max kernel.  For roofline measurements. */
+int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us);
+
+/* ---- host-only logic, exposed so that it can be tested without a GPU -------------------------- */
+
+/* The if-test of Algorithm 1: o = (o_0..o_j), x = guide with sentinels (x_0 = [BOS],
+ * last = AD_NEVER).  Finds the smallest q >= 0 for which o_{j-q..j} occurs in x; if it
+ * occurs exactly once, *i_out = the index in x of its last token and 1 is returned;
+ * otherwise (never, or every suffix occurs several times) 0 is returned. */
+int ad_suffix_match(const int32_t* o, int o_len, const int32_t* x, int x_len, int* i_out);
+
+/* Runs the library's own decode loops (the same code ad_decode_iad / ad_decode_gad run)
+ * over a model-free stand-in verifier that knows the greedy output g[0..g_len): fed a
+ * prefix that agrees with g it predicts g's next token, after a disagreement it predicts
+ * garbage.  mode 0: input-guided with `aux` = guide content ids; mode 1: positional
+ * draft `aux` with block size k.  Writes the output, per-iteration accepted counts
+ * (up to acc_cap) and stats. */
+int ad_host_simulate(int mode, const int32_t* g, int g_len, const int32_t* aux, int aux_len,
+                     int k, int k_max, int max_out, int eos, int bos,
+                     int32_t* out, int32_t* out_len, int32_t* accepted, int acc_cap,
+                     ad_stats* stats);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AD_H_ */

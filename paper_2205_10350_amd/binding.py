@@ -1,0 +1,301 @@
+"""ctypes binding of the C ABI in include/ad.h: argument marshalling only.
+
+Every step of the decoding path runs inside the HIP library; PyTorch is used here for
+device memory (weight blobs, workspace) and for the stream handle, nothing else.
+There is no fallback: if the library is missing this module raises on import of `lib()`.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libad_mi355x.so")
+
+AD_OK, AD_EINVAL, AD_ESTATE, AD_ENOMEM, AD_EDEVICE = 0, -1, -2, -3, -4
+AD_F32, AD_BF16 = 0, 1
+AD_VERIFIER, AD_DRAFTER = 0, 1
+AD_NEVER = -1
+
+EXPORTS = [
+    "ad_config_check", "ad_workspace_bytes", "ad_weights_count", "ad_weights_bytes", "ad_weights_entry",
+    "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
+    "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
+    "ad_suffix_match", "ad_host_simulate",
+]
+
+
+class AdConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "enc_layers", "dec_layers", "d_model", "n_heads", "d_ffn", "vocab",
+        "max_batch", "max_src", "max_len", "k_max", "bos", "pad", "eos", "mask",
+        "dtype", "tie_output", "debug_logits")]
+
+
+class AdStats(C.Structure):
+    _fields_ = [("iterations", C.c_int64), ("rows_verified", C.c_int64), ("draft_rows", C.c_int64),
+                ("tokens_out", C.c_int64), ("t_encode_us", C.c_double), ("t_draft_us", C.c_double),
+                ("t_verify_us", C.c_double), ("t_host_us", C.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class AdError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"ad error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+_I32P = C.POINTER(C.c_int32)
+
+
+def lib():
+    """The loaded HIP library.  Raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2205_10350_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    cfgp = C.POINTER(AdConfig)
+    L.ad_config_check.argtypes = [cfgp]; L.ad_config_check.restype = C.c_int
+    L.ad_workspace_bytes.argtypes = [cfgp, C.c_int]; L.ad_workspace_bytes.restype = C.c_size_t
+    L.ad_weights_count.argtypes = [cfgp]; L.ad_weights_count.restype = C.c_int
+    L.ad_weights_bytes.argtypes = [cfgp]; L.ad_weights_bytes.restype = C.c_size_t
+    L.ad_weights_entry.argtypes = [cfgp, C.c_int, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t), _I32P, _I32P, _I32P]
+    L.ad_weights_entry.restype = C.c_int
+    L.ad_create.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
+    L.ad_create.restype = C.c_int
+    L.ad_destroy.argtypes = [C.c_void_p]; L.ad_destroy.restype = C.c_int
+    L.ad_last_error.argtypes = [C.c_void_p]; L.ad_last_error.restype = C.c_char_p
+    L.ad_encode.argtypes = [C.c_void_p, C.c_int, _I32P, _I32P, C.c_int, _I32P]; L.ad_encode.restype = C.c_int
+    L.ad_verify.argtypes = [C.c_void_p, _I32P, _I32P, _I32P, _I32P, _I32P]; L.ad_verify.restype = C.c_int
+    L.ad_draft_nat.argtypes = [C.c_void_p, C.c_int, _I32P]; L.ad_draft_nat.restype = C.c_int
+    L.ad_output.argtypes = [C.c_void_p, _I32P, _I32P]; L.ad_output.restype = C.c_int
+    sp = C.POINTER(AdStats)
+    L.ad_decode_greedy.argtypes = [C.c_void_p, _I32P, _I32P, C.c_int, _I32P, _I32P, _I32P, sp]
+    L.ad_decode_greedy.restype = C.c_int
+    L.ad_decode_iad.argtypes = [C.c_void_p, _I32P, _I32P, _I32P, _I32P, C.c_int, C.c_int, _I32P, _I32P, _I32P, sp]
+    L.ad_decode_iad.restype = C.c_int
+    L.ad_decode_gad.argtypes = [C.c_void_p, _I32P, _I32P, C.c_int, C.c_int, C.c_int, _I32P, _I32P, C.c_int, _I32P,
+                                _I32P, _I32P, sp]
+    L.ad_decode_gad.restype = C.c_int
+    L.ad_debug_logits.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)]
+    L.ad_debug_logits.restype = C.c_int
+    L.ad_time_verify_forward.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.ad_time_verify_forward.restype = C.c_int
+    L.ad_suffix_match.argtypes = [_I32P, C.c_int, _I32P, C.c_int, C.POINTER(C.c_int)]; L.ad_suffix_match.restype = C.c_int
+    L.ad_host_simulate.argtypes = [C.c_int, _I32P, C.c_int, _I32P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                   _I32P, _I32P, _I32P, C.c_int, sp]
+    L.ad_host_simulate.restype = C.c_int
+    _lib = L
+    return L
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_I32P)
+
+
+def _check(rc, ctx=None):
+    if rc != AD_OK:
+        raise AdError(rc, (lib().ad_last_error(ctx) or b"").decode())
+
+
+def make_config(dims: dict, *, max_batch, max_src, max_len, k_max, dtype, special, tie_output=False,
+                debug_logits=False) -> AdConfig:
+    return AdConfig(dims["enc_layers"], dims["dec_layers"], dims["d_model"], dims["n_heads"], dims["d_ffn"],
+                    dims["vocab"], max_batch, max_src, max_len, k_max, special["bos"], special["pad"],
+                    special["eos"], special["mask"], AD_BF16 if dtype == "bf16" else AD_F32,
+                    int(tie_output), int(debug_logits))
+
+
+# ---- host-only calls -------------------------------------------------------------------------
+def config_check(cfg: AdConfig) -> int:
+    return lib().ad_config_check(C.byref(cfg))
+
+
+def workspace_bytes(cfg: AdConfig, with_drafter: bool) -> int:
+    return lib().ad_workspace_bytes(C.byref(cfg), int(with_drafter))
+
+
+def weights_layout(cfg: AdConfig):
+    """[(name, offset, rows, cols, elem_bytes)], total bytes."""
+    L = lib()
+    n = L.ad_weights_count(C.byref(cfg))
+    out = []
+    name = C.create_string_buffer(64)
+    off = C.c_size_t(); r = C.c_int32(); c = C.c_int32(); eb = C.c_int32()
+    for i in range(n):
+        _check(L.ad_weights_entry(C.byref(cfg), i, name, 64, C.byref(off), C.byref(r), C.byref(c), C.byref(eb)))
+        out.append((name.value.decode(), off.value, r.value, c.value, eb.value))
+    return out, L.ad_weights_bytes(C.byref(cfg))
+
+
+def suffix_match(o, x):
+    o, x = _i32(o), _i32(x)
+    i = C.c_int(-1)
+    found = lib().ad_suffix_match(_p(o), len(o), _p(x), len(x), C.byref(i))
+    return i.value if found else None
+
+
+def host_simulate(mode, g, aux, *, k=1, k_max=64, max_out=64, eos=2, bos=0):
+    g, aux = _i32(g), _i32(aux)
+    out = np.zeros(max_out, dtype=np.int32)
+    n = np.zeros(1, dtype=np.int32)
+    acc = np.zeros(max_out + 1, dtype=np.int32)
+    st = AdStats()
+    _check(lib().ad_host_simulate(mode, _p(g), len(g), _p(aux), len(aux), k, k_max, max_out, eos, bos,
+                                  _p(out), _p(n), _p(acc), len(acc), C.byref(st)))
+    return out[:n[0]].tolist(), acc[:st.iterations].tolist(), st.as_dict()
+
+
+# ---- device side ------------------------------------------------------------------------------
+def pack_weights(cfg: AdConfig, params: dict, device="cuda"):
+    """Lays a {name: fp32 ndarray} parameter set out as the library's flat blob on `device`.
+    In bf16 mode matrices are rounded to bfloat16 (nearest even); vectors stay fp32."""
+    import torch
+    layout, total = weights_layout(cfg)
+    blob = torch.zeros(total, dtype=torch.uint8)
+    for name, off, rows, cols, eb in layout:
+        w = np.ascontiguousarray(params[name], dtype=np.float32).reshape(rows, cols)
+        t = torch.from_numpy(w)
+        if eb == 2:
+            t = t.to(torch.bfloat16)
+        raw = t.contiguous().view(torch.uint8).reshape(-1)
+        blob[off:off + raw.numel()] = raw
+    return blob.to(device)
+
+
+class Context:
+    """One ad_ctx with its device memory.  Methods mirror the C entry points."""
+
+    def __init__(self, cfg: AdConfig, verifier_params: dict, drafter_params: dict | None = None, device="cuda:0"):
+        import torch
+        self._torch = torch
+        self.cfg = cfg
+        self.L = lib()
+        _check(self.L.ad_config_check(C.byref(cfg)))
+        torch.cuda.set_device(device)
+        self.w_ver = pack_weights(cfg, verifier_params, device)
+        self.w_dr = pack_weights(cfg, drafter_params, device) if drafter_params is not None else None
+        nbytes = workspace_bytes(cfg, drafter_params is not None)
+        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+        self.stream = torch.cuda.current_stream()
+        h = C.c_void_p()
+        _check(self.L.ad_create(C.byref(cfg), C.c_void_p(self.w_ver.data_ptr()),
+                                C.c_void_p(self.w_dr.data_ptr()) if self.w_dr is not None else None,
+                                C.c_void_p(self.workspace.data_ptr()), nbytes,
+                                C.c_void_p(self.stream.cuda_stream), C.byref(h)))
+        self.h = h
+        self.B = 0
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.L.ad_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- marshalling helpers
+    def _pad_rows(self, rows, width, fill=0):
+        a = np.full((len(rows), width), fill, dtype=np.int32)
+        lens = np.zeros(len(rows), dtype=np.int32)
+        for b, r in enumerate(rows):
+            r = np.asarray(r, dtype=np.int32)
+            a[b, :min(len(r), width)] = r[:width]
+            lens[b] = len(r)          # an over-long row keeps its true length: the library rejects it
+        return a, lens
+
+    def encode(self, model, srcs, max_out=None):
+        src, src_len = self._pad_rows(srcs, self.cfg.max_src)
+        mo = None if max_out is None else _i32(max_out)
+        _check(self.L.ad_encode(self.h, model, _p(src), _p(src_len), len(srcs), _p(mo)), self.h)
+        if model == AD_VERIFIER:
+            self.B = len(srcs)
+
+    def verify(self, drafts, want_verified=False):
+        """drafts: list of B token lists (empty = sit out).  Returns n_accept, next, [verified]."""
+        km = self.cfg.k_max
+        d, k = self._pad_rows(drafts, km)
+        n = np.zeros(self.B, dtype=np.int32); nx = np.zeros(self.B, dtype=np.int32)
+        ver = np.zeros((self.B, km), dtype=np.int32) if want_verified else None
+        _check(self.L.ad_verify(self.h, _p(d), _p(k), _p(n), _p(nx), _p(ver)), self.h)
+        return (n, nx, ver) if want_verified else (n, nx)
+
+    def draft_nat(self, k):
+        out = np.zeros((self.B, self.cfg.k_max), dtype=np.int32)
+        _check(self.L.ad_draft_nat(self.h, k, _p(out)), self.h)
+        return out[:, :k]
+
+    def output(self):
+        out = np.zeros((self.B, self.cfg.max_len), dtype=np.int32)
+        n = np.zeros(self.B, dtype=np.int32)
+        _check(self.L.ad_output(self.h, _p(out), _p(n)), self.h)
+        return [out[b, :n[b]].tolist() for b in range(self.B)]
+
+    def _result(self, out, n, st):
+        return [out[b, :n[b]].tolist() for b in range(len(n))], st.as_dict()
+
+    def decode_greedy(self, srcs, max_out=None):
+        src, sl = self._pad_rows(srcs, self.cfg.max_src)
+        B = len(srcs)
+        out = np.zeros((B, self.cfg.max_len), dtype=np.int32); n = np.zeros(B, dtype=np.int32); st = AdStats()
+        mo = None if max_out is None else _i32(max_out)
+        _check(self.L.ad_decode_greedy(self.h, _p(src), _p(sl), B, _p(mo), _p(out), _p(n), C.byref(st)), self.h)
+        self.B = B
+        return self._result(out, n, st)
+
+    def decode_iad(self, srcs, guides=None, max_out=None):
+        src, sl = self._pad_rows(srcs, self.cfg.max_src)
+        B = len(srcs)
+        g = gl = None
+        stride = 0
+        if guides is not None:
+            stride = max(1, max(len(x) for x in guides))
+            g, gl = self._pad_rows(guides, stride)
+        out = np.zeros((B, self.cfg.max_len), dtype=np.int32); n = np.zeros(B, dtype=np.int32); st = AdStats()
+        mo = None if max_out is None else _i32(max_out)
+        _check(self.L.ad_decode_iad(self.h, _p(src), _p(sl), _p(g), _p(gl), stride, B, _p(mo), _p(out), _p(n),
+                                    C.byref(st)), self.h)
+        self.B = B
+        return self._result(out, n, st)
+
+    def decode_gad(self, srcs, k, use_drafter=False, draft_override=None, max_out=None):
+        src, sl = self._pad_rows(srcs, self.cfg.max_src)
+        B = len(srcs)
+        D = dl = None
+        stride = 0
+        if draft_override is not None:
+            stride = max(1, max(len(x) for x in draft_override))
+            D, dl = self._pad_rows(draft_override, stride)
+        out = np.zeros((B, self.cfg.max_len), dtype=np.int32); n = np.zeros(B, dtype=np.int32); st = AdStats()
+        mo = None if max_out is None else _i32(max_out)
+        _check(self.L.ad_decode_gad(self.h, _p(src), _p(sl), B, k, int(use_drafter), _p(D), _p(dl), stride, _p(mo),
+                                    _p(out), _p(n), C.byref(st)), self.h)
+        self.B = B
+        return self._result(out, n, st)
+
+    def debug_logits(self):
+        cap = self.cfg.max_batch * self.cfg.k_max
+        buf = np.zeros((cap, self.cfg.vocab), dtype=np.float32)
+        rows = C.c_int(0)
+        _check(self.L.ad_debug_logits(self.h, buf.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(rows)), self.h)
+        return buf[:rows.value].copy()
+
+    def time_verify_forward(self, reps=20):
+        a, b = C.c_double(0), C.c_double(0)
+        _check(self.L.ad_time_verify_forward(self.h, reps, C.byref(a), C.byref(b)), self.h)
+        return a.value, b.value

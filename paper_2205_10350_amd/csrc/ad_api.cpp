@@ -1,0 +1,654 @@
+// Context, workspace plan and the forward passes (encode, verify, draft) behind the C ABI.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <chrono>
+#include <string>
+#include <vector>
+
+#include "ad_internal.h"
+
+namespace ad {
+const char* global_error();
+
+static size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------------------------
+// Workspace plan: one pass computes offsets; used both for sizing and for binding.
+struct Plan {
+  size_t total = 0;
+  int esz = 4;          // storage element size of activations / caches
+  int m_cap = 0;        // packed rows of any forward
+  int mv_cap = 0;       // rows that reach the output projection
+  int l_cap = 0;        // rows of a sequence's self-attention cache
+  int n_strips = 0;
+  int max_pos = 0;
+  size_t pe, x, s, xa, q, att, tk, tv, f, xg, part_val, part_idx, o_hat, o_val, logits;
+  size_t cache_k, cache_v, cache_layer_stride;          // [NL][B*l_cap, d]
+  size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
+  size_t row_tok, row_pos, row_seq, row_dst, row_dst2, row_start, self_desc, cross_desc, mask_rows;
+  size_t len, pending, finished, max_out, src_len[2], out, result, k_dev, draft_dev, src_dev, draft_out;
+};
+
+static Plan make_plan(const ad_config& c, bool with_drafter) {
+  Plan p;
+  p.esz = c.dtype == AD_BF16 ? 2 : 4;
+  const size_t B = c.max_batch, d = c.d_model;
+  p.l_cap = c.max_len + c.k_max;
+  p.mv_cap = (int)(B * c.k_max);
+  size_t m = std::max(B * c.k_max, B * c.max_src);
+  if (with_drafter) m = std::max(m, B * (size_t)(c.max_len + c.k_max));
+  p.m_cap = (int)m;
+  p.n_strips = c.vocab / 16;
+  p.max_pos = std::max(c.max_src, c.max_len + c.k_max);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  p.pe = take((size_t)p.max_pos * d * 4);
+  p.x = take(m * d * 4);
+  p.s = take(m * d * 4);
+  p.xa = take(m * d * p.esz);
+  p.q = take(m * d * p.esz);
+  p.att = take(m * d * p.esz);
+  p.tk = take(m * d * p.esz);
+  p.tv = take(m * d * p.esz);
+  p.f = take(m * (size_t)c.d_ffn * p.esz);
+  p.xg = take((size_t)p.mv_cap * d * p.esz);
+  p.part_val = take((size_t)p.mv_cap * p.n_strips * 4);
+  p.part_idx = take((size_t)p.mv_cap * p.n_strips * 4);
+  p.o_hat = take((size_t)p.mv_cap * 4);
+  p.o_val = take((size_t)p.mv_cap * 4);
+  p.logits = take(c.debug_logits ? (size_t)p.mv_cap * c.vocab * 4 : 0);
+  p.cache_layer_stride = align_up(B * p.l_cap * d * p.esz);
+  p.cache_k = take(p.cache_layer_stride * c.dec_layers);
+  p.cache_v = take(p.cache_layer_stride * c.dec_layers);
+  p.mem_layer_stride = align_up(B * c.max_src * d * p.esz);
+  for (int i = 0; i < 2; ++i) {
+    const bool on = i == 0 || with_drafter;
+    p.mem_k[i] = take(on ? p.mem_layer_stride * c.dec_layers : 0);
+    p.mem_v[i] = take(on ? p.mem_layer_stride * c.dec_layers : 0);
+    p.src_len[i] = take(B * 4);
+  }
+  p.row_tok = take(m * 4); p.row_pos = take(m * 4); p.row_seq = take(m * 4); p.row_dst = take(m * 4); p.row_dst2 = take(m * 4);
+  p.row_start = take((B + 1) * 4);
+  p.self_desc = take(B * sizeof(SeqDesc));
+  p.cross_desc = take(B * sizeof(SeqDesc));
+  p.mask_rows = take((size_t)p.mv_cap * 4);
+  p.len = take(B * 4); p.pending = take(B * 4); p.finished = take(B * 4); p.max_out = take(B * 4);
+  p.out = take(B * c.max_len * 4);
+  p.result = take(B * 2 * 4);
+  p.k_dev = take(B * 4 + B * c.k_max * 4);   // k[B] followed by draft[B, k_max]: one upload
+  p.draft_dev = p.k_dev + B * 4;
+  p.src_dev = take(B * 4 * 2 + B * c.max_src * 4);   // src_len[B], max_out[B], src[B, max_src]: one upload
+  p.draft_out = take(B * c.k_max * 4);
+  p.total = off;
+  return p;
+}
+
+}  // namespace ad
+
+using namespace ad;
+
+struct ad_ctx {
+  ad_config cfg;
+  Plan plan;
+  ModelW w[2];
+  bool has_drafter = false;
+  char* ws = nullptr;
+  hipStream_t stream = nullptr;
+  hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr, ev3 = nullptr;
+  int32_t* pin = nullptr;       // pinned staging, ints
+  size_t pin_ints = 0;
+  std::string err;
+  // host mirror of the decode state
+  int B = 0;
+  bool encoded[2] = {false, false};
+  std::vector<int> h_len, h_finished, h_max_out, h_src_len[2];
+  // last verify call, for ad_time_verify_forward / ad_debug_logits
+  int last_M = 0;
+  int last_logit_rows = 0;
+
+  template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
+};
+
+static int fail(ad_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  set_global_error(msg.c_str());
+  return code;
+}
+#define HIP_TRY(ctx, expr)                                                                      \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) return fail(ctx, AD_EDEVICE, std::string(#expr ": ") + hipGetErrorString(e_)); \
+  } while (0)
+
+static double now_us() {
+  return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward passes.  All launches go to ctx->stream; shapes were validated by the callers.
+
+static const void* w_rows(const ad_ctx* c, const void* w, size_t rows, size_t cols) {
+  return (const char*)w + rows * cols * (c->cfg.dtype == AD_BF16 ? 2 : 4);
+}
+
+static VerifyTables tables(const ad_ctx* c) {
+  const Plan& p = c->plan;
+  VerifyTables t;
+  t.row_tok = c->at<int>(p.row_tok); t.row_pos = c->at<int>(p.row_pos); t.row_seq = c->at<int>(p.row_seq);
+  t.row_dst = c->at<int>(p.row_dst); t.row_dst2 = c->at<int>(p.row_dst2); t.row_start = c->at<int>(p.row_start);
+  t.self_desc = c->at<SeqDesc>(p.self_desc); t.cross_desc = c->at<SeqDesc>(p.cross_desc);
+  return t;
+}
+
+static void gemm_resid_ln(ad_ctx* c, const void* A, const void* W, const float* bias, int M, int N, int K,
+                          const LnW& ln) {
+  const Plan& p = c->plan;
+  Epi e{};
+  e.mode = EPI_RESID; e.bias = bias; e.out0 = c->at<float>(p.s); e.resid = c->at<float>(p.x);
+  launch_gemm(c->cfg.dtype, A, W, M, N, K, e, c->stream);
+  launch_layernorm(c->cfg.dtype, c->at<float>(p.s), ln.g, ln.b, M, N, c->at<float>(p.x), c->at<void>(p.xa), c->stream);
+}
+
+static void ffn_block(ad_ctx* c, const FfnW& f, const LnW& ln, int M) {
+  const Plan& p = c->plan;
+  const int d = c->cfg.d_model, F = c->cfg.d_ffn;
+  Epi e{};
+  e.mode = EPI_RELU; e.bias = f.b1; e.out0 = c->at<void>(p.f);
+  launch_gemm(c->cfg.dtype, c->at<void>(p.xa), f.w1, M, F, d, e, c->stream);
+  gemm_resid_ln(c, c->at<void>(p.f), f.w2, f.b2, M, d, F, ln);
+}
+
+// Self-attention block: q,k,v projection with the key/value rows written to (Kl, Vl) at
+// row_dst, attention, output projection + residual + LayerNorm.
+static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, void* Kl, void* Vl, int max_keys) {
+  const Plan& p = c->plan;
+  const int d = c->cfg.d_model, H = c->cfg.n_heads;
+  VerifyTables t = tables(c);
+  Epi e{};
+  e.mode = EPI_QKV; e.d = d; e.bias = a.bqkv; e.out0 = c->at<void>(p.q); e.out1 = Kl; e.out2 = Vl; e.row_dst = t.row_dst;
+  launch_gemm(c->cfg.dtype, c->at<void>(p.xa), a.wqkv, M, 3 * d, d, e, c->stream);
+  launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.row_seq, t.self_desc, M, H, d / H,
+                   max_keys, c->stream);
+  gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
+}
+
+static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, const void* Km, const void* Vm) {
+  const Plan& p = c->plan;
+  const int d = c->cfg.d_model, H = c->cfg.n_heads;
+  VerifyTables t = tables(c);
+  Epi e{};
+  e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
+  launch_gemm(c->cfg.dtype, c->at<void>(p.xa), a.wqkv, M, d, d, e, c->stream);
+  launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.row_seq, t.cross_desc, M, H, d / H,
+                   c->cfg.max_src, c->stream);
+  gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
+}
+
+static void embed_rows(ad_ctx* c, const ModelW& w, int M) {
+  const Plan& p = c->plan;
+  VerifyTables t = tables(c);
+  launch_embed(c->cfg.dtype, w.emb, c->at<float>(p.pe), t.row_tok, t.row_pos, M, c->cfg.d_model,
+               sqrtf((float)c->cfg.d_model), c->at<float>(p.x), c->at<void>(p.xa), c->stream);
+}
+
+// Output projection fused with the per-row arg max; `A` holds Mv rows.
+static void vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv) {
+  const Plan& p = c->plan;
+  Epi e{};
+  e.mode = EPI_ARGMAX; e.part_val = c->at<float>(p.part_val); e.part_idx = c->at<int>(p.part_idx);
+  e.n_strips = p.n_strips; e.logits = c->cfg.debug_logits ? c->at<float>(p.logits) : nullptr;
+  launch_gemm(c->cfg.dtype, A, w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream);
+}
+static void vocab_finish(ad_ctx* c, int Mv) {
+  const Plan& p = c->plan;
+  launch_argmax_finish(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, c->at<int>(p.o_hat),
+                       c->at<float>(p.o_val), c->stream);
+}
+
+// The verify forward over the M packed rows the tables describe.  ev (optional) brackets the
+// output-projection kernel.
+static void verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr) {
+  const Plan& p = c->plan;
+  const ModelW& w = c->w[AD_VERIFIER];
+  embed_rows(c, w, M);
+  for (int l = 0; l < c->cfg.dec_layers; ++l) {
+    const DecLayerW& L = w.dec[l];
+    self_attn_block(c, L.self, L.ln1, M, c->ws + p.cache_k + l * p.cache_layer_stride,
+                    c->ws + p.cache_v + l * p.cache_layer_stride, p.l_cap);
+    cross_attn_block(c, L.cross, L.ln2, M, c->ws + p.mem_k[0] + l * p.mem_layer_stride,
+                     c->ws + p.mem_v[0] + l * p.mem_layer_stride);
+    ffn_block(c, L.ffn, L.ln3, M);
+  }
+  if (ev_a) (void)hipEventRecord(ev_a, c->stream);
+  vocab_argmax(c, w, c->at<void>(p.xa), M);
+  if (ev_b) (void)hipEventRecord(ev_b, c->stream);
+  vocab_finish(c, M);
+}
+
+static int check_batch(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!src || !src_len) return fail(c, AD_EINVAL, "null source buffer");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, AD_EINVAL, "B outside [1, max_batch]");
+  for (int b = 0; b < B; ++b) {
+    if (src_len[b] < 1 || src_len[b] > c->cfg.max_src) return fail(c, AD_EINVAL, "src_len outside [1, max_src]");
+    for (int i = 0; i < src_len[b]; ++i) {
+      int32_t t = src[(size_t)b * c->cfg.max_src + i];
+      if (t < 0 || t >= c->cfg.vocab) return fail(c, AD_EINVAL, "source token id outside the vocabulary");
+    }
+  }
+  return AD_OK;
+}
+
+// Device-backed verifier for the host loops.
+struct GpuBackend : Backend {
+  ad_ctx* c;
+  explicit GpuBackend(ad_ctx* ctx) : c(ctx) {}
+  int verify(const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next) override {
+    return ad_verify(c, draft, k, n_accept, next, nullptr);
+  }
+  int draft(int k, int32_t* out) override { return ad_draft_nat(c, k, out); }
+};
+
+static LoopIO make_io(ad_ctx* c, int B, const int32_t* max_out) {
+  LoopIO io;
+  io.B = B; io.k_max = c->cfg.k_max; io.eos = c->cfg.eos; io.bos = c->cfg.bos;
+  io.max_out.resize(B);
+  for (int b = 0; b < B; ++b) io.max_out[b] = max_out ? max_out[b] : c->cfg.max_len;
+  return io;
+}
+static void write_out(ad_ctx* c, const LoopIO& io, int32_t* out, int32_t* out_len, ad_stats* stats, double t_enc) {
+  for (int b = 0; b < io.B; ++b) {
+    out_len[b] = (int)io.o[b].size() - 1;
+    for (int i = 0; i < out_len[b]; ++i) out[(size_t)b * c->cfg.max_len + i] = io.o[b][i + 1];
+  }
+  if (stats) { *stats = io.stats; stats->t_encode_us = t_enc; }
+}
+
+// =================================================================================================
+extern "C" {
+
+const char* ad_last_error(const ad_ctx* ctx) { return ctx ? ctx->err.c_str() : ad::global_error(); }
+
+size_t ad_workspace_bytes(const ad_config* cfg, int with_drafter) {
+  if (ad_config_check(cfg) != AD_OK) return 0;
+  return make_plan(*cfg, with_drafter != 0).total;
+}
+
+int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_w, void* workspace,
+              size_t workspace_bytes, void* hip_stream, ad_ctx** out) {
+  if (!out) return fail(nullptr, AD_EINVAL, "null out pointer");
+  *out = nullptr;
+  int rc = ad_config_check(cfg);
+  if (rc != AD_OK) return rc;
+  if (!verifier_w || !workspace) return fail(nullptr, AD_EINVAL, "null verifier weights or workspace");
+  if (((uintptr_t)verifier_w | (uintptr_t)drafter_w | (uintptr_t)workspace) & 255)
+    return fail(nullptr, AD_EINVAL, "device pointers must be 256-byte aligned");
+  Plan plan = make_plan(*cfg, drafter_w != nullptr);
+  if (workspace_bytes < plan.total) return fail(nullptr, AD_ENOMEM, "workspace smaller than ad_workspace_bytes()");
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, AD_EDEVICE, "no HIP device");
+  ad_ctx* c = new ad_ctx();
+  c->cfg = *cfg;
+  c->plan = plan;
+  c->ws = (char*)workspace;
+  c->stream = (hipStream_t)hip_stream;
+  c->w[0] = bind_weights(*cfg, verifier_w);
+  c->has_drafter = drafter_w != nullptr;
+  if (c->has_drafter) c->w[1] = bind_weights(*cfg, drafter_w);
+  const size_t B = cfg->max_batch;
+  c->pin_ints = 4 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 64;
+  auto bail = [&](const char* what, hipError_t e) {
+    std::string m = std::string(what) + ": " + hipGetErrorString(e);
+    if (c->pin) (void)hipHostFree(c->pin);
+    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3})
+      if (ev) (void)hipEventDestroy(ev);
+    delete c;
+    return fail(nullptr, AD_EDEVICE, m);
+  };
+  hipError_t e;
+  if ((e = hipHostMalloc((void**)&c->pin, c->pin_ints * 4, hipHostMallocDefault)) != hipSuccess) return bail("hipHostMalloc", e);
+  if ((e = hipEventCreate(&c->ev0)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipEventCreate(&c->ev1)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipEventCreate(&c->ev2)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipEventCreate(&c->ev3)) != hipSuccess) return bail("hipEventCreate", e);
+  // sinusoidal positions: PE(p, 2i) = sin(p / 10000^(2i/d)), PE(p, 2i+1) = cos(same)
+  {
+    const int d = cfg->d_model;
+    std::vector<float> pe((size_t)plan.max_pos * d);
+    for (int i = 0; i < d / 2; ++i) {
+      const double freq = pow(10000.0, -2.0 * i / d);
+      for (int pos = 0; pos < plan.max_pos; ++pos) {
+        pe[(size_t)pos * d + 2 * i] = (float)sin(pos * freq);
+        pe[(size_t)pos * d + 2 * i + 1] = (float)cos(pos * freq);
+      }
+    }
+    if ((e = hipMemcpyAsync(c->ws + plan.pe, pe.data(), pe.size() * 4, hipMemcpyHostToDevice, c->stream)) != hipSuccess)
+      return bail("hipMemcpyAsync(pe)", e);
+    if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail("hipStreamSynchronize", e);
+  }
+  c->h_len.assign(B, 0); c->h_finished.assign(B, 1); c->h_max_out.assign(B, 0);
+  c->h_src_len[0].assign(B, 0); c->h_src_len[1].assign(B, 0);
+  *out = c;
+  return AD_OK;
+}
+
+int ad_destroy(ad_ctx* c) {
+  if (!c) return AD_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  if (c->pin) (void)hipHostFree(c->pin);
+  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3})
+    if (ev) (void)hipEventDestroy(ev);
+  delete c;
+  return AD_OK;
+}
+
+int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, int B, const int32_t* max_out) {
+  int rc = check_batch(c, src, src_len, B);
+  if (rc != AD_OK) return rc;
+  if (model != AD_VERIFIER && model != AD_DRAFTER) return fail(c, AD_EINVAL, "model must be AD_VERIFIER or AD_DRAFTER");
+  if (model == AD_DRAFTER && !c->has_drafter) return fail(c, AD_ESTATE, "context has no drafter weights");
+  if (max_out)
+    for (int b = 0; b < B; ++b)
+      if (max_out[b] < 1 || max_out[b] > c->cfg.max_len) return fail(c, AD_EINVAL, "max_out outside [1, max_len]");
+  const ad_config& cf = c->cfg;
+  const Plan& p = c->plan;
+  const int d = cf.d_model, S = cf.max_src;
+  // one upload: src_len[B], max_out[B], src[B, max_src]
+  int32_t* h = c->pin;
+  int M = 0;
+  for (int b = 0; b < B; ++b) {
+    h[b] = src_len[b];
+    h[B + b] = max_out ? max_out[b] : cf.max_len;
+    M += src_len[b];
+  }
+  memcpy(h + 2 * B, src, (size_t)B * S * 4);
+  int* dev = c->at<int>(p.src_dev);
+  HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.src_len[model]), dev, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
+  VerifyTables t = tables(c);
+  launch_assemble_encoder(dev + 2 * B, S, dev, B, S, t, c->stream);
+  const ModelW& w = c->w[model];
+  embed_rows(c, w, M);
+  for (int l = 0; l < cf.enc_layers; ++l) {
+    const EncLayerW& L = w.enc[l];
+    // the sentence's own keys/values live in the packed temporaries: key row = packed row
+    Epi e{};
+    e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
+    e.out1 = c->at<void>(p.tk); e.out2 = c->at<void>(p.tv); e.row_dst = t.row_dst;
+    launch_gemm(cf.dtype, c->at<void>(p.xa), L.self.wqkv, M, 3 * d, d, e, c->stream);
+    launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att), t.row_seq,
+                     t.self_desc, M, cf.n_heads, d / cf.n_heads, S, c->stream);
+    gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
+    ffn_block(c, L.ffn, L.ln2, M);
+  }
+  // cross-attention keys and values of every decoder layer: memory . [wk; wv]^T + [bk; bv]
+  for (int l = 0; l < cf.dec_layers; ++l) {
+    const AttnW& a = w.dec[l].cross;
+    Epi e{};
+    e.mode = EPI_KV; e.d = d; e.bias = a.bqkv + d;
+    e.out1 = c->ws + p.mem_k[model] + l * p.mem_layer_stride;
+    e.out2 = c->ws + p.mem_v[model] + l * p.mem_layer_stride;
+    e.row_dst = t.row_dst2;
+    launch_gemm(cf.dtype, c->at<void>(p.xa), w_rows(c, a.wqkv, d, d), M, 2 * d, d, e, c->stream);
+  }
+  if (model == AD_VERIFIER) {
+    launch_reset_state(c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished), B, cf.bos, c->stream);
+    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.max_out), dev + B, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipGetLastError());
+  c->h_src_len[model].assign(src_len, src_len + B);
+  c->encoded[model] = true;
+  if (model == AD_VERIFIER) {
+    c->B = B;
+    for (int b = 0; b < B; ++b) {
+      c->h_len[b] = 0; c->h_finished[b] = 0; c->h_max_out[b] = max_out ? max_out[b] : cf.max_len;
+    }
+    c->encoded[AD_DRAFTER] = false;   // a new decode needs a fresh drafter memory
+    c->last_M = 0;
+  }
+  return AD_OK;
+}
+
+int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
+              int32_t* verified) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!draft || !k || !n_accept || !next_token) return fail(c, AD_EINVAL, "null buffer");
+  if (!c->encoded[AD_VERIFIER]) return fail(c, AD_ESTATE, "ad_verify before ad_encode(AD_VERIFIER)");
+  const ad_config& cf = c->cfg;
+  const Plan& p = c->plan;
+  const int B = c->B, km = cf.k_max;
+  int M = 0;
+  for (int b = 0; b < B; ++b) {
+    if (k[b] < 0 || k[b] > km) return fail(c, AD_EINVAL, "k[b] outside [0, k_max]");
+    if (k[b] && c->h_finished[b]) return fail(c, AD_ESTATE, "k[b] > 0 for a finished sequence");
+    for (int i = 0; i < k[b]; ++i) {
+      int32_t t = draft[(size_t)b * km + i];
+      if (t == AD_NEVER ? i != k[b] - 1 : (t < 0 || t >= cf.vocab))
+        return fail(c, AD_EINVAL, "draft id outside the vocabulary (AD_NEVER is allowed last only)");
+    }
+    M += k[b];
+  }
+  if (M == 0) {
+    for (int b = 0; b < B; ++b) { n_accept[b] = 0; next_token[b] = 0; }
+    return AD_OK;
+  }
+  int32_t* h = c->pin;
+  memcpy(h, k, (size_t)B * 4);
+  for (int b = 0; b < B; ++b) memcpy(h + B + (size_t)b * km, draft + (size_t)b * km, (size_t)km * 4);
+  // the device copy of k and draft sits at k_dev = [k | draft] laid out for max_batch
+  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + B, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
+  VerifyTables t = tables(c);
+  launch_assemble_verify(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.len), c->at<int>(p.pending),
+                         c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
+  verify_forward(c, M);
+  launch_accept(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
+                cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
+                c->at<int>(p.out), c->at<int>(p.result), c->stream);
+  int32_t* res = c->pin + (size_t)B * (1 + km);
+  HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
+  int32_t* oh = res + 2 * B;
+  if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipGetLastError());
+  int r0 = 0;
+  for (int b = 0; b < B; ++b) {
+    n_accept[b] = res[2 * b];
+    next_token[b] = res[2 * b + 1];
+    if (k[b]) {
+      c->h_len[b] += n_accept[b];
+      c->h_finished[b] = (n_accept[b] > 0 && next_token[b] == cf.eos) || c->h_len[b] >= c->h_max_out[b];
+    }
+    if (verified) {
+      for (int i = 0; i < km; ++i) verified[(size_t)b * km + i] = i < k[b] ? oh[r0 + i] : AD_NEVER;
+    }
+    r0 += k[b];
+  }
+  c->last_M = M;
+  c->last_logit_rows = M;
+  return AD_OK;
+}
+
+int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!draft_out) return fail(c, AD_EINVAL, "null buffer");
+  if (!c->has_drafter) return fail(c, AD_ESTATE, "context has no drafter weights");
+  if (!c->encoded[AD_VERIFIER] || !c->encoded[AD_DRAFTER])
+    return fail(c, AD_ESTATE, "ad_draft_nat needs ad_encode for both models (verifier first)");
+  const ad_config& cf = c->cfg;
+  const Plan& p = c->plan;
+  if (k < 1 || k > cf.k_max) return fail(c, AD_EINVAL, "k outside [1, k_max]");
+  const int B = c->B, km = cf.k_max, d = cf.d_model;
+  int M = 0, live = 0;
+  for (int b = 0; b < B; ++b)
+    if (!c->h_finished[b]) { M += c->h_len[b] + 1 + k; ++live; }
+  if (live == 0) {
+    for (size_t i = 0; i < (size_t)B * km; ++i) draft_out[i] = AD_NEVER;
+    return AD_OK;
+  }
+  VerifyTables t = tables(c);
+  launch_assemble_drafter(c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
+                          c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->at<int>(p.mask_rows),
+                          c->stream);
+  const ModelW& w = c->w[AD_DRAFTER];
+  embed_rows(c, w, M);
+  for (int l = 0; l < cf.dec_layers; ++l) {
+    const DecLayerW& L = w.dec[l];
+    self_attn_block(c, L.self, L.ln1, M, c->at<void>(p.tk), c->at<void>(p.tv), cf.max_len + km);
+    cross_attn_block(c, L.cross, L.ln2, M, c->ws + p.mem_k[1] + l * p.mem_layer_stride,
+                     c->ws + p.mem_v[1] + l * p.mem_layer_stride);
+    ffn_block(c, L.ffn, L.ln3, M);
+  }
+  const int Mv = live * k;
+  launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
+  vocab_argmax(c, w, c->at<void>(p.xg), Mv);
+  vocab_finish(c, Mv);
+  launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
+  int32_t* h = c->pin;
+  HIP_TRY(c, hipMemcpyAsync(h, c->at<int>(p.draft_out), (size_t)B * km * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipGetLastError());
+  memcpy(draft_out, h, (size_t)B * km * 4);
+  c->last_logit_rows = Mv;
+  c->last_M = 0;   // the row tables now describe the drafter's rows
+  return AD_OK;
+}
+
+int ad_output(ad_ctx* c, int32_t* out, int32_t* out_len) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!out || !out_len) return fail(c, AD_EINVAL, "null buffer");
+  if (!c->encoded[AD_VERIFIER]) return fail(c, AD_ESTATE, "no decode in progress");
+  const int B = c->B, L = c->cfg.max_len;
+  HIP_TRY(c, hipMemcpyAsync(c->pin, c->at<int>(c->plan.out), (size_t)B * L * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int b = 0; b < B; ++b) {
+    out_len[b] = c->h_len[b];
+    for (int i = 0; i < L; ++i) out[(size_t)b * L + i] = i < c->h_len[b] ? c->pin[(size_t)b * L + i] : c->cfg.pad;
+  }
+  return AD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+static int begin_decode(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, const int32_t* max_out,
+                        bool drafter, double* t_enc) {
+  double t0 = now_us();
+  int rc = ad_encode(c, AD_VERIFIER, src, src_len, B, max_out);
+  if (rc == AD_OK && drafter) rc = ad_encode(c, AD_DRAFTER, src, src_len, B, nullptr);
+  *t_enc = now_us() - t0;
+  return rc;
+}
+
+int ad_decode_greedy(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, const int32_t* max_out,
+                     int32_t* out, int32_t* out_len, ad_stats* stats) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!out || !out_len) return fail(c, AD_EINVAL, "null output buffer");
+  double t_enc = 0;
+  int rc = begin_decode(c, src, src_len, B, max_out, false, &t_enc);
+  if (rc != AD_OK) return rc;
+  LoopIO io = make_io(c, B, max_out);
+  GpuBackend be(c);
+  rc = loop_greedy(be, io);
+  if (rc != AD_OK) return rc;
+  write_out(c, io, out, out_len, stats, t_enc);
+  return AD_OK;
+}
+
+int ad_decode_iad(ad_ctx* c, const int32_t* src, const int32_t* src_len, const int32_t* guide,
+                  const int32_t* guide_len, int guide_stride, int B, const int32_t* max_out, int32_t* out,
+                  int32_t* out_len, ad_stats* stats) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!out || !out_len) return fail(c, AD_EINVAL, "null output buffer");
+  if (guide && (!guide_len || guide_stride < 1)) return fail(c, AD_EINVAL, "guide without guide_len / stride");
+  int rc = check_batch(c, src, src_len, B);
+  if (rc != AD_OK) return rc;
+  std::vector<std::vector<int32_t>> g(B);
+  for (int b = 0; b < B; ++b) {
+    const int32_t* row = guide ? guide + (size_t)b * guide_stride : src + (size_t)b * c->cfg.max_src;
+    const int n = guide ? guide_len[b] : src_len[b];
+    if (n < 0 || (guide && n > guide_stride)) return fail(c, AD_EINVAL, "guide_len outside [0, guide_stride]");
+    for (int i = 0; i < n; ++i)
+      if (row[i] < 0 || row[i] >= c->cfg.vocab) return fail(c, AD_EINVAL, "guide token id outside the vocabulary");
+    g[b].assign(row, row + n);
+  }
+  double t_enc = 0;
+  rc = begin_decode(c, src, src_len, B, max_out, false, &t_enc);
+  if (rc != AD_OK) return rc;
+  LoopIO io = make_io(c, B, max_out);
+  GpuBackend be(c);
+  rc = loop_iad(be, io, g);
+  if (rc != AD_OK) return rc;
+  write_out(c, io, out, out_len, stats, t_enc);
+  return AD_OK;
+}
+
+int ad_decode_gad(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, int k, int use_drafter,
+                  const int32_t* draft_override, const int32_t* override_len, int override_stride,
+                  const int32_t* max_out, int32_t* out, int32_t* out_len, ad_stats* stats) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!out || !out_len) return fail(c, AD_EINVAL, "null output buffer");
+  if (k < 1 || k > c->cfg.k_max) return fail(c, AD_EINVAL, "k outside [1, k_max]");
+  if (use_drafter && !c->has_drafter) return fail(c, AD_ESTATE, "context has no drafter weights");
+  if (!use_drafter && !draft_override) return fail(c, AD_EINVAL, "need a drafter or a draft override");
+  if (draft_override && (!override_len || override_stride < 1)) return fail(c, AD_EINVAL, "override without lengths");
+  int rc = check_batch(c, src, src_len, B);
+  if (rc != AD_OK) return rc;
+  std::vector<std::vector<int32_t>> D(B);
+  if (draft_override)
+    for (int b = 0; b < B; ++b) {
+      const int n = override_len[b];
+      if (n < 0 || n > override_stride) return fail(c, AD_EINVAL, "override_len outside [0, override_stride]");
+      const int32_t* row = draft_override + (size_t)b * override_stride;
+      for (int i = 0; i < n; ++i)
+        if (row[i] < 0 || row[i] >= c->cfg.vocab) return fail(c, AD_EINVAL, "override token id outside the vocabulary");
+      D[b].assign(row, row + n);
+    }
+  double t_enc = 0;
+  rc = begin_decode(c, src, src_len, B, max_out, use_drafter != 0, &t_enc);
+  if (rc != AD_OK) return rc;
+  LoopIO io = make_io(c, B, max_out);
+  GpuBackend be(c);
+  rc = loop_gad(be, io, k, use_drafter != 0, draft_override ? &D : nullptr);
+  if (rc != AD_OK) return rc;
+  write_out(c, io, out, out_len, stats, t_enc);
+  return AD_OK;
+}
+
+int ad_debug_logits(ad_ctx* c, float* logits, int rows_cap, int* rows) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!logits || !rows) return fail(c, AD_EINVAL, "null buffer");
+  if (!c->cfg.debug_logits) return fail(c, AD_ESTATE, "context was created without debug_logits");
+  if (c->last_logit_rows < 1) return fail(c, AD_ESTATE, "no forward has run yet");
+  if (rows_cap < c->last_logit_rows) return fail(c, AD_EINVAL, "rows_cap too small");
+  HIP_TRY(c, hipMemcpyAsync(logits, c->at<float>(c->plan.logits), (size_t)c->last_logit_rows * c->cfg.vocab * 4,
+                            hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  *rows = c->last_logit_rows;
+  return AD_OK;
+}
+
+int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* vocab_kernel_us) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (reps < 1 || !forward_us || !vocab_kernel_us) return fail(c, AD_EINVAL, "bad argument");
+  if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
+  double tot = 0, voc = 0;
+  verify_forward(c, c->last_M);   // warm
+  for (int r = 0; r < reps; ++r) {
+    HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
+    verify_forward(c, c->last_M, c->ev1, c->ev2);
+    HIP_TRY(c, hipEventRecord(c->ev3, c->stream));
+    HIP_TRY(c, hipEventSynchronize(c->ev3));
+    float a = 0, b = 0;
+    HIP_TRY(c, hipEventElapsedTime(&a, c->ev0, c->ev3));
+    HIP_TRY(c, hipEventElapsedTime(&b, c->ev1, c->ev2));
+    tot += a * 1e3; voc += b * 1e3;
+  }
+  HIP_TRY(c, hipGetLastError());
+  *forward_us = tot / reps;
+  *vocab_kernel_us = voc / reps;
+  return AD_OK;
+}
+
+}  // extern "C"

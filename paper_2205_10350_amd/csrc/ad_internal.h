@@ -1,0 +1,122 @@
+// Internal declarations shared by the host side (ad_api.cpp, ad_hostlogic.cpp) and the
+// kernels (ad_kernels.hip).  Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/ad.h"
+
+namespace ad {
+
+// ---- weight layout ---------------------------------------------------------------------
+struct WEntry {
+  std::string name;
+  size_t offset;
+  int rows, cols;     // vectors: rows = 1
+  int elem_bytes;
+};
+// Ordered layout of one model's blob.  q,k,v of an attention block are contiguous so
+// that they form one [3d, d] matrix (cross-attention: k,v form one [2d, d] matrix).
+std::vector<WEntry> weight_layout(const ad_config& c, size_t* total_bytes);
+
+struct AttnW { const void *wqkv, *wo; const float *bqkv, *bo; };          // wqkv = [wq;wk;wv]
+struct LnW { const float *g, *b; };
+struct FfnW { const void *w1, *w2; const float *b1, *b2; };
+struct EncLayerW { AttnW self; LnW ln1; FfnW ffn; LnW ln2; };
+struct DecLayerW { AttnW self; LnW ln1; AttnW cross; LnW ln2; FfnW ffn; LnW ln3; };
+struct ModelW {
+  const void* emb = nullptr;
+  const void* out_w = nullptr;
+  std::vector<EncLayerW> enc;
+  std::vector<DecLayerW> dec;
+};
+ModelW bind_weights(const ad_config& c, const void* blob);
+
+// ---- per-call row tables (device) -----------------------------------------------------------
+// One attention problem per sequence: query rows [q_row0, q_row0+nq) of the packed
+// activation matrix; keys/values are rows kv_row0.. of a [*, d] buffer.  Query row i
+// (0-based inside the sequence) sees keys [0, causal ? nk_base + i + 1 : nk_base).
+struct SeqDesc { int q_row0, nq, kv_row0, nk_base, causal, pad0, pad1, pad2; };
+
+// ---- GEMM epilogues ----------------------------------------------------------------------------
+enum EpiMode { EPI_QKV = 0, EPI_KV = 1, EPI_STORE = 2, EPI_RELU = 3, EPI_RESID = 4, EPI_ARGMAX = 5 };
+struct Epi {
+  int mode;
+  int d;                  // model width (column split of QKV / KV)
+  const float* bias;      // [N] or null
+  void* out0;             // QKV: q [M,d];  STORE/RELU: out [M,N] (storage type);  RESID: fp32 [M,N]
+  void* out1;             // QKV/KV: key rows buffer [*, d]
+  void* out2;             // QKV/KV: value rows buffer [*, d]
+  const int* row_dst;     // QKV/KV: destination row of packed row m in out1/out2
+  const float* resid;     // RESID: fp32 [M,N]
+  float* part_val;        // ARGMAX: [M, n_strips]
+  int* part_idx;          // ARGMAX: [M, n_strips]
+  int n_strips;
+  float* logits;          // ARGMAX: optional full logits [M,N]
+};
+
+// ---- launchers (ad_kernels.hip).  dtype: AD_F32 / AD_BF16 selects storage + arithmetic ---------
+void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, const int* pos, int M,
+                  int d, float sqrt_d, float* x, void* xa, hipStream_t s);
+// C[M,N] = A[M,K] . W[N,K]^T with epilogue.  A, W in the storage type.
+void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s);
+void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const int* row_seq,
+                      const SeqDesc* desc, int M, int H, int dh, int max_keys, hipStream_t s);
+// y = LayerNorm(x) * g + b -> y (fp32) and ya (storage type)
+void launch_layernorm(int dtype, const float* x, const float* g, const float* b, int M, int d, float* y,
+                      void* ya, hipStream_t s);
+void launch_argmax_finish(const float* part_val, const int* part_idx, int M, int n_strips, int* o_hat,
+                          float* o_val, hipStream_t s);
+void launch_gather_rows(int dtype, const void* src, const int* rows, int n, int d, void* dst, hipStream_t s);
+
+// Row assembly of a verify call: from k[B], draft[B,k_max], len[B], pending[B] builds the
+// packed row tables and both attention descriptors.
+struct VerifyTables {
+  int *row_tok, *row_pos, *row_seq, *row_dst, *row_start;   // [M], [M], [M], [M], [B+1]
+  int* row_dst2;   // [M] encoder only: row of the memory key/value buffers
+  SeqDesc *self_desc, *cross_desc;                          // [B]
+};
+void launch_assemble_verify(const int* k, const int* draft, int k_max, const int* len, const int* pending,
+                            const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s);
+// Longest-prefix match, acceptance, truncation and rollback for every sequence.
+void launch_accept(const int* k, const int* draft, int k_max, const int* o_hat, const int* row_start,
+                   int B, int eos, int max_len, const int* max_out, int* len, int* pending, int* finished,
+                   int* out, int* result /* [B,2]: n_accept, last token */, hipStream_t s);
+// Row tables for the encoder (rows = source tokens) and for the drafter (prefix + masks).
+void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
+                             hipStream_t s);
+void launch_assemble_drafter(const int* out, int max_len, const int* len, const int* finished, const int* src_len,
+                             int B, int k, int bos, int mask, int s_max, VerifyTables t, int* mask_rows,
+                             hipStream_t s);
+void launch_reset_state(int* len, int* pending, int* finished, int B, int bos, hipStream_t s);
+void launch_draft_scatter(const int* o_hat, const int* finished, int B, int k, int k_max, int* draft_out,
+                          hipStream_t s);
+
+// ---- host-only decode loops (ad_hostlogic.cpp) ------------------------------------------------------
+struct Backend {
+  virtual ~Backend() {}
+  // same contract as ad_verify, minus `verified`
+  virtual int verify(const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next) = 0;
+  virtual int draft(int k, int32_t* draft_out) { (void)k; (void)draft_out; return AD_ESTATE; }
+};
+struct LoopIO {
+  int B, k_max, eos, bos;
+  std::vector<int> max_out;            // [B]
+  std::vector<std::vector<int32_t>> o; // per sequence: o_0 = bos, then output
+  std::vector<std::vector<int>> accepted;  // per iteration, summed over the batch handled by caller
+  ad_stats stats{};
+};
+int suffix_match(const int32_t* o, int o_len, const int32_t* x, int x_len, int* i_out);
+int loop_iad(Backend& be, LoopIO& io, const std::vector<std::vector<int32_t>>& guide);
+int loop_gad(Backend& be, LoopIO& io, int k, bool use_drafter,
+             const std::vector<std::vector<int32_t>>* override_draft);
+int loop_greedy(Backend& be, LoopIO& io);
+
+void set_global_error(const char* msg);
+
+}  // namespace ad

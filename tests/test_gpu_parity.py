@@ -1,0 +1,445 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer results (tokens, accepted lengths, iteration structure) are compared
+exactly; logits within 1e-4 (fp32 mode) / 2e-2 (bf16 mode).
+
+How an arg-max disagreement in bf16 mode is judged.  bf16 rounding of activations amplifies
+the fp32 summation-order difference between the two implementations up to the bf16 noise
+level of the logits (a few 1e-3 for the base model), so a top-2 margin below that can
+legitimately resolve differently.  The tests therefore check, exactly, that the fused
+epilogue returns the arg max of the library's OWN logits (lowest id on ties), check the
+logits against the oracle within tolerance, and log every position where the two arg maxes
+differ together with the oracle's margin, which must be below twice the logit deviation of
+that row (anything larger would contradict the logit check)."""
+import math
+
+import numpy as np
+import pytest
+
+import paper_2205_10350_amd as ad
+from ad_inputs import CONFIGS, SPECIAL, draw_sources, edit_guide, init_weights, model_dims, positional_draft
+from oracle import ad_oracle as O
+
+pytestmark = pytest.mark.gpu
+BOS, EOS, MASK = SPECIAL["bos"], SPECIAL["eos"], SPECIAL["mask"]
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def _bf16_weights(w):
+    return {k: (O.bf16_round(v) if v.ndim == 2 else v) for k, v in w.items()}
+
+
+class Rig:
+    """A context plus the oracle models that correspond to its arithmetic."""
+
+    def __init__(self, name, dtype, seed, *, B=1, max_src=64, max_len=32, k_max=40, drafter=False, tie=False,
+                 std=0.02, special=SPECIAL):
+        self.dims = model_dims(name)
+        self.dtype = dtype
+        self.w = init_weights(self.dims, seed, std=std, tie_output=tie)
+        self.wd = init_weights(self.dims, seed + 7, std=std, tie_output=tie) if drafter else None
+        self.cfg = ad.make_config(self.dims, max_batch=B, max_src=max_src, max_len=max_len, k_max=k_max, dtype=dtype,
+                                  special=special, tie_output=tie, debug_logits=True)
+        self.ctx = ad.Context(self.cfg, self.w, self.wd)
+        self.eos = special["eos"]
+        # the stated tolerances belong to N(0, 0.02) weights; logits (and their bf16 rounding
+        # noise) grow at least linearly with the weight scale of the stress cases
+        self.tol = TOL[dtype] * (std / 0.02 if dtype == "bf16" else 1.0)
+        pos = max(max_src, max_len + k_max) + 1
+        if dtype == "bf16":
+            # exact arithmetic over the bf16-rounded weights (the logit reference) and the
+            # contract emulation (same rounding points as the kernels; the token reference)
+            self.exact = O.Model(self.dims, _bf16_weights(self.w), np.float64, max_pos=pos)
+            self.tok = O.Model(self.dims, self.w, np.float64, contract=True, max_pos=pos)
+            self.dr = O.Model(self.dims, self.wd, np.float64, contract=True, max_pos=pos) if drafter else None
+        else:
+            self.exact = self.tok = O.Model(self.dims, self.w, np.float64, max_pos=pos)
+            self.dr = O.Model(self.dims, self.wd, np.float64, max_pos=pos) if drafter else None
+
+    def close(self):
+        self.ctx.close()
+
+
+def _sources(dims, seed, lens):
+    rng = np.random.default_rng(seed)
+    return [rng.integers(5, dims["vocab"], size=n).astype(np.int32) for n in lens]
+
+
+def _check_rows(rig, logits, o_hat, ref_logits, ref_tok_logits, label, log):
+    """logits/o_hat from the GPU; ref_logits from the exact oracle; ref_tok_logits from the token oracle."""
+    tol = rig.tol
+    dev = np.abs(logits - ref_logits).max(axis=1)
+    assert dev.max() < tol, (label, dev.max())
+    for r in range(logits.shape[0]):
+        own = int(np.flatnonzero(logits[r] == logits[r].max())[0])
+        assert o_hat[r] == own, (label, r, "fused arg max differs from the arg max of the library's own logits")
+        ref = O.argmax_lowest(ref_tok_logits[r])
+        if own != ref:
+            srt = np.sort(ref_tok_logits[r])
+            margin = float(srt[-1] - srt[-2])
+            dev_tok = float(np.abs(logits[r] - ref_tok_logits[r]).max())
+            log.append((label, r, own, ref, margin, dev_tok))
+            assert margin <= 2 * dev_tok + 1e-12 and margin < 2 * tol, (label, r, margin, dev_tok)
+    return dev.max()
+
+
+def _report(log):
+    for label, r, own, ref, margin, dev in log:
+        print(f"[near-tie] {label} row {r}: gpu {own} oracle {ref} oracle margin {margin:.3e} logit dev {dev:.3e}"
+              f"{'  (>= 1e-3)' if margin >= 1e-3 else ''}")
+
+
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,dtype,seed,std", [
+    ("tiny", "fp32", 1000, 0.02), ("tiny", "bf16", 1000, 0.02),
+    ("tiny", "fp32", 31, 0.15), ("micro", "fp32", 32, 0.3), ("tiny", "bf16", 33, 0.15),
+])
+def test_verify_logits_teacher_forced(name, dtype, seed, std):
+    """One verify forward over the oracle's own greedy prefix: logits, arg max, accepted length.
+    The large-std cases make attention sharply peaked so that a mask or head-slicing slip would
+    move logits far beyond the tolerance."""
+    rig = Rig(name, dtype, seed, std=std)
+    try:
+        src = _sources(rig.dims, seed, [24])[0]
+        g, lg_tok = O.greedy(rig.tok, src, 32, rig.eos, BOS, return_logits=True)
+        lg_exact = rig.exact.decode_full(rig.exact.encode(src), [BOS] + g[:-1])
+        log = []
+        # whole output in ragged blocks: 1, 7, 13, rest — cache append and causal mask across calls
+        rig.ctx.encode(ad.AD_VERIFIER, [src])
+        j = 0
+        for k in (1, 7, 13, 40):
+            k = min(k, len(g) - j)
+            if k <= 0 or (j and g[j - 1] == rig.eos):
+                break
+            n, nx, ver = rig.ctx.verify([g[j:j + k]], want_verified=True)
+            logits = rig.ctx.debug_logits()
+            assert logits.shape[0] == k
+            _check_rows(rig, logits, ver[0, :k], lg_exact[j:j + k], lg_tok[j:j + k], f"{name}/{dtype} j={j}", log)
+            if log:
+                break          # the accepted prefix no longer is the oracle's: stop teacher forcing
+            assert n[0] == k and nx[0] == g[j + k - 1]
+            j += k
+        _report(log)
+        if dtype == "fp32":
+            assert not log
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("name,dtype,seed,B", [("tiny", "fp32", 1000, 1), ("tiny", "fp32", 5, 3), ("tiny", "bf16", 6, 3)])
+def test_decodes_are_greedy_identical_and_match_oracle(name, dtype, seed, B):
+    """Workload 0 (tiny, fp32, k = 8, substitution rate 0.1) and batched variants: greedy,
+    input-guided and draft-verify outputs are identical to each other and to the oracle; the
+    iteration structure equals the oracle's."""
+    rig = Rig(name, dtype, seed, B=B, drafter=True)
+    try:
+        srcs = _sources(rig.dims, seed, [24 - 5 * b for b in range(B)])
+        gs = [O.greedy(rig.tok, s, 32, rig.eos, BOS) for s in srcs]
+        out_g, st_g = rig.ctx.decode_greedy(srcs)
+        assert out_g == gs
+        assert st_g["iterations"] == max(len(g) for g in gs) and st_g["tokens_out"] == sum(len(g) for g in gs)
+        guides = [edit_guide(g, 0.1, seed + b, rig.dims["vocab"]) for b, g in enumerate(gs)]
+        out_i, st_i = rig.ctx.decode_iad(srcs, guides)
+        assert out_i == gs
+        ref = [O.iad(rig.tok, s, gd, 32, rig.eos, BOS, k_max=rig.cfg.k_max) for s, gd in zip(srcs, guides)]
+        assert st_i["rows_verified"] == sum(r[1].rows_verified for r in ref)
+        assert st_i["iterations"] == max(r[1].iterations for r in ref)
+        Ds = [positional_draft(g, 0.1, seed + b, rig.dims["vocab"])[0] for b, g in enumerate(gs)]
+        out_d, st_d = rig.ctx.decode_gad(srcs, 8, use_drafter=False, draft_override=Ds)
+        assert out_d == gs
+        ref = [O.gad(rig.tok, s, 8, 32, rig.eos, BOS, draft_override=D) for s, D in zip(srcs, Ds)]
+        assert st_d["rows_verified"] == sum(r[1].rows_verified for r in ref)
+        assert st_d["iterations"] == max(r[1].iterations for r in ref)
+        # the real block drafter in the loop (random drafter: nearly nothing accepted, still greedy)
+        out_n, st_n = rig.ctx.decode_gad(srcs, 5, use_drafter=True)
+        assert out_n == gs and st_n["draft_rows"] > 0
+        # source as its own guide (the plain input-guided setting)
+        out_s, _ = rig.ctx.decode_iad(srcs, None)
+        assert out_s == gs
+    finally:
+        rig.close()
+
+
+def test_all_right_all_wrong_drafts_iteration_counts():
+    rig = Rig("tiny", "fp32", 1000)
+    try:
+        src = _sources(rig.dims, 1000, [24])[0]
+        g = O.greedy(rig.tok, src, 32, rig.eos, BOS)
+        T, V = len(g), rig.dims["vocab"]
+        out, st = rig.ctx.decode_gad([src], 8, draft_override=[g])
+        assert out == [g] and st["iterations"] == math.ceil(T / 8)
+        wrong = [(t - 5 + 1) % (V - 5) + 5 for t in g]
+        out, st = rig.ctx.decode_gad([src], 8, draft_override=[wrong])
+        assert out == [g] and st["iterations"] == T
+        out, st = rig.ctx.decode_iad([src], [g])
+        assert out == [g]
+        if len(set(g)) == len(g):
+            assert st["iterations"] == 1
+    finally:
+        rig.close()
+
+
+def test_rows_do_not_depend_on_block_or_batch_shape():
+    """Bit-exact: a row's logits are the same whether it is verified alone, in a block of k, or
+    next to other sequences (what makes draft-and-verify greedy-identical on this hardware)."""
+    rig = Rig("tiny", "bf16", 77, B=3, k_max=40)
+    try:
+        srcs = _sources(rig.dims, 77, [24, 11, 17])
+        out_g, _ = rig.ctx.decode_greedy(srcs)
+        # (a) sequence 0 alone, one row at a time
+        rig.ctx.encode(ad.AD_VERIFIER, srcs[:1])
+        single = []
+        for t in range(20):
+            rig.ctx.verify([[out_g[0][t]]])
+            single.append(rig.ctx.debug_logits()[0])
+        single = np.stack(single)
+        # (b) sequence 0 alone, one block of 20 (17..32 rows exercise the second row tile)
+        rig.ctx.encode(ad.AD_VERIFIER, srcs[:1])
+        rig.ctx.verify([out_g[0][:20]])
+        block = rig.ctx.debug_logits()
+        assert np.array_equal(single.view(np.uint32), block.view(np.uint32))
+        # (c) inside a ragged batch: blocks of 9 + 11 with other sequences around it
+        rig.ctx.encode(ad.AD_VERIFIER, [srcs[1], srcs[0], srcs[2]])
+        rig.ctx.verify([out_g[1][:3], out_g[0][:9], out_g[2][:17]])
+        a = rig.ctx.debug_logits()[3:12]
+        rig.ctx.verify([[], out_g[0][9:20], out_g[2][17:18]])
+        b = rig.ctx.debug_logits()[:11]
+        assert np.array_equal(np.concatenate([a, b]).view(np.uint32), block.view(np.uint32))
+        # (d) 84 packed rows: sequence 0 straddles the boundary between two 64-row tiles
+        rig.ctx.encode(ad.AD_VERIFIER, [srcs[1], srcs[0], srcs[2]])
+        rig.ctx.verify([out_g[1][:32], out_g[0][:20], out_g[2][:32]])
+        c = rig.ctx.debug_logits()[32:52]
+        assert np.array_equal(c.view(np.uint32), block.view(np.uint32))
+    finally:
+        rig.close()
+
+
+def test_ragged_batch_rollback_and_inactive_sequences():
+    rig = Rig("tiny", "fp32", 9, B=4, k_max=12)
+    try:
+        srcs = _sources(rig.dims, 9, [24, 7, 15, 1])
+        gs = [O.greedy(rig.tok, s, 32, rig.eos, BOS) for s in srcs]
+        rig.ctx.encode(ad.AD_VERIFIER, srcs)
+        V = rig.dims["vocab"]
+        # per-sequence drafts: right for 5 / wrong at once / inactive / right for 12
+        other = lambda t: (t - 5 + 1) % (V - 5) + 5
+        d0 = gs[0][:5] + [other(gs[0][5])] + gs[0][6:9]
+        n, nx, ver = rig.ctx.verify([d0, [other(gs[1][0]), 9, 9], [], gs[3][:12]], want_verified=True)
+        assert n.tolist() == [6, 1, 0, 12]
+        assert nx.tolist()[:2] == [gs[0][5], gs[1][0]] and nx[3] == gs[3][11]
+        assert ver[0, :6].tolist() == gs[0][:6] and (ver[2] == ad.AD_NEVER).all()
+        assert rig.ctx.output() == [gs[0][:6], gs[1][:1], [], gs[3][:12]]
+        # rejected rows were rolled back: continuing gives the greedy continuation
+        n, nx = rig.ctx.verify([gs[0][6:12], gs[1][1:4], gs[2][:7], [ad.AD_NEVER]])
+        assert n.tolist() == [6, 3, 7, 1]
+        assert rig.ctx.output() == [gs[0][:12], gs[1][:4], gs[2][:7], gs[3][:13]]
+    finally:
+        rig.close()
+
+
+def test_eos_and_output_limit_truncate_on_device():
+    """[EOS] is whatever id the configuration names: pick one the greedy output contains."""
+    probe = Rig("tiny", "fp32", 12)
+    src = _sources(probe.dims, 12, [20])[0]
+    g_free = O.greedy(probe.tok, src, 32, -5, BOS)
+    probe.close()
+    first = next(i for i in range(5, 32) if g_free[i] not in g_free[:i])   # first occurrence at index >= 5
+    special = dict(SPECIAL, eos=int(g_free[first]))
+    rig = Rig("tiny", "fp32", 12, special=special, B=2)
+    try:
+        g = O.greedy(rig.tok, src, 32, rig.eos, BOS)
+        assert g[-1] == rig.eos and len(g) == first + 1
+        out, st = rig.ctx.decode_greedy([src, src], max_out=[32, 4])
+        assert out == [g, g[:4]]
+        # a draft that is right beyond [EOS]: the block is cut after [EOS]
+        out, st = rig.ctx.decode_gad([src, src], 16, draft_override=[g_free, g_free], max_out=[32, 4])
+        assert out == [g, g[:4]] and st["iterations"] == 1
+        rig.ctx.encode(ad.AD_VERIFIER, [src, src], max_out=[32, 4])
+        n, nx = rig.ctx.verify([g_free[:16], g_free[:16]])
+        assert n.tolist() == [len(g), 4] and nx[0] == rig.eos
+        with pytest.raises(ad.AdError) as e:      # finished sequences take no more rows
+            rig.ctx.verify([[5], []])
+        assert e.value.code == ad.AD_ESTATE
+    finally:
+        rig.close()
+
+
+def test_block_drafter_matches_oracle():
+    for dtype in ("fp32", "bf16"):
+        rig = Rig("tiny", dtype, 21, B=2, drafter=True)
+        try:
+            srcs = _sources(rig.dims, 21, [18, 9])
+            gs = [O.greedy(rig.tok, s, 32, rig.eos, BOS) for s in srcs]
+            rig.ctx.encode(ad.AD_VERIFIER, srcs)
+            rig.ctx.encode(ad.AD_DRAFTER, srcs)
+            log = []
+            for step, (a, b) in enumerate([(0, 0), (4, 2), (3, 0)]):
+                if step:
+                    n, _ = rig.ctx.verify([gs[0][pa:pa + a], gs[1][pb:pb + b]])
+                    assert n.tolist() == [a, b]
+                    pa += a; pb += b
+                else:
+                    pa = pb = 0
+                k = 6
+                dr = rig.ctx.draft_nat(k)
+                logits = rig.ctx.debug_logits()
+                for i, (s, p) in enumerate(zip(srcs, (pa, pb))):
+                    mem = rig.dr.encode(s)
+                    toks = [BOS] + gs[i][:p] + [MASK] * k
+                    ref = rig.dr.decode_full(mem, toks, causal=False)[p + 1:]
+                    got = logits[i * k:(i + 1) * k]
+                    assert np.abs(got - ref).max() < TOL[dtype]
+                    for r in range(k):
+                        own = int(np.flatnonzero(got[r] == got[r].max())[0])
+                        assert dr[i, r] == own
+                        if own != O.argmax_lowest(ref[r]):
+                            srt = np.sort(ref[r]); log.append((f"draft {dtype}", r, own, 0, float(srt[-1] - srt[-2]), 0.0))
+            _report(log)
+            assert dtype != "fp32" or not log
+        finally:
+            rig.close()
+
+
+def test_argument_errors_on_device_context():
+    rig = Rig("tiny", "fp32", 3, B=2, k_max=4, max_src=16, max_len=8)
+    try:
+        src = _sources(rig.dims, 3, [10])[0]
+        with pytest.raises(ad.AdError) as e:
+            rig.ctx.verify([[5]])
+        assert e.value.code == ad.AD_ESTATE            # before encode
+        with pytest.raises(ad.AdError) as e:
+            rig.ctx.draft_nat(2)
+        assert e.value.code == ad.AD_ESTATE            # no drafter weights
+        rig.ctx.encode(ad.AD_VERIFIER, [src])
+        for bad in ([[5, 6, 7, 8, 9]], [[5, 40000]], [[ad.AD_NEVER, 5]]):
+            d = np.full((1, 8), 0, dtype=np.int32)
+            d[0, :len(bad[0])] = bad[0]
+            import ctypes as C
+            k = np.array([len(bad[0])], dtype=np.int32); n = np.zeros(1, np.int32); nx = np.zeros(1, np.int32)
+            P = C.POINTER(C.c_int32)
+            rc = rig.ctx.L.ad_verify(rig.ctx.h, d.ctypes.data_as(P), k.ctypes.data_as(P), n.ctypes.data_as(P),
+                                     nx.ctypes.data_as(P), None)
+            assert rc == ad.AD_EINVAL, bad
+        # state untouched by the failed calls
+        g = O.greedy(rig.tok, src, 8, rig.eos, BOS)
+        n, nx = rig.ctx.verify([g[:4]])
+        assert n[0] == 4
+        with pytest.raises(ad.AdError):
+            rig.ctx.encode(ad.AD_VERIFIER, [np.arange(5, 5 + 17)])   # longer than max_src
+    finally:
+        rig.close()
+
+
+# ----------------------------------------------------------------------------------------------
+# Full-size workloads (base / big models): sampled rows against the oracle, plus properties
+# that hold at any size.
+
+def _teacher_forced_base(rig, srcs, n_check, label):
+    """GPU greedy vs oracle on the oracle's prefix for the first n_check sentences."""
+    log = []
+    worst = 0.0
+    for s in srcs[:n_check]:
+        T = len(s)
+        g, lg_tok = O.greedy(rig.tok, s, T, rig.eos, BOS, return_logits=True)
+        lg_exact = rig.exact.decode_full(rig.exact.encode(s), [BOS] + g[:-1])
+        rig.ctx.encode(ad.AD_VERIFIER, [s], max_out=[T])
+        km = rig.cfg.k_max
+        for j in range(0, len(g), km):
+            blk = g[j:j + km]
+            before = len(log)
+            n, nx, ver = rig.ctx.verify([blk], want_verified=True)
+            logits = rig.ctx.debug_logits()
+            worst = max(worst, _check_rows(rig, logits, ver[0, :len(blk)], lg_exact[j:j + km], lg_tok[j:j + km],
+                                           label, log))
+            if len(log) > before:
+                break      # the accepted prefix left the oracle's: stop teacher forcing this sentence
+    _report(log)
+    print(f"[{label}] max |logit - oracle| = {worst:.3e}; near-tie rows: {len(log)}")
+    return log
+
+
+def test_workload1_base_iad_batch1():
+    cfg = CONFIGS[1]
+    rig = Rig("base", "bf16", cfg["seed"], max_src=64, max_len=64, k_max=72)
+    try:
+        srcs, max_out = draw_sources(cfg, rig.dims["vocab"], n_sent=12)
+        _teacher_forced_base(rig, srcs, 2, "workload1")
+        for s, mo in zip(srcs, max_out):
+            out_g, _ = rig.ctx.decode_greedy([s], max_out=[mo])
+            guide = edit_guide(out_g[0], cfg["rate"], cfg["seed"], rig.dims["vocab"])
+            out_i, st = rig.ctx.decode_iad([s], [guide], max_out=[mo])
+            assert out_i == out_g and len(out_g[0]) == mo
+            _, acc, st_sim = ad.host_simulate(0, out_g[0], guide, k_max=72, max_out=int(mo))
+            assert st["iterations"] == st_sim["iterations"] and st["rows_verified"] == st_sim["rows_verified"]
+    finally:
+        rig.close()
+
+
+def test_workload2_base_iad_batch32():
+    cfg = CONFIGS[2]
+    rig = Rig("base", "bf16", CONFIGS[1]["seed"], B=32, max_src=64, max_len=64, k_max=72)
+    try:
+        srcs, max_out = draw_sources(cfg, rig.dims["vocab"], n_sent=32)
+        out_g, st_g = rig.ctx.decode_greedy(srcs, max_out=max_out)
+        assert [len(o) for o in out_g] == max_out.tolist()
+        guides = [edit_guide(g, cfg["rate"], cfg["seed"] + b, rig.dims["vocab"]) for b, g in enumerate(out_g)]
+        out_i, st_i = rig.ctx.decode_iad(srcs, guides, max_out=max_out)
+        assert out_i == out_g                      # ragged accepted lengths + rollback, bit-exact
+        assert st_i["iterations"] < st_g["iterations"]
+        rows = sum(ad.host_simulate(0, g, gd, k_max=72, max_out=int(mo))[2]["rows_verified"]
+                   for g, gd, mo in zip(out_g, guides, max_out))
+        assert st_i["rows_verified"] == rows
+        # sampled sequences against single-sequence decoding (batch invariance at full size)
+        for b in (0, 13, 31):
+            single, _ = rig.ctx.decode_greedy([srcs[b]], max_out=[max_out[b]])
+            assert single[0] == out_g[b]
+    finally:
+        rig.close()
+
+
+def test_workload3_base_gad_batch1():
+    cfg = CONFIGS[3]
+    rig = Rig("base", "bf16", cfg["seed"], max_src=80, max_len=80, k_max=25, drafter=True)
+    try:
+        srcs, max_out = draw_sources(cfg, rig.dims["vocab"], n_sent=4)
+        _teacher_forced_base(rig, srcs, 1, "workload3")
+        for s, mo in zip(srcs, max_out):
+            out_g, _ = rig.ctx.decode_greedy([s], max_out=[mo])
+            D, _ = positional_draft(out_g[0], cfg["rate"], cfg["seed"], rig.dims["vocab"])
+            out_d, st = rig.ctx.decode_gad([s], cfg["k"], use_drafter=True, draft_override=[D], max_out=[mo])
+            assert out_d == out_g
+            _, acc, st_sim = ad.host_simulate(1, out_g[0], D, k=cfg["k"], k_max=25, max_out=int(mo))
+            assert st["iterations"] == st_sim["iterations"] and st["draft_rows"] > 0
+        # the drafter alone, first block, against the oracle
+        s = srcs[0]
+        rig.ctx.encode(ad.AD_VERIFIER, [s]); rig.ctx.encode(ad.AD_DRAFTER, [s])
+        dr = rig.ctx.draft_nat(25)
+        got = rig.ctx.debug_logits()
+        ref = rig.dr.decode_full(rig.dr.encode(s), [BOS] + [MASK] * 25, causal=False)[1:]
+        assert np.abs(got - ref).max() < TOL["bf16"]
+        assert dr[0].tolist() == [int(np.flatnonzero(r == r.max())[0]) for r in got]
+    finally:
+        rig.close()
+
+
+def test_workload4_big_gad_batch8():
+    cfg = CONFIGS[4]
+    rig = Rig("big", "bf16", cfg["seed"], B=8, max_src=512, max_len=128, k_max=25, drafter=True)
+    try:
+        srcs, max_out = draw_sources(cfg, rig.dims["vocab"], n_sent=8)
+        out_g, _ = rig.ctx.decode_greedy(srcs, max_out=max_out)
+        Ds = [positional_draft(g, cfg["rate"], cfg["seed"] + b, rig.dims["vocab"])[0] for b, g in enumerate(out_g)]
+        out_d, st = rig.ctx.decode_gad(srcs, cfg["k"], use_drafter=True, draft_override=Ds, max_out=max_out)
+        assert out_d == out_g and [len(o) for o in out_g] == [128] * 8
+        its = max(ad.host_simulate(1, g, D, k=25, k_max=25, max_out=128)[2]["iterations"] for g, D in zip(out_g, Ds))
+        assert st["iterations"] == its
+        # one sampled sequence, first 12 rows, against the oracle (S = 512 cross-attention keys)
+        s = srcs[3]
+        g12, lg_tok = O.greedy(rig.tok, s, 12, rig.eos, BOS, return_logits=True)
+        lg_exact = rig.exact.decode_full(rig.exact.encode(s), [BOS] + g12[:-1])
+        rig.ctx.encode(ad.AD_VERIFIER, [s])
+        n, nx, ver = rig.ctx.verify([g12], want_verified=True)
+        log = []
+        _check_rows(rig, rig.ctx.debug_logits(), ver[0, :12], lg_exact, lg_tok, "workload4", log)
+        _report(log)
+    finally:
+        rig.close()

@@ -1,0 +1,186 @@
+"""CPU-only checks of the library's host side: it loads, exports the whole C ABI, validates
+arguments, lays weights out as documented, and its decode loops (driven by a model-free
+stand-in verifier) reproduce closed forms and the oracle's iteration structure."""
+import itertools
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2205_10350_amd as ad
+from ad_inputs import SPECIAL, edit_guide, init_weights, model_dims, positional_draft
+from oracle import ad_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BOS, EOS = SPECIAL["bos"], SPECIAL["eos"]
+
+
+def cfg_for(name="tiny", **kw):
+    args = dict(max_batch=2, max_src=24, max_len=32, k_max=8, dtype="fp32", special=SPECIAL)
+    args.update(kw)
+    return ad.make_config(model_dims(name), **args)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ad.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ad_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(ad.EXPORTS)
+    L = ad.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_config_check_rejects_bad_dimensions():
+    assert ad.config_check(cfg_for()) == ad.AD_OK
+    for bad in (dict(d_model=100), dict(d_ffn=100), dict(vocab=2001), dict(n_heads=3), dict(n_heads=16)):
+        dims = dict(model_dims("tiny"), **bad)
+        cfg = ad.make_config(dims, max_batch=1, max_src=8, max_len=8, k_max=4, dtype="fp32", special=SPECIAL)
+        assert ad.config_check(cfg) == ad.AD_EINVAL, bad
+        assert ad.lib().ad_last_error(None)
+        assert ad.workspace_bytes(cfg, False) == 0
+    for bad in (dict(max_batch=0), dict(k_max=0), dict(max_len=0), dict(max_src=0)):
+        assert ad.config_check(cfg_for(**bad)) == ad.AD_EINVAL
+    cfg = cfg_for()
+    cfg.eos = 5000
+    assert ad.config_check(cfg) == ad.AD_EINVAL
+    cfg = cfg_for()
+    cfg.dtype = 7
+    assert ad.config_check(cfg) == ad.AD_EINVAL
+
+
+def test_create_without_gpu_or_with_bad_arguments_fails_cleanly():
+    import ctypes as C
+    L = ad.lib()
+    cfg = cfg_for()
+    h = C.c_void_p()
+    assert L.ad_create(C.byref(cfg), None, None, None, 0, None, C.byref(h)) == ad.AD_EINVAL
+    assert L.ad_create(C.byref(cfg), C.c_void_p(256), None, C.c_void_p(512), 16, None, C.byref(h)) == ad.AD_ENOMEM
+    assert L.ad_create(C.byref(cfg), C.c_void_p(257), None, C.c_void_p(512), 1 << 40, None, C.byref(h)) == ad.AD_EINVAL
+    assert not h.value
+    assert L.ad_verify(None, None, None, None, None, None) == ad.AD_EINVAL
+    assert L.ad_destroy(None) == ad.AD_EINVAL
+
+
+@pytest.mark.parametrize("dtype,tie", [("fp32", False), ("bf16", False), ("bf16", True)])
+def test_weight_layout_matches_parameter_set(dtype, tie):
+    from ad_inputs import param_spec
+    dims = model_dims("tiny")
+    cfg = ad.make_config(dims, max_batch=1, max_src=8, max_len=8, k_max=4, dtype=dtype, special=SPECIAL, tie_output=tie)
+    layout, total = ad.weights_layout(cfg)
+    spec = {n: s for n, s, _ in param_spec(dims, tie_output=tie)}
+    assert {e[0] for e in layout} == set(spec)
+    end = 0
+    by_name = {}
+    for name, off, rows, cols, eb in layout:
+        shape = spec[name]
+        assert (rows, cols) == (shape if len(shape) == 2 else (1, shape[0]))
+        assert eb == ((2 if dtype == "bf16" else 4) if len(shape) == 2 else 4)
+        assert off >= end and off % 4 == 0
+        end = off + rows * cols * eb
+        by_name[name] = (off, rows * cols * eb)
+    assert end <= total and total % 256 == 0
+    # q, k, v of an attention block are adjacent: one [3d, d] matrix and one [3d] bias
+    for p in ("enc.0.self", "dec.1.self", "dec.0.cross"):
+        for kind in ("w", "b"):
+            q, k, v = (by_name[f"{p}.{kind}{x}"] for x in "qkv")
+            assert q[0] % 256 == 0 and k[0] == q[0] + q[1] and v[0] == k[0] + k[1]
+    assert ad.workspace_bytes(cfg, True) > ad.workspace_bytes(cfg, False) > 0
+
+
+def test_suffix_match_agrees_with_oracle_brute_force():
+    for n in range(1, 6):
+        for x in itertools.product(range(3), repeat=n):
+            for j in range(0, 4):
+                for o in itertools.product(range(3), repeat=j + 1):
+                    assert ad.suffix_match(o, x) == O.suffix_match(list(o), list(x))
+    assert ad.suffix_match([0], [0, 7, 8, 9, -1]) == 0
+    assert ad.suffix_match([0, 8, 7], [0, 7, 8, 7, 9, -1]) == 3
+    assert ad.suffix_match([0, 5, 7], [0, 7, 8, 7, 9, -1]) is None
+
+
+def _content(rng, n, vocab=500):
+    return rng.integers(5, vocab, size=n).astype(np.int32)
+
+
+def test_simulated_loops_closed_forms():
+    rng = np.random.default_rng(0)
+    T, k = 37, 8
+    g = _content(rng, T)
+    # all right: ceil(T/k) iterations; all wrong: T iterations of one token
+    out, acc, st = ad.host_simulate(1, g, g, k=k, k_max=k, max_out=T)
+    assert out == g.tolist() and st["iterations"] == math.ceil(T / k) and sum(acc) == T
+    wrong = (g - 5 + 1) % 495 + 5
+    out, acc, st = ad.host_simulate(1, g, wrong, k=k, k_max=k, max_out=T)
+    assert out == g.tolist() and st["iterations"] == T and set(acc) == {1}
+    assert st["rows_verified"] == sum(min(k, T - j) for j in range(T))
+    # positional mask: boundaries are a function of the mask alone
+    for s in range(5):
+        D, bad = positional_draft(g, 0.2, s, 500)
+        out, acc, st = ad.host_simulate(1, g, D, k=k, k_max=k, max_out=T)
+        expect, j = [], 0
+        while j < T:
+            kk = min(k, T - j)
+            w = [p for p in range(j, j + kk) if bad[p]]
+            c = (w[0] - j + 1) if w else kk
+            expect.append(c); j += c
+        assert out == g.tolist() and acc == expect
+    # guide = g with distinct tokens: one verify forward covers the whole output
+    g2 = np.arange(5, 5 + T).astype(np.int32)
+    out, acc, st = ad.host_simulate(0, g2, g2, k_max=64, max_out=T)
+    assert out == g2.tolist() and acc == [T]
+    # ... and with k_max smaller than the guide it takes ceil(T/k_max) forwards
+    out, acc, st = ad.host_simulate(0, g2, g2, k_max=10, max_out=T)
+    assert out == g2.tolist() and acc == [10, 10, 10, 7]
+    # a single substitution in the guide: a parallel block through the corrected token; that token
+    # is not in the guide, so one autoregressive step follows before a suffix matches again
+    guide = g2.copy(); guide[20] = 499
+    out, acc, st = ad.host_simulate(0, g2, guide, k_max=64, max_out=T)
+    assert out == g2.tolist() and acc == [21, 1, T - 22]
+    # empty guide: plain autoregressive decoding
+    out, acc, st = ad.host_simulate(0, g2, [], k_max=64, max_out=T)
+    assert out == g2.tolist() and acc == [1] * T
+
+
+def test_simulated_loops_stop_at_eos_and_max_out():
+    g = np.array([9, 8, 7, EOS, 6, 5], dtype=np.int32)
+    out, acc, st = ad.host_simulate(1, g, g, k=8, k_max=8, max_out=10)
+    assert out == [9, 8, 7, EOS] and acc == [4]
+    out, acc, st = ad.host_simulate(1, g, g, k=2, k_max=8, max_out=3)
+    assert out == [9, 8, 7] and acc == [2, 1]
+    out, acc, st = ad.host_simulate(0, g, [9, 8, 7, EOS, 6], k_max=8, max_out=10)
+    assert out == [9, 8, 7, EOS]
+
+
+def test_expected_accepted_length_statistical():
+    """i.i.d. wrong positions at rate e: E[c] = (1 - (1-e)^k) / e for an unbounded sequence."""
+    rng = np.random.default_rng(1)
+    T, k, e = 20000, 25, 0.3
+    g = _content(rng, T, 30000)
+    D, bad = positional_draft(g, e, 7, 30000)
+    out, acc, st = ad.host_simulate(1, g, D, k=k, k_max=k, max_out=T)
+    assert out == g.tolist()
+    mean = np.mean(acc[:-1])
+    assert mean == pytest.approx((1 - (1 - e) ** k) / e, rel=0.03)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_library_loops_match_oracle_iteration_structure(seed):
+    """The oracle runs Algorithm 1 / the draft-verify loop with a real (tiny) model; the library's
+    loop, given only that model's greedy output, must take the same iterations."""
+    dims = model_dims("tiny")
+    m = O.Model(dims, init_weights(dims, 100 + seed), np.float64, max_pos=64)
+    src = _content(np.random.default_rng(seed), 20, dims["vocab"])
+    g = O.greedy(m, src, 30, EOS, BOS)
+    for s in range(3):
+        guide = edit_guide(g, 0.15, 10 * seed + s, dims["vocab"])
+        out_o, st_o = O.iad(m, src, guide, 30, EOS, BOS, k_max=16)
+        out_l, acc_l, st_l = ad.host_simulate(0, g, guide, k_max=16, max_out=30)
+        assert out_l == out_o == g and acc_l == st_o.accepted
+        assert st_l["rows_verified"] == st_o.rows_verified
+        D, _ = positional_draft(g, 0.2, 10 * seed + s, dims["vocab"])
+        out_o, st_o = O.gad(m, src, 6, 30, EOS, BOS, draft_override=D)
+        out_l, acc_l, st_l = ad.host_simulate(1, g, D, k=6, k_max=16, max_out=30)
+        assert out_l == out_o == g and acc_l == st_o.accepted
