@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the Aggressive Decoding hot path on one MI355X.
+
+Workload of the headline number: Transformer-base input-guided decoding at batch 1 (6+6
+layers, d 512, 8 heads, FFN 2048, vocab 32000, bf16 weights, fp32 accumulation), source
+lengths ~ N(25, 8) clipped to [5, 64], output length = source length, guide = the model's
+greedy output with i.i.d. edits at rate 0.1.  One step = one whole decode of one sentence:
+encoder forward + cross-attention keys/values, then the draft-verify loop (row assembly,
+verify forward with fused output projection / arg max, prefix match, accept, rollback)
+until the output is complete.  Value = emitted tokens per second over the timed steps; every
+emitted sequence is checked to be identical to greedy decoding on the same kernels.
+
+Also reported in the same JSON line: the verify forward's share of the HBM roofline at batch
+1 and of the bf16 MFMA roofline at batch 32 (first-iteration shape), the roofline of the
+dominant kernel (output projection + arg max, a weight-streaming HBM-bound kernel), and the
+CPU oracle timed on this machine's host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12       # B/s, MI355X published
+MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
+
+
+def decoder_stream_params(dims):
+    """Parameters a verify forward streams: per decoder layer self-attn 4d^2, cross-attn q,o 2d^2,
+    FFN 2dF; plus the output projection dV."""
+    d, F, V, NL = dims["d_model"], dims["d_ffn"], dims["vocab"], dims["dec_layers"]
+    return NL * (6 * d * d + 2 * d * F) + d * V
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bs32", action="store_true")
+    ap.add_argument("--cpu-sentences", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2205_10350_amd as ad
+    from ad_inputs import CONFIGS, SPECIAL, draw_sources, edit_guide, init_weights, model_dims
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg1, cfg2 = CONFIGS[1], CONFIGS[2]
+    dims = model_dims(cfg1["model"])
+    V = dims["vocab"]
+    w = init_weights(dims, cfg1["seed"])
+    K_MAX = 72
+    conf = ad.make_config(dims, max_batch=32, max_src=64, max_len=64, k_max=K_MAX, dtype="bf16", special=SPECIAL)
+    ctx = ad.Context(conf, w)
+
+    # ---------------- batch 1: the headline workload ------------------------------------------
+    n_sent = cfg1["n_sent"]
+    srcs, max_out = draw_sources(cfg1, V)
+    greedy_out, guides = [], []
+    t0 = time.perf_counter()
+    for s, mo in zip(srcs, max_out):
+        o, _ = ctx.decode_greedy([s], max_out=[mo])
+        greedy_out.append(o[0])
+    torch.cuda.synchronize()
+    t_greedy = time.perf_counter() - t0
+    for i, g in enumerate(greedy_out):
+        guides.append(edit_guide(g, cfg1["rate"], cfg1["seed"] + i, V))
+
+    def step(i):
+        j = i % n_sent
+        return ctx.decode_iad([srcs[j]], [guides[j]], max_out=[max_out[j]])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    toks = its = rows = 0
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        o, st = step(i)
+        toks += len(o[0]); its += st["iterations"]; rows += st["rows_verified"]
+        assert o[0] == greedy_out[i % n_sent], "draft-and-verify output differs from greedy"
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    value = toks / dt
+    greedy_tps = sum(len(g) for g in greedy_out) / t_greedy
+
+    # verify forward at the first-iteration shape of a typical sentence (whole guide + sentinel)
+    j = int(np.argsort([len(s) for s in srcs])[n_sent // 2])
+    ctx.encode(ad.AD_VERIFIER, [srcs[j]], max_out=[max_out[j]])
+    draft = (list(guides[j]) + [ad.AD_NEVER])[:int(max_out[j])]
+    ctx.verify([draft])
+    M1 = len(draft)
+    fwd_us, voc_us = ctx.time_verify_forward(50)
+    params = decoder_stream_params(dims)
+    kv_bytes = dims["dec_layers"] * 2 * 2 * dims["d_model"] * (M1 + len(srcs[j]))
+    fwd_bytes = 2 * params + kv_bytes
+    # dominant kernel: output projection + arg max.  Algorithmic bytes per launch: the [V, d] bf16
+    # matrix once, the M x d bf16 activations once, the per-row partial maxima written once.
+    voc_bytes = 2 * V * dims["d_model"] + 2 * M1 * dims["d_model"] + 8 * M1 * (V // 16)
+    roofline = {"bound": "hbm", "kernel": "k_gemm_bf16 (output projection + arg max)", "rows": M1,
+                "achieved": voc_bytes / (voc_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK, "traffic": None}
+    verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,
+                  "hbm_frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK}
+
+    # ---------------- batch 32 ---------------------------------------------------------------------
+    bs32 = None
+    if not args.no_bs32:
+        srcs2, max_out2 = draw_sources(cfg2, V)
+        B = cfg2["batch"]
+        batches = [(srcs2[i:i + B], max_out2[i:i + B]) for i in range(0, len(srcs2), B)]
+        g2, gd2 = [], []
+        t0 = time.perf_counter()
+        for ss, mo in batches:
+            o, _ = ctx.decode_greedy(ss, max_out=mo)
+            g2.append(o)
+        torch.cuda.synchronize()
+        t_g2 = time.perf_counter() - t0
+        for bi, o in enumerate(g2):
+            gd2.append([edit_guide(g, cfg2["rate"], cfg2["seed"] + bi * B + b, V) for b, g in enumerate(o)])
+        ctx.decode_iad(batches[0][0], gd2[0], max_out=batches[0][1])   # warm
+        torch.cuda.synchronize()
+        toks2 = its2 = rows2 = 0
+        t0 = time.perf_counter()
+        for (ss, mo), gd, ref in zip(batches, gd2, g2):
+            o, st = ctx.decode_iad(ss, gd, max_out=mo)
+            assert o == ref, "batched draft-and-verify output differs from greedy"
+            toks2 += sum(len(x) for x in o); its2 += st["iterations"]; rows2 += st["rows_verified"]
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t0
+        ss, mo = batches[0]
+        ctx.encode(ad.AD_VERIFIER, ss, max_out=mo)
+        drafts = [(list(g) + [ad.AD_NEVER])[:int(m)] for g, m in zip(gd2[0], mo)]
+        ctx.verify(drafts)
+        M32 = sum(len(d) for d in drafts)
+        fwd32_us, voc32_us = ctx.time_verify_forward(20)
+        flops = 2.0 * M32 * params
+        bs32 = {"tokens_per_s": toks2 / dt2, "greedy_tokens_per_s": sum(len(x) for o in g2 for x in o) / t_g2,
+                "iterations": its2, "rows_verified": rows2,
+                "verify_rows": M32, "verify_us": fwd32_us, "verify_gflop": flops / 1e9,
+                "mfma_frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK,
+                "vocab_kernel_us": voc32_us,
+                "vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
+    ctx.close()
+
+    # ---------------- CPU oracle on this machine's host cores (bounded sample) ----------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ad_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        m = O.Model(dims, w, np.float32, max_pos=160)
+        n_cpu = min(args.cpu_sentences, n_sent)
+        og = [O.greedy(m, srcs[i], int(max_out[i]), SPECIAL["eos"], SPECIAL["bos"]) for i in range(n_cpu)]
+        ogd = [edit_guide(g, cfg1["rate"], cfg1["seed"] + i, V) for i, g in enumerate(og)]
+        t0 = time.perf_counter()
+        ctoks = 0
+        for i in range(n_cpu):
+            o, _ = O.iad(m, srcs[i], ogd[i], int(max_out[i]), SPECIAL["eos"], SPECIAL["bos"], k_max=K_MAX)
+            ctoks += len(o)
+        cdt = time.perf_counter() - t0
+        cpu = {"value": ctoks / cdt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {n_cpu} sentences of the batch-1 workload, numpy float32 oracle, input-guided "
+                         f"decoding incl. encoder ({cdt:.1f} s)"}
+
+    line = {
+        "metric": "greedy_identical_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "Transformer-base IAD batch 1 (configs[1]): 6+6 layers, d512, 8 heads, FFN 2048, "
+                               "vocab 32000, source len ~N(25,8) in [5,64], guide = greedy output + edits 0.1",
+                   "batch": 1, "sentences": n_sent, "k_max": K_MAX},
+        "tokens": toks, "verify_forwards": its, "rows_verified": rows,
+        "mean_tokens_per_forward": toks / max(1, its),
+        "greedy_tokens_per_s": greedy_tps, "speedup_vs_greedy": value / greedy_tps,
+        "verify_forward_bs1": verify_bs1, "bs32": bs32,
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
