@@ -107,6 +107,9 @@ struct ad_ctx {
   // last verify call, for ad_time_verify_forward / ad_debug_logits
   int last_M = 0;
   int last_logit_rows = 0;
+  // shape of the forward being launched: attention problems and the most query rows in one
+  int fw_nseq = 0, fw_max_rows = 0;
+  int last_nseq = 0, last_max_rows = 0;
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 };
@@ -169,8 +172,8 @@ static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, voi
   Epi e{};
   e.mode = EPI_QKV; e.d = d; e.bias = a.bqkv; e.out0 = c->at<void>(p.q); e.out1 = Kl; e.out2 = Vl; e.row_dst = t.row_dst;
   launch_gemm(c->cfg.dtype, c->at<void>(p.xa), a.wqkv, M, 3 * d, d, e, c->stream);
-  launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.row_seq, t.self_desc, M, H, d / H,
-                   max_keys, c->stream);
+  launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.self_desc, c->fw_nseq, c->fw_max_rows,
+                   H, d / H, max_keys, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
 
@@ -181,8 +184,8 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
   Epi e{};
   e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
   launch_gemm(c->cfg.dtype, c->at<void>(p.xa), a.wqkv, M, d, d, e, c->stream);
-  launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.row_seq, t.cross_desc, M, H, d / H,
-                   c->cfg.max_src, c->stream);
+  launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
+                   c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
 
@@ -368,6 +371,8 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.src_len[model]), dev, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
   VerifyTables t = tables(c);
+  c->fw_nseq = B;
+  c->fw_max_rows = *std::max_element(src_len, src_len + B);
   launch_assemble_encoder(dev + 2 * B, S, dev, B, S, t, c->stream);
   const ModelW& w = c->w[model];
   embed_rows(c, w, M);
@@ -378,8 +383,8 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
     e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
     e.out1 = c->at<void>(p.tk); e.out2 = c->at<void>(p.tv); e.row_dst = t.row_dst;
     launch_gemm(cf.dtype, c->at<void>(p.xa), L.self.wqkv, M, 3 * d, d, e, c->stream);
-    launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att), t.row_seq,
-                     t.self_desc, M, cf.n_heads, d / cf.n_heads, S, c->stream);
+    launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att),
+                     t.self_desc, B, c->fw_max_rows, cf.n_heads, d / cf.n_heads, S, c->stream);
     gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
     ffn_block(c, L.ffn, L.ln2, M);
   }
@@ -442,6 +447,9 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + B, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
   VerifyTables t = tables(c);
+  c->fw_nseq = B;
+  c->fw_max_rows = *std::max_element(k, k + B);
+  c->last_nseq = B; c->last_max_rows = c->fw_max_rows;
   launch_assemble_verify(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.len), c->at<int>(p.pending),
                          c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
   verify_forward(c, M);
@@ -490,6 +498,10 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     return AD_OK;
   }
   VerifyTables t = tables(c);
+  c->fw_nseq = B;
+  c->fw_max_rows = 0;
+  for (int b = 0; b < B; ++b)
+    if (!c->h_finished[b]) c->fw_max_rows = std::max(c->fw_max_rows, c->h_len[b] + 1 + k);
   launch_assemble_drafter(c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
                           c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->at<int>(p.mask_rows),
                           c->stream);
@@ -634,6 +646,7 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   if (reps < 1 || !forward_us || !vocab_kernel_us) return fail(c, AD_EINVAL, "bad argument");
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
   double tot = 0, voc = 0;
+  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
   verify_forward(c, c->last_M);   // warm
   for (int r = 0; r < reps; ++r) {
     HIP_TRY(c, hipEventRecord(c->ev0, c->stream));

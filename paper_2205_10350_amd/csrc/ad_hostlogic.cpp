@@ -264,6 +264,13 @@ int ad_config_check(const ad_config* c) {
   if (c->enc_layers < 1 || c->dec_layers < 1) { set_global_error("need at least one encoder and one decoder layer"); return AD_EINVAL; }
   if (c->max_batch < 1 || c->max_src < 1 || c->max_len < 1 || c->k_max < 1) { set_global_error("capacities must be >= 1"); return AD_EINVAL; }
   if (c->max_batch > 4096 || c->max_src > 8192 || c->max_len > 8192 || c->k_max > 8192) { set_global_error("capacity too large"); return AD_EINVAL; }
+  {
+    // attention keeps one head's keys and values of a sequence in LDS (rows padded by a dword)
+    const size_t nk = (size_t)std::max(c->max_src, c->max_len + c->k_max);
+    const size_t esz = c->dtype == AD_BF16 ? 2 : 4;
+    const size_t need = 2 * nk * ((size_t)dh * esz / 4 + 1) * 4 + 4 * (nk + dh) * 4;
+    if (need > 160 * 1024) { set_global_error("max_src / max_len + k_max too large: a head's keys and values must fit in 160 KB of LDS"); return AD_EINVAL; }
+  }
   const int32_t ids[4] = {c->bos, c->pad, c->eos, c->mask};
   for (int i = 0; i < 4; ++i)
     if (ids[i] < 0 || ids[i] >= c->vocab) { set_global_error("special token id outside the vocabulary"); return AD_EINVAL; }

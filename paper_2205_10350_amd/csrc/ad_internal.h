@@ -65,8 +65,9 @@ void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, c
                   int d, float sqrt_d, float* x, void* xa, hipStream_t s);
 // C[M,N] = A[M,K] . W[N,K]^T with epilogue.  A, W in the storage type.
 void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s);
-void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const int* row_seq,
-                      const SeqDesc* desc, int M, int H, int dh, int max_keys, hipStream_t s);
+// one attention problem per descriptor (n_seq of them, at most max_rows query rows each)
+void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
+                      int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s);
 // y = LayerNorm(x) * g + b -> y (fp32) and ya (storage type)
 void launch_layernorm(int dtype, const float* x, const float* g, const float* b, int M, int d, float* y,
                       void* ya, hipStream_t s);

@@ -10,47 +10,9 @@
 // arithmetic).
 #include <hip/hip_runtime.h>
 
-#include "ad_internal.h"
+#include "ad_device.h"
 
 namespace ad {
-
-typedef unsigned short bf16_t;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
-__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest, ties to even
-  unsigned u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-template <typename T> struct Store;
-template <> struct Store<float> {
-  static __device__ __forceinline__ float load(const float* p) { return *p; }
-  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
-  static __device__ __forceinline__ float round(float v) { return v; }
-};
-template <> struct Store<bf16_t> {
-  static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(*p); }
-  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f2bf(v); }
-  static __device__ __forceinline__ float round(float v) { return bf2f(f2bf(v)); }
-};
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
-}
-// (value, index) maximum with the lowest index winning ties: a total order, so the result does
-// not depend on the shape of the reduction tree.
-__device__ __forceinline__ void argmax_merge(float& v, int& i, float ov, int oi) {
-  if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
-}
 
 // ------------------------------------------------------------------------------------- embed
 // x[m] = E[tok[m]] * sqrt(d) + PE[pos[m]]
@@ -61,7 +23,7 @@ __global__ void k_embed(const T* __restrict__ emb, const float* __restrict__ pe,
   const T* e = emb + (size_t)tok[m] * d;
   const float* p = pe + (size_t)pos[m] * d;
   for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = Store<T>::load(e + c) * sqrt_d + p[c];
+    const float v = embed_value(Store<T>::load(e + c), sqrt_d, p[c]);
     x[(size_t)m * d + c] = v;
     Store<T>::store(xa + (size_t)m * d + c, v);
   }
@@ -74,31 +36,6 @@ void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, c
     k_embed<bf16_t><<<M, 128, 0, s>>>((const bf16_t*)emb, pe, tok, pos, d, sqrt_d, x, (bf16_t*)xa);
   else
     k_embed<float><<<M, 128, 0, s>>>((const float*)emb, pe, tok, pos, d, sqrt_d, x, (float*)xa);
-}
-
-// ------------------------------------------------------------------------------------- GEMM epilogue
-template <typename T>
-__device__ __forceinline__ void epi_store(const Epi& e, int m, int n, int N, float acc) {
-  if (e.bias) acc += e.bias[n];
-  switch (e.mode) {
-    case EPI_QKV: {
-      const int d = e.d;
-      if (n < d) Store<T>::store((T*)e.out0 + (size_t)m * d + n, acc);
-      else if (n < 2 * d) Store<T>::store((T*)e.out1 + (size_t)e.row_dst[m] * d + (n - d), acc);
-      else Store<T>::store((T*)e.out2 + (size_t)e.row_dst[m] * d + (n - 2 * d), acc);
-      break;
-    }
-    case EPI_KV: {
-      const int d = e.d;
-      if (n < d) Store<T>::store((T*)e.out1 + (size_t)e.row_dst[m] * d + n, acc);
-      else Store<T>::store((T*)e.out2 + (size_t)e.row_dst[m] * d + (n - d), acc);
-      break;
-    }
-    case EPI_STORE: Store<T>::store((T*)e.out0 + (size_t)m * N + n, acc); break;
-    case EPI_RELU: Store<T>::store((T*)e.out0 + (size_t)m * N + n, fmaxf(acc, 0.f)); break;
-    case EPI_RESID: ((float*)e.out0)[(size_t)m * N + n] = acc + e.resid[(size_t)m * N + n]; break;
-    default: break;
-  }
 }
 
 // ------------------------------------------------------------------------------------- bf16 MFMA GEMM
@@ -138,37 +75,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
       acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[t], 0, 0, 0);
     }
   }
-  const int n = n0 + r;
-  if (e.mode == EPI_ARGMAX) {
-    const int strip = n0 >> 4;
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int m = m0 + t * 16 + kq * 4 + i;
-        float v = acc[t][i];
-        int idx = n;
-        if (e.logits && m < M) e.logits[(size_t)m * N + n] = v;
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {   // over the 16 lanes that hold this row
-          float ov = __shfl_xor(v, o, 64);
-          int oi = __shfl_xor(idx, o, 64);
-          argmax_merge(v, idx, ov, oi);
-        }
-        if (r == 0 && m < M) {
-          e.part_val[(size_t)m * e.n_strips + strip] = v;
-          e.part_idx[(size_t)m * e.n_strips + strip] = idx;
-        }
-      }
-    return;
-  }
-#pragma unroll
-  for (int t = 0; t < MT; ++t)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + t * 16 + kq * 4 + i;
-      if (m < M) epi_store<bf16_t>(e, m, n, N, acc[t][i]);
-    }
+  strip_epilogue<MT>(e, acc, MT, m0, n0, M, N, lane);
 }
 
 // ------------------------------------------------------------------------------------- fp32 GEMM
@@ -230,60 +137,36 @@ void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, c
 }
 
 // ------------------------------------------------------------------------------------- attention
-// One wave per (query row, head).  Pass 1: lane t scores key t (k ascending inside the dot
-// product), scores kept in LDS; exact row maximum; pass 2: p = exp(s - max), denominator from
-// the unrounded p, numerators rounded to the storage type; pass 3: lane e accumulates output
-// channel e over the keys in ascending order.
+// One block per (sequence, head, chunk of 64 query rows); see attn_block.
 template <typename T, int DH>
-__global__ __launch_bounds__(64) void k_attention(const T* __restrict__ q, const T* __restrict__ Kb,
-                                                  const T* __restrict__ Vb, T* __restrict__ out,
-                                                  const int* __restrict__ row_seq, const SeqDesc* __restrict__ desc,
-                                                  int d, float scale) {
-  extern __shared__ float smem[];
-  float* qs = smem;          // [DH]
-  float* sc = smem + DH;     // [max_keys]
-  const int m = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
-  const SeqDesc sd = desc[row_seq[m]];
-  const int i = m - sd.q_row0;
-  const int nk = sd.causal ? sd.nk_base + i + 1 : sd.nk_base;
-  for (int c = lane; c < DH; c += 64) qs[c] = Store<T>::load(q + (size_t)m * d + h * DH + c);
-  __syncthreads();
-  const T* kbase = Kb + (size_t)sd.kv_row0 * d + h * DH;
-  const T* vbase = Vb + (size_t)sd.kv_row0 * d + h * DH;
-  float mx = -INFINITY;
-  for (int t = lane; t < nk; t += 64) {
-    const T* kr = kbase + (size_t)t * d;
-    float a = 0.f;
-#pragma unroll 8
-    for (int c = 0; c < DH; ++c) a = fmaf(qs[c], Store<T>::load(kr + c), a);
-    a *= scale;
-    sc[t] = a;
-    mx = fmaxf(mx, a);
-  }
-  mx = wave_max(mx);
-  float l = 0.f;
-  for (int t = lane; t < nk; t += 64) {
-    const float p = expf(sc[t] - mx);
-    l += p;
-    sc[t] = Store<T>::round(p);
-  }
-  l = wave_sum(l);
-  __syncthreads();
-  for (int c = lane; c < DH; c += 64) {
-    float a = 0.f;
-    for (int t = 0; t < nk; ++t) a = fmaf(sc[t], Store<T>::load(vbase + (size_t)t * d + c), a);
-    Store<T>::store(out + (size_t)m * d + h * DH + c, a / l);
-  }
+__global__ __launch_bounds__(256) void k_attention(const T* __restrict__ q, const T* __restrict__ Kb,
+                                                   const T* __restrict__ Vb, T* __restrict__ out,
+                                                   const SeqDesc* __restrict__ desc, int d, float scale, int nk_cap) {
+  extern __shared__ unsigned att_lds[];
+  const SeqDesc sd = desc[blockIdx.x];
+  const int row_begin = blockIdx.z * 64;
+  if (row_begin >= sd.nq) return;
+  const int row_end = min(sd.nq, row_begin + 64);
+  attn_block<T, DH>(q, Kb, Vb, out, sd, row_begin, row_end, blockIdx.y, d, scale, att_lds, nk_cap);
 }
 
 template <typename T>
-static void attention_dispatch(const void* q, const void* K, const void* V, void* out, const int* row_seq,
-                               const SeqDesc* desc, int M, int H, int dh, int max_keys, hipStream_t s) {
+static void attention_dispatch(const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
+                               int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
-  const size_t sh = (size_t)(dh + max_keys) * sizeof(float);
-  dim3 g(M, H);
-#define AD_ATT(DH) \
-  k_attention<T, DH><<<g, 64, sh, s>>>((const T*)q, (const T*)K, (const T*)V, (T*)out, row_seq, desc, H * dh, scale)
+  const size_t sh = attn_lds_bytes(max_keys, dh, sizeof(T), 4);
+  dim3 g(n_seq, H, (max_rows + 63) / 64);
+#define AD_ATT(DH)                                                                                             \
+  do {                                                                                                         \
+    static size_t set_for = 0;                                                                                 \
+    if (sh > set_for) {                                                                                        \
+      (void)hipFuncSetAttribute((const void*)k_attention<T, DH>, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+                                (int)sh);                                                                      \
+      set_for = sh;                                                                                            \
+    }                                                                                                          \
+    k_attention<T, DH><<<g, 256, sh, s>>>((const T*)q, (const T*)K, (const T*)V, (T*)out, desc, H * dh, scale, \
+                                          max_keys);                                                           \
+  } while (0)
   switch (dh) {
     case 16: AD_ATT(16); break;
     case 32: AD_ATT(32); break;
@@ -292,11 +175,11 @@ static void attention_dispatch(const void* q, const void* K, const void* V, void
   }
 #undef AD_ATT
 }
-void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const int* row_seq,
-                      const SeqDesc* desc, int M, int H, int dh, int max_keys, hipStream_t s) {
-  if (M <= 0) return;
-  if (dtype == AD_BF16) attention_dispatch<bf16_t>(q, K, V, out, row_seq, desc, M, H, dh, max_keys, s);
-  else attention_dispatch<float>(q, K, V, out, row_seq, desc, M, H, dh, max_keys, s);
+void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
+                      int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s) {
+  if (n_seq <= 0 || max_rows <= 0) return;
+  if (dtype == AD_BF16) attention_dispatch<bf16_t>(q, K, V, out, desc, n_seq, max_rows, H, dh, max_keys, s);
+  else attention_dispatch<float>(q, K, V, out, desc, n_seq, max_rows, H, dh, max_keys, s);
 }
 
 // ------------------------------------------------------------------------------------- LayerNorm
@@ -308,17 +191,10 @@ __global__ __launch_bounds__(256) void k_layernorm(const float* __restrict__ x, 
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (m >= M) return;
   const float* xr = x + (size_t)m * d;
-  float s = 0.f;
-  for (int c = lane; c < d; c += 64) s += xr[c];
-  const float mean = wave_sum(s) / (float)d;
-  float v = 0.f;
+  float mean, rstd;
+  ln_stats(xr, d, lane, mean, rstd);
   for (int c = lane; c < d; c += 64) {
-    const float t = xr[c] - mean;
-    v = fmaf(t, t, v);
-  }
-  const float rstd = 1.0f / sqrtf(wave_sum(v) / (float)d + 1e-5f);
-  for (int c = lane; c < d; c += 64) {
-    const float o = (xr[c] - mean) * rstd * g[c] + b[c];
+    const float o = ln_value(xr[c], mean, rstd, g[c], b[c]);
     y[(size_t)m * d + c] = o;
     Store<T>::store(ya + (size_t)m * d + c, o);
   }
@@ -336,15 +212,9 @@ __global__ __launch_bounds__(256) void k_argmax_finish(const float* __restrict__
                                                        float* __restrict__ o_val) {
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (m >= M) return;
-  float v = -INFINITY;
-  int idx = 0x7fffffff;
-  for (int t = lane; t < n_strips; t += 64) argmax_merge(v, idx, pv[(size_t)m * n_strips + t], pi[(size_t)m * n_strips + t]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(v, o, 64);
-    int oi = __shfl_xor(idx, o, 64);
-    argmax_merge(v, idx, ov, oi);
-  }
+  float v;
+  int idx;
+  argmax_row(pv + (size_t)m * n_strips, pi + (size_t)m * n_strips, n_strips, lane, v, idx);
   if (lane == 0) {
     o_hat[m] = idx;
     if (o_val) o_val[m] = v;
