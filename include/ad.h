@@ -173,8 +173,17 @@ int ad_debug_logits(ad_ctx* ctx, float* logits, int rows_cap, int* rows);
 /* Re-launches the kernels of the last ad_verify forward `reps` times on the context's
  * stream without touching decode state (the appended cache rows are rewritten with the
  * same values) and reports the mean duration, by HIP events on that stream, of the whole
- * forward and of its output-projection/arg-max kernel.  For roofline measurements. */
+ * forward and of its output-projection/arg-max kernel (0 when the forward ran as one persistent
+ * kernel).  For roofline measurements. */
 int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us);
+
+/* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
+ * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; 0 = one
+ * launch per stage always; at most 64).  ad_create picks 64 when the device supports it, else 0;
+ * setting a positive value on a context where it is unavailable gives AD_ESTATE. */
+enum { AD_OPT_FUSED_ROWS = 0 };
+int ad_set_option(ad_ctx* ctx, int option, int value);
+int ad_get_option(ad_ctx* ctx, int option, int* value);
 
 /* ---- host-only logic, exposed so that it can be tested without a GPU -------------------------- */
 

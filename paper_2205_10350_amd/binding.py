@@ -23,8 +23,9 @@ EXPORTS = [
     "ad_config_check", "ad_workspace_bytes", "ad_weights_count", "ad_weights_bytes", "ad_weights_entry",
     "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
-    "ad_suffix_match", "ad_host_simulate",
+    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option",
 ]
+AD_OPT_FUSED_ROWS = 0
 
 
 class AdConfig(C.Structure):
@@ -89,6 +90,8 @@ def lib():
     L.ad_debug_logits.restype = C.c_int
     L.ad_time_verify_forward.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.ad_time_verify_forward.restype = C.c_int
+    L.ad_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]; L.ad_set_option.restype = C.c_int
+    L.ad_get_option.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]; L.ad_get_option.restype = C.c_int
     L.ad_suffix_match.argtypes = [_I32P, C.c_int, _I32P, C.c_int, C.POINTER(C.c_int)]; L.ad_suffix_match.restype = C.c_int
     L.ad_host_simulate.argtypes = [C.c_int, _I32P, C.c_int, _I32P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                    _I32P, _I32P, _I32P, C.c_int, sp]
@@ -287,6 +290,14 @@ class Context:
                                     _p(out), _p(n), C.byref(st)), self.h)
         self.B = B
         return self._result(out, n, st)
+
+    def set_option(self, option, value):
+        _check(self.L.ad_set_option(self.h, option, value), self.h)
+
+    def get_option(self, option):
+        v = C.c_int(0)
+        _check(self.L.ad_get_option(self.h, option, C.byref(v)), self.h)
+        return v.value
 
     def debug_logits(self):
         cap = self.cfg.max_batch * self.cfg.k_max

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libad_mi355x.so")
-SOURCES = ["ad_hostlogic.cpp", "ad_api.cpp", "ad_kernels.hip"]
+SOURCES = ["ad_hostlogic.cpp", "ad_api.cpp", "ad_kernels.hip", "ad_fused.hip"]
 
 
 def build(verbose: bool = False) -> str:

@@ -1,5 +1,7 @@
 // Context, workspace plan and the forward passes (encode, verify, draft) behind the C ABI.
 #include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -13,6 +15,12 @@ namespace ad {
 const char* global_error();
 
 static size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+// LDS bytes of the block attention: two padded [nk, dh] tiles plus per-wave query and score rows
+static size_t attn_lds_host(int nk_cap, int dh, int esz, int waves) {
+  const size_t row_dwords = (size_t)dh * esz / 4 + 1;
+  return 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Workspace plan: one pass computes offsets; used both for sizing and for binding.
@@ -29,6 +37,8 @@ struct Plan {
   size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
   size_t row_tok, row_pos, row_seq, row_dst, row_dst2, row_start, self_desc, cross_desc, mask_rows;
   size_t len, pending, finished, max_out, src_len[2], out, result, k_dev, draft_dev, src_dev, draft_out;
+  size_t stages, bar, stamps;   // fused forward: stage program, barrier words, optional stage clock stamps
+  int stage_cap = 0;
 };
 
 static Plan make_plan(const ad_config& c, bool with_drafter) {
@@ -76,7 +86,11 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.mask_rows = take((size_t)p.mv_cap * 4);
   p.len = take(B * 4); p.pending = take(B * 4); p.finished = take(B * 4); p.max_out = take(B * 4);
   p.out = take(B * c.max_len * 4);
-  p.result = take(B * 2 * 4);
+  p.result = take(B * 2 * 4 + 16);   // [B,2] results, then one int: the fused forward's abort flag copy
+  p.stage_cap = 8 * c.dec_layers + 2;
+  p.stages = take((size_t)p.stage_cap * sizeof(Stage));
+  p.stamps = take((size_t)(128 + 8 * 64) * 8);
+  p.bar = take(8 * (96 + 32 * 64));   // barrier words of the persistent forward (up to 1024 workgroups)
   p.k_dev = take(B * 4 + B * c.k_max * 4);   // k[B] followed by draft[B, k_max]: one upload
   p.draft_dev = p.k_dev + B * 4;
   p.src_dev = take(B * 4 * 2 + B * c.max_src * 4);   // src_len[B], max_out[B], src[B, max_src]: one upload
@@ -110,6 +124,12 @@ struct ad_ctx {
   // shape of the forward being launched: attention problems and the most query rows in one
   int fw_nseq = 0, fw_max_rows = 0;
   int last_nseq = 0, last_max_rows = 0;
+  // persistent fused forward (bf16, few rows)
+  int fused_rows = 0;            // largest M it takes; 0 = off
+  int fused_grid = 0, fused_stages = 0;
+  size_t fused_lds = 0;
+  unsigned long long bar_base = 0;
+  bool last_fused = false;
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 };
@@ -210,6 +230,118 @@ static void vocab_finish(ad_ctx* c, int Mv) {
                        c->at<float>(p.o_val), c->stream);
 }
 
+// Stage program of the verify forward for the persistent kernel (pointers are fixed for the
+// life of the context; only the row tables' contents and M, B change per call).
+static int build_verify_program(ad_ctx* c, std::vector<Stage>& prog) {
+  const Plan& p = c->plan;
+  const ad_config& cf = c->cfg;
+  const ModelW& w = c->w[AD_VERIFIER];
+  const int d = cf.d_model, F = cf.d_ffn;
+  VerifyTables t = tables(c);
+  auto gemm = [&](int a_mode, const void* a_src, const LnW* ln, const void* W, int N, int K, Epi e) {
+    Stage s{};
+    s.type = ST_GEMM; s.a_mode = a_mode; s.N = N; s.K = K; s.W = W; s.a_src = a_src;
+    if (ln) { s.ln_g = ln->g; s.ln_b = ln->b; }
+    s.x_out = (a_mode == A_LN || a_mode == A_EMBED) ? c->at<float>(p.x) : nullptr;
+    s.epi = e;
+    prog.push_back(s);
+  };
+  auto attn = [&](const void* K, const void* V, const SeqDesc* desc, int nk_cap) {
+    Stage s{};
+    s.type = ST_ATTN; s.q = c->at<void>(p.q); s.Kb = K; s.Vb = V; s.att_out = c->at<void>(p.att); s.desc = desc;
+    s.nk_cap = nk_cap;
+    prog.push_back(s);
+  };
+  auto resid = [&](const float* bias) {
+    Epi e{};
+    e.mode = EPI_RESID; e.bias = bias; e.out0 = c->at<float>(p.s); e.resid = c->at<float>(p.x);
+    return e;
+  };
+  for (int l = 0; l < cf.dec_layers; ++l) {
+    const DecLayerW& L = w.dec[l];
+    Epi e{};
+    e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
+    e.out1 = c->ws + p.cache_k + l * p.cache_layer_stride; e.out2 = c->ws + p.cache_v + l * p.cache_layer_stride;
+    e.row_dst = t.row_dst;
+    if (l == 0) gemm(A_EMBED, w.emb, nullptr, L.self.wqkv, 3 * d, d, e);
+    else gemm(A_LN, c->at<float>(p.s), &w.dec[l - 1].ln3, L.self.wqkv, 3 * d, d, e);
+    attn(e.out1, e.out2, t.self_desc, p.l_cap);
+    gemm(A_COPY, c->at<void>(p.att), nullptr, L.self.wo, d, d, resid(L.self.bo));
+    Epi q{};
+    q.mode = EPI_STORE; q.bias = L.cross.bqkv; q.out0 = c->at<void>(p.q);
+    gemm(A_LN, c->at<float>(p.s), &L.ln1, L.cross.wqkv, d, d, q);
+    attn(c->ws + p.mem_k[0] + l * p.mem_layer_stride, c->ws + p.mem_v[0] + l * p.mem_layer_stride, t.cross_desc,
+         cf.max_src);
+    gemm(A_COPY, c->at<void>(p.att), nullptr, L.cross.wo, d, d, resid(L.cross.bo));
+    Epi r{};
+    r.mode = EPI_RELU; r.bias = L.ffn.b1; r.out0 = c->at<void>(p.f);
+    gemm(A_LN, c->at<float>(p.s), &L.ln2, L.ffn.w1, F, d, r);
+    gemm(A_GLOBAL, c->at<void>(p.f), nullptr, L.ffn.w2, d, F, resid(L.ffn.b2));
+  }
+  Epi a{};
+  a.mode = EPI_ARGMAX; a.part_val = c->at<float>(p.part_val); a.part_idx = c->at<int>(p.part_idx);
+  a.n_strips = p.n_strips; a.logits = cf.debug_logits ? c->at<float>(p.logits) : nullptr;
+  gemm(A_LN, c->at<float>(p.s), &w.dec[cf.dec_layers - 1].ln3, w.out_w, cf.vocab, d, a);
+  Stage fin{};
+  fin.type = ST_FINISH;
+  prog.push_back(fin);
+  return (int)prog.size();
+}
+
+// Sets the persistent forward up if this context and device can run it; otherwise leaves it off.
+static void setup_fused(ad_ctx* c) {
+  c->fused_rows = 0;
+  if (c->cfg.dtype != AD_BF16) return;
+  const ad_config& cf = c->cfg;
+  const Plan& p = c->plan;
+  const size_t a_bytes = (size_t)64 * (cf.d_model + 8) * 2;
+  const size_t att_bytes = attn_lds_host(std::max(p.l_cap, cf.max_src), cf.d_model / cf.n_heads, 2, 8);
+  const size_t lds = std::max(a_bytes, att_bytes);
+  if (lds > 160 * 1024 - 1024) return;
+  hipDeviceProp_t prop;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return; }
+  if (!prop.cooperativeLaunch) return;
+  const int per_cu = fused_max_blocks_per_cu(lds);
+  if (per_cu < 1) return;
+  std::vector<Stage> prog;
+  const int n = build_verify_program(c, prog);
+  if (n > p.stage_cap) return;
+  if (hipMemcpyAsync(c->ws + p.stages, prog.data(), prog.size() * sizeof(Stage), hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+      hipMemsetAsync(c->ws + p.bar, 0, 8 * (96 + 32 * 64), c->stream) != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return;
+  }
+  c->fused_grid = std::min(prop.multiProcessorCount, 1024);
+  c->fused_stages = n;
+  c->fused_lds = lds;
+  c->bar_base = 0;
+  c->fused_rows = 64;
+}
+
+static hipError_t fused_verify_forward(ad_ctx* c, int M, int B, bool do_accept, bool stamps = false) {
+  const Plan& p = c->plan;
+  const ad_config& cf = c->cfg;
+  VerifyTables t = tables(c);
+  FusedArgs fa{};
+  fa.stages = c->at<Stage>(p.stages); fa.n_stages = c->fused_stages;
+  fa.M = M; fa.B = B; fa.d = cf.d_model; fa.H = cf.n_heads; fa.dh = cf.d_model / cf.n_heads;
+  fa.sqrt_d = sqrtf((float)cf.d_model); fa.pe = c->at<float>(p.pe);
+  fa.row_tok = t.row_tok; fa.row_pos = t.row_pos;
+  fa.bar = c->at<unsigned long long>(p.bar); fa.bar_base = c->bar_base;
+  fa.part_val = c->at<float>(p.part_val); fa.part_idx = c->at<int>(p.part_idx); fa.n_strips = p.n_strips;
+  fa.o_hat = c->at<int>(p.o_hat); fa.o_val = c->at<float>(p.o_val);
+  fa.do_accept = do_accept ? 1 : 0;
+  fa.k = c->at<int>(p.k_dev); fa.draft = c->at<int>(p.draft_dev); fa.row_start = t.row_start;
+  fa.max_out = c->at<int>(p.max_out); fa.k_max = cf.k_max; fa.eos = cf.eos; fa.max_len = cf.max_len;
+  fa.len = c->at<int>(p.len); fa.pending = c->at<int>(p.pending); fa.finished = c->at<int>(p.finished);
+  fa.out = c->at<int>(p.out); fa.result = c->at<int>(p.result);
+  fa.stamps = stamps ? c->at<unsigned long long>(p.stamps) : nullptr;
+  hipError_t e = launch_fused_forward(fa, c->fused_grid, c->fused_lds, c->stream);
+  if (e == hipSuccess) c->bar_base += (unsigned long long)(c->fused_stages - 1);
+  return e;
+}
+
 // The verify forward over the M packed rows the tables describe.  ev (optional) brackets the
 // output-projection kernel.
 static void verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr) {
@@ -301,7 +433,7 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   c->has_drafter = drafter_w != nullptr;
   if (c->has_drafter) c->w[1] = bind_weights(*cfg, drafter_w);
   const size_t B = cfg->max_batch;
-  c->pin_ints = 4 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 64;
+  c->pin_ints = (4 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 64 + 3) / 4 * 4;
   auto bail = [&](const char* what, hipError_t e) {
     std::string m = std::string(what) + ": " + hipGetErrorString(e);
     if (c->pin) (void)hipHostFree(c->pin);
@@ -333,6 +465,7 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   }
   c->h_len.assign(B, 0); c->h_finished.assign(B, 1); c->h_max_out.assign(B, 0);
   c->h_src_len[0].assign(B, 0); c->h_src_len[1].assign(B, 0);
+  setup_fused(c);
   *out = c;
   return AD_OK;
 }
@@ -452,16 +585,32 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   c->last_nseq = B; c->last_max_rows = c->fw_max_rows;
   launch_assemble_verify(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.len), c->at<int>(p.pending),
                          c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
-  verify_forward(c, M);
-  launch_accept(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
-                cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
-                c->at<int>(p.out), c->at<int>(p.result), c->stream);
+  const bool fused = c->fused_rows > 0 && M <= c->fused_rows;
+  if (fused) {
+    HIP_TRY(c, fused_verify_forward(c, M, B, true));
+  } else {
+    verify_forward(c, M);
+    launch_accept(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
+                  cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
+                  c->at<int>(p.out), c->at<int>(p.result), c->stream);
+  }
   int32_t* res = c->pin + (size_t)B * (1 + km);
   HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
+  unsigned long long* abort_flag = (unsigned long long*)(c->pin + c->pin_ints - 4);
+  *abort_flag = 0;
+  if (fused)
+    HIP_TRY(c, hipMemcpyAsync(abort_flag, c->at<unsigned long long>(p.bar) + 64, 8, hipMemcpyDeviceToHost, c->stream));
   int32_t* oh = res + 2 * B;
   if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipGetLastError());
+  if (*abort_flag) {
+    // a device-wide barrier timed out: the decode state is undefined; switch the persistent path off
+    c->fused_rows = 0;
+    c->encoded[AD_VERIFIER] = false;
+    return fail(c, AD_EDEVICE, "persistent forward: device-wide barrier timed out (state lost, encode again)");
+  }
+  c->last_fused = fused;
   int r0 = 0;
   for (int b = 0; b < B; ++b) {
     n_accept[b] = res[2 * b];
@@ -628,6 +777,21 @@ int ad_decode_gad(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, 
   return AD_OK;
 }
 
+int ad_set_option(ad_ctx* c, int option, int value) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (option != AD_OPT_FUSED_ROWS) return fail(c, AD_EINVAL, "unknown option");
+  if (value < 0 || value > 64) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, 64]");
+  if (value > 0 && c->fused_grid == 0) return fail(c, AD_ESTATE, "the persistent forward is unavailable for this context");
+  c->fused_rows = value;
+  return AD_OK;
+}
+int ad_get_option(ad_ctx* c, int option, int* value) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (option != AD_OPT_FUSED_ROWS || !value) return fail(c, AD_EINVAL, "unknown option or null pointer");
+  *value = c->fused_rows;
+  return AD_OK;
+}
+
 int ad_debug_logits(ad_ctx* c, float* logits, int rows_cap, int* rows) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
   if (!logits || !rows) return fail(c, AD_EINVAL, "null buffer");
@@ -647,6 +811,36 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
   double tot = 0, voc = 0;
   c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
+  if (c->last_fused && c->fused_rows > 0) {
+    // one kernel: the whole forward (arg max included, acceptance skipped)
+    HIP_TRY(c, fused_verify_forward(c, c->last_M, c->last_nseq, false));
+    for (int r = 0; r < reps; ++r) {
+      HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
+      HIP_TRY(c, fused_verify_forward(c, c->last_M, c->last_nseq, false));
+      HIP_TRY(c, hipEventRecord(c->ev3, c->stream));
+      HIP_TRY(c, hipEventSynchronize(c->ev3));
+      float a = 0;
+      HIP_TRY(c, hipEventElapsedTime(&a, c->ev0, c->ev3));
+      tot += a * 1e3;
+    }
+    *forward_us = tot / reps;
+    *vocab_kernel_us = 0;
+    if (getenv("AD_DEBUG_STAGES")) {
+      // diagnostic: per-stage durations of one launch (100 MHz device clock), to stderr
+      std::vector<unsigned long long> st(128 + 8 * 64);
+      HIP_TRY(c, fused_verify_forward(c, c->last_M, c->last_nseq, false, true));
+      HIP_TRY(c, hipMemcpyAsync(st.data(), c->at<unsigned long long>(c->plan.stamps), st.size() * 8, hipMemcpyDeviceToHost, c->stream));
+      HIP_TRY(c, hipStreamSynchronize(c->stream));
+      for (int i = 0; i + 1 < c->fused_stages && i < 12; ++i) {
+        const unsigned long long* f = &st[128 + i * 8];
+        fprintf(stderr, "  stage %d: start->A_staged %.2f  ->mfma_done %.2f  ->epilogue_done %.2f  ->next_barrier_entry %.2f  ->barrier_done %.2f\n", i,
+                (double)(f[1] - st[i]) * 0.01, (double)(f[2] - f[1]) * 0.01, (double)(f[3] - f[2]) * 0.01,
+                (double)(st[128 + (i + 1) * 8 + 4] - f[3]) * 0.01, (double)(st[i + 1] - st[128 + (i + 1) * 8 + 4]) * 0.01);
+      }
+      for (int i = 0; i < c->fused_stages; ++i) fprintf(stderr, "stage %2d: %.2f us  %.0f MHz\n", i, (double)(st[i + 1] - st[i]) * 0.01, i + 1 < c->fused_stages ? (double)(st[64 + i + 1] - st[64 + i]) / ((double)(st[i + 1] - st[i]) * 0.01) : 0.0);
+    }
+    return AD_OK;
+  }
   verify_forward(c, c->last_M);   // warm
   for (int r = 0; r < reps; ++r) {
     HIP_TRY(c, hipEventRecord(c->ev0, c->stream));

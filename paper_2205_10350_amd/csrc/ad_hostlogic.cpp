@@ -268,7 +268,7 @@ int ad_config_check(const ad_config* c) {
     // attention keeps one head's keys and values of a sequence in LDS (rows padded by a dword)
     const size_t nk = (size_t)std::max(c->max_src, c->max_len + c->k_max);
     const size_t esz = c->dtype == AD_BF16 ? 2 : 4;
-    const size_t need = 2 * nk * ((size_t)dh * esz / 4 + 1) * 4 + 4 * (nk + dh) * 4;
+    const size_t need = 2 * nk * ((size_t)dh * esz / 4 + 1) * 4 + 64 * (size_t)dh * 4 + 4 * nk * 4;
     if (need > 160 * 1024) { set_global_error("max_src / max_len + k_max too large: a head's keys and values must fit in 160 KB of LDS"); return AD_EINVAL; }
   }
   const int32_t ids[4] = {c->bos, c->pad, c->eos, c->mask};

@@ -60,6 +60,46 @@ struct Epi {
   float* logits;          // ARGMAX: optional full logits [M,N]
 };
 
+// ---- persistent fused forward (ad_fused.hip) ---------------------------------------------------------
+enum StageType { ST_GEMM = 0, ST_ATTN = 1, ST_FINISH = 2 };
+// where a GEMM stage takes its left operand from: LayerNorm of fp32 rows / embedding of the row
+// tokens / plain copy of storage-type rows (all three staged in LDS), or read from memory
+enum AMode { A_LN = 0, A_EMBED = 1, A_COPY = 2, A_GLOBAL = 3 };
+struct Stage {
+  int type;
+  int a_mode, N, K;          // GEMM
+  const void* W;
+  const void* a_src;
+  const float *ln_g, *ln_b;
+  float* x_out;              // A_LN / A_EMBED: workgroup 0 also stores the fp32 rows here
+  Epi epi;
+  const void *q, *Kb, *Vb;   // ATTN
+  void* att_out;
+  const SeqDesc* desc;
+  int nk_cap, pad;
+};
+struct FusedArgs {
+  const Stage* stages;
+  int n_stages;
+  int M, B, d, H, dh;
+  float sqrt_d;
+  const float* pe;
+  const int *row_tok, *row_pos;
+  unsigned long long* bar;        // barrier words (layout: see grid_barrier)
+  unsigned long long bar_base;    // barriers completed before this launch
+  // finish stage
+  const float* part_val; const int* part_idx; int n_strips;
+  int* o_hat; float* o_val;
+  int do_accept;
+  const int *k, *draft, *row_start, *max_out;
+  int k_max, eos, max_len;
+  int *len, *pending, *finished, *out, *result;
+  int dbg_si;
+  unsigned long long* stamps;     // nullable: workgroup 0 records the 100 MHz clock after every barrier
+};
+int fused_max_blocks_per_cu(size_t lds_bytes);
+hipError_t launch_fused_forward(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t s);
+
 // ---- launchers (ad_kernels.hip).  dtype: AD_F32 / AD_BF16 selects storage + arithmetic ---------
 void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, const int* pos, int M,
                   int d, float sqrt_d, float* x, void* xa, hipStream_t s);

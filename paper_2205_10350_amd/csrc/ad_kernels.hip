@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
       acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[t], 0, 0, 0);
     }
   }
-  strip_epilogue<MT>(e, acc, MT, m0, n0, M, N, lane);
+  strip_epilogue<bf16_t, MT>(e, acc, MT, m0, n0, M, N, lane);
 }
 
 // ------------------------------------------------------------------------------------- fp32 GEMM
@@ -191,12 +191,16 @@ __global__ __launch_bounds__(256) void k_layernorm(const float* __restrict__ x, 
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (m >= M) return;
   const float* xr = x + (size_t)m * d;
-  float mean, rstd;
-  ln_stats(xr, d, lane, mean, rstd);
-  for (int c = lane; c < d; c += 64) {
-    const float o = ln_value(xr[c], mean, rstd, g[c], b[c]);
-    y[(size_t)m * d + c] = o;
-    Store<T>::store(ya + (size_t)m * d + c, o);
+  float mean, rstd, xv[32];
+  ln_load_stats(xr, d, lane, xv, mean, rstd);
+#pragma unroll
+  for (int j = 0; j < 32; ++j) {
+    const int c = lane + 64 * j;
+    if (c < d) {
+      const float o = ln_value(xv[j], mean, rstd, g[c], b[c]);
+      y[(size_t)m * d + c] = o;
+      Store<T>::store(ya + (size_t)m * d + c, o);
+    }
   }
 }
 void launch_layernorm(int dtype, const float* x, const float* g, const float* b, int M, int d, float* y, void* ya,
