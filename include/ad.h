@@ -80,13 +80,24 @@ size_t ad_workspace_bytes(const ad_config* cfg, int with_drafter);
 
 /* A model's weights are one flat device blob.  Entry `index` (0 .. count-1) of its
  * layout: tensor name ("emb", "out.w", "enc.0.self.wq", "dec.3.ffn.b1", ... — a matrix
- * is [out_features, in_features] row-major), byte offset, shape, and element size
- * (2 = bf16, 4 = fp32; vectors are always fp32).  ad_weights_bytes is the blob size.
- * ad_weights_entry returns AD_EINVAL past the end. */
+ * is [out_features, in_features]), byte offset, shape, and element size (2 = bf16,
+ * 4 = fp32; vectors are always fp32).  ad_weights_bytes is the blob size.
+ * ad_weights_entry returns AD_EINVAL past the end.
+ *
+ * Byte order inside an entry.  fp32 entries and the embedding table "emb" are row-major.
+ * Every other bf16 matrix [N, K] is stored as the MFMA B operand reads it, so that a wave
+ * fetches 1 KB contiguous per 16 x 32 tile: tile (s, u) = rows 16s..16s+15 x columns
+ * 32u..32u+31 sits at element offset ((s * K/32 + u) * 64 + l) * 8 for l = 0..63, and lane
+ * slot l holds the 8 consecutive columns 32u + 8*(l/16).. of row 16s + l%16.  In bf16 mode
+ * "out.w" exists even with tie_output = 1 (fill it from the embedding table).
+ * ad_weights_pack writes one entry into a HOST copy of the blob from a row-major fp32
+ * tensor (rounding to bf16, nearest even, and tiling as needed); upload the blob afterwards. */
 int    ad_weights_count(const ad_config* cfg);
 size_t ad_weights_bytes(const ad_config* cfg);
 int    ad_weights_entry(const ad_config* cfg, int index, char* name, size_t name_cap,
                         size_t* offset, int32_t* rows, int32_t* cols, int32_t* elem_bytes);
+int    ad_weights_pack(const ad_config* cfg, int index, const float* src /* host, [rows, cols] */,
+                       void* blob /* host, ad_weights_bytes() */);
 
 /* ---- context --------------------------------------------------------------------------- */
 
@@ -179,8 +190,9 @@ int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vo
 
 /* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
  * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; 0 = one
- * launch per stage always; at most 64).  ad_create picks 64 when the device supports it, else 0;
- * setting a positive value on a context where it is unavailable gives AD_ESTATE. */
+ * launch per stage always; at most max_batch * k_max).  ad_create picks max_batch * k_max when
+ * the device and the model shape support it, else 0; setting a positive value on a context
+ * where it is unavailable gives AD_ESTATE. */
 enum { AD_OPT_FUSED_ROWS = 0 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);

@@ -21,6 +21,7 @@ AD_NEVER = -1
 
 EXPORTS = [
     "ad_config_check", "ad_workspace_bytes", "ad_weights_count", "ad_weights_bytes", "ad_weights_entry",
+    "ad_weights_pack",
     "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
     "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option",
@@ -70,6 +71,7 @@ def lib():
     L.ad_weights_bytes.argtypes = [cfgp]; L.ad_weights_bytes.restype = C.c_size_t
     L.ad_weights_entry.argtypes = [cfgp, C.c_int, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t), _I32P, _I32P, _I32P]
     L.ad_weights_entry.restype = C.c_int
+    L.ad_weights_pack.argtypes = [cfgp, C.c_int, C.POINTER(C.c_float), C.c_void_p]; L.ad_weights_pack.restype = C.c_int
     L.ad_create.argtypes = [cfgp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
     L.ad_create.restype = C.c_int
     L.ad_destroy.argtypes = [C.c_void_p]; L.ad_destroy.restype = C.c_int
@@ -162,20 +164,23 @@ def host_simulate(mode, g, aux, *, k=1, k_max=64, max_out=64, eos=2, bos=0):
 
 
 # ---- device side ------------------------------------------------------------------------------
-def pack_weights(cfg: AdConfig, params: dict, device="cuda"):
-    """Lays a {name: fp32 ndarray} parameter set out as the library's flat blob on `device`.
-    In bf16 mode matrices are rounded to bfloat16 (nearest even); vectors stay fp32."""
-    import torch
+def pack_weights_host(cfg: AdConfig, params: dict) -> np.ndarray:
+    """Lays a {name: fp32 ndarray} parameter set out as the library's flat blob (host bytes).
+    The library does the rounding to bf16 and the tiling of GEMM matrices; with a tied output
+    projection the "out.w" entry is filled from the embedding table."""
+    L = lib()
     layout, total = weights_layout(cfg)
-    blob = torch.zeros(total, dtype=torch.uint8)
-    for name, off, rows, cols, eb in layout:
-        w = np.ascontiguousarray(params[name], dtype=np.float32).reshape(rows, cols)
-        t = torch.from_numpy(w)
-        if eb == 2:
-            t = t.to(torch.bfloat16)
-        raw = t.contiguous().view(torch.uint8).reshape(-1)
-        blob[off:off + raw.numel()] = raw
-    return blob.to(device)
+    blob = np.zeros(total, dtype=np.uint8)
+    for i, (name, off, rows, cols, eb) in enumerate(layout):
+        src = params["emb"] if (name == "out.w" and name not in params) else params[name]
+        w = np.ascontiguousarray(src, dtype=np.float32).reshape(rows, cols)
+        _check(L.ad_weights_pack(C.byref(cfg), i, w.ctypes.data_as(C.POINTER(C.c_float)), C.c_void_p(blob.ctypes.data)))
+    return blob
+
+
+def pack_weights(cfg: AdConfig, params: dict, device="cuda"):
+    import torch
+    return torch.from_numpy(pack_weights_host(cfg, params)).to(device)
 
 
 class Context:

@@ -87,10 +87,10 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.len = take(B * 4); p.pending = take(B * 4); p.finished = take(B * 4); p.max_out = take(B * 4);
   p.out = take(B * c.max_len * 4);
   p.result = take(B * 2 * 4 + 16);   // [B,2] results, then one int: the fused forward's abort flag copy
-  p.stage_cap = 8 * c.dec_layers + 2;
+  p.stage_cap = 8 * c.dec_layers + 1;
   p.stages = take((size_t)p.stage_cap * sizeof(Stage));
-  p.stamps = take((size_t)(128 + 8 * 64) * 8);
-  p.bar = take(8 * (96 + 32 * 64));   // barrier words of the persistent forward (up to 1024 workgroups)
+  p.stamps = take((size_t)(8 * 64 + 64 + 4 * 64) * 8);   // stage clock stamps; also scratch for the placement probe
+  p.bar = take(8 * (size_t)kBarWords);   // barrier words of the persistent forward
   p.k_dev = take(B * 4 + B * c.k_max * 4);   // k[B] followed by draft[B, k_max]: one upload
   p.draft_dev = p.k_dev + B * 4;
   p.src_dev = take(B * 4 * 2 + B * c.max_src * 4);   // src_len[B], max_out[B], src[B, max_src]: one upload
@@ -124,12 +124,13 @@ struct ad_ctx {
   // shape of the forward being launched: attention problems and the most query rows in one
   int fw_nseq = 0, fw_max_rows = 0;
   int last_nseq = 0, last_max_rows = 0;
-  // persistent fused forward (bf16, few rows)
+  // persistent fused forward (bf16)
   int fused_rows = 0;            // largest M it takes; 0 = off
-  int fused_grid = 0, fused_stages = 0;
+  int fused_grid = 0, fused_stages = 0, fused_teams = 0;
   size_t fused_lds = 0;
-  unsigned long long bar_base = 0;
+  unsigned long long dev_base = 0, team_base[kMaxTeams] = {};
   bool last_fused = false;
+  std::vector<int> last_k;       // k[b] of the last verify call
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 };
@@ -230,8 +231,9 @@ static void vocab_finish(ad_ctx* c, int Mv) {
                        c->at<float>(p.o_val), c->stream);
 }
 
-// Stage program of the verify forward for the persistent kernel (pointers are fixed for the
-// life of the context; only the row tables' contents and M, B change per call).
+// Layer-phase stage program of the verify forward for the persistent kernel (pointers are fixed
+// for the life of the context; only the row tables' contents, the team shares, M and B change
+// per call).  The output projection, its arg max and acceptance are fixed parts of the kernel.
 static int build_verify_program(ad_ctx* c, std::vector<Stage>& prog) {
   const Plan& p = c->plan;
   const ad_config& cf = c->cfg;
@@ -276,60 +278,103 @@ static int build_verify_program(ad_ctx* c, std::vector<Stage>& prog) {
     Epi r{};
     r.mode = EPI_RELU; r.bias = L.ffn.b1; r.out0 = c->at<void>(p.f);
     gemm(A_LN, c->at<float>(p.s), &L.ln2, L.ffn.w1, F, d, r);
-    gemm(A_GLOBAL, c->at<void>(p.f), nullptr, L.ffn.w2, d, F, resid(L.ffn.b2));
+    gemm(A_COPY, c->at<void>(p.f), nullptr, L.ffn.w2, d, F, resid(L.ffn.b2));
   }
-  Epi a{};
-  a.mode = EPI_ARGMAX; a.part_val = c->at<float>(p.part_val); a.part_idx = c->at<int>(p.part_idx);
-  a.n_strips = p.n_strips; a.logits = cf.debug_logits ? c->at<float>(p.logits) : nullptr;
-  gemm(A_LN, c->at<float>(p.s), &w.dec[cf.dec_layers - 1].ln3, w.out_w, cf.vocab, d, a);
-  Stage fin{};
-  fin.type = ST_FINISH;
-  prog.push_back(fin);
+  // every GEMM stage prefetches the next GEMM stage's weights; the last one the output projection's
+  for (size_t i = 0; i < prog.size(); ++i) {
+    prog[i].pf_stage = -1;
+    if (prog[i].type != ST_GEMM) continue;
+    prog[i].pf_stage = -2;
+    for (size_t j = i + 1; j < prog.size(); ++j)
+      if (prog[j].type == ST_GEMM) { prog[i].pf_stage = (int)j; break; }
+  }
+  Stage ln{};
+  ln.pf_stage = -1;
+  ln.type = ST_LN; ln.K = d; ln.a_src = c->at<float>(p.s);
+  ln.ln_g = w.dec[cf.dec_layers - 1].ln3.g; ln.ln_b = w.dec[cf.dec_layers - 1].ln3.b;
+  ln.epi.out0 = c->at<void>(p.xa);
+  prog.push_back(ln);
   return (int)prog.size();
 }
 
 // Sets the persistent forward up if this context and device can run it; otherwise leaves it off.
 static void setup_fused(ad_ctx* c) {
   c->fused_rows = 0;
+  c->fused_grid = 0;
   if (c->cfg.dtype != AD_BF16) return;
   const ad_config& cf = c->cfg;
   const Plan& p = c->plan;
-  const size_t a_bytes = (size_t)64 * (cf.d_model + 8) * 2;
-  const size_t att_bytes = attn_lds_host(std::max(p.l_cap, cf.max_src), cf.d_model / cf.n_heads, 2, 8);
-  const size_t lds = std::max(a_bytes, att_bytes);
-  if (lds > 160 * 1024 - 1024) return;
+  const int d = cf.d_model, F = cf.d_ffn;
+  // LayerNorm rows and A tiles are at most kFusedMaxWidth wide; wider GEMMs walk whole slices
+  if (d > kFusedMaxWidth || d % 32 || F % 32 || (F > kFusedMaxWidth && F % kFusedMaxWidth)) return;
+  const size_t att_bytes = attn_lds_host(std::max(p.l_cap, cf.max_src), d / cf.n_heads, 2, kFusedWaves);
+  const size_t lds = kFusedLdsBytes;
+  if (att_bytes > lds || (size_t)cf.k_max * 4 > lds) return;
   hipDeviceProp_t prop;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return; }
   if (!prop.cooperativeLaunch) return;
-  const int per_cu = fused_max_blocks_per_cu(lds);
-  if (per_cu < 1) return;
-  std::vector<Stage> prog;
-  const int n = build_verify_program(c, prog);
-  if (n > p.stage_cap) return;
-  if (hipMemcpyAsync(c->ws + p.stages, prog.data(), prog.size() * sizeof(Stage), hipMemcpyHostToDevice, c->stream) != hipSuccess ||
-      hipMemsetAsync(c->ws + p.bar, 0, 8 * (96 + 32 * 64), c->stream) != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess) {
+  if (fused_max_blocks_per_cu(lds) < 1) return;
+  const int grid = std::min(prop.multiProcessorCount, 64 * 16);
+  // where do the workgroups of such a launch land?  Team t = workgroups with index % n == t must
+  // share one XCD.
+  int* xcc_dev = c->at<int>(p.stamps);
+  std::vector<int> xcc(grid, -1);
+  if (launch_probe_placement(xcc_dev, grid, lds, c->stream) != hipSuccess ||
+      hipMemcpyAsync(xcc.data(), xcc_dev, (size_t)grid * 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
+      hipStreamSynchronize(c->stream) != hipSuccess) {
     (void)hipGetLastError();
     return;
   }
-  c->fused_grid = std::min(prop.multiProcessorCount, 1024);
+  const int n_teams = *std::max_element(xcc.begin(), xcc.end()) + 1;
+  if (n_teams < 1 || n_teams > kMaxTeams || grid < n_teams) return;
+  // round-robin from a starting XCD that may differ from launch to launch
+  for (int b = 0; b < grid; ++b)
+    if (xcc[b] != (b + xcc[0]) % n_teams) return;
+  std::vector<Stage> prog;
+  const int n = build_verify_program(c, prog);
+  if (n > p.stage_cap || n > kFusedMaxStages) return;
+  if (hipMemcpyAsync(c->ws + p.stages, prog.data(), prog.size() * sizeof(Stage), hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+      hipMemsetAsync(c->ws + p.bar, 0, 8 * (size_t)kBarWords, c->stream) != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return;
+  }
+  c->fused_grid = grid;
+  c->fused_teams = n_teams;
   c->fused_stages = n;
   c->fused_lds = lds;
-  c->bar_base = 0;
-  c->fused_rows = 64;
+  c->dev_base = 0;
+  for (int t = 0; t < kMaxTeams; ++t) c->team_base[t] = 0;
+  c->fused_rows = p.mv_cap;
 }
 
-static hipError_t fused_verify_forward(ad_ctx* c, int M, int B, bool do_accept, bool stamps = false) {
+// One launch: the whole verify forward for the rows the tables describe.  k[b] = rows of
+// sequence b; sequences go to the teams in contiguous runs of about M / n_teams rows.
+static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bool do_accept, bool stamps = false) {
   const Plan& p = c->plan;
   const ad_config& cf = c->cfg;
   VerifyTables t = tables(c);
   FusedArgs fa{};
   fa.stages = c->at<Stage>(p.stages); fa.n_stages = c->fused_stages;
-  fa.M = M; fa.B = B; fa.d = cf.d_model; fa.H = cf.n_heads; fa.dh = cf.d_model / cf.n_heads;
+  fa.M = M; fa.B = B; fa.d = cf.d_model; fa.H = cf.n_heads; fa.dh = cf.d_model / cf.n_heads; fa.V = cf.vocab;
   fa.sqrt_d = sqrtf((float)cf.d_model); fa.pe = c->at<float>(p.pe);
   fa.row_tok = t.row_tok; fa.row_pos = t.row_pos;
-  fa.bar = c->at<unsigned long long>(p.bar); fa.bar_base = c->bar_base;
-  fa.part_val = c->at<float>(p.part_val); fa.part_idx = c->at<int>(p.part_idx); fa.n_strips = p.n_strips;
+  const int nt = c->fused_teams;
+  fa.n_teams = nt;
+  {
+    // sequence b goes to team floor(first row of b * n_teams / M): contiguous, balanced by rows
+    int b = 0, rows = 0;
+    for (int tm = 0; tm < nt; ++tm) {
+      fa.team_seq[tm] = b; fa.team_row[tm] = rows;
+      while (b < B && (tm == nt - 1 || (long long)rows * nt / M <= tm)) { rows += k[b]; ++b; }
+    }
+    fa.team_seq[nt] = B; fa.team_row[nt] = M;
+  }
+  for (int tm = 0; tm < nt; ++tm) fa.team_base[tm] = c->team_base[tm];
+  fa.bar = c->at<unsigned long long>(p.bar); fa.dev_base = c->dev_base; fa.zero = 0;
+  fa.out_w = c->w[AD_VERIFIER].out_w; fa.xa = c->at<void>(p.xa);
+  fa.logits = cf.debug_logits ? c->at<float>(p.logits) : nullptr;
+  fa.part_val = c->at<float>(p.part_val); fa.part_idx = c->at<int>(p.part_idx); fa.part_stride = p.n_strips;
   fa.o_hat = c->at<int>(p.o_hat); fa.o_val = c->at<float>(p.o_val);
   fa.do_accept = do_accept ? 1 : 0;
   fa.k = c->at<int>(p.k_dev); fa.draft = c->at<int>(p.draft_dev); fa.row_start = t.row_start;
@@ -338,7 +383,14 @@ static hipError_t fused_verify_forward(ad_ctx* c, int M, int B, bool do_accept, 
   fa.out = c->at<int>(p.out); fa.result = c->at<int>(p.result);
   fa.stamps = stamps ? c->at<unsigned long long>(p.stamps) : nullptr;
   hipError_t e = launch_fused_forward(fa, c->fused_grid, c->fused_lds, c->stream);
-  if (e == hipSuccess) c->bar_base += (unsigned long long)(c->fused_stages - 1);
+  if (e == hipSuccess) {
+    c->dev_base += 2;
+    for (int tm = 0; tm < nt; ++tm)
+      if (fa.team_row[tm + 1] > fa.team_row[tm]) {
+        const int T = (c->fused_grid - tm + nt - 1) / nt;
+        c->team_base[tm] += (unsigned long long)(c->fused_stages - 1) * T;
+      }
+  }
   return e;
 }
 
@@ -433,7 +485,7 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   c->has_drafter = drafter_w != nullptr;
   if (c->has_drafter) c->w[1] = bind_weights(*cfg, drafter_w);
   const size_t B = cfg->max_batch;
-  c->pin_ints = (4 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 64 + 3) / 4 * 4;
+  c->pin_ints = (4 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 128 + 3) / 4 * 4;
   auto bail = [&](const char* what, hipError_t e) {
     std::string m = std::string(what) + ": " + hipGetErrorString(e);
     if (c->pin) (void)hipHostFree(c->pin);
@@ -585,32 +637,45 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   c->last_nseq = B; c->last_max_rows = c->fw_max_rows;
   launch_assemble_verify(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.len), c->at<int>(p.pending),
                          c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
-  const bool fused = c->fused_rows > 0 && M <= c->fused_rows;
-  if (fused) {
-    HIP_TRY(c, fused_verify_forward(c, M, B, true));
-  } else {
-    verify_forward(c, M);
-    launch_accept(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
-                  cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
-                  c->at<int>(p.out), c->at<int>(p.result), c->stream);
-  }
   int32_t* res = c->pin + (size_t)B * (1 + km);
-  HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
-  unsigned long long* abort_flag = (unsigned long long*)(c->pin + c->pin_ints - 4);
-  *abort_flag = 0;
-  if (fused)
-    HIP_TRY(c, hipMemcpyAsync(abort_flag, c->at<unsigned long long>(p.bar) + 64, 8, hipMemcpyDeviceToHost, c->stream));
   int32_t* oh = res + 2 * B;
-  if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipGetLastError());
-  if (*abort_flag) {
-    // a device-wide barrier timed out: the decode state is undefined; switch the persistent path off
-    c->fused_rows = 0;
-    c->encoded[AD_VERIFIER] = false;
-    return fail(c, AD_EDEVICE, "persistent forward: device-wide barrier timed out (state lost, encode again)");
+  unsigned long long* flags = (unsigned long long*)(c->pin + c->pin_ints - 2 * (kBarPlacement - kBarAbort + 2) - 2);
+  bool fused = c->fused_rows > 0 && M <= c->fused_rows;
+  for (;;) {
+    if (fused) {
+      HIP_TRY(c, fused_verify_forward(c, k, M, B, true));
+    } else {
+      verify_forward(c, M);
+      launch_accept(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
+                    cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
+                    c->at<int>(p.out), c->at<int>(p.result), c->stream);
+    }
+    HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
+    flags[0] = 0; flags[kBarPlacement - kBarAbort] = 1; flags[kBarPlacement - kBarAbort + 1] = 1;
+    const int place_word = kBarPlacement - kBarAbort + (int)(((c->dev_base >> 1) + 1) & 1);   // of the launch above
+    if (fused)
+      HIP_TRY(c, hipMemcpyAsync(flags, c->at<unsigned long long>(p.bar) + kBarAbort,
+                                8 * (size_t)(kBarPlacement - kBarAbort + 2), hipMemcpyDeviceToHost, c->stream));
+    if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipGetLastError());
+    if (flags[0]) {
+      // a barrier timed out: the decode state is undefined; switch the persistent path off
+      c->fused_rows = 0;
+      c->encoded[AD_VERIFIER] = false;
+      return fail(c, AD_EDEVICE, "persistent forward: a barrier timed out (state lost, encode again)");
+    }
+    if (fused && (flags[place_word] & (flags[place_word] - 1)) != 0) {
+      // a team was spread over several XCDs: the kernel left the decode state alone;
+      // run this call, and all later ones, with one launch per stage
+      c->fused_rows = 0;
+      fused = false;
+      continue;
+    }
+    break;
   }
   c->last_fused = fused;
+  c->last_k.assign(k, k + B);
   int r0 = 0;
   for (int b = 0; b < B; ++b) {
     n_accept[b] = res[2 * b];
@@ -780,7 +845,7 @@ int ad_decode_gad(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, 
 int ad_set_option(ad_ctx* c, int option, int value) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
   if (option != AD_OPT_FUSED_ROWS) return fail(c, AD_EINVAL, "unknown option");
-  if (value < 0 || value > 64) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, 64]");
+  if (value < 0 || value > c->plan.mv_cap) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, max_batch * k_max]");
   if (value > 0 && c->fused_grid == 0) return fail(c, AD_ESTATE, "the persistent forward is unavailable for this context");
   c->fused_rows = value;
   return AD_OK;
@@ -813,10 +878,11 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
   if (c->last_fused && c->fused_rows > 0) {
     // one kernel: the whole forward (arg max included, acceptance skipped)
-    HIP_TRY(c, fused_verify_forward(c, c->last_M, c->last_nseq, false));
+    const int* k = c->last_k.data();
+    HIP_TRY(c, fused_verify_forward(c, k, c->last_M, c->last_nseq, false));
     for (int r = 0; r < reps; ++r) {
       HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
-      HIP_TRY(c, fused_verify_forward(c, c->last_M, c->last_nseq, false));
+      HIP_TRY(c, fused_verify_forward(c, k, c->last_M, c->last_nseq, false));
       HIP_TRY(c, hipEventRecord(c->ev3, c->stream));
       HIP_TRY(c, hipEventSynchronize(c->ev3));
       float a = 0;
@@ -826,18 +892,33 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
     *forward_us = tot / reps;
     *vocab_kernel_us = 0;
     if (getenv("AD_DEBUG_STAGES")) {
-      // diagnostic: per-stage durations of one launch (100 MHz device clock), to stderr
-      std::vector<unsigned long long> st(128 + 8 * 64);
-      HIP_TRY(c, fused_verify_forward(c, c->last_M, c->last_nseq, false, true));
-      HIP_TRY(c, hipMemcpyAsync(st.data(), c->at<unsigned long long>(c->plan.stamps), st.size() * 8, hipMemcpyDeviceToHost, c->stream));
+      // diagnostic: stage start times of one launch as seen by workgroup 0 (100 MHz clock), to stderr
+      const int n = c->fused_stages + 5, nw = 64 + 8 * 64 + 4 * 64;
+      std::vector<unsigned long long> st(nw);
+      HIP_TRY(c, fused_verify_forward(c, k, c->last_M, c->last_nseq, false, true));
+      HIP_TRY(c, hipMemcpyAsync(st.data(), c->at<unsigned long long>(c->plan.stamps), (size_t)nw * 8, hipMemcpyDeviceToHost, c->stream));
       HIP_TRY(c, hipStreamSynchronize(c->stream));
-      for (int i = 0; i + 1 < c->fused_stages && i < 12; ++i) {
-        const unsigned long long* f = &st[128 + i * 8];
-        fprintf(stderr, "  stage %d: start->A_staged %.2f  ->mfma_done %.2f  ->epilogue_done %.2f  ->next_barrier_entry %.2f  ->barrier_done %.2f\n", i,
-                (double)(f[1] - st[i]) * 0.01, (double)(f[2] - f[1]) * 0.01, (double)(f[3] - f[2]) * 0.01,
-                (double)(st[128 + (i + 1) * 8 + 4] - f[3]) * 0.01, (double)(st[i + 1] - st[128 + (i + 1) * 8 + 4]) * 0.01);
+      for (int i = 0; i + 1 < n; ++i) {
+        const unsigned long long* f = &st[64 + 8 * i];
+        const unsigned long long* g = &st[64 + 8 * (i + 1)];
+        fprintf(stderr, "stage %2d: %6.2f us", i, (double)(st[i + 1] - st[i]) * 0.01);
+        if (i > 0 && i < c->fused_stages) fprintf(stderr, " [weights fetched in %5.2f]", (double)(f[6] - f[1]) * 0.01);
+        if (i < c->fused_stages) { const unsigned long long* q = &st[576 + 4 * i]; fprintf(stderr, " [to stage_a +%5.2f, stage_a +%5.2f, vmcnt +%5.2f, sync +%5.2f]", (double)(q[0] - st[i]) * 0.01, (double)(q[1] - q[0]) * 0.01, (double)(q[2] - q[1]) * 0.01, (double)(f[3] - q[2]) * 0.01); }
+        if (i < c->fused_stages)
+          fprintf(stderr, " | A staged +%5.2f  mfma +%5.2f  epilogue +%5.2f | to barrier +%5.2f  stores done +%5.2f  wait +%5.2f",
+                  (double)(f[3] - st[i]) * 0.01, (double)(f[4] - f[3]) * 0.01, (double)(f[5] - f[4]) * 0.01,
+                  (double)(g[0] - f[5]) * 0.01, (double)(g[1] - g[0]) * 0.01, (double)(g[2] - g[1]) * 0.01);
+        fprintf(stderr, "\n");
       }
-      for (int i = 0; i < c->fused_stages; ++i) fprintf(stderr, "stage %2d: %.2f us  %.0f MHz\n", i, (double)(st[i + 1] - st[i]) * 0.01, i + 1 < c->fused_stages ? (double)(st[64 + i + 1] - st[64 + i]) / ((double)(st[i + 1] - st[i]) * 0.01) : 0.0);
+      fprintf(stderr, "total %.2f us\n", (double)(st[n - 1] - st[0]) * 0.01);
+    }
+    unsigned long long flags[kBarPlacement - kBarAbort + 2];
+    const int place_word = kBarPlacement - kBarAbort + (int)(((c->dev_base >> 1) + 1) & 1);   // of the last launch
+    HIP_TRY(c, hipMemcpyAsync(flags, c->at<unsigned long long>(c->plan.bar) + kBarAbort, sizeof(flags), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (flags[0] || (flags[place_word] & (flags[place_word] - 1)) != 0) {
+      c->fused_rows = 0;
+      return fail(c, AD_EDEVICE, "persistent forward: barrier time-out or misplaced workgroup while timing");
     }
     return AD_OK;
   }

@@ -20,25 +20,82 @@ __device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest, ties to
   return (bf16_t)(u >> 16);
 }
 // Memory access policy.  COH = false: ordinary cached accesses (data produced by an earlier
-// launch).  COH = true: device-coherent accesses that bypass the per-XCD L2 (volatile accesses:
-// ordinary coalesced vector loads/stores carrying the system-coherence cache policy).  The
-// persistent kernel uses them for everything one workgroup writes and another reads in a later
-// stage, so that its stage barrier needs no cache write-back or invalidate.
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+// launch, or weights).  COH = true: the access carries the device-scope cache policy (relaxed
+// device-scope atomics: ordinary vector loads/stores that miss the compute unit's L1; a store
+// writes through to memory).  The persistent kernel uses coherent LOADS for everything another
+// workgroup wrote earlier in the same launch.  Workgroups of one XCD share that XCD's L2, so data
+// exchanged inside an XCD needs plain stores only; data that crosses XCDs is stored coherently.
+// All of these address device (global) memory; the explicit address space keeps the compiler
+// from falling back to the slower flat instructions when it cannot see where a pointer came from
+// (pointers loaded from a stage program in memory).
+#define AD_GLOBAL __attribute__((address_space(1)))
+// (class types are moved as raw 16-, 8-, 4- or 2-byte pieces: their copy constructors take
+// generic references, which would undo the address space)
+template <int BYTES> struct RawPiece;
+template <> struct RawPiece<16> { typedef unsigned type __attribute__((ext_vector_type(4))); };
+template <> struct RawPiece<8> { typedef unsigned type __attribute__((ext_vector_type(2))); };
+template <> struct RawPiece<4> { typedef unsigned type; };
+template <> struct RawPiece<2> { typedef unsigned short type; };
+template <typename V> struct RawOf {
+  static constexpr int kPiece = sizeof(V) % 16 == 0 ? 16 : (sizeof(V) % 8 == 0 ? 8 : (sizeof(V) % 4 == 0 ? 4 : 2));
+  typedef typename RawPiece<kPiece>::type piece;
+  static constexpr int kCount = sizeof(V) / kPiece;
+  struct Raw { piece v[kCount]; };
+};
+template <typename V> __device__ __forceinline__ V gload(const V* p) {
+  typedef RawOf<V> R;
+  typename R::Raw raw;
+  const AD_GLOBAL typename R::piece* gp = (const AD_GLOBAL typename R::piece*)p;
+#pragma unroll
+  for (int i = 0; i < R::kCount; ++i) raw.v[i] = gp[i];
+  return __builtin_bit_cast(V, raw);
+}
+template <typename V> __device__ __forceinline__ void gstore(V* p, V v) {
+  typedef RawOf<V> R;
+  const typename R::Raw raw = __builtin_bit_cast(typename R::Raw, v);
+  AD_GLOBAL typename R::piece* gp = (AD_GLOBAL typename R::piece*)p;
+#pragma unroll
+  for (int i = 0; i < R::kCount; ++i) gp[i] = raw.v[i];
+}
 template <bool COH, typename V> __device__ __forceinline__ V ldg(const V* p) {
-  if constexpr (COH) return *(const volatile V*)p;
-  else return *p;
+  if constexpr (COH) {
+    if constexpr (sizeof(V) == 2) {
+      const unsigned short u = __hip_atomic_load((const AD_GLOBAL unsigned short*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return __builtin_bit_cast(V, u);
+    } else if constexpr (sizeof(V) == 4) {
+      const unsigned u = __hip_atomic_load((const AD_GLOBAL unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return __builtin_bit_cast(V, u);
+    } else {
+      static_assert(sizeof(V) == 8, "coherent loads: 2, 4 or 8 bytes");
+      const unsigned long long u = __hip_atomic_load((const AD_GLOBAL unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return __builtin_bit_cast(V, u);
+    }
+  } else {
+    return gload(p);
+  }
 }
 template <bool COH, typename V> __device__ __forceinline__ void stg(V* p, V v) {
-  if constexpr (COH) *(volatile V*)p = v;
-  else *p = v;
+  if constexpr (COH) {
+    if constexpr (sizeof(V) == 2) {
+      __hip_atomic_store((AD_GLOBAL unsigned short*)p, __builtin_bit_cast(unsigned short, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if constexpr (sizeof(V) == 4) {
+      __hip_atomic_store((AD_GLOBAL unsigned*)p, __builtin_bit_cast(unsigned, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      static_assert(sizeof(V) == 8, "coherent stores: 2, 4 or 8 bytes");
+      __hip_atomic_store((AD_GLOBAL unsigned long long*)p, __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  } else {
+    gstore(p, v);
+  }
 }
+// 16 bytes (16-byte aligned): coherent = two 8-byte halves
 template <bool COH> __device__ __forceinline__ uint4 ldg16(const void* p) {
   if constexpr (COH) {
-    const u32x4_t v = *(const volatile u32x4_t*)p;
-    return uint4{v[0], v[1], v[2], v[3]};
+    const unsigned long long lo = __hip_atomic_load((const AD_GLOBAL unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load((const AD_GLOBAL unsigned long long*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return uint4{(unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32)};
   } else {
-    return *(const uint4*)p;
+    return gload((const uint4*)p);
   }
 }
 
@@ -54,15 +111,34 @@ template <> struct Store<bf16_t> {
   static __device__ __forceinline__ float round(float v) { return bf2f(f2bf(v)); }
 };
 
+// Wave-wide sum / maximum, all 64 lanes active, the same value in every lane.  Data-parallel
+// lane moves (no LDS traffic): xor 1, xor 2 inside quads, mirror inside half rows, mirror inside
+// rows of 16 lanes (every lane of a row then holds the row's total, built from commutative
+// pairs, hence identical across the row), then the four rows: (r0 + r1) + (r2 + r3).
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return (r0 + r1) + (r2 + r3);
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 // (value, index) maximum with the lowest index winning ties: a total order, so the result does
 // not depend on the shape of the reduction tree.
@@ -74,36 +150,65 @@ __device__ __forceinline__ void argmax_merge(float& v, int& i, float ov, int oi)
 __device__ __forceinline__ float embed_value(float e, float sqrt_d, float pe) { return fmaf(e, sqrt_d, pe); }
 
 // LayerNorm statistics of one row by one wave: lane l owns elements l, l+64, ... (kept in
-// registers, at most 32 per lane: d <= 2048); mean, then the biased variance of the centred
-// values; eps = 1e-5.
-template <bool COH = false>
-__device__ __forceinline__ void ln_load(const float* __restrict__ xr, int d, int lane, float (&xv)[32]) {
+// registers, NJ per lane: d <= 64*NJ); mean, then the biased variance of the centred values;
+// eps = 1e-5.  NJ only bounds the register array: the arithmetic depends on d alone.
+template <bool COH = false, int NJ = 32, bool EXACT = false>   // EXACT: d == 64 * NJ, no bounds tests
+__device__ __forceinline__ void ln_load(const float* __restrict__ xr, int d, int lane, float (&xv)[NJ]) {
 #pragma unroll
-  for (int j = 0; j < 32; ++j) {
+  for (int j = 0; j < NJ; ++j) {
     const int c = lane + 64 * j;
-    xv[j] = c < d ? ldg<COH>(xr + c) : 0.f;
+    xv[j] = (EXACT || c < d) ? ldg<COH>(xr + c) : 0.f;
   }
 }
-__device__ __forceinline__ void ln_stats(const float (&xv)[32], int d, int lane, float& mean, float& rstd) {
+template <int NJ = 32, bool EXACT = false>
+__device__ __forceinline__ void ln_stats(const float (&xv)[NJ], int d, int lane, float& mean, float& rstd) {
   float s = 0.f;
 #pragma unroll
-  for (int j = 0; j < 32; ++j)
-    if (lane + 64 * j < d) s += xv[j];
+  for (int j = 0; j < NJ; ++j)
+    if (EXACT || lane + 64 * j < d) s += xv[j];
   mean = wave_sum(s) / (float)d;
   float v = 0.f;
 #pragma unroll
-  for (int j = 0; j < 32; ++j)
-    if (lane + 64 * j < d) {
+  for (int j = 0; j < NJ; ++j)
+    if (EXACT || lane + 64 * j < d) {
       const float t = xv[j] - mean;
       v = fmaf(t, t, v);
     }
   rstd = 1.0f / sqrtf(wave_sum(v) / (float)d + 1e-5f);
 }
+// Rows whose width is 256, 512, 1024 or 2048 use 16-byte accesses instead: lane l owns the four
+// consecutive elements at 4*l + 256*j, j < NV = d / 256 (ln_vector_width says which rule a width
+// takes; every kernel follows it, so a row's statistics never depend on the kernel).
+__host__ __device__ inline int ln_vector_width(int d) { return (d == 256 || d == 512 || d == 1024 || d == 2048) ? d / 256 : 0; }
+template <bool COH, int NV>
+__device__ __forceinline__ void ln_load4(const float* __restrict__ xr, int lane, float4 (&xv)[NV]) {
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const uint4 u = ldg16<COH>(xr + 4 * lane + 256 * j);
+    xv[j] = float4{__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w)};
+  }
+}
+template <int NV>
+__device__ __forceinline__ void ln_stats4(const float4 (&xv)[NV], int d, float& mean, float& rstd) {
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) { s += xv[j].x; s += xv[j].y; s += xv[j].z; s += xv[j].w; }
+  mean = wave_sum(s) / (float)d;
+  float v = 0.f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    float t = xv[j].x - mean; v = fmaf(t, t, v);
+    t = xv[j].y - mean; v = fmaf(t, t, v);
+    t = xv[j].z - mean; v = fmaf(t, t, v);
+    t = xv[j].w - mean; v = fmaf(t, t, v);
+  }
+  rstd = 1.0f / sqrtf(wave_sum(v) / (float)d + 1e-5f);
+}
 template <bool COH = false>
 __device__ __forceinline__ void ln_load_stats(const float* __restrict__ xr, int d, int lane, float (&xv)[32],
                                               float& mean, float& rstd) {
-  ln_load<COH>(xr, d, lane, xv);
-  ln_stats(xv, d, lane, mean, rstd);
+  ln_load<COH, 32>(xr, d, lane, xv);
+  ln_stats<32>(xv, d, lane, mean, rstd);
 }
 __device__ __forceinline__ float ln_value(float x, float mean, float rstd, float g, float b) {
   const float t = (x - mean) * rstd;
@@ -111,11 +216,78 @@ __device__ __forceinline__ float ln_value(float x, float mean, float rstd, float
 }
 
 // ------------------------------------------------------------------------------------- GEMM epilogue
+// Operands of a strip's epilogue that do not depend on the accumulators: bias, destination rows
+// (key/value rows of the cache), residual values.  Loaded in one batch, possibly long before the
+// accumulators are ready, so that no store waits behind a load.
+template <int MT> struct EpiRegs {
+  float bias;
+  unsigned aux[MT * 4];   // destination row (QKV / KV) or the residual value's bits (RESID): never both
+};
+template <int MT, bool LDC = false>
+__device__ __forceinline__ void epi_preload(const Epi& e, int mt_used, int m0, int n0, int M, int N, int lane,
+                                            EpiRegs<MT>& g) {
+  const int r = lane & 15, kq = lane >> 4, n = n0 + r;
+  g.bias = e.bias ? gload(e.bias + n) : 0.f;
+  const int mode = e.mode;
+  const bool want_dst = (mode == EPI_QKV && n0 >= e.d) || mode == EPI_KV, want_res = mode == EPI_RESID;
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + t * 16 + kq * 4 + i;
+      const bool live = t < mt_used && m < M;
+      unsigned a = 0u;
+      if (want_dst && live) a = (unsigned)gload(e.row_dst + m);
+      if (want_res && live) a = __float_as_uint(ldg<LDC>(e.resid + (size_t)m * N + n));
+      g.aux[t * 4 + i] = a;
+    }
+}
+// value = acc + bias, then the mode's operation.  A strip of 16 columns lies inside one of the
+// q / k / v column ranges (d is a multiple of 16), so the destination is uniform over the wave.
+template <typename T, int MT, bool STC = false>
+__device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], const EpiRegs<MT>& g, int mt_used,
+                                          int m0, int n0, int M, int N, int lane) {
+  const int r = lane & 15, kq = lane >> 4, n = n0 + r;
+  const int mode = e.mode, d = e.d;
+  const bool has_bias = e.bias != nullptr;
+  // destination of (row m, this lane's column) for the row-indexed modes
+  T* base = nullptr;
+  int ld = N, col = n;
+  bool by_dst = false;
+  if (mode == EPI_QKV) {
+    ld = d;
+    if (n0 < d) base = (T*)e.out0;
+    else if (n0 < 2 * d) { base = (T*)e.out1; col = n - d; by_dst = true; }
+    else { base = (T*)e.out2; col = n - 2 * d; by_dst = true; }
+  } else if (mode == EPI_KV) {
+    ld = d; by_dst = true;
+    if (n0 < d) base = (T*)e.out1;
+    else { base = (T*)e.out2; col = n - d; }
+  } else if (mode == EPI_STORE || mode == EPI_RELU) {
+    base = (T*)e.out0;
+  }
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + t * 16 + kq * 4 + i;
+      if (t >= mt_used || m >= M) continue;
+      float v = acc[t][i];
+      if (has_bias) v += g.bias;
+      if (mode == EPI_RESID) {
+        stg<STC>((float*)e.out0 + (size_t)m * N + n, v + __uint_as_float(g.aux[t * 4 + i]));
+      } else {
+        if (mode == EPI_RELU) v = fmaxf(v, 0.f);
+        const size_t row = by_dst ? (size_t)g.aux[t * 4 + i] : (size_t)m;
+        Store<T>::template store<STC>(base + row * ld + col, v);
+      }
+    }
+}
+
 // Epilogue of one 16-column strip held in MFMA C layout (lane l: column n0 + l%16, rows
-// m0 + 4*(l/16) + i of tile t).  Everything the stores depend on (bias, destination rows,
-// residual values) is loaded first, in one batch, so that no store waits behind a load.
-// For EPI_ARGMAX the 16 lanes of a row reduce to one (value, index) partial.
-template <typename T, int MT, bool COH = false>
+// m0 + 4*(l/16) + i of tile t).  For EPI_ARGMAX the 16 lanes of a row reduce to one
+// (value, index) partial.
+template <typename T, int MT, bool LDC = false, bool STC = false>
 __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[MT], int mt_used, int m0, int n0,
                                                int M, int N, int lane) {
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
@@ -129,7 +301,7 @@ __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[
         const int m = m0 + t * 16 + kq * 4 + i;
         float v = acc[t][i];
         int idx = n;
-        if (e.logits && m < M) e.logits[(size_t)m * N + n] = v;
+        if (e.logits && m < M) gstore(e.logits + (size_t)m * N + n, v);
 #pragma unroll
         for (int o = 8; o > 0; o >>= 1) {
           float ov = __shfl_xor(v, o, 64);
@@ -137,50 +309,16 @@ __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[
           argmax_merge(v, idx, ov, oi);
         }
         if (r == 0 && m < M) {
-          stg<COH>(e.part_val + (size_t)m * e.n_strips + strip, v);
-          stg<COH>(e.part_idx + (size_t)m * e.n_strips + strip, idx);
+          stg<STC>(e.part_val + (size_t)m * e.n_strips + strip, v);
+          stg<STC>(e.part_idx + (size_t)m * e.n_strips + strip, idx);
         }
       }
     }
     return;
   }
-  const float bias = e.bias ? e.bias[n] : 0.f;
-  const int mode = e.mode, d = e.d;
-  int dst[MT * 4];
-  float res[MT * 4];
-#pragma unroll
-  for (int t = 0; t < MT; ++t)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + t * 16 + kq * 4 + i;
-      const bool live = t < mt_used && m < M;
-      dst[t * 4 + i] = (live && (mode == EPI_QKV || mode == EPI_KV)) ? e.row_dst[m] : 0;
-      res[t * 4 + i] = (live && mode == EPI_RESID) ? ldg<COH>(e.resid + (size_t)m * N + n) : 0.f;
-    }
-#pragma unroll
-  for (int t = 0; t < MT; ++t)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + t * 16 + kq * 4 + i;
-      if (t >= mt_used || m >= M) continue;
-      float v = acc[t][i];
-      if (e.bias) v += bias;
-      switch (mode) {
-        case EPI_QKV:
-          if (n < d) Store<T>::template store<COH>((T*)e.out0 + (size_t)m * d + n, v);
-          else if (n < 2 * d) Store<T>::template store<COH>((T*)e.out1 + (size_t)dst[t * 4 + i] * d + (n - d), v);
-          else Store<T>::template store<COH>((T*)e.out2 + (size_t)dst[t * 4 + i] * d + (n - 2 * d), v);
-          break;
-        case EPI_KV:
-          if (n < d) Store<T>::template store<COH>((T*)e.out1 + (size_t)dst[t * 4 + i] * d + n, v);
-          else Store<T>::template store<COH>((T*)e.out2 + (size_t)dst[t * 4 + i] * d + (n - d), v);
-          break;
-        case EPI_STORE: Store<T>::template store<COH>((T*)e.out0 + (size_t)m * N + n, v); break;
-        case EPI_RELU: Store<T>::template store<COH>((T*)e.out0 + (size_t)m * N + n, fmaxf(v, 0.f)); break;
-        case EPI_RESID: stg<COH>((float*)e.out0 + (size_t)m * N + n, v + res[t * 4 + i]); break;
-        default: break;
-      }
-    }
+  EpiRegs<MT> g;
+  epi_preload<MT, LDC>(e, mt_used, m0, n0, M, N, lane, g);
+  epi_apply<T, MT, STC>(e, acc, g, mt_used, m0, n0, M, N, lane);
 }
 
 // Epilogue of a single element (fp32 GEMM path).
@@ -261,7 +399,7 @@ __host__ __device__ inline size_t attn_lds_bytes(int nk_cap, int dh, int esz, in
   return 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
 }
 
-template <typename T, int DH, bool COH = false>
+template <typename T, int DH, bool COH = false, bool STC = false>
 __device__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, const T* __restrict__ Vb,
                            T* __restrict__ out, const SeqDesc sd, int row_begin, int row_end, int h, int d,
                            float scale, unsigned* lds, int nk_cap) {
@@ -361,7 +499,7 @@ __device__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, co
         const float* vcol = (const float*)Vs + c;
         for (int t = 0; t < nk; ++t) a = fmaf(sc[t], vcol[(size_t)t * RS], a);
       }
-      Store<T>::template store<COH>(out + (size_t)m * d + h * DH + c, a / l);
+      Store<T>::template store<STC>(out + (size_t)m * d + h * DH + c, a / l);
     }
     __builtin_amdgcn_wave_barrier();
   }

@@ -23,12 +23,14 @@ std::vector<WEntry> weight_layout(const ad_config& c, size_t* total_bytes) {
   size_t off = 0;
   const int d = c.d_model, f = c.d_ffn;
   const int mb = c.dtype == AD_BF16 ? 2 : 4;   // matrix element bytes
-  auto mat = [&](const std::string& n, int rows, int cols) {
-    v.push_back({n, off, rows, cols, mb});
+  // bf16 matrices that feed a GEMM are stored as MFMA B-operand tiles (see ad.h); the embedding
+  // table is gathered by row and stays row-major
+  auto mat = [&](const std::string& n, int rows, int cols, bool gemm = true) {
+    v.push_back({n, off, rows, cols, mb, (gemm && c.dtype == AD_BF16) ? 1 : 0});
     off += (size_t)rows * cols * mb;
   };
   auto vec = [&](const std::string& n, int cols) {
-    v.push_back({n, off, 1, cols, 4});
+    v.push_back({n, off, 1, cols, 4, 0});
     off += (size_t)cols * 4;
   };
   auto group = [&]() { off = align_up(off, 256); };
@@ -43,8 +45,9 @@ std::vector<WEntry> weight_layout(const ad_config& c, size_t* total_bytes) {
     group(); mat(p + ".w1", f, d); group(); vec(p + ".b1", f);
     group(); mat(p + ".w2", d, f); group(); vec(p + ".b2", d);
   };
-  group(); mat("emb", c.vocab, d);
-  if (!c.tie_output) { group(); mat("out.w", c.vocab, d); }
+  group(); mat("emb", c.vocab, d, false);
+  // a tied output projection still gets its own (tiled) copy of the table in bf16 mode
+  if (!c.tie_output || c.dtype == AD_BF16) { group(); mat("out.w", c.vocab, d); }
   for (int l = 0; l < c.enc_layers; ++l) {
     std::string p = "enc." + std::to_string(l);
     attn(p + ".self"); ln(p + ".ln1"); ffn(p + ".ffn"); ln(p + ".ln2");
@@ -79,7 +82,7 @@ ModelW bind_weights(const ad_config& c, const void* blob) {
   };
   ModelW m;
   m.emb = find("emb");
-  m.out_w = c.tie_output ? m.emb : find("out.w");
+  m.out_w = (c.tie_output && c.dtype != AD_BF16) ? m.emb : find("out.w");
   for (int l = 0; l < c.enc_layers; ++l) {
     std::string p = "enc." + std::to_string(l);
     m.enc.push_back({attn(p + ".self"), ln(p + ".ln1"), ffn(p + ".ffn"), ln(p + ".ln2")});
@@ -301,6 +304,42 @@ int ad_weights_entry(const ad_config* c, int index, char* name, size_t name_cap,
   if (rows) *rows = e.rows;
   if (cols) *cols = e.cols;
   if (elem_bytes) *elem_bytes = e.elem_bytes;
+  return AD_OK;
+}
+
+int ad_weights_pack(const ad_config* c, int index, const float* src, void* blob) {
+  if (ad_config_check(c) != AD_OK) return AD_EINVAL;
+  if (!src || !blob) { ad::set_global_error("null buffer"); return AD_EINVAL; }
+  std::vector<ad::WEntry> v = ad::weight_layout(*c, nullptr);
+  if (index < 0 || index >= (int)v.size()) { ad::set_global_error("weight entry index out of range"); return AD_EINVAL; }
+  const ad::WEntry& e = v[index];
+  char* dst = (char*)blob + e.offset;
+  const size_t n = (size_t)e.rows * e.cols;
+  if (e.elem_bytes == 4) {
+    memcpy(dst, src, n * 4);
+    return AD_OK;
+  }
+  auto bf16 = [](float f) {   // round to nearest, ties to even
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  };
+  uint16_t* d16 = (uint16_t*)dst;
+  if (!e.tiled) {
+    for (size_t i = 0; i < n; ++i) d16[i] = bf16(src[i]);
+    return AD_OK;
+  }
+  // tile (s, u) = rows 16s..16s+15 x columns 32u..32u+31, 1 KB: lane l (0..63) owns 8 consecutive
+  // columns 32u + 8*(l/16) .. of row 16s + l%16
+  const int K = e.cols, ku = K / 32;
+  for (int s = 0; s < e.rows / 16; ++s)
+    for (int u = 0; u < ku; ++u)
+      for (int l = 0; l < 64; ++l) {
+        const float* sp = src + (size_t)(16 * s + l % 16) * K + 32 * u + 8 * (l / 16);
+        uint16_t* dp = d16 + (((size_t)s * ku + u) * 64 + l) * 8;
+        for (int j = 0; j < 8; ++j) dp[j] = bf16(sp[j]);
+      }
   return AD_OK;
 }
 

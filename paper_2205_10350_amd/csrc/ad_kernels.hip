@@ -41,9 +41,10 @@ void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, c
 // ------------------------------------------------------------------------------------- bf16 MFMA GEMM
 // C[M,N] = A[M,K] * W[N,K]^T.  One wave owns 16 output columns and MT*16 rows and walks the
 // whole K range with v_mfma_f32_16x16x32_bf16, 32 k-values per step in ascending order, into
-// one accumulator chain per 16x16 tile.  Weights go from memory straight into the B operand
-// (lane l holds 8 consecutive k of column l%16, k-group l/16), so for M <= MT*16 each weight
-// is read from HBM exactly once.
+// one accumulator chain per 16x16 tile.  Weights are stored as B-operand tiles (1 KB per 16
+// columns x 32 k, lane slot l = column l%16, k-group l/16) and go from memory straight into the
+// operand, one fully coalesced 1 KB fetch per step; for M <= MT*16 each weight is read from
+// HBM exactly once.
 //   operand layout   A: lane l -> row l%16, k = 8*(l/16) .. +7
 //                    B: lane l -> col l%16, k = 8*(l/16) .. +7
 //                    C: lane l -> col l%16, rows 4*(l/16) .. +3
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   const int m0 = blockIdx.y * (MT * 16);
   if (n0 >= N) return;
   const int r = lane & 15, kq = lane >> 4;
-  const bf16_t* wp = W + (size_t)(n0 + r) * K + kq * 8;
+  const bf16_t* wp = W + (size_t)n0 * K + lane * 8;   // tile (strip, step u) at + u * 512 elements
   const bf16_t* ap[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
   for (int k0 = 0; k0 < K; k0 += 32) {
-    const bf16x8 b = __builtin_bit_cast(bf16x8, *(const uint4*)(wp + k0));
+    const bf16x8 b = __builtin_bit_cast(bf16x8, *(const uint4*)(wp + k0 * 16));
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
       const bf16x8 a = __builtin_bit_cast(bf16x8, *(const uint4*)(ap[t] + k0));
@@ -184,6 +185,25 @@ void launch_attention(int dtype, const void* q, const void* K, const void* V, vo
 
 // ------------------------------------------------------------------------------------- LayerNorm
 // One wave per row; mean, then biased variance of the centred values, eps = 1e-5.
+template <typename T, int NV>
+__device__ __forceinline__ void layernorm_row4(const float* __restrict__ xr, const float* __restrict__ g,
+                                               const float* __restrict__ b, int d, int lane, float* __restrict__ yr,
+                                               T* __restrict__ yar) {
+  float4 xv[NV];
+  float mean, rstd;
+  ln_load4<false, NV>(xr, lane, xv);
+  ln_stats4<NV>(xv, d, mean, rstd);
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int c = 4 * lane + 256 * j;
+    const float4 gv = *(const float4*)(g + c), bv = *(const float4*)(b + c);
+    const float4 o = float4{ln_value(xv[j].x, mean, rstd, gv.x, bv.x), ln_value(xv[j].y, mean, rstd, gv.y, bv.y),
+                            ln_value(xv[j].z, mean, rstd, gv.z, bv.z), ln_value(xv[j].w, mean, rstd, gv.w, bv.w)};
+    *(float4*)(yr + c) = o;
+    Store<T>::store(yar + c, o.x); Store<T>::store(yar + c + 1, o.y);
+    Store<T>::store(yar + c + 2, o.z); Store<T>::store(yar + c + 3, o.w);
+  }
+}
 template <typename T>
 __global__ __launch_bounds__(256) void k_layernorm(const float* __restrict__ x, const float* __restrict__ g,
                                                    const float* __restrict__ b, int M, int d, float* __restrict__ y,
@@ -191,6 +211,15 @@ __global__ __launch_bounds__(256) void k_layernorm(const float* __restrict__ x, 
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (m >= M) return;
   const float* xr = x + (size_t)m * d;
+  float* yr = y + (size_t)m * d;
+  T* yar = ya + (size_t)m * d;
+  switch (ln_vector_width(d)) {
+    case 1: layernorm_row4<T, 1>(xr, g, b, d, lane, yr, yar); return;
+    case 2: layernorm_row4<T, 2>(xr, g, b, d, lane, yr, yar); return;
+    case 4: layernorm_row4<T, 4>(xr, g, b, d, lane, yr, yar); return;
+    case 8: layernorm_row4<T, 8>(xr, g, b, d, lane, yr, yar); return;
+    default: break;
+  }
   float mean, rstd, xv[32];
   ln_load_stats(xr, d, lane, xv, mean, rstd);
 #pragma unroll
@@ -198,8 +227,8 @@ __global__ __launch_bounds__(256) void k_layernorm(const float* __restrict__ x, 
     const int c = lane + 64 * j;
     if (c < d) {
       const float o = ln_value(xv[j], mean, rstd, g[c], b[c]);
-      y[(size_t)m * d + c] = o;
-      Store<T>::store(ya + (size_t)m * d + c, o);
+      yr[c] = o;
+      Store<T>::store(yar + c, o);
     }
   }
 }

@@ -71,6 +71,8 @@ def test_weight_layout_matches_parameter_set(dtype, tie):
     cfg = ad.make_config(dims, max_batch=1, max_src=8, max_len=8, k_max=4, dtype=dtype, special=SPECIAL, tie_output=tie)
     layout, total = ad.weights_layout(cfg)
     spec = {n: s for n, s, _ in param_spec(dims, tie_output=tie)}
+    if tie and dtype == "bf16":
+        spec["out.w"] = spec["emb"]     # a tied projection keeps its own (tiled) copy in bf16 mode
     assert {e[0] for e in layout} == set(spec)
     end = 0
     by_name = {}
@@ -88,6 +90,37 @@ def test_weight_layout_matches_parameter_set(dtype, tie):
             q, k, v = (by_name[f"{p}.{kind}{x}"] for x in "qkv")
             assert q[0] % 256 == 0 and k[0] == q[0] + q[1] and v[0] == k[0] + k[1]
     assert ad.workspace_bytes(cfg, True) > ad.workspace_bytes(cfg, False) > 0
+
+
+@pytest.mark.parametrize("tie", [False, True])
+def test_weight_packing_rounds_to_bf16_and_tiles_gemm_matrices(tie):
+    """ad_weights_pack against the layout the header states: fp32 entries and "emb" row-major,
+    every other bf16 matrix as 16 x 32 tiles of 64 lane slots x 8 values."""
+    from ad_inputs import init_weights
+    dims = model_dims("tiny")
+    w = init_weights(dims, 5, tie_output=tie)
+    for dtype in ("fp32", "bf16"):
+        cfg = ad.make_config(dims, max_batch=1, max_src=8, max_len=8, k_max=4, dtype=dtype, special=SPECIAL, tie_output=tie)
+        layout, total = ad.weights_layout(cfg)
+        blob = ad.pack_weights_host(cfg, w)
+        assert blob.nbytes == total
+        for name, off, rows, cols, eb in layout:
+            src = np.asarray(w["emb"] if (name == "out.w" and name not in w) else w[name], dtype=np.float32).reshape(rows, cols)
+            raw = blob[off:off + rows * cols * eb]
+            if eb == 4:
+                assert np.array_equal(raw.view(np.float32).reshape(rows, cols), src), name
+                continue
+            ref = (O.bf16_round(src).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)   # bf16 bit patterns
+            got = raw.view(np.uint16)
+            if name == "emb":
+                assert np.array_equal(got.reshape(rows, cols), ref), name
+                continue
+            t = got.reshape(rows // 16, cols // 32, 64, 8)
+            l = np.arange(64)
+            for s_ in range(rows // 16):
+                for u in range(cols // 32):
+                    tile = np.stack([ref[16 * s_ + (li % 16), 32 * u + 8 * (li // 16): 32 * u + 8 * (li // 16) + 8] for li in l])
+                    assert np.array_equal(t[s_, u], tile), (name, s_, u)
 
 
 def test_suffix_match_agrees_with_oracle_brute_force():
