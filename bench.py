@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bs32", action="store_true")
-    ap.add_argument("--cpu-sentences", type=int, default=256)
+    ap.add_argument("--cpu-sentences", type=int, default=64)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -104,13 +104,14 @@ def main():
     params = decoder_stream_params(dims)
     kv_bytes = dims["dec_layers"] * 2 * 2 * dims["d_model"] * (M1 + len(srcs[j]))
     fwd_bytes = 2 * params + kv_bytes
-    fused = ctx.get_option(ad.AD_OPT_FUSED_ROWS) >= M1
+    fused_rows = ctx.get_option(ad.AD_OPT_FUSED_ROWS)
+    fused = fused_rows >= M1
     # the same forward as one launch per stage, for the output-projection kernel's own figure
     ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
     ctx.encode(ad.AD_VERIFIER, [srcs[j]], max_out=[max_out[j]])
     ctx.verify([draft])
     staged_us, voc_us = ctx.time_verify_forward(50)
-    ctx.set_option(ad.AD_OPT_FUSED_ROWS, 64 if fused else 0)
+    ctx.set_option(ad.AD_OPT_FUSED_ROWS, fused_rows)
     # output projection + arg max: the [V, d] bf16 matrix once, the M x d bf16 rows once, the
     # per-row partial maxima written once
     voc_bytes = 2 * V * dims["d_model"] + 2 * M1 * dims["d_model"] + 8 * M1 * (V // 16)

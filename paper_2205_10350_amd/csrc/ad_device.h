@@ -145,6 +145,26 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ void argmax_merge(float& v, int& i, float ov, int oi) {
   if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
 }
+// (value, index) maximum over each row of 16 lanes (every lane of the row gets it), and over the
+// whole wave; lane moves as in wave_sum.  All 64 lanes active.
+template <int CTRL> __device__ __forceinline__ int dpp_move_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+__device__ __forceinline__ void argmax_row16(float& v, int& i) {
+  argmax_merge(v, i, dpp_move<0xB1>(v), dpp_move_i<0xB1>(i));
+  argmax_merge(v, i, dpp_move<0x4E>(v), dpp_move_i<0x4E>(i));
+  argmax_merge(v, i, dpp_move<0x141>(v), dpp_move_i<0x141>(i));
+  argmax_merge(v, i, dpp_move<0x140>(v), dpp_move_i<0x140>(i));
+}
+__device__ __forceinline__ void argmax_wave(float& v, int& i) {
+  argmax_row16(v, i);
+  float rv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  int ri = __builtin_amdgcn_readlane(i, 0);
+#pragma unroll
+  for (int r = 1; r < 4; ++r)
+    argmax_merge(rv, ri, __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16 * r)), __builtin_amdgcn_readlane(i, 16 * r));
+  v = rv; i = ri;
+}
 
 // x = E[tok] * sqrt(d) + PE[pos], one element
 __device__ __forceinline__ float embed_value(float e, float sqrt_d, float pe) { return fmaf(e, sqrt_d, pe); }
@@ -302,12 +322,7 @@ __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[
         float v = acc[t][i];
         int idx = n;
         if (e.logits && m < M) gstore(e.logits + (size_t)m * N + n, v);
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {
-          float ov = __shfl_xor(v, o, 64);
-          int oi = __shfl_xor(idx, o, 64);
-          argmax_merge(v, idx, ov, oi);
-        }
+        argmax_row16(v, idx);
         if (r == 0 && m < M) {
           stg<STC>(e.part_val + (size_t)m * e.n_strips + strip, v);
           stg<STC>(e.part_idx + (size_t)m * e.n_strips + strip, idx);
@@ -364,12 +379,7 @@ __device__ __forceinline__ void argmax_row(const float* __restrict__ pv, const i
 #pragma unroll
     for (int u = 0; u < 8; ++u) argmax_merge(v, idx, pvv[u], pii[u]);
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    float ov = __shfl_xor(v, o, 64);
-    int oi = __shfl_xor(idx, o, 64);
-    argmax_merge(v, idx, ov, oi);
-  }
+  argmax_wave(v, idx);
 }
 
 // ------------------------------------------------------------------------------------- attention
@@ -460,22 +470,33 @@ __device__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, co
   for (int i = row_begin + wave; i < row_end; i += waves) {
     const int m = sd.q_row0 + i;
     const int nk = sd.causal ? sd.nk_base + i + 1 : sd.nk_base;
-    const float* qs = Qs + (i - row_begin) * DH;
+    // Operands are read in batches (the whole query row once, a key row at a time, eight
+    // value rows at a time) before the arithmetic that uses them, so that a wave that has its
+    // SIMD to itself waits for LDS once per batch; the arithmetic order is the one stated above.
+    float qv[DH];
+    {
+      const float* qs = Qs + (i - row_begin) * DH;
+#pragma unroll
+      for (int c = 0; c < DH; ++c) qv[c] = qs[c];
+    }
     float mx = -INFINITY;
     for (int t = lane; t < nk; t += 64) {
       const unsigned* kr = Ks + t * RS;
+      unsigned kw[RD];
+#pragma unroll
+      for (int w = 0; w < RD; ++w) kw[w] = kr[w];
       float a = 0.f;
       if constexpr (sizeof(T) == 2) {
-#pragma unroll 8
+#pragma unroll
         for (int w = 0; w < RD; ++w) {
           float lo, hi;
-          LdsRow<bf16_t>::unpack(kr[w], lo, hi);
-          a = fmaf(qs[2 * w], lo, a);
-          a = fmaf(qs[2 * w + 1], hi, a);
+          LdsRow<bf16_t>::unpack(kw[w], lo, hi);
+          a = fmaf(qv[2 * w], lo, a);
+          a = fmaf(qv[2 * w + 1], hi, a);
         }
       } else {
-#pragma unroll 8
-        for (int w = 0; w < RD; ++w) a = fmaf(qs[w], __uint_as_float(kr[w]), a);
+#pragma unroll
+        for (int w = 0; w < RD; ++w) a = fmaf(qv[w], __uint_as_float(kw[w]), a);
       }
       a *= scale;
       sc[t] = a;
@@ -492,12 +513,18 @@ __device__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, co
     __builtin_amdgcn_wave_barrier();
     for (int c = lane; c < DH; c += 64) {
       float a = 0.f;
-      if constexpr (sizeof(T) == 2) {
-        const bf16_t* vcol = (const bf16_t*)Vs + c;
-        for (int t = 0; t < nk; ++t) a = fmaf(sc[t], bf2f(vcol[(size_t)t * RS * 2]), a);
-      } else {
-        const float* vcol = (const float*)Vs + c;
-        for (int t = 0; t < nk; ++t) a = fmaf(sc[t], vcol[(size_t)t * RS], a);
+      for (int t0 = 0; t0 < nk; t0 += 8) {
+        float pt[8], vt[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int t = t0 + j < nk ? t0 + j : nk - 1;    // (past the end: re-read the last key, not used)
+          pt[j] = sc[t];
+          if constexpr (sizeof(T) == 2) vt[j] = bf2f(((const bf16_t*)Vs)[(size_t)t * RS * 2 + c]);
+          else vt[j] = ((const float*)Vs)[(size_t)t * RS + c];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (t0 + j < nk) a = fmaf(pt[j], vt[j], a);
       }
       Store<T>::template store<STC>(out + (size_t)m * d + h * DH + c, a / l);
     }

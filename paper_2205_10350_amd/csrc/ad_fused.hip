@@ -311,15 +311,52 @@ __device__ __forceinline__ void stage_a(int a_mode, int K, const void* a_src, co
     else if (K < 256) stage_ln<4, false>(s, ln_g, ln_b, x_out, A, ld, mc, rows, K, write_x);
     else stage_ln<16, false>(s, ln_g, ln_b, x_out, A, ld, mc, rows, K, write_x);
   } else if (a_mode == A_EMBED) {
+    // one wave per row, four rows per wave in flight; a lane owns 8 consecutive columns
     const bf16_t* emb = (const bf16_t*)a_src;
-    for (int i = wave; i < rows; i += kWaves) {
-      const int tok = gload(fa.row_tok + mc + i), pos = gload(fa.row_pos + mc + i);
-      const bf16_t* e = emb + (size_t)tok * K;
-      const float* p = fa.pe + (size_t)pos * K;
-      for (int c = lane; c < K; c += 64) {
-        const float o = embed_value(bf2f(gload(e + c)), fa.sqrt_d, gload(p + c));
-        A[i * ld + c] = f2bf(o);
-        if (write_x) gstore(x_out + (size_t)(mc + i) * K + c, o);
+    for (int i0 = wave; i0 < rows; i0 += 4 * kWaves) {
+      int tok[4], pos[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * kWaves;
+        tok[u] = i < rows ? gload(fa.row_tok + mc + i) : 0;
+        pos[u] = i < rows ? gload(fa.row_pos + mc + i) : 0;
+      }
+      for (int c0 = lane * 8; c0 < K; c0 += 512) {
+        uint4 ev[4];
+        float4 p0[4], p1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u * kWaves;
+          if (i < rows) {
+            ev[u] = gload((const uint4*)(emb + (size_t)tok[u] * K + c0));
+            p0[u] = gload((const float4*)(fa.pe + (size_t)pos[u] * K + c0));
+            p1[u] = gload((const float4*)(fa.pe + (size_t)pos[u] * K + c0 + 4));
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u * kWaves;
+          if (i < rows) {
+            const unsigned w[4] = {ev[u].x, ev[u].y, ev[u].z, ev[u].w};
+            const float pe[8] = {p0[u].x, p0[u].y, p0[u].z, p0[u].w, p1[u].x, p1[u].y, p1[u].z, p1[u].w};
+            float o[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              o[2 * j] = embed_value(__uint_as_float(w[j] << 16), fa.sqrt_d, pe[2 * j]);
+              o[2 * j + 1] = embed_value(__uint_as_float(w[j] & 0xFFFF0000u), fa.sqrt_d, pe[2 * j + 1]);
+            }
+            uint4 pk;
+            pk.x = (unsigned)f2bf(o[0]) | ((unsigned)f2bf(o[1]) << 16);
+            pk.y = (unsigned)f2bf(o[2]) | ((unsigned)f2bf(o[3]) << 16);
+            pk.z = (unsigned)f2bf(o[4]) | ((unsigned)f2bf(o[5]) << 16);
+            pk.w = (unsigned)f2bf(o[6]) | ((unsigned)f2bf(o[7]) << 16);
+            *(uint4*)(A + i * ld + c0) = pk;
+            if (write_x) {
+              gstore((float4*)(x_out + (size_t)(mc + i) * K + c0), float4{o[0], o[1], o[2], o[3]});
+              gstore((float4*)(x_out + (size_t)(mc + i) * K + c0 + 4), float4{o[4], o[5], o[6], o[7]});
+            }
+          }
+        }
       }
     }
   } else {   // A_COPY: storage-type rows [*, K]; one wave per row, lanes over its 16-byte vectors
@@ -363,28 +400,42 @@ __device__ __forceinline__ void stage_a(int a_mode, int K, const void* a_src, co
   }
 }
 
-// MFMA over `k_len` k-values (a multiple of 32) for the first MT 16-row tiles: A from the LDS
-// tile (`a_lds` = this lane's row and k-group), B from memory into registers, four steps at a
-// time (`wp` = strip base + first step * 512 + lane * 8).  The path of weights that were not
-// fetched ahead.
+// MFMA over k for the first MT 16-row tiles, in groups of G steps of 32 k: first every operand
+// read of the group is issued (A from the LDS tile, B from the weight slot or from memory), then
+// its MFMAs run, so that a wave that has its SIMD to itself pays the read latency once per group.
+// `a_lds` = this lane's row and k-group in the A tile.
+//
+// B from memory into registers (`wp` = strip base + first step * 512 + lane * 8): the path of
+// weights that were not fetched ahead.
 template <int MT>
 __device__ __forceinline__ void mfma_regs(const bf16_t* __restrict__ a_lds, int ld, const bf16_t* __restrict__ wp,
                                           int k_len, f32x4 (&acc)[4]) {
+  constexpr int G = MT <= 2 ? 4 : 2;
+  const int steps = k_len >> 5;
 #pragma unroll 1
-  for (int u0 = 0; 32 * u0 < k_len; u0 += 4) {
-    uint4 b[4];
+  for (int s0 = 0; s0 < steps; s0 += 16) {      // up to 512 k: all their weights are requested at once
+    uint4 b[16];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (32 * (u0 + j) < k_len) b[j] = gload((const uint4*)(wp + 512 * (u0 + j)));
+    for (int u = 0; u < 16; ++u)
+      if (s0 + u < steps) b[u] = gload((const uint4*)(wp + 512 * (s0 + u)));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (32 * (u0 + j) < k_len) {
-        const bf16x8 bv = __builtin_bit_cast(bf16x8, b[j]);
+    for (int g0 = 0; g0 < 16; g0 += G) {
+      if (s0 + g0 < steps) {
+        uint4 a[G][MT];
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, *(const uint4*)(a_lds + t * 16 * ld + 32 * (u0 + j)));
-          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc[t], 0, 0, 0);
-        }
+        for (int g = 0; g < G; ++g)
+          if (s0 + g0 + g < steps) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t) a[g][t] = *(const uint4*)(a_lds + t * 16 * ld + 32 * (s0 + g0 + g));
+          }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+          if (s0 + g0 + g < steps) {
+            const bf16x8 bv = __builtin_bit_cast(bf16x8, b[g0 + g]);
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[g][t]), bv, acc[t], 0, 0, 0);
+          }
       }
     }
   }
@@ -400,19 +451,29 @@ __device__ __forceinline__ void mfma_k(int mt, const bf16_t* __restrict__ a_lds,
   }
 }
 
-// The same with B read back from the wave's weight slot (`w_lds` = slot + first step * 1 KB +
-// lane * 16), `steps` steps of 32 k.
+// B read back from the wave's weight slot (`w_lds` = slot + first step * 1 KB + lane * 16).
 template <int MT>
 __device__ __forceinline__ void mfma_lds(const bf16_t* __restrict__ a_lds, int ld, const char* __restrict__ w_lds,
                                          int steps, f32x4 (&acc)[4]) {
-#pragma unroll 4
-  for (int u = 0; u < steps; ++u) {
-    const bf16x8 bv = __builtin_bit_cast(bf16x8, *(const uint4*)(w_lds + 1024 * u));
+  constexpr int G = MT <= 2 ? 4 : 2;
+#pragma unroll 1
+  for (int u0 = 0; u0 < steps; u0 += G) {
+    uint4 b[G], a[G][MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-      const bf16x8 av = __builtin_bit_cast(bf16x8, *(const uint4*)(a_lds + t * 16 * ld + 32 * u));
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, acc[t], 0, 0, 0);
-    }
+    for (int g = 0; g < G; ++g)
+      if (u0 + g < steps) {
+        b[g] = *(const uint4*)(w_lds + 1024 * (u0 + g));
+#pragma unroll
+        for (int t = 0; t < MT; ++t) a[g][t] = *(const uint4*)(a_lds + t * 16 * ld + 32 * (u0 + g));
+      }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (u0 + g < steps) {
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, b[g]);
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[g][t]), bv, acc[t], 0, 0, 0);
+      }
   }
 }
 __device__ __forceinline__ void mfma_k_lds(int mt, const bf16_t* __restrict__ a_lds, int ld, const char* __restrict__ w_lds,
@@ -452,20 +513,23 @@ __device__ __forceinline__ bool gemm_stage(const Stage& st, const Stage* prog, c
       const int rows = min(MC, m_hi - mc);
       const int mt = (rows + 15) >> 4;
       EpiRegs<4> eg;
+      eg.bias = 0.f;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) eg.aux[q] = 0u;   // (destination row 0 / residual 0 if the preload is skipped)
       f32x4 acc[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
       for (int kp = 0; kp < K; kp += KP) {
         if (!first) __syncthreads();            // the previous tile is no longer read
         if (stp && threadIdx.x == 0 && first) fa.stamps[576 + 4 * si + 0] = wall_clock64();
-        stage_a(st.a_mode, K, st.a_src, st.ln_g, st.ln_b, st.x_out, fa, A, mc, rows, kp, KP, write_x);
+        if (!(fa.skip & 1)) stage_a(st.a_mode, K, st.a_src, st.ln_g, st.ln_b, st.x_out, fa, A, mc, rows, kp, KP, write_x);
         if (stp && threadIdx.x == 0 && first) fa.stamps[576 + 4 * si + 1] = wall_clock64();
         // the tile's loads, the x rows' stores and the weight slot's fetches are done
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (stp && threadIdx.x == 0 && first) fa.stamps[576 + 4 * si + 2] = wall_clock64();
         __syncthreads();
         if (stp && threadIdx.x == 0) stp[3] = wall_clock64();
-        if (first && st.pf_stage != -1 && wave >= ws.n_active) {
+        if (first && st.pf_stage != -1 && wave >= ws.n_active && !(fa.skip & 64)) {
           // Waves without a strip in this stage start the weights of a later stage streaming into
           // the XCD's L2 (they have no loads of their own left that could queue up behind these).
           if (st.pf_stage >= 0) {
@@ -478,17 +542,17 @@ __device__ __forceinline__ bool gemm_stage(const Stage& st, const Stage* prog, c
         }
         if (active) {
           // the epilogue's operands: in flight under the last pass's MFMAs
-          if (kp + KP >= K) epi_preload<4, true>(epi, mt, mc, n0, m_hi, N, lane, eg);
+          if (kp + KP >= K && !(fa.skip & 4)) epi_preload<4, true>(epi, mt, mc, n0, m_hi, N, lane, eg);
           const bf16_t* a_lane = A + r * ld + kq * 8;
           // k in [kp, kp + KP): first what sits in the weight slot, then the rest from memory
           const int lds_end = min(max(in_lds, kp), kp + KP);
-          if (lds_end > kp) mfma_k_lds(mt, a_lane, ld, my_slot + (size_t)(kp >> 5) * 1024, (lds_end - kp) >> 5, acc);
-          if (lds_end < kp + KP) mfma_k(mt, a_lane + (lds_end - kp), ld, wp + (size_t)lds_end * 16, kp + KP - lds_end, acc);
+          if (lds_end > kp && !(fa.skip & 2)) mfma_k_lds(mt, a_lane, ld, my_slot + (size_t)(kp >> 5) * 1024, (lds_end - kp) >> 5, acc);
+          if (lds_end < kp + KP && !(fa.skip & 2)) mfma_k(mt, a_lane + (lds_end - kp), ld, wp + (size_t)lds_end * 16, kp + KP - lds_end, acc);
         }
         first = false;
       }
       if (stp && threadIdx.x == 0) stp[4] = wall_clock64();
-      if (active) epi_apply<bf16_t, 4, false>(epi, acc, eg, mt, mc, n0, m_hi, N, lane);
+      if (active && !(fa.skip & 8)) epi_apply<bf16_t, 4, false>(epi, acc, eg, mt, mc, n0, m_hi, N, lane);
       if (stp && threadIdx.x == 0) stp[5] = wall_clock64();
     }
   }
@@ -582,6 +646,11 @@ __device__ __forceinline__ void vocab_prefetch(const FusedArgs& fa, char* wbase,
   w_prefetch(base, depth >> 5, wbase + wave * (kFusedWSlotBytes / kWaves));
   const int lines = (fa.d * 32) >> 7;
   for (int j = ((depth * 32) >> 7) + lane; j < lines; j += 64) l2_touch((const char*)base + (j << 7), junk);
+  // the strips of later rounds come from memory during the stage: touch them whole
+  for (int s2 = strip + gridDim.x * kWaves; s2 < (fa.V >> 4); s2 += gridDim.x * kWaves) {
+    const char* b2 = (const char*)fa.out_w + (size_t)(s2 << 4) * fa.d * 2;
+    for (int j = lane; j < lines; j += 64) l2_touch(b2 + (j << 7), junk);
+  }
 }
 __device__ __forceinline__ void vocab_tile(const FusedArgs& fa, const bf16_t* A, const char* wbase, float* red_val,
                                            int* red_idx, int mc, int mt, int MC) {
@@ -615,12 +684,7 @@ __device__ __forceinline__ void vocab_tile(const FusedArgs& fa, const bf16_t* A,
         float v = acc[t][i];
         int idx = n0 + r;
         if (fa.logits && m < M) gstore(fa.logits + (size_t)m * N + n0 + r, v);
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {
-          const float ov = __shfl_xor(v, o, 64);
-          const int oi = __shfl_xor(idx, o, 64);
-          argmax_merge(v, idx, ov, oi);
-        }
+        argmax_row16(v, idx);
         if (r == 0) {
           float cv = red_val[wave * 64 + ml];
           int ci = red_idx[wave * 64 + ml];
@@ -670,37 +734,77 @@ __device__ __forceinline__ void finish_stage(const FusedArgs& fa, int* o_lds) {
   for (int b = blockIdx.x; b < fa.B; b += G) {
     const int kb = gload(fa.k + b), r0 = gload(fa.row_start + b);
     __syncthreads();
-    for (int i = wave; i < kb; i += kWaves) {
-      float v;
-      int idx;
-      const size_t o = (size_t)(r0 + i) * fa.part_stride;
-      argmax_row<true>(fa.part_val + o, fa.part_idx + o, n_part, lane, v, idx);
-      if (lane == 0) {
-        stg<true>(fa.o_hat + r0 + i, idx);
-        stg<true>(fa.o_val + r0 + i, v);
-        o_lds[i] = idx;
+    // second arg-max stage: one wave per row, four rows per wave in flight (up to 256 partials
+    // per row are held four per lane; more go through the general routine)
+    for (int i0 = wave; i0 < kb; i0 += 4 * kWaves) {
+      float pv[4][4];
+      int pi[4][4];
+      if (n_part <= 256) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + u * kWaves;
+          const size_t o = (size_t)(r0 + i) * fa.part_stride;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int t = lane + 64 * j;
+            const bool live = i < kb && t < n_part;
+            pv[u][j] = live ? ldg<true>(fa.part_val + o + t) : -INFINITY;
+            pi[u][j] = live ? ldg<true>(fa.part_idx + o + t) : 0x7fffffff;
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u * kWaves;
+        if (i >= kb) break;
+        float v;
+        int idx;
+        if (n_part <= 256) {
+          v = pv[u][0]; idx = pi[u][0];
+#pragma unroll
+          for (int j = 1; j < 4; ++j) argmax_merge(v, idx, pv[u][j], pi[u][j]);
+          argmax_wave(v, idx);
+        } else {
+          const size_t o = (size_t)(r0 + i) * fa.part_stride;
+          argmax_row<true>(fa.part_val + o, fa.part_idx + o, n_part, lane, v, idx);
+        }
+        if (lane == 0) {
+          stg<true>(fa.o_hat + r0 + i, idx);
+          stg<true>(fa.o_val + r0 + i, v);
+          o_lds[i] = idx;
+        }
       }
     }
     __syncthreads();
-    if (threadIdx.x != 0 || !fa.do_accept) continue;
-    if (kb == 0) { stg<true>(fa.result + 2 * b, 0); stg<true>(fa.result + 2 * b + 1, 0); continue; }
-    int c = kb;
-    for (int i = 0; i < kb; ++i)
-      if (gload(fa.draft + b * fa.k_max + i) != o_lds[i]) { c = i + 1; break; }
-    const int L = gload(fa.len + b), lim = gload(fa.max_out + b);
-    int n = 0, last = 0;
-    for (int i = 0; i < c; ++i) {
-      if (L + n >= lim) break;
-      last = o_lds[i];
-      stg<true>(fa.out + b * fa.max_len + L + n, last);
-      ++n;
-      if (last == fa.eos) break;
+    if (wave != 0 || !fa.do_accept) continue;
+    // wave 0: c = first position whose draft token differs from the arg max (else k); the block
+    // o_hat_1..o_hat_c is cut after the first [EOS] and at the output limit
+    if (kb == 0) {
+      if (lane == 0) { stg<true>(fa.result + 2 * b, 0); stg<true>(fa.result + 2 * b + 1, 0); }
+      continue;
     }
-    stg<true>(fa.len + b, L + n);
-    if (n > 0) stg<true>(fa.pending + b, last);
-    stg<true>(fa.finished + b, (int)((n > 0 && last == fa.eos) || (L + n >= lim)));
-    stg<true>(fa.result + 2 * b, n);
-    stg<true>(fa.result + 2 * b + 1, last);
+    const int L = gload(fa.len + b), lim = gload(fa.max_out + b);
+    int c = kb, e = kb;                     // first mismatch (1-based length), first [EOS] position (0-based)
+    for (int i0 = 0; i0 < kb && c == kb && e == kb; i0 += 64) {
+      const int i = i0 + lane;
+      const int oh = i < kb ? o_lds[i] : 0;
+      const bool mis = i < kb && gload(fa.draft + b * fa.k_max + i) != oh;
+      const bool eos = i < kb && oh == fa.eos;
+      const unsigned long long mm = __ballot(mis), me = __ballot(eos);
+      if (mm) c = i0 + __builtin_ctzll(mm) + 1;
+      if (me) e = i0 + __builtin_ctzll(me);
+    }
+    int n = min(c, max(lim - L, 0));
+    if (e < n) n = e + 1;                   // keep the [EOS] itself
+    for (int i = lane; i < n; i += 64) stg<true>(fa.out + b * fa.max_len + L + i, o_lds[i]);
+    if (lane == 0) {
+      const int last = n > 0 ? o_lds[n - 1] : 0;
+      stg<true>(fa.len + b, L + n);
+      if (n > 0) stg<true>(fa.pending + b, last);
+      stg<true>(fa.finished + b, (int)((n > 0 && last == fa.eos) || (L + n >= lim)));
+      stg<true>(fa.result + 2 * b, n);
+      stg<true>(fa.result + 2 * b + 1, last);
+    }
   }
 }
 
@@ -751,7 +855,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_fused_forward(FusedArgs fa) {
         if (stp && threadIdx.x == 0) stp[0] = wall_clock64();
         barrier_stores_done(wave_stored);
         if (stp && threadIdx.x == 0) stp[1] = wall_clock64();
-        if (st.type == ST_GEMM) gemm_prefetch(st, rank, T, wbase);
+        if (st.type == ST_GEMM && !(fa.skip & 32)) gemm_prefetch(st, rank, T, wbase);
         if (stp) {   // diagnostic: how long this wave's weight fetch takes when nothing else is in flight
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           if (threadIdx.x == 0) stp[6] = wall_clock64();
@@ -763,7 +867,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_fused_forward(FusedArgs fa) {
       if (fa.stamps && rank == 0 && threadIdx.x == 0) { fa.stamps[si] = wall_clock64(); }
       wave_stored = true;
       if (st.type == ST_GEMM) wave_stored = gemm_stage(st, prog, fa, m_lo, m_hi, rank, T, A, wbase, junk_lds, stp, si);
-      else if (st.type == ST_ATTN) attn_stage(st, fa, s_lo, s_hi, rank, T, (unsigned*)fused_lds);
+      else if (st.type == ST_ATTN) { if (!(fa.skip & 16)) attn_stage(st, fa, s_lo, s_hi, rank, T, (unsigned*)fused_lds); }
       else ln_stage(st, m_lo, m_hi, rank, T);
     }
     __syncthreads();   // the last stage no longer reads the weight slots

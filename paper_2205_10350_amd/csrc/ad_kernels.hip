@@ -107,12 +107,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
     float v = acc;
     int idx = n;
     if (e.logits && m < M && n < N) e.logits[(size_t)m * N + n] = v;
-#pragma unroll
-    for (int o = 8; o > 0; o >>= 1) {
-      float ov = __shfl_xor(v, o, 64);
-      int oi = __shfl_xor(idx, o, 64);
-      argmax_merge(v, idx, ov, oi);
-    }
+    argmax_row16(v, idx);
     if (tx == 0 && m < M) {
       e.part_val[(size_t)m * e.n_strips + blockIdx.x] = v;
       e.part_idx[(size_t)m * e.n_strips + blockIdx.x] = idx;
