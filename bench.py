@@ -42,7 +42,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bs32", action="store_true")
-    ap.add_argument("--cpu-sentences", type=int, default=64)
+    ap.add_argument("--cpu-sentences", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -160,14 +160,21 @@ def main():
         drafts = [(list(g) + [ad.AD_NEVER])[:int(m)] for g, m in zip(gd2[0], mo)]
         ctx.verify(drafts)
         M32 = sum(len(d) for d in drafts)
-        fwd32_us, voc32_us = ctx.time_verify_forward(20)
+        fwd32_us, _ = ctx.time_verify_forward(20)
+        fused32 = ctx.get_option(ad.AD_OPT_FUSED_ROWS) >= M32
+        # the same forward as one launch per stage (the output-projection kernel can be timed alone there)
+        ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
+        ctx.encode(ad.AD_VERIFIER, ss, max_out=mo)
+        ctx.verify(drafts)
+        staged32_us, voc32_us = ctx.time_verify_forward(20)
+        ctx.set_option(ad.AD_OPT_FUSED_ROWS, fused_rows)
         flops = 2.0 * M32 * params
         bs32 = {"tokens_per_s": toks2 / dt2, "greedy_tokens_per_s": sum(len(x) for o in g2 for x in o) / t_g2,
                 "iterations": its2, "rows_verified": rows2,
-                "verify_rows": M32, "verify_us": fwd32_us, "verify_gflop": flops / 1e9,
+                "verify_rows": M32, "verify_us": fwd32_us, "single_launch": bool(fused32), "verify_gflop": flops / 1e9,
                 "mfma_frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK,
-                "vocab_kernel_us": voc32_us,
-                "vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
+                "staged_launches_us": staged32_us, "staged_vocab_kernel_us": voc32_us,
+                "staged_vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
     ctx.close()
 
     # ---------------- CPU oracle on this machine's host cores (bounded sample) ----------------------

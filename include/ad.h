@@ -190,9 +190,9 @@ int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vo
 
 /* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
  * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; 0 = one
- * launch per stage always; at most max_batch * k_max).  ad_create picks max_batch * k_max when
- * the device and the model shape support it, else 0; setting a positive value on a context
- * where it is unavailable gives AD_ESTATE. */
+ * launch per stage always; at most max_batch * k_max).  ad_create picks min(128, max_batch * k_max)
+ * when the device and the model shape support the persistent kernel, else 0; setting a positive
+ * value on a context where it is unavailable gives AD_ESTATE. */
 enum { AD_OPT_FUSED_ROWS = 0 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);

@@ -345,7 +345,9 @@ static void setup_fused(ad_ctx* c) {
   c->fused_lds = lds;
   c->dev_base = 0;
   for (int t = 0; t < kMaxTeams; ++t) c->team_base[t] = 0;
-  c->fused_rows = p.mv_cap;
+  // Large calls are throughput-bound and go one launch per stage (big MFMA tiles); the persistent
+  // kernel is for the latency-bound small ones.
+  c->fused_rows = std::min(p.mv_cap, 128);
 }
 
 // One launch: the whole verify forward for the rows the tables describe.  k[b] = rows of

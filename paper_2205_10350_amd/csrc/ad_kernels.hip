@@ -67,16 +67,181 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   f32x4 acc[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-  for (int k0 = 0; k0 < K; k0 += 32) {
-    const bf16x8 b = __builtin_bit_cast(bf16x8, *(const uint4*)(wp + k0 * 16));
+  // 512 k at a time: all sixteen 1 KB weight fetches of the strip are requested before the first
+  // is used (a weight-streaming kernel lives on the bytes it keeps in flight)
+  for (int k0 = 0; k0 < K; k0 += 512) {
+    uint4 b[16];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *(const uint4*)(ap[t] + k0));
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[t], 0, 0, 0);
+    for (int u = 0; u < 16; ++u)
+      if (k0 + 32 * u < K) b[u] = *(const uint4*)(wp + (k0 + 32 * u) * 16);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if (k0 + 32 * u < K) {
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, b[u]);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, *(const uint4*)(ap[t] + k0 + 32 * u));
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bv, acc[t], 0, 0, 0);
+        }
+      }
     }
   }
   strip_epilogue<bf16_t, MT>(e, acc, MT, m0, n0, M, N, lane);
+}
+
+// ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows
+// The same product for M >= 128 rows, where the weight-streaming kernel above would re-read
+// every operand from the L2: 128 x 128 output tile per workgroup, four waves of 64 x 64
+// (4 x 4 MFMA tiles each), k walked 32 at a time through a three-stage LDS ring.  Both operands
+// reach LDS by loads that write it directly, one 1 KB operand fragment per instruction, already
+// in the order the MFMA reads back (A: lane l = row l%16, k-group l/16 of a 16-row tile; B: the
+// stored weight tile as is).  Per step a wave issues four such loads (two A tiles, two B strips)
+// and reads eight fragments for sixteen MFMAs.  Each output element still sums k ascending 32
+// at a time into one accumulator: bit-identical to the kernel above.
+// The ring's stages are separate arrays and the k loop is unrolled by the ring size, so that the
+// compiler can tell a stage being filled from the stage being read (it would otherwise wait for
+// every outstanding fill before each LDS read).
+template <int STEP_MOD>
+__device__ __forceinline__ void tiled_issue(char* st, const bf16_t* const (&ga)[2], const bf16_t* const (&gb)[2], int step,
+                                            int wave) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    __builtin_amdgcn_global_load_lds((const AD_GLOBAL void*)(ga[j] + step * 32),
+                                     (__attribute__((address_space(3))) void*)(st + (2 * wave + j) * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const AD_GLOBAL void*)(gb[j] + step * 512),
+                                     (__attribute__((address_space(3))) void*)(st + 8192 + (2 * wave + j) * 1024), 16, 0, 0);
+  }
+}
+__device__ __forceinline__ void tiled_compute(const char* st, int wm, int wn, int lane, f32x4 (&acc)[4][4]) {
+  uint4 af[4], bf[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) af[t] = *(const uint4*)(st + (wm * 4 + t) * 1024 + lane * 16);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) bf[j] = *(const uint4*)(st + 8192 + (wn * 4 + j) * 1024 + lane * 16);
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, bf[j]),
+                                                         acc[j][t], 0, 0, 0);
+}
+__global__ __launch_bounds__(256, 2) void k_gemm_bf16_tiled(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                            int M, int N, int K, Epi e) {
+  __shared__ __attribute__((aligned(1024))) char ring0[16 * 1024];   // [A | B][fragment][1 KB]
+  __shared__ __attribute__((aligned(1024))) char ring1[16 * 1024];
+  __shared__ __attribute__((aligned(1024))) char ring2[16 * 1024];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int n_strips = N >> 4;
+  const int strip0 = blockIdx.x * 8, m0 = blockIdx.y * 128;
+  const int nk = K >> 5;
+  // this wave's share of the loads of a step: A tiles 2*wave, 2*wave+1; B strips 2*wave, 2*wave+1
+  // (rows past M and strips past N are clamped to valid ones: never stored, but every wave
+  // issues exactly four loads per step, which the waits below count on)
+  const bf16_t* ga[2];
+  const bf16_t* gb[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = min(m0 + (2 * wave + j) * 16 + (lane & 15), M - 1);
+    ga[j] = A + (size_t)row * K + (lane >> 4) * 8;
+    const int strip = min(strip0 + 2 * wave + j, n_strips - 1);
+    gb[j] = W + (size_t)(strip << 4) * K + lane * 8;
+  }
+  f32x4 acc[4][4];   // [strip j][row tile t]
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  tiled_issue<0>(ring0, ga, gb, 0, wave);
+  if (nk > 1) tiled_issue<1>(ring1, ga, gb, 1, wave);
+  // Step k: its fragments have landed (this wave's; the barrier covers the others') while step
+  // k+1's four loads may still be in flight; the stage of step k+2 was read in step k-1, which
+  // every wave has finished once it is past the barrier.
+#define AD_TILED_STEP(KK, CUR, NXT2)                                                  \
+  if ((KK) < nk) {                                                                    \
+    if ((KK) + 1 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");               \
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                             \
+    __builtin_amdgcn_s_barrier();                                                     \
+    if ((KK) + 2 < nk) tiled_issue<0>(NXT2, ga, gb, (KK) + 2, wave);                  \
+    tiled_compute(CUR, wm, wn, lane, acc);                                            \
+  }
+  for (int k = 0; k < nk; k += 3) {
+    AD_TILED_STEP(k, ring0, ring2)
+    AD_TILED_STEP(k + 1, ring1, ring0)
+    AD_TILED_STEP(k + 2, ring2, ring1)
+  }
+#undef AD_TILED_STEP
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int strip = strip0 + wn * 4 + j;
+    if (strip < n_strips) strip_epilogue<bf16_t, 4>(e, acc[j], 4, m0 + wm * 64, strip << 4, M, N, lane);
+  }
+}
+
+// ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows, K = 512 or 1024
+// A stays put, weights stream: a workgroup stages 64 rows of A (all K) in LDS once and then walks
+// a run of 16-column strips, each wave two strips at a time.  A strip pair's weights for 512 k
+// (32 fully coalesced 1 KB fetches) are requested at once, straight into the B operand registers;
+// per 32-k step the wave reads four A fragments from LDS and issues eight MFMAs (each fragment
+// serves both strips, which halves the LDS traffic per MFMA).  Accumulation order per output
+// element as in every other kernel: k ascending, 32 at a time, one accumulator.
+constexpr int kAstatRows = 64;
+__global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                         int M, int N, int K, Epi e, int strips_per_wg) {
+  extern __shared__ uint4 astat_lds[];
+  bf16_t* At = (bf16_t*)astat_lds;          // [64][K + 8]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int ld = K + 8, n_strips = N >> 4;
+  const int m0 = blockIdx.y * kAstatRows;
+  // stage the rows (past M: the last valid row, computed and never stored)
+  {
+    const int vpr = K >> 3;
+    for (int i = wave; i < kAstatRows; i += 4) {
+      const bf16_t* src = A + (size_t)min(m0 + i, M - 1) * K;
+      for (int v = lane; v < vpr; v += 64) *(uint4*)(At + i * ld + v * 8) = *(const uint4*)(src + v * 8);
+    }
+  }
+  __syncthreads();
+  const bf16_t* a_lane = At + r * ld + kq * 8;
+  const int s_begin = blockIdx.x * strips_per_wg, s_end = min(n_strips, s_begin + strips_per_wg);
+  for (int s0 = s_begin + 2 * wave; s0 < s_end; s0 += 8) {
+    const bool two = s0 + 1 < s_end;
+    const bf16_t* w0 = W + (size_t)(s0 << 4) * K + lane * 8;
+    const bf16_t* w1 = W + (size_t)((two ? s0 + 1 : s0) << 4) * K + lane * 8;
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < K; k0 += 512) {
+      uint4 b0[16], b1[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        b0[u] = *(const uint4*)(w0 + (k0 + 32 * u) * 16);
+        b1[u] = *(const uint4*)(w1 + (k0 + 32 * u) * 16);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep all 32 fetches ahead of the first MFMA
+      uint4 af[2][4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) af[0][t] = *(const uint4*)(a_lane + t * 16 * ld + k0);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        // the next step's A fragments leave LDS while this step's MFMAs run
+        if (u + 1 < 16) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) af[(u + 1) & 1][t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * (u + 1));
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u & 1][t]), __builtin_bit_cast(bf16x8, b0[u]), acc[0][t], 0, 0, 0);
+          acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u & 1][t]), __builtin_bit_cast(bf16x8, b1[u]), acc[1][t], 0, 0, 0);
+        }
+      }
+    }
+    strip_epilogue<bf16_t, 4>(e, acc[0], 4, m0, s0 << 4, M, N, lane);
+    if (two) strip_epilogue<bf16_t, 4>(e, acc[1], 4, m0, (s0 + 1) << 4, M, N, lane);
+  }
 }
 
 // ------------------------------------------------------------------------------------- fp32 GEMM
@@ -121,6 +286,26 @@ void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, c
   if (M <= 0) return;
   if (dtype == AD_BF16) {
     const int nb = (N / 16 + 3) / 4;
+    const int tiles_x = (N / 16 + 7) / 8, tiles_y = (M + 127) / 128;
+    if (M >= 128 && K <= 1024 && K % 512 == 0) {
+      // enough workgroups to fill the chip a few times over, each with a long run of strips
+      const int chunks = (M + kAstatRows - 1) / kAstatRows, n_strips = N / 16;
+      int per_wg = 64;
+      while (per_wg > 8 && chunks * ((n_strips + per_wg - 1) / per_wg) < 512) per_wg >>= 1;
+      const size_t lds = (size_t)kAstatRows * (K + 8) * 2;
+      static size_t set_for = 0;
+      if (lds > set_for) {
+        (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        set_for = lds;
+      }
+      k_gemm_bf16_astat<<<dim3((n_strips + per_wg - 1) / per_wg, chunks), 256, lds, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K,
+                                                                                       e, per_wg);
+      return;
+    }
+    if (M >= 128 && tiles_x * tiles_y >= 96) {
+      k_gemm_bf16_tiled<<<dim3(tiles_x, tiles_y), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);
+      return;
+    }
     if (M <= 16)
       k_gemm_bf16<1><<<dim3(nb, 1), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);
     else if (M <= 32)
