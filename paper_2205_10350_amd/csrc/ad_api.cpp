@@ -218,16 +218,16 @@ static void embed_rows(ad_ctx* c, const ModelW& w, int M) {
 }
 
 // Output projection fused with the per-row arg max; `A` holds Mv rows.
-static void vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv) {
+static int vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv) {
   const Plan& p = c->plan;
   Epi e{};
   e.mode = EPI_ARGMAX; e.part_val = c->at<float>(p.part_val); e.part_idx = c->at<int>(p.part_idx);
   e.n_strips = p.n_strips; e.logits = c->cfg.debug_logits ? c->at<float>(p.logits) : nullptr;
-  launch_gemm(c->cfg.dtype, A, w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream);
+  return launch_gemm(c->cfg.dtype, A, w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream);
 }
-static void vocab_finish(ad_ctx* c, int Mv) {
+static void vocab_finish(ad_ctx* c, int Mv, int n_part) {
   const Plan& p = c->plan;
-  launch_argmax_finish(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, c->at<int>(p.o_hat),
+  launch_argmax_finish(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, n_part, c->at<int>(p.o_hat),
                        c->at<float>(p.o_val), c->stream);
 }
 
@@ -412,9 +412,9 @@ static void verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent
     ffn_block(c, L.ffn, L.ln3, M);
   }
   if (ev_a) (void)hipEventRecord(ev_a, c->stream);
-  vocab_argmax(c, w, c->at<void>(p.xa), M);
+  const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), M);
   if (ev_b) (void)hipEventRecord(ev_b, c->stream);
-  vocab_finish(c, M);
+  vocab_finish(c, M, n_part);
 }
 
 static int check_batch(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B) {
@@ -733,8 +733,7 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   }
   const int Mv = live * k;
   launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
-  vocab_argmax(c, w, c->at<void>(p.xg), Mv);
-  vocab_finish(c, Mv);
+  vocab_finish(c, Mv, vocab_argmax(c, w, c->at<void>(p.xg), Mv));
   launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
   int32_t* h = c->pin;
   HIP_TRY(c, hipMemcpyAsync(h, c->at<int>(p.draft_out), (size_t)B * km * 4, hipMemcpyDeviceToHost, c->stream));

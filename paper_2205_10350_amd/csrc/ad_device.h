@@ -250,17 +250,27 @@ __device__ __forceinline__ void epi_preload(const Epi& e, int mt_used, int m0, i
   g.bias = e.bias ? gload(e.bias + n) : 0.f;
   const int mode = e.mode;
   const bool want_dst = (mode == EPI_QKV && n0 >= e.d) || mode == EPI_KV, want_res = mode == EPI_RESID;
+  // all MT tiles inside the matrix: no per-row tests (the common case away from the last rows)
+  const bool full = mt_used == MT && m0 + MT * 16 <= M;
 #pragma unroll
-  for (int t = 0; t < MT; ++t)
+  for (int x = 0; x < MT * 4; ++x) g.aux[x] = 0u;
+  if (want_dst) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int m = m0 + t * 16 + kq * 4 + i;
-      const bool live = t < mt_used && m < M;
-      unsigned a = 0u;
-      if (want_dst && live) a = (unsigned)gload(e.row_dst + m);
-      if (want_res && live) a = __float_as_uint(ldg<LDC>(e.resid + (size_t)m * N + n));
-      g.aux[t * 4 + i] = a;
-    }
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + t * 16 + kq * 4 + i;
+        if (full || (t < mt_used && m < M)) g.aux[t * 4 + i] = (unsigned)gload(e.row_dst + m);
+      }
+  } else if (want_res) {
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + t * 16 + kq * 4 + i;
+        if (full || (t < mt_used && m < M)) g.aux[t * 4 + i] = __float_as_uint(ldg<LDC>(e.resid + (size_t)m * N + n));
+      }
+  }
 }
 // value = acc + bias, then the mode's operation.  A strip of 16 columns lies inside one of the
 // q / k / v column ranges (d is a multiple of 16), so the destination is uniform over the wave.
@@ -270,6 +280,20 @@ __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], 
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
   const int mode = e.mode, d = e.d;
   const bool has_bias = e.bias != nullptr;
+  const bool full = mt_used == MT && m0 + MT * 16 <= M;
+  if (mode == EPI_RESID) {
+    float* out = (float*)e.out0 + n;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + t * 16 + kq * 4 + i;
+        float v = acc[t][i];
+        if (has_bias) v += g.bias;
+        if (full || (t < mt_used && m < M)) stg<STC>(out + (size_t)m * N, v + __uint_as_float(g.aux[t * 4 + i]));
+      }
+    return;
+  }
   // destination of (row m, this lane's column) for the row-indexed modes
   T* base = nullptr;
   int ld = N, col = n;
@@ -286,21 +310,17 @@ __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], 
   } else if (mode == EPI_STORE || mode == EPI_RELU) {
     base = (T*)e.out0;
   }
+  base += col;
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int m = m0 + t * 16 + kq * 4 + i;
-      if (t >= mt_used || m >= M) continue;
       float v = acc[t][i];
       if (has_bias) v += g.bias;
-      if (mode == EPI_RESID) {
-        stg<STC>((float*)e.out0 + (size_t)m * N + n, v + __uint_as_float(g.aux[t * 4 + i]));
-      } else {
-        if (mode == EPI_RELU) v = fmaxf(v, 0.f);
-        const size_t row = by_dst ? (size_t)g.aux[t * 4 + i] : (size_t)m;
-        Store<T>::template store<STC>(base + row * ld + col, v);
-      }
+      if (mode == EPI_RELU) v = fmaxf(v, 0.f);
+      const size_t row = by_dst ? (size_t)g.aux[t * 4 + i] : (size_t)m;
+      if (full || (t < mt_used && m < M)) Store<T>::template store<STC>(base + row * ld, v);
     }
 }
 

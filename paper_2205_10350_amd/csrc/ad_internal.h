@@ -132,14 +132,16 @@ hipError_t launch_fused_forward(const FusedArgs& fa, int grid, size_t lds_bytes,
 void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, const int* pos, int M,
                   int d, float sqrt_d, float* x, void* xa, hipStream_t s);
 // C[M,N] = A[M,K] . W[N,K]^T with epilogue.  A, W in the storage type.
-void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s);
+// returns the number of arg-max partials per row an EPI_ARGMAX launch wrote (row stride e.n_strips)
+int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s);
 // one attention problem per descriptor (n_seq of them, at most max_rows query rows each)
 void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
                       int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s);
 // y = LayerNorm(x) * g + b -> y (fp32) and ya (storage type)
 void launch_layernorm(int dtype, const float* x, const float* g, const float* b, int M, int d, float* y,
                       void* ya, hipStream_t s);
-void launch_argmax_finish(const float* part_val, const int* part_idx, int M, int n_strips, int* o_hat,
+// second stage of the arg max: n_part partials per row, rows `stride` entries apart
+void launch_argmax_finish(const float* part_val, const int* part_idx, int M, int stride, int n_part, int* o_hat,
                           float* o_val, hipStream_t s);
 void launch_gather_rows(int dtype, const void* src, const int* rows, int n, int d, void* dst, hipStream_t s);
 

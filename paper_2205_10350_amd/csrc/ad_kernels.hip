@@ -178,70 +178,236 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_tiled(const bf16_t* __rest
   }
 }
 
-// ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows, K = 512 or 1024
-// A stays put, weights stream: a workgroup stages 64 rows of A (all K) in LDS once and then walks
-// a run of 16-column strips, each wave two strips at a time.  A strip pair's weights for 512 k
-// (32 fully coalesced 1 KB fetches) are requested at once, straight into the B operand registers;
-// per 32-k step the wave reads four A fragments from LDS and issues eight MFMAs (each fragment
-// serves both strips, which halves the LDS traffic per MFMA).  Accumulation order per output
-// element as in every other kernel: k ascending, 32 at a time, one accumulator.
-constexpr int kAstatRows = 64;
+// ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows, K a multiple of 512
+// A stays put, weights stream: a workgroup stages MT*16 rows of A (all K) in LDS once and then
+// walks a run of 16-column strips, each wave two strips at a time.  Work unit = (strip pair,
+// 512-k slice): 32 weight fragments (fully coalesced 1 KB fetches straight into B operand
+// registers).  The registers are refilled on a rolling basis: as soon as step u's MFMAs are
+// issued, step u of the NEXT unit is requested into the same registers, so every fetch has a
+// whole unit's time before it is needed and one register set suffices; two workgroups share a CU
+// and cover each other's gaps.  Per 32-k step the wave reads MT A fragments from LDS and issues
+// 2*MT MFMAs (each fragment serves both strips, which halves the LDS traffic per MFMA).
+// Accumulation order per output element as in every other kernel: k ascending, 32 at a time,
+// one accumulator.
+// EPI_ARGMAX: one (value, column) partial per (row, workgroup) instead of one per strip.
+template <int MT, bool AMAX>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                         int M, int N, int K, Epi e, int strips_per_wg) {
+                                                            int M, int N, int K, Epi e, int strips_per_wg, int groups,
+                                                            int chunks) {
+  constexpr int ROWS = MT * 16;
   extern __shared__ uint4 astat_lds[];
-  bf16_t* At = (bf16_t*)astat_lds;          // [64][K + 8]
+  bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 8]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, kq = lane >> 4;
   const int ld = K + 8, n_strips = N >> 4;
-  const int m0 = blockIdx.y * kAstatRows;
-  // stage the rows (past M: the last valid row, computed and never stored)
+  // Workgroup -> (strip group, row chunk).  Consecutive workgroups go to consecutive XCDs, each
+  // with its own L2: with eight or more strip groups, group g runs on XCD g % 8 only, its row
+  // chunks back to back, so that a group's weights come from HBM once and from that L2 afterwards.
+  int group, chunk;
+  if (groups >= 8) {
+    const int t = blockIdx.x >> 3;
+    chunk = t % chunks;
+    group = (t / chunks) * 8 + (blockIdx.x & 7);
+    if (group >= groups) return;
+  } else {
+    group = blockIdx.x % groups;
+    chunk = blockIdx.x / groups;
+  }
+  const int m0 = chunk * ROWS;
+  const int halves = K >> 9;
+  const bf16_t* a_lane = At + r * ld + kq * 8;
+  const int s_begin = group * strips_per_wg, s_end = min(n_strips, s_begin + strips_per_wg);
+  const int s_first = s_begin + 2 * wave;
+  const int n_units = s_first < s_end ? ((s_end - s_first + 7) >> 3) * halves : 0;
+  // this lane's fragment addresses of unit q (clamped: the refill after the last unit re-reads it;
+  // a wave without strips reads the workgroup's first strip and never uses it)
+  auto unit_ptrs = [&](int q, const bf16_t*& w0, const bf16_t*& w1) {
+    q = max(0, min(q, n_units - 1));
+    const int p = q / halves, k0 = (q - p * halves) << 9;
+    const int s0 = n_units > 0 ? s_first + 8 * p : s_begin, s1 = s0 + 1 < s_end ? s0 + 1 : s0;
+    w0 = W + ((size_t)(s0 << 4) * K + (size_t)k0 * 16 + lane * 8);
+    w1 = W + ((size_t)(s1 << 4) * K + (size_t)k0 * 16 + lane * 8);
+  };
+  uint4 b0[16], b1[16];
   {
-    const int vpr = K >> 3;
-    for (int i = wave; i < kAstatRows; i += 4) {
-      const bf16_t* src = A + (size_t)min(m0 + i, M - 1) * K;
-      for (int v = lane; v < vpr; v += 64) *(uint4*)(At + i * ld + v * 8) = *(const uint4*)(src + v * 8);
+    const bf16_t *w0, *w1;
+    unit_ptrs(0, w0, w1);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      b0[u] = *(const uint4*)(w0 + u * 512);
+      b1[u] = *(const uint4*)(w1 + u * 512);
     }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // unit 0 is in flight while the rows are staged
+  // stage the rows (past M: the last valid row, computed and never stored); a wave's loads of a
+  // 512-column slice are all issued before the first LDS store
+  for (int h = 0; h < halves; ++h) {
+    uint4 av[MT * 4];
+#pragma unroll
+    for (int i = 0; i < MT * 4; ++i)
+      av[i] = *(const uint4*)(A + (size_t)min(m0 + wave * MT * 4 + i, M - 1) * K + h * 512 + lane * 8);
+#pragma unroll
+    for (int i = 0; i < MT * 4; ++i) *(uint4*)(At + (wave * MT * 4 + i) * ld + h * 512 + lane * 8) = av[i];
   }
   __syncthreads();
-  const bf16_t* a_lane = At + r * ld + kq * 8;
-  const int s_begin = blockIdx.x * strips_per_wg, s_end = min(n_strips, s_begin + strips_per_wg);
-  for (int s0 = s_begin + 2 * wave; s0 < s_end; s0 += 8) {
-    const bool two = s0 + 1 < s_end;
-    const bf16_t* w0 = W + (size_t)(s0 << 4) * K + lane * 8;
-    const bf16_t* w1 = W + (size_t)((two ? s0 + 1 : s0) << 4) * K + lane * 8;
-    f32x4 acc[2][4];
+  f32x4 acc[2][MT];
+  // EPI_ARGMAX: every lane keeps the best (value, column) of its MT*4 (row, column-residue) slots
+  // over all strips of the wave.  A lane meets its columns in ascending order, so "strictly
+  // greater" keeps the smallest column among equal values; the start value (-inf at the lane's
+  // first column) makes that hold for a row of -inf too.  A lane without strips keeps the
+  // neutral element.
+  constexpr int NB = AMAX ? MT * 4 : 1;
+  float bv[NB];
+  int bi[NB];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+  for (int x = 0; x < NB; ++x) { bv[x] = -INFINITY; bi[x] = n_units > 0 ? (s_first << 4) + r : 0x7fffffff; }
+  for (int q = 0; q < n_units; ++q) {
+    const int p = q / halves, k0 = (q - p * halves) << 9;
+    const bool last = k0 + 512 == K;
+    const int s0 = s_first + 8 * p;
+    const bf16_t *wn0, *wn1;
+    unit_ptrs(q + 1, wn0, wn1);
+    if (k0 == 0) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < K; k0 += 512) {
-      uint4 b0[16], b1[16];
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        b0[u] = *(const uint4*)(w0 + (k0 + 32 * u) * 16);
-        b1[u] = *(const uint4*)(w1 + (k0 + 32 * u) * 16);
-      }
-      __builtin_amdgcn_sched_barrier(0);  // keep all 32 fetches ahead of the first MFMA
-      uint4 af[2][4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) af[0][t] = *(const uint4*)(a_lane + t * 16 * ld + k0);
-#pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        // the next step's A fragments leave LDS while this step's MFMAs run
-        if (u + 1 < 16) {
-#pragma unroll
-          for (int t = 0; t < 4; ++t) af[(u + 1) & 1][t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * (u + 1));
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u & 1][t]), __builtin_bit_cast(bf16x8, b0[u]), acc[0][t], 0, 0, 0);
-          acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u & 1][t]), __builtin_bit_cast(bf16x8, b1[u]), acc[1][t], 0, 0, 0);
-        }
+        for (int t = 0; t < MT; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // operands of the epilogue that do not depend on the accumulators are requested before the
+    // last slice's MFMAs (only where the registers are there for it)
+    constexpr bool PRE = !AMAX && MT <= 2;
+    EpiRegs<MT> g0{}, g1{};
+    if constexpr (PRE) {
+      if (last) {
+        epi_preload<MT>(e, MT, m0, s0 << 4, M, N, lane, g0);
+        if (s0 + 1 < s_end) epi_preload<MT>(e, MT, m0, (s0 + 1) << 4, M, N, lane, g1);
       }
     }
-    strip_epilogue<bf16_t, 4>(e, acc[0], 4, m0, s0 << 4, M, N, lane);
-    if (two) strip_epilogue<bf16_t, 4>(e, acc[1], 4, m0, (s0 + 1) << 4, M, N, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    // A fragments are read one step ahead of their MFMAs where the registers allow it (MT < 4);
+    // with MT = 4 the co-resident wave covers the LDS latency instead
+    constexpr int AFB = MT < 4 ? 2 : 1;
+    uint4 af[AFB][MT];
+    if constexpr (AFB == 2) {
+#pragma unroll
+      for (int t = 0; t < MT; ++t) af[0][t] = *(const uint4*)(a_lane + t * 16 * ld + k0);
+      __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int ur = AFB == 2 ? u + 1 : u;   // step whose fragments are read now
+      if (ur < 16) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) af[ur % AFB][t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * ur);
+      }
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b0[u]), acc[0][t], 0, 0, 0);
+        acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b1[u]), acc[1][t], 0, 0, 0);
+      }
+      // rolling refill: the same step of the next unit
+      b0[u] = *(const uint4*)(wn0 + u * 512);
+      b1[u] = *(const uint4*)(wn1 + u * 512);
+      // issue order per step: LDS reads, this step's MFMAs, the two refills
+      if (ur < 16) __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * MT, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (last) {
+      if constexpr (AMAX) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          if (j == 1 && s0 + 1 >= s_end) break;
+          const int n = ((s0 + j) << 4) + r;
+#pragma unroll
+          for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float v = acc[j][t][i];
+              const bool better = v > bv[t * 4 + i];
+              bv[t * 4 + i] = better ? v : bv[t * 4 + i];
+              bi[t * 4 + i] = better ? n : bi[t * 4 + i];
+            }
+          if (e.logits) {
+            for (int t = 0; t < MT; ++t)
+              for (int i = 0; i < 4; ++i) {
+                const int m = m0 + t * 16 + kq * 4 + i;
+                if (m < M) e.logits[(size_t)m * N + n] = acc[j][t][i];
+              }
+          }
+        }
+      } else if constexpr (PRE) {
+        epi_apply<bf16_t, MT>(e, acc[0], g0, MT, m0, s0 << 4, M, N, lane);
+        if (s0 + 1 < s_end) epi_apply<bf16_t, MT>(e, acc[1], g1, MT, m0, (s0 + 1) << 4, M, N, lane);
+      } else {
+        strip_epilogue<bf16_t, MT>(e, acc[0], MT, m0, s0 << 4, M, N, lane);
+        if (s0 + 1 < s_end) strip_epilogue<bf16_t, MT>(e, acc[1], MT, m0, (s0 + 1) << 4, M, N, lane);
+      }
+    }
   }
+  if constexpr (AMAX) {
+    // rows of 16 lanes reduce by lane moves, the four waves through LDS
+    float* mv = (float*)(At + ROWS * ld);   // [4 waves][ROWS]
+    int* mi = (int*)(mv + 4 * ROWS);
+#pragma unroll
+    for (int x = 0; x < MT * 4; ++x) {
+      argmax_row16(bv[x], bi[x]);
+      if (r == 0) {
+        const int row = (x >> 2) * 16 + kq * 4 + (x & 3);
+        mv[wave * ROWS + row] = bv[x];
+        mi[wave * ROWS + row] = bi[x];
+      }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < ROWS && m0 + (int)threadIdx.x < M) {
+      float v = mv[threadIdx.x];
+      int idx = mi[threadIdx.x];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) argmax_merge(v, idx, mv[w * ROWS + threadIdx.x], mi[w * ROWS + threadIdx.x]);
+      e.part_val[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = v;
+      e.part_idx[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = idx;
+    }
+  }
+}
+// Launch shape of the kernel above.  Rough cost model (microseconds) of a shape: the busiest
+// XCD runs its workgroups in rounds of (32 CUs x workgroups per CU); a workgroup costs a fixed
+// part (launch, staging the rows, drain) plus its units.  Strips per workgroup are a multiple of
+// eight (four waves, two strips each).
+static size_t astat_lds_bytes(int mt, int K) { return (size_t)mt * 16 * (K + 8) * 2 + 4 * (size_t)mt * 16 * 8; }
+static float astat_plan(int mt, int M, int N, int K, int* per_wg_out) {
+  const int chunks = (M + mt * 16 - 1) / (mt * 16), n_strips = N / 16, halves = K / 512;
+  const size_t lds = astat_lds_bytes(mt, K);
+  const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
+  const float unit_us = 0.25f * mt + 0.15f, wg_us = 2.0f;
+  float best = 1e30f;
+  for (int per_wg = 8; per_wg <= 128; per_wg += 8) {
+    const int groups = (n_strips + per_wg - 1) / per_wg;
+    const int wgs_xcd = groups >= 8 ? (groups + 7) / 8 * chunks : (groups * chunks + 7) / 8;
+    const int rounds = (wgs_xcd + 32 * per_cu - 1) / (32 * per_cu);
+    // co-resident workgroups share the MFMA pipes
+    const int together = wgs_xcd > 32 ? per_cu : 1;
+    const float cost = rounds * (wg_us + (per_wg / 8) * halves * unit_us * together);
+    if (cost < best) { best = cost; *per_wg_out = per_wg; }
+    if (groups == 1) break;
+  }
+  return best;
+}
+template <int MT>
+static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epi& e, int per_wg, hipStream_t s) {
+  const int chunks = (M + MT * 16 - 1) / (MT * 16), n_strips = N / 16;
+  const size_t lds = astat_lds_bytes(MT, K);
+  static size_t set_for = 0;
+  if (lds > set_for) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    set_for = lds;
+  }
+  const int gx = (n_strips + per_wg - 1) / per_wg;
+  const int grid = (gx >= 8 ? (gx + 7) / 8 * 8 : gx) * chunks;
+  if (e.mode == EPI_ARGMAX) k_gemm_bf16_astat<MT, true><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks);
+  else k_gemm_bf16_astat<MT, false><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks);
+  return gx;
 }
 
 // ------------------------------------------------------------------------------------- fp32 GEMM
@@ -282,29 +448,26 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
   if (m < M && n < N) epi_store<float>(e, m, n, N, acc);
 }
 
-void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s) {
-  if (M <= 0) return;
+int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s) {
+  if (M <= 0) return 0;
   if (dtype == AD_BF16) {
     const int nb = (N / 16 + 3) / 4;
     const int tiles_x = (N / 16 + 7) / 8, tiles_y = (M + 127) / 128;
-    if (M >= 128 && K <= 1024 && K % 512 == 0) {
-      // enough workgroups to fill the chip a few times over, each with a long run of strips
-      const int chunks = (M + kAstatRows - 1) / kAstatRows, n_strips = N / 16;
-      int per_wg = 64;
-      while (per_wg > 8 && chunks * ((n_strips + per_wg - 1) / per_wg) < 512) per_wg >>= 1;
-      const size_t lds = (size_t)kAstatRows * (K + 8) * 2;
-      static size_t set_for = 0;
-      if (lds > set_for) {
-        (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        set_for = lds;
-      }
-      k_gemm_bf16_astat<<<dim3((n_strips + per_wg - 1) / per_wg, chunks), 256, lds, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K,
-                                                                                       e, per_wg);
-      return;
+    if (M >= 128 && K <= 4096 && K % 512 == 0) {
+      // rows per workgroup (16, 32 or 64, as far as the A tile fits in LDS) and strips per
+      // workgroup by the cost model
+      const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
+      int pw[3] = {8, 8, 8};
+      const float c1 = astat_plan(1, M, N, K, &pw[0]);
+      const float c2 = K <= 2048 ? astat_plan(2, M, N, K, &pw[1]) : 1e30f;
+      const float c4 = K <= 1024 ? astat_plan(4, M, N, K, &pw[2]) : 1e30f;
+      if (c4 <= c2 && c4 <= c1) return launch_astat<4>(a, w, M, N, K, e, pw[2], s);
+      if (c2 <= c1) return launch_astat<2>(a, w, M, N, K, e, pw[1], s);
+      return launch_astat<1>(a, w, M, N, K, e, pw[0], s);
     }
     if (M >= 128 && tiles_x * tiles_y >= 96) {
       k_gemm_bf16_tiled<<<dim3(tiles_x, tiles_y), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);
-      return;
+      return N / 16;
     }
     if (M <= 16)
       k_gemm_bf16<1><<<dim3(nb, 1), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);
@@ -315,6 +478,7 @@ void launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, c
   } else {
     k_gemm_f32<<<dim3(N / 16, (M + 15) / 16), 256, 0, s>>>((const float*)A, (const float*)W, M, N, K, e);
   }
+  return N / 16;
 }
 
 // ------------------------------------------------------------------------------------- attention
@@ -421,22 +585,22 @@ void launch_layernorm(int dtype, const float* x, const float* g, const float* b,
 
 // ------------------------------------------------------------------------------------- arg max, second stage
 __global__ __launch_bounds__(256) void k_argmax_finish(const float* __restrict__ pv, const int* __restrict__ pi,
-                                                       int M, int n_strips, int* __restrict__ o_hat,
+                                                       int M, int stride, int n_part, int* __restrict__ o_hat,
                                                        float* __restrict__ o_val) {
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (m >= M) return;
   float v;
   int idx;
-  argmax_row(pv + (size_t)m * n_strips, pi + (size_t)m * n_strips, n_strips, lane, v, idx);
+  argmax_row(pv + (size_t)m * stride, pi + (size_t)m * stride, n_part, lane, v, idx);
   if (lane == 0) {
     o_hat[m] = idx;
     if (o_val) o_val[m] = v;
   }
 }
-void launch_argmax_finish(const float* pv, const int* pi, int M, int n_strips, int* o_hat, float* o_val,
+void launch_argmax_finish(const float* pv, const int* pi, int M, int stride, int n_part, int* o_hat, float* o_val,
                           hipStream_t s) {
   if (M <= 0) return;
-  k_argmax_finish<<<(M + 3) / 4, 256, 0, s>>>(pv, pi, M, n_strips, o_hat, o_val);
+  k_argmax_finish<<<(M + 3) / 4, 256, 0, s>>>(pv, pi, M, stride, n_part, o_hat, o_val);
 }
 
 template <typename T>
