@@ -16,10 +16,15 @@ const char* global_error();
 
 static size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
-// LDS bytes of the block attention: two padded [nk, dh] tiles plus per-wave query and score rows
+// LDS bytes of the block attention (the device code's attn_lds_bytes): the larger of the scalar
+// path's need (two padded [nk, dh] tiles plus per-wave query and score rows) and the matrix-core
+// path's (transposed values [dh][keys + 8] and one 16-row probability tile per wave)
 static size_t attn_lds_host(int nk_cap, int dh, int esz, int waves) {
   const size_t row_dwords = (size_t)dh * esz / 4 + 1;
-  return 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
+  const size_t scalar_path = 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
+  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 8;
+  const size_t mfma_path = ((size_t)dh + 16 * (size_t)waves) * ldv * 2;
+  return std::max(scalar_path, mfma_path);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -307,6 +312,8 @@ static void setup_fused(ad_ctx* c) {
   const int d = cf.d_model, F = cf.d_ffn;
   // LayerNorm rows and A tiles are at most kFusedMaxWidth wide; wider GEMMs walk whole slices
   if (d > kFusedMaxWidth || d % 32 || F % 32 || (F > kFusedMaxWidth && F % kFusedMaxWidth)) return;
+  const int dh_f = d / cf.n_heads;
+  if (dh_f != 16 && dh_f != 32 && dh_f != 64) return;   // the head widths the persistent kernel is built for
   const size_t att_bytes = attn_lds_host(std::max(p.l_cap, cf.max_src), d / cf.n_heads, 2, kFusedWaves);
   const size_t lds = kFusedLdsBytes;
   if (att_bytes > lds || (size_t)cf.k_max * 4 > lds) return;

@@ -426,13 +426,182 @@ template <> struct LdsRow<float> {
 
 __host__ __device__ inline size_t attn_lds_bytes(int nk_cap, int dh, int esz, int waves) {
   const size_t row_dwords = (size_t)dh * esz / 4 + 1;
-  return 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
+  const size_t scalar_path = 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
+  // matrix-core path: transposed values [dh][keys + 8] and one 16-row probability tile per wave
+  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 8;
+  const size_t mfma_path = ((size_t)dh + 16 * (size_t)waves) * ldv * 2;
+  return scalar_path > mfma_path ? scalar_path : mfma_path;
+}
+
+// Maximum / sum over each row of 16 lanes (every lane of the row gets it); lane moves as in
+// wave_sum, so the pairing depends on the lane's position in the row only.
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
+  return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  v += dpp_move<0x140>(v);
+  return v;
+}
+
+// Attention of one (sequence, head) on the matrix cores, bf16 storage, head width a multiple of
+// 32, at most 16 * NT keys.  The workgroup stages the head's values transposed in LDS (keys past
+// the last needed one as zeros); then each wave takes 16 query rows at a time:
+//   scores   S = Q K^T by MFMA, Q and K fragments straight from memory (k = head channel, 32 at
+//            a time, ascending); times `scale`; keys a row must not see become -inf
+//   softmax  exact row maximum; p = exp(s - max); the denominator sums the unrounded p: each of
+//            the 16 lanes of a row adds its keys (key % 16 = lane) in ascending order, then the
+//            lanes combine by row16_sum; numerators are rounded to bf16 and go through LDS to
+//            become the left operand of
+//   output   O = P V by MFMA (k = key, 32 at a time, ascending), divided by the denominator.
+// Every step treats a query row independently of the other rows of its tile and of how many
+// tiles or keys the call covers (keys a row does not see contribute exact zeros), so a row's
+// result does not depend on the shape of the block it is verified in.
+template <int DH, int NT, bool COH, bool STC>
+__device__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
+                                const SeqDesc sd, int row_begin, int row_end, int h, int d, float scale,
+                                const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all) {
+  constexpr int KS = DH / 32, CT = DH / 16;
+  const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
+  const int n_tiles = (row_end - row_begin + 15) >> 4;
+  for (int rt = wave; rt < n_tiles; rt += waves) {
+    const int row0 = row_begin + rt * 16;
+    const int tile_end = min(row0 + 16, row_end);
+    const int nk_tile = sd.causal ? sd.nk_base + tile_end : sd.nk_base;   // keys the tile's last row sees
+    const int nt = (nk_tile + 15) >> 4, nb = (nk_tile + 31) >> 5;
+    uint4 qf[KS];
+    {
+      const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row0 + r, row_end - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
+    }
+    f32x4 S[NT];
+#pragma unroll
+    for (int j0 = 0; j0 < NT; j0 += 4) {
+      uint4 kf[4][KS];
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j = j0 + jj;
+        if (j < NT && j < nt) {
+          const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+          for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+        }
+      }
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const int j = j0 + jj;
+        if (j < NT) {
+          S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (j < nt) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+              S[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s]), __builtin_bit_cast(bf16x8, kf[jj][s]), S[j], 0, 0, 0);
+          }
+        }
+      }
+    }
+    // this lane: rows row0 + 4*kq + i, key 16*j + r
+    float mx[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = row0 + 4 * kq + i;
+      const int nkr = sd.causal ? sd.nk_base + row + 1 : sd.nk_base;
+      float m = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const float v = (j < nt && 16 * j + r < nkr) ? S[j][i] * scale : -INFINITY;
+        S[j][i] = v;
+        m = fmaxf(m, v);
+      }
+      mx[i] = row16_max(m);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float sum = 0.f;
+      bf16_t* pr = Pw + (4 * kq + i) * ldv + r;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        if (j < 2 * nb) {   // the tiles the output product reads (an odd count is padded with zeros)
+          const float pv = expf(S[j][i] - mx[i]);   // exp(-inf) = 0 for the keys the row does not see
+          sum += pv;
+          pr[16 * j] = f2bf(pv);
+        }
+      }
+      l[i] = row16_sum(sum);
+    }
+    __builtin_amdgcn_wave_barrier();
+    f32x4 O[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kb = 0; kb < nb; ++kb) {
+      const uint4 pa = *(const uint4*)(Pw + r * ldv + 32 * kb + 8 * kq);
+      uint4 vb[CT];
+#pragma unroll
+      for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vt + (16 * c + r) * ldv + 32 * kb + 8 * kq);
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+        O[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), O[c], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = row0 + 4 * kq + i;
+      if (row < row_end) {
+        bf16_t* op = out + (size_t)(sd.q_row0 + row) * d + h * DH + r;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) Store<bf16_t>::template store<STC>(op + 16 * c, O[c][i] / l[i]);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the wave's next rows
+  }
+}
+template <int DH, bool COH, bool STC>
+__device__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
+                                const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
+                                int row_begin, int row_end, int h, int d, float scale, unsigned* lds, int nk_all) {
+  const int wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+  const int nkp = (nk_all + 31) & ~31, ldv = nkp + 8;
+  bf16_t* Vt = (bf16_t*)lds;                      // [DH][ldv]: Vt[c][t] = V[t][c]
+  bf16_t* Pw = Vt + DH * ldv + wave * 16 * ldv;   // this wave's probability tile [16][ldv]
+  {
+    constexpr int G = DH / 8;   // 16-byte pieces per key row
+    const bf16_t* vg = Vb + (size_t)sd.kv_row0 * d + h * DH;
+    for (int i = threadIdx.x; i < nkp * G; i += blockDim.x) {
+      const int g = i / nkp, t = i - g * nkp;
+      uint4 v = uint4{0u, 0u, 0u, 0u};
+      if (t < nk_all) v = ldg16<COH>(vg + (size_t)t * d + g * 8);
+      bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
+      dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
+      dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
+      dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
+      dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
+    }
+  }
+  __syncthreads();
+  if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all);
+  else attn_tiles_mfma<DH, 16, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all);
+  __syncthreads();   // LDS is free for the next call
 }
 
 template <typename T, int DH, bool COH = false, bool STC = false>
 __device__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, const T* __restrict__ Vb,
                            T* __restrict__ out, const SeqDesc sd, int row_begin, int row_end, int h, int d,
                            float scale, unsigned* lds, int nk_cap) {
+  if constexpr (sizeof(T) == 2 && DH % 32 == 0) {
+    const int nk_need = sd.causal ? sd.nk_base + row_end : sd.nk_base;
+    if (nk_need <= 256) {
+      attn_block_mfma<DH, COH, STC>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
+      return;
+    }
+  }
   constexpr int RD = DH * (int)sizeof(T) / 4;   // dwords per key row
   constexpr int RS = RD + 1;                    // padded row stride
   const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

@@ -585,7 +585,7 @@ __device__ __forceinline__ void attn_stage(const Stage& st, const FusedArgs& fa,
         case 16: attn_block<bf16_t, 16, true, false>(q, Kb, Vb, out, sd, r0, r1, h, fa.d, scale, lds, st.nk_cap); break;
         case 32: attn_block<bf16_t, 32, true, false>(q, Kb, Vb, out, sd, r0, r1, h, fa.d, scale, lds, st.nk_cap); break;
         case 64: attn_block<bf16_t, 64, true, false>(q, Kb, Vb, out, sd, r0, r1, h, fa.d, scale, lds, st.nk_cap); break;
-        default: attn_block<bf16_t, 128, true, false>(q, Kb, Vb, out, sd, r0, r1, h, fa.d, scale, lds, st.nk_cap); break;
+        default: break;   // other head widths never reach this kernel (the host keeps them on the staged path)
       }
     }
   }
