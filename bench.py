@@ -114,7 +114,7 @@ def main():
     ctx.set_option(ad.AD_OPT_FUSED_ROWS, fused_rows)
     # output projection + arg max: the [V, d] bf16 matrix once, the M x d bf16 rows once, the
     # per-row partial maxima written once
-    voc_bytes = 2 * V * dims["d_model"] + 2 * M1 * dims["d_model"] + 8 * M1 * (V // 16)
+    voc_bytes = 2 * V * dims["d_model"] + 2 * M1 * dims["d_model"] + 8 * M1 * ((V // 16 + 7) // 8)
     if fused:
         # dominant kernel = the persistent forward itself (one launch per verify call).  Algorithmic
         # bytes per launch: every decoder weight the forward streams, once, plus the KV rows read.
@@ -122,7 +122,9 @@ def main():
                     "achieved": fwd_bytes / (fwd_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                     "frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "traffic": None}
     else:
-        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16 (output projection + arg max)", "rows": M1,
+        # dominant kernel by bytes: the output projection + arg max (42 % of the forward's
+        # algorithmic bytes); timed alone, back to back, between two HIP events on its stream
+        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<2, true, 1> (output projection + arg max)", "rows": M1,
                     "achieved": voc_bytes / (voc_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                     "frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK, "traffic": None}
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,

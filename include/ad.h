@@ -189,11 +189,12 @@ int ad_debug_logits(ad_ctx* ctx, float* logits, int rows_cap, int* rows);
 int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us);
 
 /* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
- * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; 0 = one
- * launch per stage always; at most max_batch * k_max).  ad_create picks min(128, max_batch * k_max)
- * when the device and the model shape support the persistent kernel, else 0; setting a positive
- * value on a context where it is unavailable gives AD_ESTATE. */
-enum { AD_OPT_FUSED_ROWS = 0 };
+ * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; at most
+ * max_batch * k_max).  Default 0: one launch per stage always, the faster path at every size
+ * measured.  Setting a positive value on a context where the persistent kernel is unavailable
+ * (device, model shape) gives AD_ESTATE.  AD_OPT_FUSED_AVAILABLE (read only): 1 if it is
+ * available. */
+enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option",
 ]
 AD_OPT_FUSED_ROWS = 0
+AD_OPT_FUSED_AVAILABLE = 1
 
 
 class AdConfig(C.Structure):

@@ -131,6 +131,9 @@ struct ad_ctx {
   int last_nseq = 0, last_max_rows = 0;
   // persistent fused forward (bf16)
   int fused_rows = 0;            // largest M it takes; 0 = off
+  // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
+  const LnW* ln_pending = nullptr;
+  const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
   int fused_grid = 0, fused_stages = 0, fused_teams = 0;
   size_t fused_lds = 0;
   unsigned long long dev_base = 0, team_base[kMaxTeams] = {};
@@ -171,13 +174,33 @@ static VerifyTables tables(const ad_ctx* c) {
   return t;
 }
 
+// s = x + A W^T + bias; the LayerNorm s -> (x, xa) is left to the next consumer of the rows:
+// gemm_rows() applies it while staging its operand where the kernel can, flush_ln() runs it as
+// a launch of its own.
 static void gemm_resid_ln(ad_ctx* c, const void* A, const void* W, const float* bias, int M, int N, int K,
                           const LnW& ln) {
   const Plan& p = c->plan;
   Epi e{};
   e.mode = EPI_RESID; e.bias = bias; e.out0 = c->at<float>(p.s); e.resid = c->at<float>(p.x);
   launch_gemm(c->cfg.dtype, A, W, M, N, K, e, c->stream);
-  launch_layernorm(c->cfg.dtype, c->at<float>(p.s), ln.g, ln.b, M, N, c->at<float>(p.x), c->at<void>(p.xa), c->stream);
+  c->ln_pending = &ln;
+}
+static void flush_ln(ad_ctx* c, int M) {
+  if (!c->ln_pending) return;
+  const Plan& p = c->plan;
+  launch_layernorm(c->cfg.dtype, c->at<float>(p.s), c->ln_pending->g, c->ln_pending->b, M, c->cfg.d_model,
+                   c->at<float>(p.x), c->at<void>(p.xa), c->stream);
+  c->ln_pending = nullptr;
+}
+// GEMM over the current rows (xa, or the pending LayerNorm of s)
+static int gemm_rows(ad_ctx* c, const void* W, int M, int N, const Epi& e) {
+  const Plan& p = c->plan;
+  LnA ln{};
+  if (c->ln_pending) {
+    ln.x = c->at<float>(p.s); ln.g = c->ln_pending->g; ln.b = c->ln_pending->b; ln.y = c->at<float>(p.x);
+    c->ln_pending = nullptr;
+  }
+  return launch_gemm(c->cfg.dtype, c->at<void>(p.xa), W, M, N, c->cfg.d_model, e, c->stream, ln);
 }
 
 static void ffn_block(ad_ctx* c, const FfnW& f, const LnW& ln, int M) {
@@ -185,7 +208,7 @@ static void ffn_block(ad_ctx* c, const FfnW& f, const LnW& ln, int M) {
   const int d = c->cfg.d_model, F = c->cfg.d_ffn;
   Epi e{};
   e.mode = EPI_RELU; e.bias = f.b1; e.out0 = c->at<void>(p.f);
-  launch_gemm(c->cfg.dtype, c->at<void>(p.xa), f.w1, M, F, d, e, c->stream);
+  gemm_rows(c, f.w1, M, F, e);
   gemm_resid_ln(c, c->at<void>(p.f), f.w2, f.b2, M, d, F, ln);
 }
 
@@ -197,7 +220,7 @@ static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, voi
   VerifyTables t = tables(c);
   Epi e{};
   e.mode = EPI_QKV; e.d = d; e.bias = a.bqkv; e.out0 = c->at<void>(p.q); e.out1 = Kl; e.out2 = Vl; e.row_dst = t.row_dst;
-  launch_gemm(c->cfg.dtype, c->at<void>(p.xa), a.wqkv, M, 3 * d, d, e, c->stream);
+  gemm_rows(c, a.wqkv, M, 3 * d, e);
   launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.self_desc, c->fw_nseq, c->fw_max_rows,
                    H, d / H, max_keys, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
@@ -209,7 +232,7 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
   VerifyTables t = tables(c);
   Epi e{};
   e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
-  launch_gemm(c->cfg.dtype, c->at<void>(p.xa), a.wqkv, M, d, d, e, c->stream);
+  gemm_rows(c, a.wqkv, M, d, e);
   launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
                    c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
@@ -217,18 +240,21 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
 
 static void embed_rows(ad_ctx* c, const ModelW& w, int M) {
   const Plan& p = c->plan;
+  c->ln_pending = nullptr;
   VerifyTables t = tables(c);
   launch_embed(c->cfg.dtype, w.emb, c->at<float>(p.pe), t.row_tok, t.row_pos, M, c->cfg.d_model,
                sqrtf((float)c->cfg.d_model), c->at<float>(p.x), c->at<void>(p.xa), c->stream);
 }
 
 // Output projection fused with the per-row arg max; `A` holds Mv rows.
-static int vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv) {
+static int vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv, const LnW* ln_of_s = nullptr) {
   const Plan& p = c->plan;
   Epi e{};
   e.mode = EPI_ARGMAX; e.part_val = c->at<float>(p.part_val); e.part_idx = c->at<int>(p.part_idx);
   e.n_strips = p.n_strips; e.logits = c->cfg.debug_logits ? c->at<float>(p.logits) : nullptr;
-  return launch_gemm(c->cfg.dtype, A, w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream);
+  LnA ln{};
+  if (ln_of_s) { ln.x = c->at<float>(p.s); ln.g = ln_of_s->g; ln.b = ln_of_s->b; ln.y = c->at<float>(p.x); }
+  return launch_gemm(c->cfg.dtype, A, w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream, ln);
 }
 static void vocab_finish(ad_ctx* c, int Mv, int n_part) {
   const Plan& p = c->plan;
@@ -352,9 +378,10 @@ static void setup_fused(ad_ctx* c) {
   c->fused_lds = lds;
   c->dev_base = 0;
   for (int t = 0; t < kMaxTeams; ++t) c->team_base[t] = 0;
-  // Large calls are throughput-bound and go one launch per stage (big MFMA tiles); the persistent
-  // kernel is for the latency-bound small ones.
-  c->fused_rows = std::min(p.mv_cap, 128);
+  // Off unless asked for: one launch per stage is the faster path at every size measured (a
+  // kernel boundary costs no more than a device-wide barrier inside the persistent kernel, and
+  // the per-stage kernels pick their own grid).
+  c->fused_rows = 0;
 }
 
 // One launch: the whole verify forward for the rows the tables describe.  k[b] = rows of
@@ -419,7 +446,9 @@ static void verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent
     ffn_block(c, L.ffn, L.ln3, M);
   }
   if (ev_a) (void)hipEventRecord(ev_a, c->stream);
-  const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), M);
+  c->ln_vocab = c->ln_pending;
+  c->ln_pending = nullptr;
+  const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), M, c->ln_vocab);
   if (ev_b) (void)hipEventRecord(ev_b, c->stream);
   vocab_finish(c, M, n_part);
 }
@@ -577,13 +606,14 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
     Epi e{};
     e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
     e.out1 = c->at<void>(p.tk); e.out2 = c->at<void>(p.tv); e.row_dst = t.row_dst;
-    launch_gemm(cf.dtype, c->at<void>(p.xa), L.self.wqkv, M, 3 * d, d, e, c->stream);
+    gemm_rows(c, L.self.wqkv, M, 3 * d, e);
     launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att),
                      t.self_desc, B, c->fw_max_rows, cf.n_heads, d / cf.n_heads, S, c->stream);
     gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
     ffn_block(c, L.ffn, L.ln2, M);
   }
   // cross-attention keys and values of every decoder layer: memory . [wk; wv]^T + [bk; bv]
+  flush_ln(c, M);
   for (int l = 0; l < cf.dec_layers; ++l) {
     const AttnW& a = w.dec[l].cross;
     Epi e{};
@@ -739,6 +769,7 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     ffn_block(c, L.ffn, L.ln3, M);
   }
   const int Mv = live * k;
+  flush_ln(c, M);
   launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
   vocab_finish(c, Mv, vocab_argmax(c, w, c->at<void>(p.xg), Mv));
   launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
@@ -861,8 +892,10 @@ int ad_set_option(ad_ctx* c, int option, int value) {
 }
 int ad_get_option(ad_ctx* c, int option, int* value) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
-  if (option != AD_OPT_FUSED_ROWS || !value) return fail(c, AD_EINVAL, "unknown option or null pointer");
-  *value = c->fused_rows;
+  if (!value) return fail(c, AD_EINVAL, "null pointer");
+  if (option == AD_OPT_FUSED_ROWS) *value = c->fused_rows;
+  else if (option == AD_OPT_FUSED_AVAILABLE) *value = c->fused_grid > 0 ? 1 : 0;
+  else return fail(c, AD_EINVAL, "unknown option");
   return AD_OK;
 }
 
@@ -932,16 +965,22 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
     return AD_OK;
   }
   verify_forward(c, c->last_M);   // warm
-  for (int r = 0; r < reps; ++r) {
-    HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
-    verify_forward(c, c->last_M, c->ev1, c->ev2);
-    HIP_TRY(c, hipEventRecord(c->ev3, c->stream));
-    HIP_TRY(c, hipEventSynchronize(c->ev3));
-    float a = 0, b = 0;
-    HIP_TRY(c, hipEventElapsedTime(&a, c->ev0, c->ev3));
-    HIP_TRY(c, hipEventElapsedTime(&b, c->ev1, c->ev2));
-    tot += a * 1e3; voc += b * 1e3;
-  }
+  // the whole forward, reps times back to back between two events
+  HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
+  for (int r = 0; r < reps; ++r) verify_forward(c, c->last_M);
+  HIP_TRY(c, hipEventRecord(c->ev3, c->stream));
+  HIP_TRY(c, hipEventSynchronize(c->ev3));
+  float a = 0, b = 0;
+  HIP_TRY(c, hipEventElapsedTime(&a, c->ev0, c->ev3));
+  tot = a * 1e3;
+  // the output projection + arg max kernel alone, on the rows the forward left, likewise
+  const ModelW& w = c->w[AD_VERIFIER];
+  HIP_TRY(c, hipEventRecord(c->ev1, c->stream));
+  for (int r = 0; r < reps; ++r) (void)vocab_argmax(c, w, c->at<void>(c->plan.xa), c->last_M, c->ln_vocab);
+  HIP_TRY(c, hipEventRecord(c->ev2, c->stream));
+  HIP_TRY(c, hipEventSynchronize(c->ev2));
+  HIP_TRY(c, hipEventElapsedTime(&b, c->ev1, c->ev2));
+  voc = b * 1e3;
   HIP_TRY(c, hipGetLastError());
   *forward_us = tot / reps;
   *vocab_kernel_us = voc / reps;

@@ -44,6 +44,16 @@ ModelW bind_weights(const ad_config& c, const void* blob);
 // (0-based inside the sequence) sees keys [0, causal ? nk_base + i + 1 : nk_base).
 struct SeqDesc { int q_row0, nq, kv_row0, nk_base, causal, pad0, pad1, pad2; };
 
+// ---- GEMM left operand given as rows still to be normalised -------------------------------------
+// A = LayerNorm(x) * g + b over fp32 rows x [M, K]; the fp32 result also goes to y [M, K] (the
+// residual input of a later sublayer).  x == nullptr: A is given as is.
+struct LnA {
+  const float* x = nullptr;
+  const float* g = nullptr;
+  const float* b = nullptr;
+  float* y = nullptr;
+};
+
 // ---- GEMM epilogues ----------------------------------------------------------------------------
 enum EpiMode { EPI_QKV = 0, EPI_KV = 1, EPI_STORE = 2, EPI_RELU = 3, EPI_RESID = 4, EPI_ARGMAX = 5 };
 struct Epi {
@@ -133,7 +143,11 @@ void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, c
                   int d, float sqrt_d, float* x, void* xa, hipStream_t s);
 // C[M,N] = A[M,K] . W[N,K]^T with epilogue.  A, W in the storage type.
 // returns the number of arg-max partials per row an EPI_ARGMAX launch wrote (row stride e.n_strips)
-int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s);
+// With `ln` set, A is LayerNorm(ln.x): kernels that can, normalise the rows while staging them
+// (then the storage-type rows `A` are NOT written); otherwise a LayerNorm launch fills ln.y and A
+// first.  Same values either way.
+int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s,
+                const LnA& ln = LnA{}, bool* a_written = nullptr);
 // one attention problem per descriptor (n_seq of them, at most max_rows query rows each)
 void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
                       int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s);

@@ -10,6 +10,8 @@
 // arithmetic).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "ad_device.h"
 
 namespace ad {
@@ -180,20 +182,57 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_tiled(const bf16_t* __rest
 
 // ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows, K a multiple of 512
 // A stays put, weights stream: a workgroup stages MT*16 rows of A (all K) in LDS once and then
-// walks a run of 16-column strips, each wave two strips at a time.  Work unit = (strip pair,
-// 512-k slice): 32 weight fragments (fully coalesced 1 KB fetches straight into B operand
+// walks a run of 16-column strips, each wave SP strips at a time (two where rows are many and
+// LDS traffic per MFMA matters, one where rows are few and parallelism does).  Work unit = (SP
+// strips, 512-k slice): 16*SP weight fragments (fully coalesced 1 KB fetches straight into B operand
 // registers).  The registers are refilled on a rolling basis: as soon as step u's MFMAs are
 // issued, step u of the NEXT unit is requested into the same registers, so every fetch has a
 // whole unit's time before it is needed and one register set suffices; two workgroups share a CU
 // and cover each other's gaps.  Per 32-k step the wave reads MT A fragments from LDS and issues
-// 2*MT MFMAs (each fragment serves both strips, which halves the LDS traffic per MFMA).
+// SP*MT MFMAs.
 // Accumulation order per output element as in every other kernel: k ascending, 32 at a time,
 // one accumulator.
 // EPI_ARGMAX: one (value, column) partial per (row, workgroup) instead of one per strip.
-template <int MT, bool AMAX>
+// A tile rows [row0, row0 + n_rows) of a workgroup from fp32 rows through LayerNorm (width
+// 256 * NV, the 16-byte rule of ln_load4 / ln_stats4), RB rows in flight at a time.
+template <int NV, int RB>
+__device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld, int row0, int n_rows, int m0, int M,
+                                               int lane, bool store_y) {
+  constexpr int K = 256 * NV;
+  float4 gv[NV], bv[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    gv[j] = *(const float4*)(ln.g + 4 * lane + 256 * j);
+    bv[j] = *(const float4*)(ln.b + 4 * lane + 256 * j);
+  }
+  for (int i0 = 0; i0 < n_rows; i0 += RB) {
+    float4 xv[RB][NV];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+      if (i0 + i < n_rows) ln_load4<false, NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+      if (i0 + i >= n_rows) break;
+      const int row = row0 + i0 + i, m = m0 + row;
+      float mean, rstd;
+      ln_stats4<NV>(xv[i], K, mean, rstd);
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = 4 * lane + 256 * j;
+        const float4 o = float4{ln_value(xv[i][j].x, mean, rstd, gv[j].x, bv[j].x), ln_value(xv[i][j].y, mean, rstd, gv[j].y, bv[j].y),
+                                ln_value(xv[i][j].z, mean, rstd, gv[j].z, bv[j].z), ln_value(xv[i][j].w, mean, rstd, gv[j].w, bv[j].w)};
+        const unsigned lo = (unsigned)f2bf(o.x) | ((unsigned)f2bf(o.y) << 16), hi = (unsigned)f2bf(o.z) | ((unsigned)f2bf(o.w) << 16);
+        *(uint2*)(At + row * ld + c) = uint2{lo, hi};
+        if (store_y && m < M) *(float4*)(ln.y + (size_t)m * K + c) = o;
+      }
+    }
+  }
+}
+
+template <int MT, bool AMAX, int SP>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, Epi e, int strips_per_wg, int groups,
-                                                            int chunks) {
+                                                            int chunks, LnA ln) {
   constexpr int ROWS = MT * 16;
   extern __shared__ uint4 astat_lds[];
   bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 8]
@@ -217,30 +256,36 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   const int halves = K >> 9;
   const bf16_t* a_lane = At + r * ld + kq * 8;
   const int s_begin = group * strips_per_wg, s_end = min(n_strips, s_begin + strips_per_wg);
-  const int s_first = s_begin + 2 * wave;
-  const int n_units = s_first < s_end ? ((s_end - s_first + 7) >> 3) * halves : 0;
+  const int s_first = s_begin + SP * wave;
+  const int n_units = s_first < s_end ? ((s_end - s_first + 4 * SP - 1) / (4 * SP)) * halves : 0;
   // this lane's fragment addresses of unit q (clamped: the refill after the last unit re-reads it;
   // a wave without strips reads the workgroup's first strip and never uses it)
-  auto unit_ptrs = [&](int q, const bf16_t*& w0, const bf16_t*& w1) {
+  auto unit_ptrs = [&](int q, const bf16_t* (&w)[SP]) {
     q = max(0, min(q, n_units - 1));
     const int p = q / halves, k0 = (q - p * halves) << 9;
-    const int s0 = n_units > 0 ? s_first + 8 * p : s_begin, s1 = s0 + 1 < s_end ? s0 + 1 : s0;
-    w0 = W + ((size_t)(s0 << 4) * K + (size_t)k0 * 16 + lane * 8);
-    w1 = W + ((size_t)(s1 << 4) * K + (size_t)k0 * 16 + lane * 8);
-  };
-  uint4 b0[16], b1[16];
-  {
-    const bf16_t *w0, *w1;
-    unit_ptrs(0, w0, w1);
+    const int s0 = n_units > 0 ? s_first + 4 * SP * p : s_begin;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      b0[u] = *(const uint4*)(w0 + u * 512);
-      b1[u] = *(const uint4*)(w1 + u * 512);
-    }
+    for (int j = 0; j < SP; ++j)
+      w[j] = W + ((size_t)(min(s0 + j, s_end - 1) << 4) * K + (size_t)k0 * 16 + lane * 8);
+  };
+  uint4 b[SP][16];
+  {
+    const bf16_t* w[SP];
+    unit_ptrs(0, w);
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+#pragma unroll
+      for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(w[j] + u * 512);
   }
   __builtin_amdgcn_sched_barrier(0);   // unit 0 is in flight while the rows are staged
-  // stage the rows (past M: the last valid row, computed and never stored); a wave's loads of a
-  // 512-column slice are all issued before the first LDS store
+  // stage the rows (past M: the last valid row, computed and never stored)
+  if (ln.x) {
+    // rows to be normalised first (K = 512 or 1024): the statistics and values of the LayerNorm
+    // kernel; the workgroups of strip group 0 also store the fp32 rows
+    if (K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, group == 0);
+    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, group == 0);
+  } else
+  // a wave's loads of a 512-column slice are all issued before the first LDS store
   for (int h = 0; h < halves; ++h) {
     uint4 av[MT * 4];
 #pragma unroll
@@ -250,7 +295,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     for (int i = 0; i < MT * 4; ++i) *(uint4*)(At + (wave * MT * 4 + i) * ld + h * 512 + lane * 8) = av[i];
   }
   __syncthreads();
-  f32x4 acc[2][MT];
+  f32x4 acc[SP][MT];
   // EPI_ARGMAX: every lane keeps the best (value, column) of its MT*4 (row, column-residue) slots
   // over all strips of the wave.  A lane meets its columns in ascending order, so "strictly
   // greater" keeps the smallest column among equal values; the start value (-inf at the lane's
@@ -264,23 +309,24 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   for (int q = 0; q < n_units; ++q) {
     const int p = q / halves, k0 = (q - p * halves) << 9;
     const bool last = k0 + 512 == K;
-    const int s0 = s_first + 8 * p;
-    const bf16_t *wn0, *wn1;
-    unit_ptrs(q + 1, wn0, wn1);
+    const int s0 = s_first + 4 * SP * p;
+    const bf16_t* wn[SP];
+    unit_ptrs(q + 1, wn);
     if (k0 == 0) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < SP; ++j)
 #pragma unroll
         for (int t = 0; t < MT; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     // operands of the epilogue that do not depend on the accumulators are requested before the
     // last slice's MFMAs (only where the registers are there for it)
-    constexpr bool PRE = !AMAX && MT <= 2;
-    EpiRegs<MT> g0{}, g1{};
+    constexpr bool PRE = !AMAX && MT * SP <= 4;
+    EpiRegs<MT> g[SP];
     if constexpr (PRE) {
       if (last) {
-        epi_preload<MT>(e, MT, m0, s0 << 4, M, N, lane, g0);
-        if (s0 + 1 < s_end) epi_preload<MT>(e, MT, m0, (s0 + 1) << 4, M, N, lane, g1);
+#pragma unroll
+        for (int j = 0; j < SP; ++j)
+          if (s0 + j < s_end) epi_preload<MT>(e, MT, m0, (s0 + j) << 4, M, N, lane, g[j]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -301,24 +347,24 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
         for (int t = 0; t < MT; ++t) af[ur % AFB][t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * ur);
       }
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b0[u]), acc[0][t], 0, 0, 0);
-        acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b1[u]), acc[1][t], 0, 0, 0);
-      }
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int j = 0; j < SP; ++j)
+          acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b[j][u]), acc[j][t], 0, 0, 0);
       // rolling refill: the same step of the next unit
-      b0[u] = *(const uint4*)(wn0 + u * 512);
-      b1[u] = *(const uint4*)(wn1 + u * 512);
-      // issue order per step: LDS reads, this step's MFMAs, the two refills
+#pragma unroll
+      for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(wn[j] + u * 512);
+      // issue order per step: LDS reads, this step's MFMAs, the refills
       if (ur < 16) __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * MT, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, SP * MT, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, SP, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     if (last) {
       if constexpr (AMAX) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          if (j == 1 && s0 + 1 >= s_end) break;
+        for (int j = 0; j < SP; ++j) {
+          if (s0 + j >= s_end) break;
           const int n = ((s0 + j) << 4) + r;
 #pragma unroll
           for (int t = 0; t < MT; ++t)
@@ -338,11 +384,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
           }
         }
       } else if constexpr (PRE) {
-        epi_apply<bf16_t, MT>(e, acc[0], g0, MT, m0, s0 << 4, M, N, lane);
-        if (s0 + 1 < s_end) epi_apply<bf16_t, MT>(e, acc[1], g1, MT, m0, (s0 + 1) << 4, M, N, lane);
+#pragma unroll
+        for (int j = 0; j < SP; ++j)
+          if (s0 + j < s_end) epi_apply<bf16_t, MT>(e, acc[j], g[j], MT, m0, (s0 + j) << 4, M, N, lane);
       } else {
-        strip_epilogue<bf16_t, MT>(e, acc[0], MT, m0, s0 << 4, M, N, lane);
-        if (s0 + 1 < s_end) strip_epilogue<bf16_t, MT>(e, acc[1], MT, m0, (s0 + 1) << 4, M, N, lane);
+#pragma unroll
+        for (int j = 0; j < SP; ++j)
+          if (s0 + j < s_end) strip_epilogue<bf16_t, MT>(e, acc[j], MT, m0, (s0 + j) << 4, M, N, lane);
       }
     }
   }
@@ -393,20 +441,21 @@ static float astat_plan(int mt, int M, int N, int K, int* per_wg_out) {
   }
   return best;
 }
-template <int MT>
-static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epi& e, int per_wg, hipStream_t s) {
+template <int MT, int SP>
+static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epi& e, int per_wg, hipStream_t s,
+                        const LnA& ln) {
   const int chunks = (M + MT * 16 - 1) / (MT * 16), n_strips = N / 16;
   const size_t lds = astat_lds_bytes(MT, K);
   static size_t set_for = 0;
   if (lds > set_for) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, false, SP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, true, SP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     set_for = lds;
   }
   const int gx = (n_strips + per_wg - 1) / per_wg;
   const int grid = (gx >= 8 ? (gx + 7) / 8 * 8 : gx) * chunks;
-  if (e.mode == EPI_ARGMAX) k_gemm_bf16_astat<MT, true><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks);
-  else k_gemm_bf16_astat<MT, false><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks);
+  if (e.mode == EPI_ARGMAX) k_gemm_bf16_astat<MT, true, SP><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
+  else k_gemm_bf16_astat<MT, false, SP><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
   return gx;
 }
 
@@ -448,22 +497,42 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
   if (m < M && n < N) epi_store<float>(e, m, n, N, acc);
 }
 
-int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s) {
+int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s,
+                const LnA& ln_in, bool* a_written) {
   if (M <= 0) return 0;
+  if (a_written) *a_written = true;
+  LnA ln = ln_in;
+  const bool streams = dtype == AD_BF16 && K <= 4096 && K % 512 == 0;   // the A-in-LDS kernel takes it
+  if (ln.x && !(streams && (K == 512 || K == 1024))) {
+    launch_layernorm(dtype, ln.x, ln.g, ln.b, M, K, ln.y, const_cast<void*>(A), s);
+    ln = LnA{};
+  }
+  if (ln.x && a_written) *a_written = false;
   if (dtype == AD_BF16) {
     const int nb = (N / 16 + 3) / 4;
     const int tiles_x = (N / 16 + 7) / 8, tiles_y = (M + 127) / 128;
-    if (M >= 128 && K <= 4096 && K % 512 == 0) {
-      // rows per workgroup (16, 32 or 64, as far as the A tile fits in LDS) and strips per
-      // workgroup by the cost model
+    if (K <= 4096 && K % 512 == 0) {
       const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
-      int pw[3] = {8, 8, 8};
-      const float c1 = astat_plan(1, M, N, K, &pw[0]);
-      const float c2 = K <= 2048 ? astat_plan(2, M, N, K, &pw[1]) : 1e30f;
-      const float c4 = K <= 1024 ? astat_plan(4, M, N, K, &pw[2]) : 1e30f;
-      if (c4 <= c2 && c4 <= c1) return launch_astat<4>(a, w, M, N, K, e, pw[2], s);
-      if (c2 <= c1) return launch_astat<2>(a, w, M, N, K, e, pw[1], s);
-      return launch_astat<1>(a, w, M, N, K, e, pw[0], s);
+      const int mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+      if (M <= 64 && astat_lds_bytes(mt, K) <= 150 * 1024) {
+        // few rows: one strip per wave, workgroups of four strips until the chip is covered
+        {
+          const int per_wg = 4 * std::max(1, (N / 16 + 4 * 384 - 1) / (4 * 384));
+          if (mt == 1) return launch_astat<1, 1>(a, w, M, N, K, e, per_wg, s, ln);
+          if (mt == 2) return launch_astat<2, 1>(a, w, M, N, K, e, per_wg, s, ln);
+          return launch_astat<4, 1>(a, w, M, N, K, e, per_wg, s, ln);
+        }
+      } else {
+        // rows per workgroup (16, 32 or 64, as far as the A tile fits in LDS) and strips per
+        // workgroup by the cost model
+        int pw[3] = {8, 8, 8};
+        const float c1 = astat_plan(1, M, N, K, &pw[0]);
+        const float c2 = K <= 2048 ? astat_plan(2, M, N, K, &pw[1]) : 1e30f;
+        const float c4 = K <= 1024 ? astat_plan(4, M, N, K, &pw[2]) : 1e30f;
+        if (c4 <= c2 && c4 <= c1) return launch_astat<4, 2>(a, w, M, N, K, e, pw[2], s, ln);
+        if (c2 <= c1) return launch_astat<2, 2>(a, w, M, N, K, e, pw[1], s, ln);
+        return launch_astat<1, 2>(a, w, M, N, K, e, pw[0], s, ln);
+      }
     }
     if (M >= 128 && tiles_x * tiles_y >= 96) {
       k_gemm_bf16_tiled<<<dim3(tiles_x, tiles_y), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);

@@ -452,7 +452,8 @@ def test_workload4_big_gad_batch8():
 def test_persistent_forward_is_bit_identical_to_staged_launches(name, B):
     rig = Rig(name, "bf16", 55, B=B, max_src=40, max_len=40, k_max=24)
     try:
-        assert rig.ctx.get_option(ad.AD_OPT_FUSED_ROWS) == min(128, B * 24), "persistent forward unavailable on this device"
+        assert rig.ctx.get_option(ad.AD_OPT_FUSED_ROWS) == 0          # one launch per stage unless asked otherwise
+        assert rig.ctx.get_option(ad.AD_OPT_FUSED_AVAILABLE) == 1, "persistent forward unavailable on this device"
         full = B * 24
         rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, full)
         srcs = _sources(rig.dims, 55, [30 - 7 * b for b in range(B)])
