@@ -28,6 +28,13 @@ HBM_PEAK = 8.0e12       # B/s, MI355X published
 MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 
 
+# HBM bytes per launch of the output-projection kernel at the headline shape (base model, 17..32
+# rows), from two rocprofv3 --pmc runs of this file (FETCH_SIZE 16411.8 KiB x 2.000, WRITE_SIZE
+# 543.2 KiB x 1.0; factors from k_calibration_copy's readings for a 256 MiB copy in the same runs;
+# profiles/bench_base_bs1_vocab_kernel_hbm_traffic.md)
+VOCAB_KERNEL_TRAFFIC_BYTES = int(16411.8 * 1024 * (262144.0 / 131089.0) + 543.2 * 1024)
+
+
 def decoder_stream_params(dims):
     """Parameters a verify forward streams: per decoder layer self-attn 4d^2, cross-attn q,o 2d^2,
     FFN 2dF; plus the output projection dV."""
@@ -43,6 +50,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bs32", action="store_true")
     ap.add_argument("--cpu-sentences", type=int, default=256)
+    ap.add_argument("--sentences", type=int, default=0,
+                    help="use only the first N sentences of the batch-1 workload (counter runs, where every "
+                         "launch is serialised); 0 = all")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one plain 256 MiB device copy (k_calibration_copy): the known-size "
+                         "launch a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading is scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -62,10 +75,19 @@ def main():
     K_MAX = 72
     conf = ad.make_config(dims, max_batch=32, max_src=64, max_len=64, k_max=K_MAX, dtype="bf16", special=SPECIAL)
     ctx = ad.Context(conf, w)
+    if args.calibration_copy:
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        ad.calibration_copy(b, a)
+        torch.cuda.synchronize()
+        del a, b
 
     # ---------------- batch 1: the headline workload ------------------------------------------
     n_sent = cfg1["n_sent"]
     srcs, max_out = draw_sources(cfg1, V)
+    if args.sentences > 0:
+        n_sent = min(n_sent, args.sentences)
+        srcs, max_out = srcs[:n_sent], max_out[:n_sent]
     greedy_out, guides = [], []
     t0 = time.perf_counter()
     for s, mo in zip(srcs, max_out):
@@ -110,7 +132,7 @@ def main():
     ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
     ctx.encode(ad.AD_VERIFIER, [srcs[j]], max_out=[max_out[j]])
     ctx.verify([draft])
-    staged_us, voc_us = ctx.time_verify_forward(50)
+    staged_us, voc_us, voc_b2b_us = ctx.time_verify_forward(50, back_to_back=True)
     ctx.set_option(ad.AD_OPT_FUSED_ROWS, fused_rows)
     # output projection + arg max: the [V, d] bf16 matrix once, the M x d bf16 rows once, the
     # per-row partial maxima written once
@@ -126,10 +148,12 @@ def main():
         # algorithmic bytes); timed alone, back to back, between two HIP events on its stream
         roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<2, true, 1> (output projection + arg max)", "rows": M1,
                     "achieved": voc_bytes / (voc_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                    "frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK, "traffic": None}
+                    "frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK, "traffic": VOCAB_KERNEL_TRAFFIC_BYTES}
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,
                   "hbm_frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "single_launch": bool(fused),
                   "staged_launches_us": staged_us, "staged_vocab_kernel_us": voc_us,
+                  "staged_vocab_kernel_back_to_back_us": voc_b2b_us,
+                  "staged_vocab_kernel_back_to_back_hbm_frac": voc_bytes / (voc_b2b_us * 1e-6) / HBM_PEAK,
                   "staged_vocab_kernel_hbm_frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK}
 
     # ---------------- batch 32 ---------------------------------------------------------------------

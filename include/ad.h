@@ -181,12 +181,23 @@ int ad_decode_gad(ad_ctx* ctx, const int32_t* src, const int32_t* src_len, int B
  * packed order (sequence by sequence).  Needs cfg.debug_logits; AD_ESTATE otherwise. */
 int ad_debug_logits(ad_ctx* ctx, float* logits, int rows_cap, int* rows);
 
-/* Re-launches the kernels of the last ad_verify forward `reps` times on the context's
- * stream without touching decode state (the appended cache rows are rewritten with the
- * same values) and reports the mean duration, by HIP events on that stream, of the whole
- * forward and of its output-projection/arg-max kernel (0 when the forward ran as one persistent
- * kernel).  For roofline measurements. */
-int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us);
+/* Re-launches the kernels of the last ad_verify forward on the context's stream without touching
+ * decode state (the appended cache rows are rewritten with the same values) and reports, by HIP
+ * events on that stream: forward_us = the whole forward, mean of `reps` forwards back to back;
+ * vocab_kernel_us = its output-projection/arg-max kernel, mean over `reps` forwards of one launch
+ * bracketed by two events (what a kernel trace reports for it); vocab_back_to_back_us (may be
+ * null) = the same kernel, `reps` launches back to back divided by reps (launch overheads of
+ * consecutive launches overlap).  Both kernel figures are 0 when the forward ran as one
+ * persistent kernel.  For roofline measurements. */
+int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us,
+                           double* vocab_back_to_back_us);
+
+/* Measurement aid, no part of the method: copies `bytes` (a multiple of 16) from src to dst, both
+ * device memory, with one plain kernel (16 bytes per lane per step) on `stream`.  A hardware
+ * memory-traffic counter read for this launch, whose traffic is known (`bytes` read, `bytes`
+ * written), gives the factor that turns the counter's reading for other kernels into bytes.
+ * Returns AD_OK or AD_EINVAL / AD_EDEVICE. */
+int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
 
 /* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
  * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; at most

@@ -24,7 +24,7 @@ EXPORTS = [
     "ad_weights_pack",
     "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
-    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option",
+    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy",
 ]
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
@@ -91,8 +91,11 @@ def lib():
     L.ad_decode_gad.restype = C.c_int
     L.ad_debug_logits.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int, C.POINTER(C.c_int)]
     L.ad_debug_logits.restype = C.c_int
-    L.ad_time_verify_forward.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.ad_time_verify_forward.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                         C.POINTER(C.c_double)]
     L.ad_time_verify_forward.restype = C.c_int
+    L.ad_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.ad_calibration_copy.restype = C.c_int
     L.ad_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]; L.ad_set_option.restype = C.c_int
     L.ad_get_option.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]; L.ad_get_option.restype = C.c_int
     L.ad_suffix_match.argtypes = [_I32P, C.c_int, _I32P, C.c_int, C.POINTER(C.c_int)]; L.ad_suffix_match.restype = C.c_int
@@ -182,6 +185,16 @@ def pack_weights_host(cfg: AdConfig, params: dict) -> np.ndarray:
 def pack_weights(cfg: AdConfig, params: dict, device="cuda"):
     import torch
     return torch.from_numpy(pack_weights_host(cfg, params)).to(device)
+
+
+def calibration_copy(dst, src, stream=None):
+    """Plain device copy of known size (torch tensors on the GPU, equal byte sizes, a multiple of
+    16): the launch that memory-traffic counters are calibrated against."""
+    import torch
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    _check(lib().ad_calibration_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(st)))
 
 
 class Context:
@@ -312,7 +325,7 @@ class Context:
         _check(self.L.ad_debug_logits(self.h, buf.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(rows)), self.h)
         return buf[:rows.value].copy()
 
-    def time_verify_forward(self, reps=20):
-        a, b = C.c_double(0), C.c_double(0)
-        _check(self.L.ad_time_verify_forward(self.h, reps, C.byref(a), C.byref(b)), self.h)
-        return a.value, b.value
+    def time_verify_forward(self, reps=20, back_to_back=False):
+        a, b, d = C.c_double(0), C.c_double(0), C.c_double(0)
+        _check(self.L.ad_time_verify_forward(self.h, reps, C.byref(a), C.byref(b), C.byref(d)), self.h)
+        return (a.value, b.value, d.value) if back_to_back else (a.value, b.value)

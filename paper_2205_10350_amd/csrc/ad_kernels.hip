@@ -652,6 +652,18 @@ void launch_layernorm(int dtype, const float* x, const float* g, const float* b,
   else k_layernorm<float><<<(M + 3) / 4, 256, 0, s>>>(x, g, b, M, d, y, (float*)ya);
 }
 
+// ------------------------------------------------------------------------------------- counter calibration copy
+__global__ __launch_bounds__(256) void k_calibration_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 16;
+  if (n == 0) return hipSuccess;
+  const int grid = (int)std::min<size_t>((n + 255) / 256, 256 * 32);
+  k_calibration_copy<<<grid, 256, 0, s>>>((const uint4*)src, (uint4*)dst, n);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------- arg max, second stage
 __global__ __launch_bounds__(256) void k_argmax_finish(const float* __restrict__ pv, const int* __restrict__ pi,
                                                        int M, int stride, int n_part, int* __restrict__ o_hat,
