@@ -14,10 +14,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest, ties to even
-  unsigned u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+__device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest, ties to even (the hardware conversion)
+  return __builtin_bit_cast(bf16_t, (__bf16)f);
 }
 // Memory access policy.  COH = false: ordinary cached accesses (data produced by an earlier
 // launch, or weights).  COH = true: the access carries the device-scope cache policy (relaxed
@@ -213,7 +211,9 @@ __device__ __forceinline__ void ln_stats4(const float4 (&xv)[NV], int d, float& 
   float s = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) { s += xv[j].x; s += xv[j].y; s += xv[j].z; s += xv[j].w; }
-  mean = wave_sum(s) / (float)d;
+  // d is a power of two here: multiplying by 1/d is the division, exactly
+  const float inv_d = 1.0f / (float)d;
+  mean = wave_sum(s) * inv_d;
   float v = 0.f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
@@ -222,7 +222,7 @@ __device__ __forceinline__ void ln_stats4(const float4 (&xv)[NV], int d, float& 
     t = xv[j].z - mean; v = fmaf(t, t, v);
     t = xv[j].w - mean; v = fmaf(t, t, v);
   }
-  rstd = 1.0f / sqrtf(wave_sum(v) / (float)d + 1e-5f);
+  rstd = __builtin_amdgcn_rsqf(fmaf(wave_sum(v), inv_d, 1e-5f));   // hardware reciprocal square root (1 ulp)
 }
 template <bool COH = false>
 __device__ __forceinline__ void ln_load_stats(const float* __restrict__ xr, int d, int lane, float (&xv)[32],

@@ -15,6 +15,9 @@
 #include "ad_device.h"
 
 namespace ad {
+#ifdef ASTAT_TUNE
+static int g_tune_per_wg = 0;
+#endif
 
 // ------------------------------------------------------------------------------------- embed
 // x[m] = E[tok[m]] * sqrt(d) + PE[pos[m]]
@@ -517,7 +520,10 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
       if (M <= 64 && astat_lds_bytes(mt, K) <= 150 * 1024) {
         // few rows: one strip per wave, workgroups of four strips until the chip is covered
         {
-          const int per_wg = 4 * std::max(1, (N / 16 + 4 * 384 - 1) / (4 * 384));
+          int per_wg = 4 * std::max(1, (N / 16 + 4 * 384 - 1) / (4 * 384));
+#ifdef ASTAT_TUNE
+          if (g_tune_per_wg > 0) per_wg = g_tune_per_wg;
+#endif
           if (mt == 1) return launch_astat<1, 1>(a, w, M, N, K, e, per_wg, s, ln);
           if (mt == 2) return launch_astat<2, 1>(a, w, M, N, K, e, per_wg, s, ln);
           return launch_astat<4, 1>(a, w, M, N, K, e, per_wg, s, ln);
