@@ -146,7 +146,7 @@ def main():
     else:
         # dominant kernel by bytes: the output projection + arg max (42 % of the forward's
         # algorithmic bytes); timed alone, back to back, between two HIP events on its stream
-        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<2, true, 1> (output projection + arg max)", "rows": M1,
+        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<1, true, 1> (output projection + arg max)", "rows": M1,
                     "achieved": voc_bytes / (voc_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                     "frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK, "traffic": VOCAB_KERNEL_TRAFFIC_BYTES}
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,

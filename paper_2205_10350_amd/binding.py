@@ -28,6 +28,7 @@ EXPORTS = [
 ]
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
+AD_OPT_PROJ_ATTENTION_ROWS = 2
 
 
 class AdConfig(C.Structure):

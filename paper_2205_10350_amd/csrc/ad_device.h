@@ -464,7 +464,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 // tiles or keys the call covers (keys a row does not see contribute exact zeros), so a row's
 // result does not depend on the shape of the block it is verified in.
 template <int DH, int NT, bool COH, bool STC>
-__device__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
+__device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
                                 const SeqDesc sd, int row_begin, int row_end, int h, int d, float scale,
                                 const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all) {
   constexpr int KS = DH / 32, CT = DH / 16;
@@ -563,7 +563,7 @@ __device__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __re
   }
 }
 template <int DH, bool COH, bool STC>
-__device__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
+__device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
                                 int row_begin, int row_end, int h, int d, float scale, unsigned* lds, int nk_all) {
   const int wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
@@ -592,7 +592,7 @@ __device__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __re
 }
 
 template <typename T, int DH, bool COH = false, bool STC = false>
-__device__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, const T* __restrict__ Vb,
+__device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, const T* __restrict__ Vb,
                            T* __restrict__ out, const SeqDesc sd, int row_begin, int row_end, int h, int d,
                            float scale, unsigned* lds, int nk_cap) {
   if constexpr (sizeof(T) == 2 && DH % 32 == 0) {
