@@ -16,7 +16,7 @@
 
 namespace ad {
 #ifdef ASTAT_TUNE
-static int g_tune_per_wg = 0;
+static int g_tune_per_wg = 0, g_tune_mt = 0, g_tune_print = 0;
 #endif
 
 // ------------------------------------------------------------------------------------- embed
@@ -426,11 +426,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
 // part (launch, staging the rows, drain) plus its units.  Strips per workgroup are a multiple of
 // eight (four waves, two strips each).
 static size_t astat_lds_bytes(int mt, int K) { return (size_t)mt * 16 * (K + 8) * 2 + 4 * (size_t)mt * 16 * 8; }
-static float astat_plan(int mt, int M, int N, int K, int* per_wg_out) {
+static float astat_plan(int mt, int M, int N, int K, bool with_ln, int* per_wg_out) {
   const int chunks = (M + mt * 16 - 1) / (mt * 16), n_strips = N / 16, halves = K / 512;
   const size_t lds = astat_lds_bytes(mt, K);
   const int per_cu = lds * 2 <= 160 * 1024 ? 2 : 1;
-  const float unit_us = 0.25f * mt + 0.15f, wg_us = 2.0f;
+  // staging: a wave brings in 4 * mt rows, one after the other when they go through LayerNorm
+  const float unit_us = 0.25f * mt + 0.15f, wg_us = 2.0f + 4 * mt * (with_ln ? 0.2f : 0.03f);
   float best = 1e30f;
   for (int per_wg = 8; per_wg <= 128; per_wg += 8) {
     const int groups = (n_strips + per_wg - 1) / per_wg;
@@ -532,9 +533,16 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
         // rows per workgroup (16, 32 or 64, as far as the A tile fits in LDS) and strips per
         // workgroup by the cost model
         int pw[3] = {8, 8, 8};
-        const float c1 = astat_plan(1, M, N, K, &pw[0]);
-        const float c2 = K <= 2048 ? astat_plan(2, M, N, K, &pw[1]) : 1e30f;
-        const float c4 = K <= 1024 ? astat_plan(4, M, N, K, &pw[2]) : 1e30f;
+        const float c1 = astat_plan(1, M, N, K, ln.x != nullptr, &pw[0]);
+        const float c2 = K <= 2048 ? astat_plan(2, M, N, K, ln.x != nullptr, &pw[1]) : 1e30f;
+        const float c4 = K <= 1024 ? astat_plan(4, M, N, K, ln.x != nullptr, &pw[2]) : 1e30f;
+#ifdef ASTAT_TUNE
+        if (g_tune_mt == 1) return launch_astat<1, 2>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
+        if (g_tune_mt == 2) return launch_astat<2, 2>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
+        if (g_tune_mt == 4) return launch_astat<4, 2>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
+        if (g_tune_mt == 11) return launch_astat<1, 1>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
+        if (g_tune_print) printf("  plan: c1 %.1f (pw %d) c2 %.1f (pw %d) c4 %.1f (pw %d)\n", c1, pw[0], c2, pw[1], c4, pw[2]);
+#endif
         if (c4 <= c2 && c4 <= c1) return launch_astat<4, 2>(a, w, M, N, K, e, pw[2], s, ln);
         if (c2 <= c1) return launch_astat<2, 2>(a, w, M, N, K, e, pw[1], s, ln);
         return launch_astat<1, 2>(a, w, M, N, K, e, pw[0], s, ln);
