@@ -29,6 +29,8 @@ EXPORTS = [
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
 AD_OPT_PROJ_ATTENTION_ROWS = 2
+AD_OPT_GRAPHS = 3
+AD_OPT_GRAPHS_CAPTURED = 4
 
 
 class AdConfig(C.Structure):
@@ -212,7 +214,10 @@ class Context:
         self.w_dr = pack_weights(cfg, drafter_params, device) if drafter_params is not None else None
         nbytes = workspace_bytes(cfg, drafter_params is not None)
         self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=device)
-        self.stream = torch.cuda.current_stream()
+        # a stream of the context's own (default priority): the null stream cannot be captured
+        # into graphs.  Everything queued so far (weights, workspace) is finished first.
+        torch.cuda.synchronize()
+        self.stream = torch.cuda.Stream(device=device)
         h = C.c_void_p()
         _check(self.L.ad_create(C.byref(cfg), C.c_void_p(self.w_ver.data_ptr()),
                                 C.c_void_p(self.w_dr.data_ptr()) if self.w_dr is not None else None,

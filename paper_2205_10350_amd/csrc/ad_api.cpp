@@ -6,7 +6,9 @@
 
 #include <algorithm>
 #include <chrono>
+#include <functional>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "ad_internal.h"
@@ -117,6 +119,7 @@ struct ad_ctx {
   hipStream_t stream = nullptr;
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr, ev3 = nullptr;
   int32_t* pin = nullptr;       // pinned staging, ints
+  int32_t* pin_dev = nullptr;   // the same buffer as the device addresses it (null: not mapped, use copies)
   size_t pin_ints = 0;
   std::string err;
   // host mirror of the decode state
@@ -139,6 +142,11 @@ struct ad_ctx {
   size_t fused_lds = 0;
   unsigned long long dev_base = 0, team_base[kMaxTeams] = {};
   bool last_fused = false;
+  // One launch per stage: the launches of a verify call (row assembly, forward, acceptance) are
+  // captured into a graph per call shape on the shape's second appearance and replayed after.
+  bool graphs_on = true;
+  std::unordered_map<unsigned long long, hipGraphExec_t> graphs;
+  std::unordered_map<unsigned long long, int> graph_seen;
   std::vector<int> last_k;       // k[b] of the last verify call
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
@@ -559,7 +567,12 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
     return fail(nullptr, AD_EDEVICE, m);
   };
   hipError_t e;
-  if ((e = hipHostMalloc((void**)&c->pin, c->pin_ints * 4, hipHostMallocDefault)) != hipSuccess) return bail("hipHostMalloc", e);
+  if ((e = hipHostMalloc((void**)&c->pin, c->pin_ints * 4, hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
+  {
+    void* dp = nullptr;
+    if (hipHostGetDevicePointer(&dp, c->pin, 0) == hipSuccess) c->pin_dev = (int32_t*)dp;
+    else (void)hipGetLastError();
+  }
   if ((e = hipEventCreate(&c->ev0)) != hipSuccess) return bail("hipEventCreate", e);
   if ((e = hipEventCreate(&c->ev1)) != hipSuccess) return bail("hipEventCreate", e);
   if ((e = hipEventCreate(&c->ev2)) != hipSuccess) return bail("hipEventCreate", e);
@@ -590,6 +603,7 @@ int ad_destroy(ad_ctx* c) {
   if (!c) return AD_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   if (c->pin) (void)hipHostFree(c->pin);
+  for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
   for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3})
     if (ev) (void)hipEventDestroy(ev);
   delete c;
@@ -667,6 +681,43 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   return AD_OK;
 }
 
+// Runs `launches` (kernel launches on the context's stream, nothing else) as a graph: replay if
+// this call shape has one, capture + instantiate + launch on the shape's second appearance.
+// false = nothing was launched, the caller launches eagerly.  Any failure switches graphs off
+// for the context (a stream that cannot be captured, e.g. the null stream, is such a failure).
+static bool run_as_graph(ad_ctx* c, unsigned long long key, const std::function<void()>& launches) {
+  if (!c->graphs_on) return false;
+  auto it = c->graphs.find(key);
+  if (it != c->graphs.end()) {
+    if (hipGraphLaunch(it->second, c->stream) == hipSuccess) return true;
+    (void)hipGetLastError();
+    c->graphs_on = false;
+    return false;
+  }
+  if (++c->graph_seen[key] < 2 || c->graphs.size() >= 512) return false;
+  if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+    (void)hipGetLastError();
+    c->graphs_on = false;
+    return false;
+  }
+  launches();
+  hipGraph_t g = nullptr;
+  hipGraphExec_t ge = nullptr;
+  hipError_t e = hipStreamEndCapture(c->stream, &g);
+  if (e == hipSuccess && g) e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+  if (g) (void)hipGraphDestroy(g);
+  if (e != hipSuccess || !ge) {
+    (void)hipGetLastError();
+    c->graphs_on = false;
+    return false;
+  }
+  c->graphs[key] = ge;
+  if (hipGraphLaunch(ge, c->stream) == hipSuccess) return true;
+  (void)hipGetLastError();
+  c->graphs_on = false;
+  return false;
+}
+
 int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
               int32_t* verified) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
@@ -693,29 +744,51 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   int32_t* h = c->pin;
   memcpy(h, k, (size_t)B * 4);
   for (int b = 0; b < B; ++b) memcpy(h + B + (size_t)b * km, draft + (size_t)b * km, (size_t)km * 4);
-  // the device copy of k and draft sits at k_dev = [k | draft] laid out for max_batch
-  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + B, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
+  bool fused = c->fused_rows > 0 && M <= c->fused_rows;
+  // One launch per stage: the two small kernels that need k and the draft read them where they
+  // are, in the pinned (device-visible) staging buffer, and the result is written there too: no
+  // copy operations around the forward.  The persistent kernel works on device copies at
+  // k_dev = [k | draft] laid out for max_batch.
+  const bool mapped = c->pin_dev != nullptr;
+  const int* k_src = mapped ? c->pin_dev : nullptr;
+  const int* draft_src = mapped ? c->pin_dev + B : nullptr;
+  if (fused || !mapped) {
+    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + B, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
+    k_src = c->at<int>(p.k_dev);
+    draft_src = c->at<int>(p.draft_dev);
+  }
   VerifyTables t = tables(c);
   c->fw_nseq = B;
   c->fw_max_rows = *std::max_element(k, k + B);
   c->last_nseq = B; c->last_max_rows = c->fw_max_rows;
-  launch_assemble_verify(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.len), c->at<int>(p.pending),
-                         c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
+  auto assemble = [&]() {
+    launch_assemble_verify(k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
+                           c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
+  };
+  if (fused) assemble();
   int32_t* res = c->pin + (size_t)B * (1 + km);
   int32_t* oh = res + 2 * B;
   unsigned long long* flags = (unsigned long long*)(c->pin + c->pin_ints - 2 * (kBarPlacement - kBarAbort + 2) - 2);
-  bool fused = c->fused_rows > 0 && M <= c->fused_rows;
   for (;;) {
     if (fused) {
       HIP_TRY(c, fused_verify_forward(c, k, M, B, true));
+      HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     } else {
-      verify_forward(c, M);
-      launch_accept(c->at<int>(p.k_dev), c->at<int>(p.draft_dev), km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
-                    cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
-                    c->at<int>(p.out), c->at<int>(p.result), c->stream);
+      auto launches = [&]() {
+        assemble();
+        verify_forward(c, M);
+        launch_accept(k_src, draft_src, km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
+                      cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
+                      c->at<int>(p.out), mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result), c->stream);
+      };
+      // every launch argument is a function of (rows, sequences, longest block, launch knobs) and
+      // of pointers fixed for the context's life
+      const unsigned long long key = (unsigned long long)M | ((unsigned long long)c->fw_max_rows << 16) |
+                                     ((unsigned long long)B << 24) | ((unsigned long long)c->fuse_attention_rows << 32);
+      if (!mapped || !run_as_graph(c, key, launches)) launches();
+      if (!mapped) HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     }
-    HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     flags[0] = 0; flags[kBarPlacement - kBarAbort] = 1; flags[kBarPlacement - kBarAbort + 1] = 1;
     const int place_word = kBarPlacement - kBarAbort + (int)(((c->dev_base >> 1) + 1) & 1);   // of the launch above
     if (fused)
@@ -914,6 +987,11 @@ int ad_set_option(ad_ctx* c, int option, int value) {
     c->fuse_attention_rows = value;
     return AD_OK;
   }
+  if (option == AD_OPT_GRAPHS) {
+    if (value != 0 && value != 1) return fail(c, AD_EINVAL, "AD_OPT_GRAPHS must be 0 or 1");
+    c->graphs_on = value != 0;
+    return AD_OK;
+  }
   if (option != AD_OPT_FUSED_ROWS) return fail(c, AD_EINVAL, "unknown option");
   if (value < 0 || value > c->plan.mv_cap) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, max_batch * k_max]");
   if (value > 0 && c->fused_grid == 0) return fail(c, AD_ESTATE, "the persistent forward is unavailable for this context");
@@ -926,6 +1004,8 @@ int ad_get_option(ad_ctx* c, int option, int* value) {
   if (option == AD_OPT_FUSED_ROWS) *value = c->fused_rows;
   else if (option == AD_OPT_FUSED_AVAILABLE) *value = c->fused_grid > 0 ? 1 : 0;
   else if (option == AD_OPT_PROJ_ATTENTION_ROWS) *value = c->fuse_attention_rows;
+  else if (option == AD_OPT_GRAPHS) *value = c->graphs_on ? 1 : 0;
+  else if (option == AD_OPT_GRAPHS_CAPTURED) *value = (int)c->graphs.size();
   else return fail(c, AD_EINVAL, "unknown option");
   return AD_OK;
 }

@@ -492,3 +492,57 @@ def test_persistent_forward_is_bit_identical_to_staged_launches(name, B):
         assert oi0 == oi1 == out_ref and si0["rows_verified"] == si1["rows_verified"]
     finally:
         rig.close()
+
+
+# ----------------------------------------------------------------------------------------------
+# Graph replay of a verify call's launches against the same launches made one by one.
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,B", [("tiny", 2), ("base", 1), ("base", 3)])
+def test_graph_replays_equal_eager_launches(name, B):
+    """Every replay of a captured call shape, with the library's own eager work (encode, other
+    shapes, synchronisations) between the replays, gives the bits the eager launches give."""
+    rig = Rig(name, "bf16", 77, B=B, max_src=40, max_len=40, k_max=24)
+    try:
+        assert rig.ctx.get_option(ad.AD_OPT_GRAPHS) == 1
+        V = rig.dims["vocab"]
+        srcs = _sources(rig.dims, 77, [28 - 5 * b for b in range(B)])
+        rig.ctx.set_option(ad.AD_OPT_GRAPHS, 0)
+        out_ref, _ = rig.ctx.decode_greedy(srcs)
+        # the same three-call script, six times: eager first, then with graphs (call shapes are
+        # captured on their second appearance and replayed on the later ones)
+        d1 = [out_ref[b][:4] for b in range(B)]
+        d2 = [[(out_ref[b][4] - 5 + 1) % (V - 5) + 5] + out_ref[b][5:9] for b in range(B)]   # wrong first token
+        d3 = [out_ref[b][5:9] for b in range(B)]
+
+        def script():
+            rig.ctx.encode(ad.AD_VERIFIER, srcs)
+            r = []
+            for d in (d1, d2, d3):
+                r.append(rig.ctx.verify(d, want_verified=True))
+                r.append(rig.ctx.debug_logits().view(np.uint32).copy())
+            r.append(rig.ctx.output())
+            return r
+
+        ref = script()
+        rig.ctx.set_option(ad.AD_OPT_GRAPHS, 1)
+        for rep in range(5):
+            got = script()
+            for x, y in zip(ref, got):
+                if isinstance(x, tuple):
+                    for u, v in zip(x, y):
+                        assert np.array_equal(u, v), rep
+                elif isinstance(x, np.ndarray):
+                    assert np.array_equal(x, y), rep
+                else:
+                    assert x == y, rep
+        assert rig.ctx.get_option(ad.AD_OPT_GRAPHS) == 1, "graph capture failed and was switched off"
+        assert rig.ctx.get_option(ad.AD_OPT_GRAPHS_CAPTURED) >= 2
+        # whole decodes through replays
+        guides = [edit_guide(g, 0.1, 5 + b, V) for b, g in enumerate(out_ref)]
+        for rep in range(2):
+            og, _ = rig.ctx.decode_greedy(srcs)
+            oi, _ = rig.ctx.decode_iad(srcs, guides)
+            assert og == out_ref and oi == out_ref
+    finally:
+        rig.close()
