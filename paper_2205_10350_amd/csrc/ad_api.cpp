@@ -610,78 +610,14 @@ int ad_destroy(ad_ctx* c) {
   return AD_OK;
 }
 
-int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, int B, const int32_t* max_out) {
-  int rc = check_batch(c, src, src_len, B);
-  if (rc != AD_OK) return rc;
-  if (model != AD_VERIFIER && model != AD_DRAFTER) return fail(c, AD_EINVAL, "model must be AD_VERIFIER or AD_DRAFTER");
-  if (model == AD_DRAFTER && !c->has_drafter) return fail(c, AD_ESTATE, "context has no drafter weights");
-  if (max_out)
-    for (int b = 0; b < B; ++b)
-      if (max_out[b] < 1 || max_out[b] > c->cfg.max_len) return fail(c, AD_EINVAL, "max_out outside [1, max_len]");
-  const ad_config& cf = c->cfg;
-  const Plan& p = c->plan;
-  const int d = cf.d_model, S = cf.max_src;
-  // one upload: src_len[B], max_out[B], src[B, max_src]
-  int32_t* h = c->pin;
-  int M = 0;
-  for (int b = 0; b < B; ++b) {
-    h[b] = src_len[b];
-    h[B + b] = max_out ? max_out[b] : cf.max_len;
-    M += src_len[b];
-  }
-  memcpy(h + 2 * B, src, (size_t)B * S * 4);
-  int* dev = c->at<int>(p.src_dev);
-  HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.src_len[model]), dev, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
-  VerifyTables t = tables(c);
-  c->fw_nseq = B;
-  c->fw_max_rows = *std::max_element(src_len, src_len + B);
-  launch_assemble_encoder(dev + 2 * B, S, dev, B, S, t, c->stream);
-  const ModelW& w = c->w[model];
-  embed_rows(c, w, M);
-  for (int l = 0; l < cf.enc_layers; ++l) {
-    const EncLayerW& L = w.enc[l];
-    // the sentence's own keys/values live in the packed temporaries: key row = packed row
-    Epi e{};
-    e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
-    e.out1 = c->at<void>(p.tk); e.out2 = c->at<void>(p.tv); e.row_dst = t.row_dst;
-    gemm_rows(c, L.self.wqkv, M, 3 * d, e);
-    launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att),
-                     t.self_desc, B, c->fw_max_rows, cf.n_heads, d / cf.n_heads, S, c->stream);
-    gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
-    ffn_block(c, L.ffn, L.ln2, M);
-  }
-  // cross-attention keys and values of every decoder layer: memory . [wk; wv]^T + [bk; bv]
-  flush_ln(c, M);
-  for (int l = 0; l < cf.dec_layers; ++l) {
-    const AttnW& a = w.dec[l].cross;
-    Epi e{};
-    e.mode = EPI_KV; e.d = d; e.bias = a.bqkv + d;
-    e.out1 = c->ws + p.mem_k[model] + l * p.mem_layer_stride;
-    e.out2 = c->ws + p.mem_v[model] + l * p.mem_layer_stride;
-    e.row_dst = t.row_dst2;
-    launch_gemm(cf.dtype, c->at<void>(p.xa), w_rows(c, a.wqkv, d, d), M, 2 * d, d, e, c->stream);
-  }
-  if (model == AD_VERIFIER) {
-    launch_reset_state(c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished), B, cf.bos, c->stream);
-    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.max_out), dev + B, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
-  }
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipGetLastError());
-  c->h_src_len[model].assign(src_len, src_len + B);
-  c->encoded[model] = true;
-  if (model == AD_VERIFIER) {
-    c->B = B;
-    for (int b = 0; b < B; ++b) {
-      c->h_len[b] = 0; c->h_finished[b] = 0; c->h_max_out[b] = max_out ? max_out[b] : cf.max_len;
-    }
-    c->encoded[AD_DRAFTER] = false;   // a new decode needs a fresh drafter memory
-    c->last_M = 0;
-  }
-  return AD_OK;
+// rows < 2^26, longest block < 2^14, sequences < 2^13, knob < 2^6 (the configuration check's
+// capacities): disjoint bit fields, bits 62 and 63 left to the caller
+static unsigned long long shape_key(int rows, int max_rows, int n_seq, int knob) {
+  return (unsigned long long)rows | ((unsigned long long)max_rows << 26) | ((unsigned long long)n_seq << 40) |
+         ((unsigned long long)knob << 53);
 }
-
-// Runs `launches` (kernel launches on the context's stream, nothing else) as a graph: replay if
+// Runs `launches` (kernel launches and device-to-device copies on the context's stream, nothing
+// else) as a graph: replay if
 // this call shape has one, capture + instantiate + launch on the shape's second appearance.
 // false = nothing was launched, the caller launches eagerly.  Any failure switches graphs off
 // for the context (a stream that cannot be captured, e.g. the null stream, is such a failure).
@@ -716,6 +652,82 @@ static bool run_as_graph(ad_ctx* c, unsigned long long key, const std::function<
   (void)hipGetLastError();
   c->graphs_on = false;
   return false;
+}
+
+int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, int B, const int32_t* max_out) {
+  int rc = check_batch(c, src, src_len, B);
+  if (rc != AD_OK) return rc;
+  if (model != AD_VERIFIER && model != AD_DRAFTER) return fail(c, AD_EINVAL, "model must be AD_VERIFIER or AD_DRAFTER");
+  if (model == AD_DRAFTER && !c->has_drafter) return fail(c, AD_ESTATE, "context has no drafter weights");
+  if (max_out)
+    for (int b = 0; b < B; ++b)
+      if (max_out[b] < 1 || max_out[b] > c->cfg.max_len) return fail(c, AD_EINVAL, "max_out outside [1, max_len]");
+  const ad_config& cf = c->cfg;
+  const Plan& p = c->plan;
+  const int d = cf.d_model, S = cf.max_src;
+  // one upload: src_len[B], max_out[B], src[B, max_src]
+  int32_t* h = c->pin;
+  int M = 0;
+  for (int b = 0; b < B; ++b) {
+    h[b] = src_len[b];
+    h[B + b] = max_out ? max_out[b] : cf.max_len;
+    M += src_len[b];
+  }
+  memcpy(h + 2 * B, src, (size_t)B * S * 4);
+  int* dev = c->at<int>(p.src_dev);
+  HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.src_len[model]), dev, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
+  VerifyTables t = tables(c);
+  c->fw_nseq = B;
+  c->fw_max_rows = *std::max_element(src_len, src_len + B);
+  // kernels and device-to-device copies of the encoder forward: replayed as a graph per call shape
+  auto launches = [&]() {
+    launch_assemble_encoder(dev + 2 * B, S, dev, B, S, t, c->stream);
+    const ModelW& w = c->w[model];
+    embed_rows(c, w, M);
+    for (int l = 0; l < cf.enc_layers; ++l) {
+      const EncLayerW& L = w.enc[l];
+      // the sentence's own keys/values live in the packed temporaries: key row = packed row
+      Epi e{};
+      e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
+      e.out1 = c->at<void>(p.tk); e.out2 = c->at<void>(p.tv); e.row_dst = t.row_dst;
+      gemm_rows(c, L.self.wqkv, M, 3 * d, e);
+      launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att),
+                       t.self_desc, B, c->fw_max_rows, cf.n_heads, d / cf.n_heads, S, c->stream);
+      gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
+      ffn_block(c, L.ffn, L.ln2, M);
+    }
+    // cross-attention keys and values of every decoder layer: memory . [wk; wv]^T + [bk; bv]
+    flush_ln(c, M);
+    for (int l = 0; l < cf.dec_layers; ++l) {
+      const AttnW& a = w.dec[l].cross;
+      Epi e{};
+      e.mode = EPI_KV; e.d = d; e.bias = a.bqkv + d;
+      e.out1 = c->ws + p.mem_k[model] + l * p.mem_layer_stride;
+      e.out2 = c->ws + p.mem_v[model] + l * p.mem_layer_stride;
+      e.row_dst = t.row_dst2;
+      launch_gemm(cf.dtype, c->at<void>(p.xa), w_rows(c, a.wqkv, d, d), M, 2 * d, d, e, c->stream);
+    }
+    if (model == AD_VERIFIER) {
+      launch_reset_state(c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished), B, cf.bos, c->stream);
+      (void)hipMemcpyAsync(c->at<int>(p.max_out), dev + B, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream);
+    }
+  };
+  const unsigned long long key = (1ull << 63) | ((unsigned long long)model << 62) | shape_key(M, c->fw_max_rows, B, 0);
+  if (!run_as_graph(c, key, launches)) launches();
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipGetLastError());
+  c->h_src_len[model].assign(src_len, src_len + B);
+  c->encoded[model] = true;
+  if (model == AD_VERIFIER) {
+    c->B = B;
+    for (int b = 0; b < B; ++b) {
+      c->h_len[b] = 0; c->h_finished[b] = 0; c->h_max_out[b] = max_out ? max_out[b] : cf.max_len;
+    }
+    c->encoded[AD_DRAFTER] = false;   // a new decode needs a fresh drafter memory
+    c->last_M = 0;
+  }
+  return AD_OK;
 }
 
 int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
@@ -784,8 +796,7 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
       };
       // every launch argument is a function of (rows, sequences, longest block, launch knobs) and
       // of pointers fixed for the context's life
-      const unsigned long long key = (unsigned long long)M | ((unsigned long long)c->fw_max_rows << 16) |
-                                     ((unsigned long long)B << 24) | ((unsigned long long)c->fuse_attention_rows << 32);
+      const unsigned long long key = shape_key(M, c->fw_max_rows, B, c->fuse_attention_rows);
       if (!mapped || !run_as_graph(c, key, launches)) launches();
       if (!mapped) HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     }
