@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "ad_device.h"
 
@@ -309,7 +310,10 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   int bi[NB];
 #pragma unroll
   for (int x = 0; x < NB; ++x) { bv[x] = -INFINITY; bi[x] = n_units > 0 ? (s_first << 4) + r : 0x7fffffff; }
-  for (int q = 0; q < n_units; ++q) {
+  // REFILL = false for the wave's last unit: nothing is fetched that nobody will use (the
+  // epilogue would wait for it)
+  auto unit = [&](auto refill_c, int q) {
+    constexpr bool REFILL = decltype(refill_c)::value;
     const int p = q / halves, k0 = (q - p * halves) << 9;
     const bool last = k0 + 512 == K;
     const int s0 = s_first + 4 * SP * p;
@@ -355,12 +359,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
         for (int j = 0; j < SP; ++j)
           acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b[j][u]), acc[j][t], 0, 0, 0);
       // rolling refill: the same step of the next unit
+      if constexpr (REFILL) {
 #pragma unroll
-      for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(wn[j] + u * 512);
+        for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(wn[j] + u * 512);
+      }
       // issue order per step: LDS reads, this step's MFMAs, the refills
       if (ur < 16) __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, SP * MT, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, SP, 0);
+      if constexpr (REFILL) __builtin_amdgcn_sched_group_barrier(0x020, SP, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     if (last) {
@@ -396,7 +402,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
           if (s0 + j < s_end) strip_epilogue<bf16_t, MT>(e, acc[j], MT, m0, (s0 + j) << 4, M, N, lane);
       }
     }
-  }
+  };
+  for (int q = 0; q + 1 < n_units; ++q) unit(std::true_type{}, q);
+  if (n_units > 0) unit(std::false_type{}, n_units - 1);
   if constexpr (AMAX) {
     // rows of 16 lanes reduce by lane moves, the four waves through LDS
     float* mv = (float*)(At + ROWS * ld);   // [4 waves][ROWS]
