@@ -204,16 +204,12 @@ int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* 
  * max_batch * k_max).  Default 0: one launch per stage always, the faster path at every size
  * measured.  Setting a positive value on a context where the persistent kernel is unavailable
  * (device, model shape) gives AD_ESTATE.  AD_OPT_FUSED_AVAILABLE (read only): 1 if it is
- * available.  AD_OPT_PROJ_ATTENTION_ROWS (0..16): in the launch-per-stage path, the q (k, v)
- * projection and the attention of a block run as one launch when no sequence of the call has more
- * rows than this and the call has at least 64 (sequence, head) pairs (bf16, heads of width 64
- * only; default 16; 0 = always two launches).  AD_OPT_GRAPHS (0/1, default 1): in the
+ * available.  AD_OPT_GRAPHS (0/1, default 1): in the
  * launch-per-stage path the launches of an ad_verify call are captured into a HIP graph per call
  * shape (rows, sequences, longest block) on the shape's second appearance and replayed afterwards
  * (at most 512 shapes); the library switches it off by itself when the context's stream cannot be
  * captured (the null stream cannot).  AD_OPT_GRAPHS_CAPTURED (read only): graphs held. */
-enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_PROJ_ATTENTION_ROWS = 2, AD_OPT_GRAPHS = 3,
-       AD_OPT_GRAPHS_CAPTURED = 4 };
+enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 

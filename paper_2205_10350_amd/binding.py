@@ -28,7 +28,6 @@ EXPORTS = [
 ]
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
-AD_OPT_PROJ_ATTENTION_ROWS = 2
 AD_OPT_GRAPHS = 3
 AD_OPT_GRAPHS_CAPTURED = 4
 

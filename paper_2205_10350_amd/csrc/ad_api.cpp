@@ -135,7 +135,6 @@ struct ad_ctx {
   // persistent fused forward (bf16)
   int fused_rows = 0;            // largest M it takes; 0 = off
   // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
-  int fuse_attention_rows = 16;   // projection + attention as one launch for sequences of at most this many rows
   const LnW* ln_pending = nullptr;
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
   int fused_grid = 0, fused_stages = 0, fused_teams = 0;
@@ -212,26 +211,6 @@ static int gemm_rows(ad_ctx* c, const void* W, int M, int N, const Epi& e) {
   return launch_gemm(c->cfg.dtype, c->at<void>(p.xa), W, M, N, c->cfg.d_model, e, c->stream, ln);
 }
 
-// q (np = 1) or q, k, v (np = 3) projection of the current rows and the attention over (K, V), as
-// one launch where the shape allows (bf16, heads of width 64, few rows per sequence); false = not
-// launched, the caller takes the two-launch path.  Consumes a pending LayerNorm like gemm_rows.
-static bool proj_attention(ad_ctx* c, int np, const void* W, const Epi& e, const void* K, const void* V,
-                           const SeqDesc* desc, int max_keys) {
-  const Plan& p = c->plan;
-  const int d = c->cfg.d_model, H = c->cfg.n_heads;
-  if (c->cfg.dtype != AD_BF16 || d != 64 * H || c->fw_max_rows > c->fuse_attention_rows) return false;
-  // one workgroup per (sequence, head): worth it once those cover a good part of the chip
-  // (measured: a gain from 8 sequences x 8 heads on, none for a single sequence)
-  if (c->fw_nseq * H < 64) return false;
-  LnA ln{};
-  if (c->ln_pending) { ln.x = c->at<float>(p.s); ln.g = c->ln_pending->g; ln.b = c->ln_pending->b; ln.y = c->at<float>(p.x); }
-  if (!launch_proj_attention(np, c->at<void>(p.xa), W, d, e, ln, c->at<void>(p.q), K, V, c->at<void>(p.att), desc,
-                             c->fw_nseq, c->fw_max_rows, H, max_keys, c->stream))
-    return false;
-  c->ln_pending = nullptr;
-  return true;
-}
-
 static void ffn_block(ad_ctx* c, const FfnW& f, const LnW& ln, int M) {
   const Plan& p = c->plan;
   const int d = c->cfg.d_model, F = c->cfg.d_ffn;
@@ -249,11 +228,9 @@ static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, voi
   VerifyTables t = tables(c);
   Epi e{};
   e.mode = EPI_QKV; e.d = d; e.bias = a.bqkv; e.out0 = c->at<void>(p.q); e.out1 = Kl; e.out2 = Vl; e.row_dst = t.row_dst;
-  if (!proj_attention(c, 3, a.wqkv, e, Kl, Vl, t.self_desc, max_keys)) {
-    gemm_rows(c, a.wqkv, M, 3 * d, e);
-    launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.self_desc, c->fw_nseq, c->fw_max_rows,
-                     H, d / H, max_keys, c->stream);
-  }
+  gemm_rows(c, a.wqkv, M, 3 * d, e);
+  launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.self_desc, c->fw_nseq, c->fw_max_rows,
+                   H, d / H, max_keys, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
 
@@ -263,11 +240,9 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
   VerifyTables t = tables(c);
   Epi e{};
   e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
-  if (!proj_attention(c, 1, a.wqkv, e, Km, Vm, t.cross_desc, c->cfg.max_src)) {
-    gemm_rows(c, a.wqkv, M, d, e);
-    launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
-                     c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
-  }
+  gemm_rows(c, a.wqkv, M, d, e);
+  launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
+                   c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
 
@@ -794,9 +769,9 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
                       cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
                       c->at<int>(p.out), mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result), c->stream);
       };
-      // every launch argument is a function of (rows, sequences, longest block, launch knobs) and
+      // every launch argument is a function of (rows, sequences, longest block) and
       // of pointers fixed for the context's life
-      const unsigned long long key = shape_key(M, c->fw_max_rows, B, c->fuse_attention_rows);
+      const unsigned long long key = shape_key(M, c->fw_max_rows, B, 0);
       if (!mapped || !run_as_graph(c, key, launches)) launches();
       if (!mapped) HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     }
@@ -993,11 +968,6 @@ int ad_decode_gad(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, 
 
 int ad_set_option(ad_ctx* c, int option, int value) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
-  if (option == AD_OPT_PROJ_ATTENTION_ROWS) {
-    if (value < 0 || value > 16) return fail(c, AD_EINVAL, "AD_OPT_PROJ_ATTENTION_ROWS must be in [0, 16]");
-    c->fuse_attention_rows = value;
-    return AD_OK;
-  }
   if (option == AD_OPT_GRAPHS) {
     if (value != 0 && value != 1) return fail(c, AD_EINVAL, "AD_OPT_GRAPHS must be 0 or 1");
     c->graphs_on = value != 0;
@@ -1014,7 +984,6 @@ int ad_get_option(ad_ctx* c, int option, int* value) {
   if (!value) return fail(c, AD_EINVAL, "null pointer");
   if (option == AD_OPT_FUSED_ROWS) *value = c->fused_rows;
   else if (option == AD_OPT_FUSED_AVAILABLE) *value = c->fused_grid > 0 ? 1 : 0;
-  else if (option == AD_OPT_PROJ_ATTENTION_ROWS) *value = c->fuse_attention_rows;
   else if (option == AD_OPT_GRAPHS) *value = c->graphs_on ? 1 : 0;
   else if (option == AD_OPT_GRAPHS_CAPTURED) *value = (int)c->graphs.size();
   else return fail(c, AD_EINVAL, "unknown option");

@@ -149,11 +149,6 @@ void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, c
 int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, const Epi& e, hipStream_t s,
                 const LnA& ln = LnA{}, bool* a_written = nullptr);
 // one attention problem per descriptor (n_seq of them, at most max_rows query rows each)
-// projection of the rows onto q (np = 1) or q, k, v (np = 3) of every head and the attention, one
-// launch; returns false (nothing launched) where the shape does not allow it
-bool launch_proj_attention(int np, const void* A, const void* W, int K, const Epi& e, const LnA& ln, const void* q,
-                           const void* Kb, const void* Vb, void* out, const SeqDesc* desc, int n_seq, int max_rows,
-                           int H, int max_keys, hipStream_t s);
 void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
                       int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s);
 // y = LayerNorm(x) * g + b -> y (fp32) and ya (storage type)

@@ -525,13 +525,16 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
     const int tiles_x = (N / 16 + 7) / 8, tiles_y = (M + 127) / 128;
     if (K <= 4096 && K % 512 == 0) {
       const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
-      // Few rows (measured: up to 64 for the wide output projection, up to 256 for the layer
+      // Few rows (measured: up to 64 for the wide output projection, up to 768 for the layer
       // GEMMs): latency decides, so 16 rows per workgroup, one strip per wave, workgroups of four
-      // strips until the chip is covered; more rows are more row chunks of the same shape.
+      // strips until the chip is covered (at most about 512 workgroups for the layer GEMMs); more
+      // rows are more row chunks of the same shape.
       const int mt = 1;
-      if ((M <= 64 || (M <= 256 && N <= 4096)) && astat_lds_bytes(mt, K) <= 150 * 1024) {
+      if ((M <= 64 || (M <= 768 && N <= 4096)) && astat_lds_bytes(mt, K) <= 150 * 1024) {
         {
-          int per_wg = 4 * std::max(1, (N / 16 + 4 * 384 - 1) / (4 * 384));
+          const int n_strips = N / 16, chunks = (M + 15) / 16;
+          int per_wg = 4 * std::max(1, (n_strips + 4 * 384 - 1) / (4 * 384));
+          if (N <= 4096) per_wg = 4 * std::max(1, (n_strips * chunks + 4 * 512 - 1) / (4 * 512));
 #ifdef ASTAT_TUNE
           if (g_tune_per_wg > 0) per_wg = g_tune_per_wg;
 #endif
@@ -616,119 +619,6 @@ void launch_attention(int dtype, const void* q, const void* K, const void* V, vo
   if (n_seq <= 0 || max_rows <= 0) return;
   if (dtype == AD_BF16) attention_dispatch<bf16_t>(q, K, V, out, desc, n_seq, max_rows, H, dh, max_keys, s);
   else attention_dispatch<float>(q, K, V, out, desc, n_seq, max_rows, H, dh, max_keys, s);
-}
-
-// ------------------------------------------------------------------------------------- projection + attention, one launch
-// One workgroup per (sequence, head of width 64): it projects the sequence's rows onto the
-// head's 64 columns of q (NP = 1: cross-attention, keys and values given) or of q, k and v
-// (NP = 3: self-attention; k and v rows go to the cache), exactly as the GEMM kernel above would
-// (A rows staged in LDS, through LayerNorm if asked; wave w owns strip w of each projection; k
-// ascending, 32 at a time, one accumulator; the same epilogue), and then runs attn_block on what
-// it has just stored.  Saves a launch boundary per attention block; the values are those of the
-// two separate launches.
-template <int MT, int NP>
-__global__ __launch_bounds__(256) void k_proj_attention(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, int N,
-                                                        int K, Epi e, LnA ln, const bf16_t* __restrict__ q,
-                                                        const bf16_t* __restrict__ Kb, const bf16_t* __restrict__ Vb,
-                                                        bf16_t* __restrict__ out, const SeqDesc* __restrict__ desc,
-                                                        float scale, int nk_cap) {
-  constexpr int DH = 64;
-  extern __shared__ uint4 pa_lds[];
-  const SeqDesc sd = desc[blockIdx.x];
-  if (sd.nq <= 0) return;
-  const int h = blockIdx.y, d = K;
-  bf16_t* At = (bf16_t*)pa_lds;   // [MT*16][K + 8], then the attention's LDS
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, kq = lane >> 4;
-  const int ld = K + 8, halves = K >> 9;
-  const int m0 = sd.q_row0, m_end = sd.q_row0 + sd.nq;   // rows of this sequence (nq <= MT*16, checked by the host)
-  const int n_units = NP * halves;
-  auto unit_ptr = [&](int u) {
-    u = min(u, n_units - 1);
-    const int p = u / halves, k0 = (u - p * halves) << 9;
-    const int strip = p * (d >> 4) + h * (DH / 16) + wave;
-    return W + ((size_t)(strip << 4) * K + (size_t)k0 * 16 + lane * 8);
-  };
-  uint4 b[16];
-  {
-    const bf16_t* w = unit_ptr(0);
-#pragma unroll
-    for (int u = 0; u < 16; ++u) b[u] = *(const uint4*)(w + u * 512);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  if (ln.x) {
-    if (K == 512) astat_stage_ln<2, 8>(ln, At, ld, wave * MT * 4, MT * 4, m0, m_end, lane, h == 0);
-    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, m_end, lane, h == 0);
-  } else {
-    for (int hh = 0; hh < halves; ++hh) {
-      uint4 av[MT * 4];
-#pragma unroll
-      for (int i = 0; i < MT * 4; ++i)
-        av[i] = *(const uint4*)(A + (size_t)min(m0 + wave * MT * 4 + i, m_end - 1) * K + hh * 512 + lane * 8);
-#pragma unroll
-      for (int i = 0; i < MT * 4; ++i) *(uint4*)(At + (wave * MT * 4 + i) * ld + hh * 512 + lane * 8) = av[i];
-    }
-  }
-  __syncthreads();
-  const bf16_t* a_lane = At + r * ld + kq * 8;
-  f32x4 acc[MT];
-  for (int u = 0; u < n_units; ++u) {
-    const int p = u / halves, k0 = (u - p * halves) << 9;
-    const bf16_t* wn = unit_ptr(u + 1);
-    if (k0 == 0) {
-#pragma unroll
-      for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-    const int n0 = p * d + h * DH + wave * 16;
-    const bool last = k0 + 512 == K;
-    EpiRegs<MT> g;
-    if (last) epi_preload<MT>(e, MT, m0, n0, m_end, N, lane, g);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      uint4 af[MT];
-#pragma unroll
-      for (int t = 0; t < MT; ++t) af[t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * s);
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, b[s]), acc[t], 0, 0, 0);
-      b[s] = *(const uint4*)(wn + s * 512);   // rolling refill: the same step of the next unit
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (last) epi_apply<bf16_t, MT>(e, acc, g, MT, m0, n0, m_end, N, lane);
-  }
-  __syncthreads();   // the head's q (and k, v) rows are in memory, visible to the whole workgroup
-  unsigned* att_lds = (unsigned*)(At + MT * 16 * ld);
-  attn_block<bf16_t, DH>(q, Kb, Vb, out, sd, 0, sd.nq, h, d, scale, att_lds, nk_cap);
-}
-// true if the launch was made (bf16, head width 64, width 512 or 1024, at most 16 rows per sequence)
-bool launch_proj_attention(int np, const void* A, const void* W, int K, const Epi& e, const LnA& ln, const void* q,
-                           const void* Kb, const void* Vb, void* out, const SeqDesc* desc, int n_seq, int max_rows,
-                           int H, int max_keys, hipStream_t s) {
-  if (n_seq <= 0 || max_rows <= 0) return true;
-  if ((K != 512 && K != 1024) || H * 64 != K || max_rows > 16) return false;   // one 16-row tile per sequence
-  const size_t a_bytes = (size_t)16 * (K + 8) * 2;
-  const size_t lds = a_bytes + attn_lds_bytes(max_keys, 64, 2, 4);
-  if (lds > 150 * 1024) return false;
-  const float scale = 1.0f / sqrtf(64.0f);
-  const int N = np * K;
-  dim3 g(n_seq, H);
-#define AD_PA(MT, NP)                                                                                                  \
-  do {                                                                                                                 \
-    static size_t set_for = 0;                                                                                         \
-    if (lds > set_for) {                                                                                               \
-      (void)hipFuncSetAttribute((const void*)k_proj_attention<MT, NP>, hipFuncAttributeMaxDynamicSharedMemorySize,     \
-                                (int)lds);                                                                             \
-      set_for = lds;                                                                                                   \
-    }                                                                                                                  \
-    k_proj_attention<MT, NP><<<g, 256, lds, s>>>((const bf16_t*)A, (const bf16_t*)W, N, K, e, ln, (const bf16_t*)q,    \
-                                                 (const bf16_t*)Kb, (const bf16_t*)Vb, (bf16_t*)out, desc, scale,      \
-                                                 max_keys);                                                            \
-  } while (0)
-  if (np == 3) AD_PA(1, 3);
-  else AD_PA(1, 1);
-#undef AD_PA
-  return true;
 }
 
 // ------------------------------------------------------------------------------------- LayerNorm
