@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ad_internal.h"
 
 namespace ad {
@@ -466,18 +468,25 @@ __device__ __forceinline__ float row16_sum(float v) {
 template <int DH, int NT, bool COH, bool STC>
 __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
                                 const SeqDesc sd, int row_begin, int row_end, int h, int d, float scale,
-                                const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all) {
+                                const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all,
+                                const uint4 (&qf_pre)[DH / 32], const uint4 (&kf_pre)[4][DH / 32]) {
   constexpr int KS = DH / 32, CT = DH / 16;
   const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 15, kq = lane >> 4;
   const int n_tiles = (row_end - row_begin + 15) >> 4;
-  for (int rt = wave; rt < n_tiles; rt += waves) {
+  // pre_c: the wave's first tile, whose query fragments and first four key tiles were requested
+  // before the values were staged (attn_preload)
+  auto tile = [&](auto pre_c, int rt) {
+    constexpr bool PRE = decltype(pre_c)::value;
     const int row0 = row_begin + rt * 16;
     const int tile_end = min(row0 + 16, row_end);
     const int nk_tile = sd.causal ? sd.nk_base + tile_end : sd.nk_base;   // keys the tile's last row sees
     const int nt = (nk_tile + 15) >> 4, nb = (nk_tile + 31) >> 5;
     uint4 qf[KS];
-    {
+    if constexpr (PRE) {
+#pragma unroll
+      for (int s = 0; s < KS; ++s) qf[s] = qf_pre[s];
+    } else {
       const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row0 + r, row_end - 1)) * d + h * DH + kq * 8;
 #pragma unroll
       for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
@@ -490,9 +499,14 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       for (int jj = 0; jj < 4; ++jj) {
         const int j = j0 + jj;
         if (j < NT && j < nt) {
-          const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
+          if (PRE && j0 == 0) {
 #pragma unroll
-          for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+            for (int s = 0; s < KS; ++s) kf[jj][s] = kf_pre[jj][s];
+          } else {
+            const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+          }
         }
       }
 #pragma unroll
@@ -560,6 +574,35 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       }
     }
     __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the wave's next rows
+  };
+  if (wave < n_tiles) tile(std::true_type{}, wave);
+  for (int rt = wave + waves; rt < n_tiles; rt += waves) tile(std::false_type{}, rt);
+}
+// Query fragments and the first four key tiles of the wave's first 16-row tile (what
+// attn_tiles_mfma takes as qf_pre / kf_pre): same addresses, same clamping.
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_preload(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, const SeqDesc sd,
+                                             int row_begin, int row_end, int h, int d, int nk_all,
+                                             uint4 (&qf)[DH / 32], uint4 (&kf)[4][DH / 32]) {
+  constexpr int KS = DH / 32;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
+  const int n_tiles = (row_end - row_begin + 15) >> 4;
+  if (wave >= n_tiles) return;
+  const int row0 = row_begin + wave * 16;
+  const int tile_end = min(row0 + 16, row_end);
+  const int nk_tile = sd.causal ? sd.nk_base + tile_end : sd.nk_base;
+  const int nt = (nk_tile + 15) >> 4;
+  const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row0 + r, row_end - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+  for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j < nt) {
+      const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) kf[j][s] = ldg16<COH>(kp + 32 * s);
+    }
   }
 }
 template <int DH, bool COH, bool STC>
@@ -570,6 +613,10 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
   const int nkp = (nk_all + 31) & ~31, ldv = nkp + 8;
   bf16_t* Vt = (bf16_t*)lds;                      // [DH][ldv]: Vt[c][t] = V[t][c]
   bf16_t* Pw = Vt + DH * ldv + wave * 16 * ldv;   // this wave's probability tile [16][ldv]
+  // the first tile's operands of the score product are requested before the values are staged:
+  // the two fetch latencies overlap
+  uint4 qf_pre[DH / 32], kf_pre[4][DH / 32];
+  attn_preload<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, qf_pre, kf_pre);
   {
     constexpr int G = DH / 8;   // 16-byte pieces per key row
     const bf16_t* vg = Vb + (size_t)sd.kv_row0 * d + h * DH;
@@ -585,9 +632,9 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
     }
   }
   __syncthreads();
-  if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all);
-  else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all);
-  else attn_tiles_mfma<DH, 16, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all);
+  if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre);
+  else attn_tiles_mfma<DH, 16, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre);
   __syncthreads();   // LDS is free for the next call
 }
 
