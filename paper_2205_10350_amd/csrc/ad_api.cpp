@@ -441,7 +441,8 @@ static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bo
 
 // The verify forward over the M packed rows the tables describe.  ev (optional) brackets the
 // output-projection kernel.
-static void verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr) {
+// finish = false: the caller finishes the arg max itself (n_part partials per row are returned)
+static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr, bool finish = true) {
   const Plan& p = c->plan;
   const ModelW& w = c->w[AD_VERIFIER];
   embed_rows(c, w, M);
@@ -458,7 +459,8 @@ static void verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent
   c->ln_pending = nullptr;
   const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), M, c->ln_vocab);
   if (ev_b) (void)hipEventRecord(ev_b, c->stream);
-  vocab_finish(c, M, n_part);
+  if (finish) vocab_finish(c, M, n_part);
+  return n_part;
 }
 
 static int check_batch(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B) {
@@ -764,10 +766,11 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
     } else {
       auto launches = [&]() {
         assemble();
-        verify_forward(c, M);
-        launch_accept(k_src, draft_src, km, c->at<int>(p.o_hat), t.row_start, B, cf.eos,
-                      cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
-                      c->at<int>(p.out), mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result), c->stream);
+        const int n_part = verify_forward(c, M, nullptr, nullptr, false);
+        launch_argmax_accept(c->at<float>(p.part_val), c->at<int>(p.part_idx), p.n_strips, n_part, c->at<int>(p.o_hat),
+                             c->at<float>(p.o_val), k_src, draft_src, km, t.row_start, B, cf.eos, cf.max_len,
+                             c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
+                             c->at<int>(p.out), mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result), c->stream);
       };
       // every launch argument is a function of (rows, sequences, longest block) and
       // of pointers fixed for the context's life

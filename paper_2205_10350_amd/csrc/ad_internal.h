@@ -170,6 +170,11 @@ struct VerifyTables {
 void launch_assemble_verify(const int* k, const int* draft, int k_max, const int* len, const int* pending,
                             const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s);
 // Longest-prefix match, acceptance, truncation and rollback for every sequence.
+// second stage of the arg max (as launch_argmax_finish) and acceptance in one launch
+void launch_argmax_accept(const float* part_val, const int* part_idx, int stride, int n_part, int* o_hat, float* o_val,
+                          const int* k, const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
+                          const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
+                          hipStream_t s);
 void launch_accept(const int* k, const int* draft, int k_max, const int* o_hat, const int* row_start,
                    int B, int eos, int max_len, const int* max_out, int* len, int* pending, int* finished,
                    int* out, int* result /* [B,2]: n_accept, last token */, hipStream_t s);
