@@ -175,9 +175,6 @@ void launch_argmax_accept(const float* part_val, const int* part_idx, int stride
                           const int* k, const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
                           hipStream_t s);
-void launch_accept(const int* k, const int* draft, int k_max, const int* o_hat, const int* row_start,
-                   int B, int eos, int max_len, const int* max_out, int* len, int* pending, int* finished,
-                   int* out, int* result /* [B,2]: n_accept, last token */, hipStream_t s);
 // Row tables for the encoder (rows = source tokens) and for the drafter (prefix + masks).
 void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
                              hipStream_t s);

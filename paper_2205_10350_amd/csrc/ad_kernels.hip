@@ -852,36 +852,8 @@ void launch_draft_scatter(const int* o_hat, const int* finished, int B, int k, i
 // differs the whole block is accepted).  Appends o_hat_1..o_hat_c cut after the first [EOS] and
 // at the output limit; the cache keeps one row per appended token (len += n), everything past
 // it is dead and overwritten by the next call.
-__global__ void k_accept(const int* __restrict__ k, const int* __restrict__ draft, int k_max,
-                         const int* __restrict__ o_hat, const int* __restrict__ row_start, int B, int eos,
-                         int max_len, const int* __restrict__ max_out, int* __restrict__ len,
-                         int* __restrict__ pending, int* __restrict__ finished, int* __restrict__ out,
-                         int* __restrict__ result) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  const int kb = k[b];
-  if (kb == 0) { result[2 * b] = 0; result[2 * b + 1] = 0; return; }
-  const int r0 = row_start[b];
-  int c = kb;
-  for (int i = 0; i < kb; ++i)
-    if (draft[b * k_max + i] != o_hat[r0 + i]) { c = i + 1; break; }
-  const int L = len[b], lim = max_out[b];
-  int n = 0, last = 0;
-  for (int i = 0; i < c; ++i) {
-    if (L + n >= lim) break;
-    last = o_hat[r0 + i];
-    out[b * max_len + L + n] = last;
-    ++n;
-    if (last == eos) break;
-  }
-  len[b] = L + n;
-  if (n > 0) pending[b] = last;
-  finished[b] = (n > 0 && last == eos) || (L + n >= lim);
-  result[2 * b] = n;
-  result[2 * b + 1] = last;
-}
-// The same after finishing the arg max itself: one workgroup per sequence; its waves reduce the
-// partials of the sequence's rows (argmax_row, as k_argmax_finish does), then one thread accepts.
+// One workgroup per sequence: its waves finish the arg max of the sequence's rows (argmax_row over
+// the partials, as k_argmax_finish does), then one thread accepts.
 __global__ __launch_bounds__(256) void k_argmax_accept(const float* __restrict__ pv, const int* __restrict__ pi, int stride,
                                                        int n_part, int* __restrict__ o_hat, float* __restrict__ o_val,
                                                        const int* __restrict__ k, const int* __restrict__ draft, int k_max,
@@ -933,13 +905,6 @@ void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part
   k_argmax_accept<<<B, 256, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
                                     max_out, len, pending, finished, out, result);
 }
-void launch_accept(const int* k, const int* draft, int k_max, const int* o_hat, const int* row_start, int B, int eos,
-                   int max_len, const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                   hipStream_t s) {
-  k_accept<<<(B + 63) / 64, 64, 0, s>>>(k, draft, k_max, o_hat, row_start, B, eos, max_len, max_out, len, pending,
-                                        finished, out, result);
-}
-
 __global__ void k_reset_state(int* len, int* pending, int* finished, int B, int bos) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
