@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bs32", action="store_true")
+    ap.add_argument("--no-gad", action="store_true", help="skip the block-drafter workloads 3 and 4")
     ap.add_argument("--cpu-sentences", type=int, default=256)
     ap.add_argument("--sentences", type=int, default=0,
                     help="use only the first N sentences of the batch-1 workload (counter runs, where every "
@@ -65,7 +66,7 @@ def main():
     import numpy as np
     import torch
     import paper_2205_10350_amd as ad
-    from ad_inputs import CONFIGS, SPECIAL, draw_sources, edit_guide, init_weights, model_dims
+    from ad_inputs import CONFIGS, SPECIAL, draw_sources, edit_guide, init_weights, model_dims, positional_draft
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg1, cfg2 = CONFIGS[1], CONFIGS[2]
@@ -203,6 +204,64 @@ def main():
                 "staged_vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
     ctx.close()
 
+    # ---------------- draft-and-verify with the block drafter (workloads 3 and 4) ---------------------
+    # The drafter forward runs and is timed inside every iteration; its output is replaced by a
+    # positional draft with substitutions at the workload's rate (random weights draft nothing useful).
+    gad = None
+    if not args.no_gad:
+        gad = {}
+        for wl, n_take, kw in ((3, 64, dict(max_batch=1, max_src=80, max_len=80)),
+                               (4, 16, dict(max_batch=8, max_src=512, max_len=128))):
+            cfgw = CONFIGS[wl]
+            dimsw = model_dims(cfgw["model"])
+            ww = init_weights(dimsw, cfgw["seed"])
+            wd = init_weights(dimsw, cfgw["seed"] + 7)
+            confw = ad.make_config(dimsw, k_max=cfgw["k"], dtype="bf16", special=SPECIAL, **kw)
+            cx = ad.Context(confw, ww, wd)
+            srcw, mow = draw_sources(cfgw, dimsw["vocab"], n_sent=n_take)
+            Bw = cfgw["batch"]
+            groups = [(srcw[i:i + Bw], mow[i:i + Bw]) for i in range(0, len(srcw), Bw)]
+            refs, drafts = [], []
+            cx.decode_greedy(groups[0][0], max_out=groups[0][1])   # warm
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for ss, mo in groups:
+                o, _ = cx.decode_greedy(ss, max_out=mo)
+                refs.append(o)
+            torch.cuda.synchronize()
+            t_gr = time.perf_counter() - t0
+            for gi, o in enumerate(refs):
+                drafts.append([positional_draft(g, cfgw["rate"], cfgw["seed"] + gi * Bw + b, dimsw["vocab"])[0]
+                               for b, g in enumerate(o)])
+            cx.decode_gad(groups[0][0], cfgw["k"], use_drafter=True, draft_override=drafts[0], max_out=groups[0][1])   # warm
+            torch.cuda.synchronize()
+            tk = it = 0
+            t0 = time.perf_counter()
+            for (ss, mo), D, ref in zip(groups, drafts, refs):
+                o, st = cx.decode_gad(ss, cfgw["k"], use_drafter=True, draft_override=D, max_out=mo)
+                assert o == ref, "draft-and-verify output differs from greedy"
+                tk += sum(len(x) for x in o); it += st["iterations"]
+            torch.cuda.synchronize()
+            t_gad = time.perf_counter() - t0
+            gad[f"workload{wl}"] = {"model": cfgw["model"], "batch": Bw, "sentences": len(srcw), "k": cfgw["k"],
+                                    "tokens_per_s": tk / t_gad, "greedy_tokens_per_s": tk / t_gr,
+                                    "speedup_vs_greedy": t_gr / t_gad, "iterations": it,
+                                    "mean_tokens_per_iteration": tk / max(1, it) / Bw}
+            cx.close()
+
+    # ---------------- measured peaks of this machine (context for the nominal ones) -------------------
+    a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    ad.calibration_copy(b, a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        ad.calibration_copy(b, a)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+
     # ---------------- CPU oracle on this machine's host cores (bounded sample) ----------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -236,7 +295,8 @@ def main():
         "tokens": toks, "verify_forwards": its, "rows_verified": rows,
         "mean_tokens_per_forward": toks / max(1, its),
         "greedy_tokens_per_s": greedy_tps, "speedup_vs_greedy": value / greedy_tps,
-        "verify_forward_bs1": verify_bs1, "bs32": bs32,
+        "verify_forward_bs1": verify_bs1, "bs32": bs32, "gad": gad,
+        "measured_copy_GBps": copy_gbps,
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -453,7 +453,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 }
 
 // Attention of one (sequence, head) on the matrix cores, bf16 storage, head width a multiple of
-// 32, at most 16 * NT keys.  The workgroup stages the head's values transposed in LDS (keys past
+// 32; the keys are walked NT tiles of 16 at a time.  The workgroup stages the head's values transposed in LDS (keys past
 // the last needed one as zeros); then each wave takes 16 query rows at a time:
 //   scores   S = Q K^T by MFMA, Q and K fragments straight from memory (k = head channel, 32 at
 //            a time, ascending); times `scale`; keys a row must not see become -inf
@@ -482,6 +482,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
     const int tile_end = min(row0 + 16, row_end);
     const int nk_tile = sd.causal ? sd.nk_base + tile_end : sd.nk_base;   // keys the tile's last row sees
     const int nt = (nk_tile + 15) >> 4, nb = (nk_tile + 31) >> 5;
+    const int nch = (nt + NT - 1) / NT;   // the key tiles are walked NT at a time
     uint4 qf[KS];
     if constexpr (PRE) {
 #pragma unroll
@@ -491,79 +492,99 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
 #pragma unroll
       for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
     }
+    // this lane: rows row0 + 4*kq + i, key 16*(tile) + r
+    int nkr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) nkr[i] = sd.causal ? sd.nk_base + row0 + 4 * kq + i + 1 : sd.nk_base;
+    // scores of key tiles ch*NT .. ch*NT + NT - 1, scaled, -inf where the row must not see the key
+    auto scores = [&](int ch, f32x4 (&S)[NT]) {
+#pragma unroll
+      for (int j0 = 0; j0 < NT; j0 += 4) {
+        uint4 kf[4][KS];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int jg = ch * NT + j0 + jj;
+          if (j0 + jj < NT && jg < nt) {
+            if (PRE && j0 == 0 && ch == 0) {
+#pragma unroll
+              for (int s = 0; s < KS; ++s) kf[jj][s] = kf_pre[jj][s];
+            } else {
+              const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * jg + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+              for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+            }
+          }
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int j = j0 + jj, jg = ch * NT + j;
+          if (j < NT) {
+            S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (jg < nt) {
+#pragma unroll
+              for (int s = 0; s < KS; ++s)
+                S[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s]), __builtin_bit_cast(bf16x8, kf[jj][s]), S[j], 0, 0, 0);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int jg = ch * NT + j;
+          S[j][i] = (jg < nt && 16 * jg + r < nkr[i]) ? S[j][i] * scale : -INFINITY;
+        }
+    };
     f32x4 S[NT];
+    float mx[4], sum[4], l[4];
+    // exact row maximum: one pass over all key tiles (more than NT of them: the scores are
+    // computed again, tile group by tile group, in the pass below)
+    {
+      float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      for (int ch = 0; ch < max(nch, 1); ++ch) {
+        scores(ch, S);
 #pragma unroll
-    for (int j0 = 0; j0 < NT; j0 += 4) {
-      uint4 kf[4][KS];
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j = j0 + jj;
-        if (j < NT && j < nt) {
-          if (PRE && j0 == 0) {
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kf[jj][s] = kf_pre[jj][s];
-          } else {
-            const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
-          }
-        }
+          for (int j = 0; j < NT; ++j) m[i] = fmaxf(m[i], S[j][i]);
       }
 #pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        const int j = j0 + jj;
-        if (j < NT) {
-          S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-          if (j < nt) {
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-              S[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s]), __builtin_bit_cast(bf16x8, kf[jj][s]), S[j], 0, 0, 0);
-          }
-        }
-      }
+      for (int i = 0; i < 4; ++i) { mx[i] = row16_max(m[i]); sum[i] = 0.f; }
     }
-    // this lane: rows row0 + 4*kq + i, key 16*j + r
-    float mx[4], l[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = row0 + 4 * kq + i;
-      const int nkr = sd.causal ? sd.nk_base + row + 1 : sd.nk_base;
-      float m = -INFINITY;
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        const float v = (j < nt && 16 * j + r < nkr) ? S[j][i] * scale : -INFINITY;
-        S[j][i] = v;
-        m = fmaxf(m, v);
-      }
-      mx[i] = row16_max(m);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float sum = 0.f;
-      bf16_t* pr = Pw + (4 * kq + i) * ldv + r;
-#pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        if (j < 2 * nb) {   // the tiles the output product reads (an odd count is padded with zeros)
-          const float pv = expf(S[j][i] - mx[i]);   // exp(-inf) = 0 for the keys the row does not see
-          sum += pv;
-          pr[16 * j] = f2bf(pv);
-        }
-      }
-      l[i] = row16_sum(sum);
-    }
-    __builtin_amdgcn_wave_barrier();
     f32x4 O[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int kb = 0; kb < nb; ++kb) {
-      const uint4 pa = *(const uint4*)(Pw + r * ldv + 32 * kb + 8 * kq);
-      uint4 vb[CT];
+    for (int ch = 0; ch < max(nch, 1); ++ch) {
+      if (nch > 1) scores(ch, S);
+      const int tiles_here = 2 * nb - ch * NT;   // tiles of this group the output product reads (an odd count is padded with zeros)
 #pragma unroll
-      for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vt + (16 * c + r) * ldv + 32 * kb + 8 * kq);
+      for (int i = 0; i < 4; ++i) {
+        bf16_t* pr = Pw + (4 * kq + i) * ldv + r;
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
-        O[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), O[c], 0, 0, 0);
+        for (int j = 0; j < NT; ++j) {
+          if (j < tiles_here) {
+            const float pv = expf(S[j][i] - mx[i]);   // exp(-inf) = 0 for the keys the row does not see
+            sum[i] += pv;
+            pr[16 * j] = f2bf(pv);
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      const int kb_end = min(nb, (ch + 1) * (NT / 2));
+      for (int kb = ch * (NT / 2); kb < kb_end; ++kb) {
+        const uint4 pa = *(const uint4*)(Pw + r * ldv + 32 * (kb - ch * (NT / 2)) + 8 * kq);
+        uint4 vb[CT];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vt + (16 * c + r) * ldv + 32 * kb + 8 * kq);
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          O[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), O[c], 0, 0, 0);
+      }
+      __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the next group and the wave's next rows
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) l[i] = row16_sum(sum[i]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = row0 + 4 * kq + i;
@@ -573,7 +594,6 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
         for (int c = 0; c < CT; ++c) Store<bf16_t>::template store<STC>(op + 16 * c, O[c][i] / l[i]);
       }
     }
-    __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the wave's next rows
   };
   if (wave < n_tiles) tile(std::true_type{}, wave);
   for (int rt = wave + waves; rt < n_tiles; rt += waves) tile(std::false_type{}, rt);
@@ -644,10 +664,8 @@ __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __r
                            float scale, unsigned* lds, int nk_cap) {
   if constexpr (sizeof(T) == 2 && DH % 32 == 0) {
     const int nk_need = sd.causal ? sd.nk_base + row_end : sd.nk_base;
-    if (nk_need <= 256) {
-      attn_block_mfma<DH, COH, STC>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
-      return;
-    }
+    attn_block_mfma<DH, COH, STC>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
+    return;
   }
   constexpr int RD = DH * (int)sizeof(T) / 4;   // dwords per key row
   constexpr int RS = RD + 1;                    // padded row stride
