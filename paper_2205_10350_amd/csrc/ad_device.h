@@ -498,14 +498,16 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
     for (int i = 0; i < 4; ++i) nkr[i] = sd.causal ? sd.nk_base + row0 + 4 * kq + i + 1 : sd.nk_base;
     // scores of key tiles ch*NT .. ch*NT + NT - 1, scaled, -inf where the row must not see the key
     auto scores = [&](int ch, f32x4 (&S)[NT]) {
+      // all key fragments of the group are requested before the first product (one fetch latency
+      // per group; the loads are strided, 16 key rows x 128 bytes each, and slow one by one)
 #pragma unroll
-      for (int j0 = 0; j0 < NT; j0 += 4) {
-        uint4 kf[4][KS];
+      for (int j0 = 0; j0 < NT; j0 += NT) {
+        uint4 kf[NT][KS];
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < NT; ++jj) {
           const int jg = ch * NT + j0 + jj;
           if (j0 + jj < NT && jg < nt) {
-            if (PRE && j0 == 0 && ch == 0) {
+            if (PRE && jj < 4 && ch == 0) {
 #pragma unroll
               for (int s = 0; s < KS; ++s) kf[jj][s] = kf_pre[jj][s];
             } else {
@@ -516,7 +518,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
           }
         }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < NT; ++jj) {
           const int j = j0 + jj, jg = ch * NT + j;
           if (j < NT) {
             S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -638,17 +640,32 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
   uint4 qf_pre[DH / 32], kf_pre[4][DH / 32];
   attn_preload<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, qf_pre, kf_pre);
   {
+    // Values transposed into LDS, 8 keys x 8 channels per step and thread: eight 16-byte loads
+    // (one key row piece each), an 8 x 8 transpose of 16-bit values in registers (byte permutes),
+    // eight 16-byte LDS stores (one channel row piece each).  Keys past the last needed one: zeros.
     constexpr int G = DH / 8;   // 16-byte pieces per key row
     const bf16_t* vg = Vb + (size_t)sd.kv_row0 * d + h * DH;
-    for (int i = threadIdx.x; i < nkp * G; i += blockDim.x) {
-      const int g = i / nkp, t = i - g * nkp;
-      uint4 v = uint4{0u, 0u, 0u, 0u};
-      if (t < nk_all) v = ldg16<COH>(vg + (size_t)t * d + g * 8);
-      bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
-      dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
-      dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
-      dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
-      dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
+    const int n_items = (nkp >> 3) * G;
+    for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
+      const int g = it % G, t0 = (it / G) << 3;
+      unsigned in[8][4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint4 v = uint4{0u, 0u, 0u, 0u};
+        if (t0 + i < nk_all) v = ldg16<COH>(vg + (size_t)(t0 + i) * d + g * 8);
+        in[i][0] = v.x; in[i][1] = v.y; in[i][2] = v.z; in[i][3] = v.w;
+      }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        // channel c of keys t0 .. t0+7: the low (c even) or high (c odd) half of dword c/2 of every key
+        unsigned o[4];
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+          const unsigned lo = in[2 * pr][c >> 1], hi = in[2 * pr + 1][c >> 1];
+          o[pr] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+        *(uint4*)(Vt + (size_t)(g * 8 + c) * ldv + t0) = uint4{o[0], o[1], o[2], o[3]};
+      }
     }
   }
   __syncthreads();
