@@ -8,7 +8,8 @@
 #include <chrono>
 #include <functional>
 #include <string>
-#include <unordered_map>
+#include <map>
+#include <utility>
 #include <vector>
 
 #include "ad_internal.h"
@@ -144,8 +145,9 @@ struct ad_ctx {
   // One launch per stage: the launches of a verify call (row assembly, forward, acceptance) are
   // captured into a graph per call shape on the shape's second appearance and replayed after.
   bool graphs_on = true;
-  std::unordered_map<unsigned long long, hipGraphExec_t> graphs;
-  std::unordered_map<unsigned long long, int> graph_seen;
+  typedef std::pair<unsigned long long, unsigned long long> GraphKey;   // (kind | shape, further shape values)
+  std::map<GraphKey, hipGraphExec_t> graphs;
+  std::map<GraphKey, int> graph_seen;
   std::vector<int> last_k;       // k[b] of the last verify call
 
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
@@ -598,8 +600,10 @@ static unsigned long long shape_key(int rows, int max_rows, int n_seq, int knob)
 // this call shape has one, capture + instantiate + launch on the shape's second appearance.
 // false = nothing was launched, the caller launches eagerly.  Any failure switches graphs off
 // for the context (a stream that cannot be captured, e.g. the null stream, is such a failure).
-static bool run_as_graph(ad_ctx* c, unsigned long long key, const std::function<void()>& launches) {
+static bool run_as_graph(ad_ctx* c, unsigned long long shape, const std::function<void()>& launches,
+                         unsigned long long more = 0) {
   if (!c->graphs_on) return false;
+  const ad_ctx::GraphKey key(shape, more);
   auto it = c->graphs.find(key);
   if (it != c->graphs.end()) {
     if (hipGraphLaunch(it->second, c->stream) == hipSuccess) return true;
@@ -843,23 +847,28 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   c->fw_max_rows = 0;
   for (int b = 0; b < B; ++b)
     if (!c->h_finished[b]) c->fw_max_rows = std::max(c->fw_max_rows, c->h_len[b] + 1 + k);
-  launch_assemble_drafter(c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
-                          c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->at<int>(p.mask_rows),
-                          c->stream);
-  const ModelW& w = c->w[AD_DRAFTER];
-  embed_rows(c, w, M);
-  for (int l = 0; l < cf.dec_layers; ++l) {
-    const DecLayerW& L = w.dec[l];
-    self_attn_block(c, L.self, L.ln1, M, c->at<void>(p.tk), c->at<void>(p.tv), cf.max_len + km);
-    cross_attn_block(c, L.cross, L.ln2, M, c->ws + p.mem_k[1] + l * p.mem_layer_stride,
-                     c->ws + p.mem_v[1] + l * p.mem_layer_stride);
-    ffn_block(c, L.ffn, L.ln3, M);
-  }
   const int Mv = live * k;
-  flush_ln(c, M);
-  launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
-  vocab_finish(c, Mv, vocab_argmax(c, w, c->at<void>(p.xg), Mv));
-  launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
+  // the drafter forward's launches (made one by one: the prefix is recomputed every iteration,
+  // so a call shape seldom comes back and a graph per shape costs more to build than it saves)
+  auto launches = [&]() {
+    launch_assemble_drafter(c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
+                            c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->at<int>(p.mask_rows),
+                            c->stream);
+    const ModelW& w = c->w[AD_DRAFTER];
+    embed_rows(c, w, M);
+    for (int l = 0; l < cf.dec_layers; ++l) {
+      const DecLayerW& L = w.dec[l];
+      self_attn_block(c, L.self, L.ln1, M, c->at<void>(p.tk), c->at<void>(p.tv), cf.max_len + km);
+      cross_attn_block(c, L.cross, L.ln2, M, c->ws + p.mem_k[1] + l * p.mem_layer_stride,
+                       c->ws + p.mem_v[1] + l * p.mem_layer_stride);
+      ffn_block(c, L.ffn, L.ln3, M);
+    }
+    flush_ln(c, M);
+    launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
+    vocab_finish(c, Mv, vocab_argmax(c, w, c->at<void>(p.xg), Mv));
+    launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
+  };
+  launches();
   int32_t* h = c->pin;
   HIP_TRY(c, hipMemcpyAsync(h, c->at<int>(p.draft_out), (size_t)B * km * 4, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));

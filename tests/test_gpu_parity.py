@@ -502,7 +502,7 @@ def test_persistent_forward_is_bit_identical_to_staged_launches(name, B):
 def test_graph_replays_equal_eager_launches(name, B):
     """Every replay of a captured call shape, with the library's own eager work (encode, other
     shapes, synchronisations) between the replays, gives the bits the eager launches give."""
-    rig = Rig(name, "bf16", 77, B=B, max_src=40, max_len=40, k_max=24)
+    rig = Rig(name, "bf16", 77, B=B, max_src=40, max_len=40, k_max=24, drafter=(name == "tiny" or B == 3))
     try:
         assert rig.ctx.get_option(ad.AD_OPT_GRAPHS) == 1
         V = rig.dims["vocab"]
@@ -538,6 +538,20 @@ def test_graph_replays_equal_eager_launches(name, B):
                     assert x == y, rep
         assert rig.ctx.get_option(ad.AD_OPT_GRAPHS) == 1, "graph capture failed and was switched off"
         assert rig.ctx.get_option(ad.AD_OPT_GRAPHS_CAPTURED) >= 2
+        # the block drafter's forward between replayed verify and encode calls (its own launches are
+        # made one by one)
+        if rig.wd is not None:
+            def draft_script():
+                rig.ctx.encode(ad.AD_VERIFIER, srcs); rig.ctx.encode(ad.AD_DRAFTER, srcs)
+                a = rig.ctx.draft_nat(6).copy()
+                rig.ctx.verify([out_ref[b][:3] for b in range(B)])
+                return a, rig.ctx.draft_nat(6).copy(), rig.ctx.draft_nat(4).copy()
+            rig.ctx.set_option(ad.AD_OPT_GRAPHS, 0)
+            dref = draft_script()
+            rig.ctx.set_option(ad.AD_OPT_GRAPHS, 1)
+            for rep in range(4):
+                for x, y in zip(dref, draft_script()):
+                    assert np.array_equal(x, y), rep
         # whole decodes through replays
         guides = [edit_guide(g, 0.1, 5 + b, V) for b, g in enumerate(out_ref)]
         for rep in range(2):
