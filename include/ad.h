@@ -206,7 +206,7 @@ int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* 
  * (device, model shape) gives AD_ESTATE.  AD_OPT_FUSED_AVAILABLE (read only): 1 if it is
  * available.  AD_OPT_GRAPHS (0/1, default 1): in the
  * launch-per-stage path the launches of an ad_verify call are captured into a HIP graph per call
- * shape (rows, sequences, longest block) on the shape's second appearance and replayed afterwards
+ * shape (rows, sequences, longest block) on the shape's third appearance and replayed afterwards
  * (at most 512 shapes); the library switches it off by itself when the context's stream cannot be
  * captured (the null stream cannot).  AD_OPT_GRAPHS_CAPTURED (read only): graphs held. */
 enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4 };

@@ -143,7 +143,7 @@ struct ad_ctx {
   unsigned long long dev_base = 0, team_base[kMaxTeams] = {};
   bool last_fused = false;
   // One launch per stage: the launches of a verify call (row assembly, forward, acceptance) are
-  // captured into a graph per call shape on the shape's second appearance and replayed after.
+  // captured into a graph per call shape on the shape's third appearance and replayed after.
   bool graphs_on = true;
   typedef std::pair<unsigned long long, unsigned long long> GraphKey;   // (kind | shape, further shape values)
   std::map<GraphKey, hipGraphExec_t> graphs;
@@ -597,7 +597,7 @@ static unsigned long long shape_key(int rows, int max_rows, int n_seq, int knob)
 }
 // Runs `launches` (kernel launches and device-to-device copies on the context's stream, nothing
 // else) as a graph: replay if
-// this call shape has one, capture + instantiate + launch on the shape's second appearance.
+// this call shape has one, capture + instantiate + launch on the shape's third appearance.
 // false = nothing was launched, the caller launches eagerly.  Any failure switches graphs off
 // for the context (a stream that cannot be captured, e.g. the null stream, is such a failure).
 static bool run_as_graph(ad_ctx* c, unsigned long long shape, const std::function<void()>& launches,
@@ -611,7 +611,7 @@ static bool run_as_graph(ad_ctx* c, unsigned long long shape, const std::functio
     c->graphs_on = false;
     return false;
   }
-  if (++c->graph_seen[key] < 2 || c->graphs.size() >= 512) return false;
+  if (++c->graph_seen[key] < 3 || c->graphs.size() >= 512) return false;   // worth building once a shape keeps coming back
   if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
     (void)hipGetLastError();
     c->graphs_on = false;

@@ -510,7 +510,7 @@ def test_graph_replays_equal_eager_launches(name, B):
         rig.ctx.set_option(ad.AD_OPT_GRAPHS, 0)
         out_ref, _ = rig.ctx.decode_greedy(srcs)
         # the same three-call script, six times: eager first, then with graphs (call shapes are
-        # captured on their second appearance and replayed on the later ones)
+        # captured on their third appearance and replayed on the later ones)
         d1 = [out_ref[b][:4] for b in range(B)]
         d2 = [[(out_ref[b][4] - 5 + 1) % (V - 5) + 5] + out_ref[b][5:9] for b in range(B)]   # wrong first token
         d3 = [out_ref[b][5:9] for b in range(B)]
