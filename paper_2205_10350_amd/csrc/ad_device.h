@@ -457,7 +457,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 // the last needed one as zeros); then each wave takes 16 query rows at a time:
 //   scores   S = Q K^T by MFMA, Q and K fragments straight from memory (k = head channel, 32 at
 //            a time, ascending); times `scale`; keys a row must not see become -inf
-//   softmax  exact row maximum; p = exp(s - max); the denominator sums the unrounded p: each of
+//   softmax  exact row maximum; p = exp(s - max) (hardware 2^x of (s - max) log2 e); the denominator sums the unrounded p: each of
 //            the 16 lanes of a row adds its keys (key % 16 = lane) in ascending order, then the
 //            lanes combine by row16_sum; numerators are rounded to bf16 and go through LDS to
 //            become the left operand of
@@ -469,7 +469,8 @@ template <int DH, int NT, bool COH, bool STC>
 __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
                                 const SeqDesc sd, int row_begin, int row_end, int h, int d, float scale,
                                 const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all,
-                                const uint4 (&qf_pre)[DH / 32], const uint4 (&kf_pre)[4][DH / 32]) {
+                                const uint4 (&qf_pre)[DH / 32], const uint4 (&kf_pre)[4][DH / 32],
+                                const float* Sbuf, int lds_s) {
   constexpr int KS = DH / 32, CT = DH / 16;
   const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 15, kq = lane >> 4;
@@ -498,35 +499,50 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
     for (int i = 0; i < 4; ++i) nkr[i] = sd.causal ? sd.nk_base + row0 + 4 * kq + i + 1 : sd.nk_base;
     // scores of key tiles ch*NT .. ch*NT + NT - 1, scaled, -inf where the row must not see the key
     auto scores = [&](int ch, f32x4 (&S)[NT]) {
-      // all key fragments of the group are requested before the first product (one fetch latency
-      // per group; the loads are strided, 16 key rows x 128 bytes each, and slow one by one)
+      // Loads are unconditional inside a group of four key tiles (indices clamped to the last tile
+      // that exists; what lies past it is masked below): a load under its own branch would be
+      // waited for on its own.
+      if (Sbuf) {
+        // the raw products were left in LDS by all waves together (attn_coop_scores)
 #pragma unroll
-      for (int j0 = 0; j0 < NT; j0 += NT) {
+        for (int j = 0; j < NT; ++j) {
+          const int jc = min(ch * NT + j, nt - 1);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) S[j][i] = Sbuf[(4 * kq + i) * lds_s + 16 * jc + r];
+        }
+      } else {
         uint4 kf[NT][KS];
 #pragma unroll
-        for (int jj = 0; jj < NT; ++jj) {
-          const int jg = ch * NT + j0 + jj;
-          if (j0 + jj < NT && jg < nt) {
-            if (PRE && jj < 4 && ch == 0) {
+        for (int j0 = 0; j0 < NT; j0 += 4) {
+          if (ch * NT + j0 < nt) {
 #pragma unroll
-              for (int s = 0; s < KS; ++s) kf[jj][s] = kf_pre[jj][s];
-            } else {
-              const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * jg + r, nk_all - 1)) * d + h * DH + kq * 8;
+            for (int jj = 0; jj < 4; ++jj) {
+              const int j = j0 + jj, jc = min(ch * NT + j, nt - 1);
+              if (PRE && j0 == 0 && ch == 0 && jc == j) {
 #pragma unroll
-              for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+                for (int s = 0; s < KS; ++s) kf[j][s] = kf_pre[jj][s];
+              } else {
+                const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * jc + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) kf[j][s] = ldg16<COH>(kp + 32 * s);
+              }
             }
           }
         }
 #pragma unroll
-        for (int jj = 0; jj < NT; ++jj) {
-          const int j = j0 + jj, jg = ch * NT + j;
-          if (j < NT) {
-            S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (jg < nt) {
+        for (int j0 = 0; j0 < NT; j0 += 4) {
+          if (ch * NT + j0 < nt) {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              const int j = j0 + jj;
+              S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int s = 0; s < KS; ++s)
-                S[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s]), __builtin_bit_cast(bf16x8, kf[jj][s]), S[j], 0, 0, 0);
+                S[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s]), __builtin_bit_cast(bf16x8, kf[j][s]), S[j], 0, 0, 0);
             }
+          } else {
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) S[j0 + jj] = f32x4{0.f, 0.f, 0.f, 0.f};
           }
         }
       }
@@ -562,11 +578,15 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       const int tiles_here = 2 * nb - ch * NT;   // tiles of this group the output product reads (an odd count is padded with zeros)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        // slot i holds rows row0 + 4*kq + i: none of them exists if the first (kq = 0) does not;
+        // such rows keep whatever the probability tile held and are never stored
+        if (row0 + i >= row_end) continue;
         bf16_t* pr = Pw + (4 * kq + i) * ldv + r;
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
           if (j < tiles_here) {
-            const float pv = expf(S[j][i] - mx[i]);   // exp(-inf) = 0 for the keys the row does not see
+            // e^x as 2^(x log2 e) on the hardware exponential; 2^(-inf) = 0 for the keys the row does not see
+            const float pv = __builtin_amdgcn_exp2f((S[j][i] - mx[i]) * 1.44269504088896340736f);
             sum[i] += pv;
             pr[16 * j] = f2bf(pv);
           }
@@ -627,6 +647,47 @@ __device__ __forceinline__ void attn_preload(const bf16_t* __restrict__ q, const
     }
   }
 }
+// One 16-row tile, many keys: the score products Q K^T are independent per key tile, so all waves
+// of the workgroup compute them together (wave w: key tiles w, w + waves, ..; one fetch latency
+// instead of one per group of tiles on a single wave) and leave the raw fp32 products in LDS,
+// [16 rows][lds_s]; the tile's wave then goes on exactly as if it had computed them itself.
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_coop_scores(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, const SeqDesc sd,
+                                                 int row_begin, int row_end, int h, int d, int nk_all, int nt,
+                                                 float* Sbuf, int lds_s) {
+  constexpr int KS = DH / 32, TB = 8;   // key tiles per batch of loads
+  const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
+  uint4 qf[KS];
+  {
+    const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row_begin + r, row_end - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
+  }
+  for (int b0 = wave; b0 < nt; b0 += waves * TB) {
+    uint4 kf[TB][KS];
+#pragma unroll
+    for (int jj = 0; jj < TB; ++jj) {
+      // unconditional (clamped to the last tile): a load under its own branch is waited for on its own
+      const int jc = min(b0 + jj * waves, nt - 1);
+      const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * jc + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+    }
+#pragma unroll
+    for (int jj = 0; jj < TB; ++jj) {
+      const int jg = b0 + jj * waves;
+      if (jg < nt) {
+        f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s]), __builtin_bit_cast(bf16x8, kf[jj][s]), S, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Sbuf[(4 * kq + i) * lds_s + 16 * jg + r] = S[i];
+      }
+    }
+  }
+}
 template <int DH, bool COH, bool STC>
 __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
@@ -639,13 +700,32 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
   // the two fetch latencies overlap
   uint4 qf_pre[DH / 32], kf_pre[4][DH / 32];
   attn_preload<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, qf_pre, kf_pre);
+  // a single row tile against more than 128 keys: the waves share the score products; the buffer
+  // lies over the probability tiles of the waves that have no rows
+  const int nt_all = (nk_all + 15) >> 4;
+  const bool coop = row_end - row_begin <= 16 && nt_all > 8 && waves >= 3;
+  float* Sbuf = coop ? (float*)(Vt + DH * ldv + 16 * ldv) : nullptr;
+  if (coop) attn_coop_scores<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, nt_all, Sbuf, nkp);
   {
-    // Values transposed into LDS, 8 keys x 8 channels per step and thread: eight 16-byte loads
+    // Values transposed into LDS.  Many keys: 8 keys x 8 channels per step and thread: eight 16-byte loads
     // (one key row piece each), an 8 x 8 transpose of 16-bit values in registers (byte permutes),
     // eight 16-byte LDS stores (one channel row piece each).  Keys past the last needed one: zeros.
     constexpr int G = DH / 8;   // 16-byte pieces per key row
     const bf16_t* vg = Vb + (size_t)sd.kv_row0 * d + h * DH;
-    const int n_items = (nkp >> 3) * G;
+    // few keys: one 16-byte piece per thread and step, eight 2-byte LDS stores (more threads in
+    // flight, which is what counts there); many keys: the transposing path below
+    if (nkp <= 128)
+    for (int i = threadIdx.x; i < nkp * G; i += blockDim.x) {
+      const int g = i / nkp, t = i - g * nkp;
+      uint4 v = uint4{0u, 0u, 0u, 0u};
+      if (t < nk_all) v = ldg16<COH>(vg + (size_t)t * d + g * 8);
+      bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
+      dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
+      dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
+      dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
+      dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
+    }
+    const int n_items = nkp <= 128 ? 0 : (nkp >> 3) * G;
     for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
       const int g = it % G, t0 = (it / G) << 3;
       unsigned in[8][4];
@@ -669,9 +749,9 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
     }
   }
   __syncthreads();
-  if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre);
-  else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre);
-  else attn_tiles_mfma<DH, 16, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre);
+  if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else attn_tiles_mfma<DH, 16, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   __syncthreads();   // LDS is free for the next call
 }
 
