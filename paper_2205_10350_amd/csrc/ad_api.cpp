@@ -428,7 +428,6 @@ static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bo
   fa.len = c->at<int>(p.len); fa.pending = c->at<int>(p.pending); fa.finished = c->at<int>(p.finished);
   fa.out = c->at<int>(p.out); fa.result = c->at<int>(p.result);
   fa.stamps = stamps ? c->at<unsigned long long>(p.stamps) : nullptr;
-  fa.skip = (!do_accept && getenv("AD_DEBUG_SKIP")) ? atoi(getenv("AD_DEBUG_SKIP")) : 0;   // timing runs only
   hipError_t e = launch_fused_forward(fa, c->fused_grid, c->fused_lds, c->stream);
   if (e == hipSuccess) {
     c->dev_base += 2;
@@ -1045,27 +1044,6 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
     *forward_us = tot / reps;
     *vocab_kernel_us = 0;
     if (vocab_back_to_back_us) *vocab_back_to_back_us = 0;
-    if (getenv("AD_DEBUG_STAGES")) {
-      // diagnostic: stage start times of one launch as seen by workgroup 0 (100 MHz clock), to stderr
-      const int n = c->fused_stages + 5, nw = 64 + 8 * 64 + 4 * 64;
-      std::vector<unsigned long long> st(nw);
-      HIP_TRY(c, fused_verify_forward(c, k, c->last_M, c->last_nseq, false, true));
-      HIP_TRY(c, hipMemcpyAsync(st.data(), c->at<unsigned long long>(c->plan.stamps), (size_t)nw * 8, hipMemcpyDeviceToHost, c->stream));
-      HIP_TRY(c, hipStreamSynchronize(c->stream));
-      for (int i = 0; i + 1 < n; ++i) {
-        const unsigned long long* f = &st[64 + 8 * i];
-        const unsigned long long* g = &st[64 + 8 * (i + 1)];
-        fprintf(stderr, "stage %2d: %6.2f us", i, (double)(st[i + 1] - st[i]) * 0.01);
-        if (i > 0 && i < c->fused_stages) fprintf(stderr, " [weights fetched in %5.2f]", (double)(f[6] - f[1]) * 0.01);
-        if (i < c->fused_stages) { const unsigned long long* q = &st[576 + 4 * i]; fprintf(stderr, " [to stage_a +%5.2f, stage_a +%5.2f, vmcnt +%5.2f, sync +%5.2f]", (double)(q[0] - st[i]) * 0.01, (double)(q[1] - q[0]) * 0.01, (double)(q[2] - q[1]) * 0.01, (double)(f[3] - q[2]) * 0.01); }
-        if (i < c->fused_stages)
-          fprintf(stderr, " | A staged +%5.2f  mfma +%5.2f  epilogue +%5.2f | to barrier +%5.2f  stores done +%5.2f  wait +%5.2f",
-                  (double)(f[3] - st[i]) * 0.01, (double)(f[4] - f[3]) * 0.01, (double)(f[5] - f[4]) * 0.01,
-                  (double)(g[0] - f[5]) * 0.01, (double)(g[1] - g[0]) * 0.01, (double)(g[2] - g[1]) * 0.01);
-        fprintf(stderr, "\n");
-      }
-      fprintf(stderr, "total %.2f us\n", (double)(st[n - 1] - st[0]) * 0.01);
-    }
     unsigned long long flags[kBarPlacement - kBarAbort + 2];
     const int place_word = kBarPlacement - kBarAbort + (int)(((c->dev_base >> 1) + 1) & 1);   // of the last launch
     HIP_TRY(c, hipMemcpyAsync(flags, c->at<unsigned long long>(c->plan.bar) + kBarAbort, sizeof(flags), hipMemcpyDeviceToHost, c->stream));

@@ -515,21 +515,21 @@ __device__ __forceinline__ bool gemm_stage(const Stage& st, const Stage* prog, c
       EpiRegs<4> eg;
       eg.bias = 0.f;
 #pragma unroll
-      for (int q = 0; q < 16; ++q) eg.aux[q] = 0u;   // (destination row 0 / residual 0 if the preload is skipped)
+      for (int q = 0; q < 16; ++q) eg.aux[q] = 0u;
       f32x4 acc[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
       for (int kp = 0; kp < K; kp += KP) {
         if (!first) __syncthreads();            // the previous tile is no longer read
         if (stp && threadIdx.x == 0 && first) fa.stamps[576 + 4 * si + 0] = wall_clock64();
-        if (!(fa.skip & 1)) stage_a(st.a_mode, K, st.a_src, st.ln_g, st.ln_b, st.x_out, fa, A, mc, rows, kp, KP, write_x);
+        stage_a(st.a_mode, K, st.a_src, st.ln_g, st.ln_b, st.x_out, fa, A, mc, rows, kp, KP, write_x);
         if (stp && threadIdx.x == 0 && first) fa.stamps[576 + 4 * si + 1] = wall_clock64();
         // the tile's loads, the x rows' stores and the weight slot's fetches are done
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (stp && threadIdx.x == 0 && first) fa.stamps[576 + 4 * si + 2] = wall_clock64();
         __syncthreads();
         if (stp && threadIdx.x == 0) stp[3] = wall_clock64();
-        if (first && st.pf_stage != -1 && wave >= ws.n_active && !(fa.skip & 64)) {
+        if (first && st.pf_stage != -1 && wave >= ws.n_active) {
           // Waves without a strip in this stage start the weights of a later stage streaming into
           // the XCD's L2 (they have no loads of their own left that could queue up behind these).
           if (st.pf_stage >= 0) {
@@ -542,17 +542,17 @@ __device__ __forceinline__ bool gemm_stage(const Stage& st, const Stage* prog, c
         }
         if (active) {
           // the epilogue's operands: in flight under the last pass's MFMAs
-          if (kp + KP >= K && !(fa.skip & 4)) epi_preload<4, true>(epi, mt, mc, n0, m_hi, N, lane, eg);
+          if (kp + KP >= K) epi_preload<4, true>(epi, mt, mc, n0, m_hi, N, lane, eg);
           const bf16_t* a_lane = A + r * ld + kq * 8;
           // k in [kp, kp + KP): first what sits in the weight slot, then the rest from memory
           const int lds_end = min(max(in_lds, kp), kp + KP);
-          if (lds_end > kp && !(fa.skip & 2)) mfma_k_lds(mt, a_lane, ld, my_slot + (size_t)(kp >> 5) * 1024, (lds_end - kp) >> 5, acc);
-          if (lds_end < kp + KP && !(fa.skip & 2)) mfma_k(mt, a_lane + (lds_end - kp), ld, wp + (size_t)lds_end * 16, kp + KP - lds_end, acc);
+          if (lds_end > kp) mfma_k_lds(mt, a_lane, ld, my_slot + (size_t)(kp >> 5) * 1024, (lds_end - kp) >> 5, acc);
+          if (lds_end < kp + KP) mfma_k(mt, a_lane + (lds_end - kp), ld, wp + (size_t)lds_end * 16, kp + KP - lds_end, acc);
         }
         first = false;
       }
       if (stp && threadIdx.x == 0) stp[4] = wall_clock64();
-      if (active && !(fa.skip & 8)) epi_apply<bf16_t, 4, false>(epi, acc, eg, mt, mc, n0, m_hi, N, lane);
+      if (active) epi_apply<bf16_t, 4, false>(epi, acc, eg, mt, mc, n0, m_hi, N, lane);
       if (stp && threadIdx.x == 0) stp[5] = wall_clock64();
     }
   }
@@ -855,7 +855,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_fused_forward(FusedArgs fa) {
         if (stp && threadIdx.x == 0) stp[0] = wall_clock64();
         barrier_stores_done(wave_stored);
         if (stp && threadIdx.x == 0) stp[1] = wall_clock64();
-        if (st.type == ST_GEMM && !(fa.skip & 32)) gemm_prefetch(st, rank, T, wbase);
+        if (st.type == ST_GEMM) gemm_prefetch(st, rank, T, wbase);
         if (stp) {   // diagnostic: how long this wave's weight fetch takes when nothing else is in flight
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           if (threadIdx.x == 0) stp[6] = wall_clock64();
@@ -867,7 +867,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_fused_forward(FusedArgs fa) {
       if (fa.stamps && rank == 0 && threadIdx.x == 0) { fa.stamps[si] = wall_clock64(); }
       wave_stored = true;
       if (st.type == ST_GEMM) wave_stored = gemm_stage(st, prog, fa, m_lo, m_hi, rank, T, A, wbase, junk_lds, stp, si);
-      else if (st.type == ST_ATTN) { if (!(fa.skip & 16)) attn_stage(st, fa, s_lo, s_hi, rank, T, (unsigned*)fused_lds); }
+      else if (st.type == ST_ATTN) attn_stage(st, fa, s_lo, s_hi, rank, T, (unsigned*)fused_lds);
       else ln_stage(st, m_lo, m_hi, rank, T);
     }
     __syncthreads();   // the last stage no longer reads the weight slots

@@ -132,7 +132,6 @@ struct FusedArgs {
   int k_max, eos, max_len;
   int *len, *pending, *finished, *out, *result;
   unsigned long long* stamps;     // nullable: workgroup 0 records the 100 MHz clock at every stage start
-  int skip;                       // diagnostic bit mask: parts of a stage to leave out (timing only, results are garbage)
 };
 int fused_max_blocks_per_cu(size_t lds_bytes);
 hipError_t launch_probe_placement(int* xcc_dev, int grid, size_t lds_bytes, hipStream_t s);

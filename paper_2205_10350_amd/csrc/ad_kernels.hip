@@ -16,9 +16,6 @@
 #include "ad_device.h"
 
 namespace ad {
-#ifdef ASTAT_TUNE
-static int g_tune_per_wg = 0, g_tune_mt = 0, g_tune_print = 0;
-#endif
 
 // ------------------------------------------------------------------------------------- embed
 // x[m] = E[tok[m]] * sqrt(d) + PE[pos[m]]
@@ -535,9 +532,6 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
           const int n_strips = N / 16, chunks = (M + 15) / 16;
           int per_wg = 4 * std::max(1, (n_strips + 4 * 384 - 1) / (4 * 384));
           if (N <= 4096) per_wg = 4 * std::max(1, (n_strips * chunks + 4 * 512 - 1) / (4 * 512));
-#ifdef ASTAT_TUNE
-          if (g_tune_per_wg > 0) per_wg = g_tune_per_wg;
-#endif
           return launch_astat<1, 1>(a, w, M, N, K, e, per_wg, s, ln);
         }
       } else {
@@ -547,13 +541,6 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
         const float c1 = astat_plan(1, M, N, K, ln.x != nullptr, &pw[0]);
         const float c2 = K <= 2048 ? astat_plan(2, M, N, K, ln.x != nullptr, &pw[1]) : 1e30f;
         const float c4 = K <= 1024 ? astat_plan(4, M, N, K, ln.x != nullptr, &pw[2]) : 1e30f;
-#ifdef ASTAT_TUNE
-        if (g_tune_mt == 1) return launch_astat<1, 2>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
-        if (g_tune_mt == 2) return launch_astat<2, 2>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
-        if (g_tune_mt == 4) return launch_astat<4, 2>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
-        if (g_tune_mt == 11) return launch_astat<1, 1>(a, w, M, N, K, e, g_tune_per_wg, s, ln);
-        if (g_tune_print) printf("  plan: c1 %.1f (pw %d) c2 %.1f (pw %d) c4 %.1f (pw %d)\n", c1, pw[0], c2, pw[1], c4, pw[2]);
-#endif
         if (c4 <= c2 && c4 <= c1) return launch_astat<4, 2>(a, w, M, N, K, e, pw[2], s, ln);
         if (c2 <= c1) return launch_astat<2, 2>(a, w, M, N, K, e, pw[1], s, ln);
         return launch_astat<1, 2>(a, w, M, N, K, e, pw[0], s, ln);
