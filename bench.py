@@ -29,10 +29,10 @@ MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 
 
 # HBM bytes per launch of the output-projection kernel at the headline shape (base model, 17..32
-# rows), from two rocprofv3 --pmc runs of this file (FETCH_SIZE 16357.3 KiB x 2.000, WRITE_SIZE
+# rows), from two rocprofv3 --pmc runs of this file (FETCH_SIZE 16356.2 KiB x 2.000, WRITE_SIZE
 # 544.1 KiB x 1.0; factors from k_calibration_copy's readings for a 256 MiB copy in the same runs;
 # profiles/bench_base_bs1_vocab_kernel_hbm_traffic.md)
-VOCAB_KERNEL_TRAFFIC_BYTES = int(16357.3 * 1024 * (262144.0 / 131091.0) + 544.1 * 1024)
+VOCAB_KERNEL_TRAFFIC_BYTES = int(16356.2 * 1024 * (262144.0 / 131078.0) + 544.1 * 1024)
 
 
 def decoder_stream_params(dims):
@@ -146,10 +146,12 @@ def main():
                     "frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "traffic": None}
     else:
         # dominant kernel by bytes: the output projection + arg max (42 % of the forward's
-        # algorithmic bytes); timed alone, back to back, between two HIP events on its stream
+        # algorithmic bytes).  Average launch duration = 50 launches back to back between two HIP
+        # events on the kernel's stream / 50 (a single launch bracketed by two events inside a
+        # forward reads 3-4 us more, the cost of the two event records: staged_vocab_kernel_us).
         roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<1, true, 1> (output projection + arg max)", "rows": M1,
-                    "achieved": voc_bytes / (voc_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                    "frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK, "traffic": VOCAB_KERNEL_TRAFFIC_BYTES}
+                    "achieved": voc_bytes / (voc_b2b_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                    "frac": voc_bytes / (voc_b2b_us * 1e-6) / HBM_PEAK, "traffic": VOCAB_KERNEL_TRAFFIC_BYTES}
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,
                   "hbm_frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "single_launch": bool(fused),
                   "staged_launches_us": staged_us, "staged_vocab_kernel_us": voc_us,
