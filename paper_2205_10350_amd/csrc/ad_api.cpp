@@ -25,7 +25,7 @@ static size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 static size_t attn_lds_host(int nk_cap, int dh, int esz, int waves) {
   const size_t row_dwords = (size_t)dh * esz / 4 + 1;
   const size_t scalar_path = 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
-  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 8;
+  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
   const size_t mfma_path = ((size_t)dh + 16 * (size_t)waves) * ldv * 2;
   return std::max(scalar_path, mfma_path);
 }

@@ -429,8 +429,9 @@ template <> struct LdsRow<float> {
 __host__ __device__ inline size_t attn_lds_bytes(int nk_cap, int dh, int esz, int waves) {
   const size_t row_dwords = (size_t)dh * esz / 4 + 1;
   const size_t scalar_path = 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
-  // matrix-core path: transposed values [dh][keys + 8] and one 16-row probability tile per wave
-  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 8;
+  // matrix-core path: transposed values [dh][keys + 16] and one 16-row probability tile per wave
+  // (row stride = 32 bytes past a multiple of 64: the 16-byte fragment reads meet no bank twice)
+  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
   const size_t mfma_path = ((size_t)dh + 16 * (size_t)waves) * ldv * 2;
   return scalar_path > mfma_path ? scalar_path : mfma_path;
 }
@@ -693,7 +694,7 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
                                 int row_begin, int row_end, int h, int d, float scale, unsigned* lds, int nk_all) {
   const int wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
-  const int nkp = (nk_all + 31) & ~31, ldv = nkp + 8;
+  const int nkp = (nk_all + 31) & ~31, ldv = nkp + 16;
   bf16_t* Vt = (bf16_t*)lds;                      // [DH][ldv]: Vt[c][t] = V[t][c]
   bf16_t* Pw = Vt + DH * ldv + wave * 16 * ldv;   // this wave's probability tile [16][ldv]
   // the first tile's operands of the score product are requested before the values are staged:

@@ -230,16 +230,21 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
   }
 }
 
-template <int MT, bool AMAX, int SP>
+// AMAX: 0 = an ordinary epilogue, 1 = output projection with the running arg max, 2 = the same and the
+// logits are also stored (tests; only instantiated for MT = 1, SP = 1: a store inside the unit
+// loop makes the compiler wait for every weight fetch in flight at each unit)
+template <int MT, int AMAX, int SP, bool ONE>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, Epi e, int strips_per_wg, int groups,
                                                             int chunks, LnA ln) {
   constexpr int ROWS = MT * 16;
   extern __shared__ uint4 astat_lds[];
-  bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 8]
+  bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 16]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, kq = lane >> 4;
-  const int ld = K + 8, n_strips = N >> 4;
+  // row stride K + 16 elements = 8 dwords past a multiple of 64 banks: the 16-byte fragment reads of a wave
+  // (lane = row + 16 * k-group) then meet no bank twice (measured: K + 8 costs every read 4 extra cycles)
+  const int ld = ONE ? 528 : K + 16, n_strips = N >> 4;
   // Workgroup -> (strip group, row chunk).  Consecutive workgroups go to consecutive XCDs, each
   // with its own L2: with eight or more strip groups, group g runs on XCD g % 8 only, its row
   // chunks back to back, so that a group's weights come from HBM once and from that L2 afterwards.
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     chunk = blockIdx.x / groups;
   }
   const int m0 = chunk * ROWS;
-  const int halves = K >> 9;
+  const int halves = ONE ? 1 : K >> 9;
   const bf16_t* a_lane = At + r * ld + kq * 8;
   const int s_begin = group * strips_per_wg, s_end = min(n_strips, s_begin + strips_per_wg);
   const int s_first = s_begin + SP * wave;
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     for (int i = 0; i < MT * 4; ++i) *(uint4*)(At + (wave * MT * 4 + i) * ld + h * 512 + lane * 8) = av[i];
   }
   __syncthreads();
-  f32x4 acc[SP][MT];
+  f32x4 acc_x[SP][MT];   // lives across the units of a strip when K has several 512-slices
   // EPI_ARGMAX: every lane keeps the best (value, column) of its MT*4 (row, column-residue) slots
   // over all strips of the wave.  A lane meets its columns in ascending order, so "strictly
   // greater" keeps the smallest column among equal values; the start value (-inf at the lane's
@@ -307,6 +312,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   int bi[NB];
 #pragma unroll
   for (int x = 0; x < NB; ++x) { bv[x] = -INFINITY; bi[x] = n_units > 0 ? (s_first << 4) + r : 0x7fffffff; }
+  // MT = 4: the A fragments in flight across steps and units (see the unit)
+  constexpr int AFB = MT < 4 ? 2 : 1;
+  uint4 ar[AFB == 1 ? MT : 1];
+  if constexpr (AFB == 1) {
+#pragma unroll
+    for (int t = 0; t < MT; ++t) ar[t] = *(const uint4*)(a_lane + t * 16 * ld);
+  }
   // REFILL = false for the wave's last unit: nothing is fetched that nobody will use (the
   // epilogue would wait for it)
   auto unit = [&](auto refill_c, int q) {
@@ -316,7 +328,10 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     const int s0 = s_first + 4 * SP * p;
     const bf16_t* wn[SP];
     unit_ptrs(q + 1, wn);
-    if (k0 == 0) {
+    // ONE (K = 512): a unit is a whole dot product; its accumulators are the unit's own
+    f32x4 acc_l[SP][MT];
+    f32x4 (&acc)[SP][MT] = *(ONE ? &acc_l : &acc_x);
+    if (ONE || k0 == 0) {
 #pragma unroll
       for (int j = 0; j < SP; ++j)
 #pragma unroll
@@ -334,38 +349,62 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    // A fragments are read one step ahead of their MFMAs where the registers allow it (MT < 4);
-    // with MT = 4 the co-resident wave covers the LDS latency instead
-    constexpr int AFB = MT < 4 ? 2 : 1;
+    // A fragments: with MT < 4 a second register set holds the next step's, read while this
+    // step's MFMAs run.  With MT = 4 there are no registers for that; instead a row tile's
+    // fragment register is refilled with the next step's as soon as the MFMAs that read it are
+    // issued (the same rolling scheme as for the weights), so an LDS read has the rest of the
+    // step's MFMAs to arrive; the last step reads the first fragments of the next unit.
     uint4 af[AFB][MT];
     if constexpr (AFB == 2) {
 #pragma unroll
       for (int t = 0; t < MT; ++t) af[0][t] = *(const uint4*)(a_lane + t * 16 * ld + k0);
       __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
     }
+    const int k0n = ONE ? 0 : (k0 + 512 == K ? 0 : k0 + 512);   // the next unit's slice
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      const int ur = AFB == 2 ? u + 1 : u;   // step whose fragments are read now
-      if (ur < 16) {
+      if constexpr (AFB == 2) {
+        if (u + 1 < 16) {
 #pragma unroll
-        for (int t = 0; t < MT; ++t) af[ur % AFB][t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * ur);
+          for (int t = 0; t < MT; ++t) af[(u + 1) % 2][t] = *(const uint4*)(a_lane + t * 16 * ld + k0 + 32 * (u + 1));
+        }
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int j = 0; j < SP; ++j)
+            acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % 2][t]), __builtin_bit_cast(bf16x8, b[j][u]), acc[j][t], 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+          for (int j = 0; j < SP; ++j)
+            acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ar[t]), __builtin_bit_cast(bf16x8, b[j][u]), acc[j][t], 0, 0, 0);
+          ar[t] = *(const uint4*)(a_lane + t * 16 * ld + (u + 1 < 16 ? k0 + 32 * (u + 1) : k0n));
+        }
       }
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int j = 0; j < SP; ++j)
-          acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[u % AFB][t]), __builtin_bit_cast(bf16x8, b[j][u]), acc[j][t], 0, 0, 0);
       // rolling refill: the same step of the next unit
       if constexpr (REFILL) {
 #pragma unroll
         for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(wn[j] + u * 512);
       }
-      // issue order per step: LDS reads, this step's MFMAs, the refills
-      if (ur < 16) __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, SP * MT, 0);
+      // issue order per step
+      if constexpr (AFB == 2) {
+        if (u + 1 < 16) __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, SP * MT, 0);
+      } else {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+          __builtin_amdgcn_sched_group_barrier(0x008, SP, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      }
       if constexpr (REFILL) __builtin_amdgcn_sched_group_barrier(0x020, SP, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
+    // the epilogue's row addressing depends on the chunk only; computed once before the loop it
+    // would occupy registers (or scratch) through every unit, so it is tied to this unit
+    int m0e = m0;
+    asm volatile("" : "+s"(m0e));
     if (last) {
       if constexpr (AMAX) {
 #pragma unroll
@@ -381,10 +420,10 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
               bv[t * 4 + i] = better ? v : bv[t * 4 + i];
               bi[t * 4 + i] = better ? n : bi[t * 4 + i];
             }
-          if (e.logits) {
+          if constexpr (AMAX == 2) {
             for (int t = 0; t < MT; ++t)
               for (int i = 0; i < 4; ++i) {
-                const int m = m0 + t * 16 + kq * 4 + i;
+                const int m = m0e + t * 16 + kq * 4 + i;
                 if (m < M) e.logits[(size_t)m * N + n] = acc[j][t][i];
               }
           }
@@ -392,11 +431,11 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
       } else if constexpr (PRE) {
 #pragma unroll
         for (int j = 0; j < SP; ++j)
-          if (s0 + j < s_end) epi_apply<bf16_t, MT>(e, acc[j], g[j], MT, m0, (s0 + j) << 4, M, N, lane);
+          if (s0 + j < s_end) epi_apply<bf16_t, MT>(e, acc[j], g[j], MT, m0e, (s0 + j) << 4, M, N, lane);
       } else {
 #pragma unroll
         for (int j = 0; j < SP; ++j)
-          if (s0 + j < s_end) strip_epilogue<bf16_t, MT>(e, acc[j], MT, m0, (s0 + j) << 4, M, N, lane);
+          if (s0 + j < s_end) strip_epilogue<bf16_t, MT>(e, acc[j], MT, m0e, (s0 + j) << 4, M, N, lane);
       }
     }
   };
@@ -430,7 +469,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
 // XCD runs its workgroups in rounds of (32 CUs x workgroups per CU); a workgroup costs a fixed
 // part (launch, staging the rows, drain) plus its units.  Strips per workgroup are a multiple of
 // eight (four waves, two strips each).
-static size_t astat_lds_bytes(int mt, int K) { return (size_t)mt * 16 * (K + 8) * 2 + 4 * (size_t)mt * 16 * 8; }
+static size_t astat_lds_bytes(int mt, int K) { return (size_t)mt * 16 * (K + 16) * 2 + 4 * (size_t)mt * 16 * 8; }
 static float astat_plan(int mt, int M, int N, int K, bool with_ln, int* per_wg_out) {
   const int chunks = (M + mt * 16 - 1) / (mt * 16), n_strips = N / 16, halves = K / 512;
   const size_t lds = astat_lds_bytes(mt, K);
@@ -455,16 +494,36 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
                         const LnA& ln) {
   const int chunks = (M + MT * 16 - 1) / (MT * 16), n_strips = N / 16;
   const size_t lds = astat_lds_bytes(MT, K);
-  static size_t set_for = 0;
-  if (lds > set_for) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, false, SP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, true, SP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    set_for = lds;
-  }
   const int gx = (n_strips + per_wg - 1) / per_wg;
   const int grid = (gx >= 8 ? (gx + 7) / 8 * 8 : gx) * chunks;
-  if (e.mode == EPI_ARGMAX) k_gemm_bf16_astat<MT, true, SP><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
-  else k_gemm_bf16_astat<MT, false, SP><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
+  auto go = [&](auto amax_c, auto one_c) {
+    constexpr int AMAX = decltype(amax_c)::value;
+    constexpr bool ONE = decltype(one_c)::value;
+    static size_t set_for = 0;
+    if (lds > set_for) {
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, AMAX, SP, ONE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      set_for = lds;
+    }
+    k_gemm_bf16_astat<MT, AMAX, SP, ONE><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  const bool amax = e.mode == EPI_ARGMAX;
+  if constexpr (MT == 1 && SP == 1) {
+    if (amax && e.logits) {   // launch_gemm sends every request for logits here
+      if (K == 512) go(I2{}, std::true_type{});
+      else go(I2{}, std::false_type{});
+      return gx;
+    }
+  }
+  if (K == 512) {
+    if (amax) go(I1{}, std::true_type{});
+    else go(I0{}, std::true_type{});
+  } else {
+    if (amax) go(I1{}, std::false_type{});
+    else go(I0{}, std::false_type{});
+  }
   return gx;
 }
 
@@ -527,7 +586,8 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
       // strips until the chip is covered (at most about 512 workgroups for the layer GEMMs); more
       // rows are more row chunks of the same shape.
       const int mt = 1;
-      if ((M <= 64 || (M <= 768 && N <= 4096)) && astat_lds_bytes(mt, K) <= 150 * 1024) {
+      const bool want_logits = e.mode == EPI_ARGMAX && e.logits != nullptr;
+      if ((M <= 64 || (M <= 768 && N <= 4096) || want_logits) && astat_lds_bytes(mt, K) <= 150 * 1024) {
         {
           const int n_strips = N / 16, chunks = (M + 15) / 16;
           int per_wg = 4 * std::max(1, (n_strips + 4 * 384 - 1) / (4 * 384));
