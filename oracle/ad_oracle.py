@@ -12,7 +12,9 @@ What it computes, each part written out from the paper's definitions:
   equation, the bifurcation position c, the accepted block);
 * Input-guided Aggressive Decoding (Section 3.1, Algorithm 1);
 * Generalized Aggressive Decoding (Section 3.2, draft and verify substeps) with a
-  non-autoregressive block drafter (Section 3.2.1).
+  non-autoregressive block drafter (Section 3.2.1);
+* the relaxed verification of GAD++ (Section 3.2.3: a drafted token stands if it is among the
+  verifier's top-beta candidates and its log-likelihood is within tau of the top-1's).
 
 Arithmetic is plain numpy in the dtype chosen at construction (float32 by default,
 float64 for a reference of higher precision).  A matmul is the only library
@@ -270,11 +272,32 @@ def greedy(model: Model, src, max_len: int, eos: int, bos: int, incremental: boo
     return (out, np.stack(rows)) if return_logits else out
 
 
-def verify(st: DecoderState, pending: int, draft, return_logits: bool = False):
+def gadpp_requirement(row_logits: np.ndarray, token: int, beta: int, tau: float) -> bool:
+    """GAD++ requirement for one position (Section 3.2.3, its two inequalities), written out
+    from the definition: log P(token) >= log P(the beta-th ranked token) and
+    log P(top-1) - log P(token) <= tau.
+
+    log P = logit - logsumexp(logits), so both inequalities are statements about logits: the
+    normaliser is the same on both sides and cancels.  They are decided on the float32 values of
+    the logits (the precision the HIP path decides them in); the gap is one float32 subtraction.
+    The never-matching id meets no requirement."""
+    if token < 0:
+        return False
+    lg = np.asarray(row_logits, dtype=np.float32)
+    ranked = np.sort(lg)[::-1]                   # descending: ranked[b - 1] is the b-th ranked score
+    beta = min(int(beta), lg.shape[0])
+    in_top_beta = lg[token] >= ranked[beta - 1]
+    within_tau = np.float32(ranked[0] - lg[token]) <= np.float32(tau)
+    return bool(in_top_beta and within_tau)
+
+
+def verify(st: DecoderState, pending: int, draft, return_logits: bool = False, beta: int = 1, tau: float = 0.0):
     """Parallel verification of a k-token draft after the accepted prefix.
 
     Rows fed: (o_j, d_1, .., d_{k-1}); row i predicts position j+i.  The last draft
-    token is compared but never fed.  c = first i with d_i != o_hat_i, else k.
+    token is compared but never fed.  o_hat_i = arg max of row i (verifier equation); with
+    beta > 1 (GAD++, Section 3.2.3) o_hat_i = d_i wherever d_i meets the GAD++ requirement.
+    c = first i with d_i != o_hat_i, else k.
     Accepted block = (d_1..d_{c-1}, o_hat_c) = o_hat_{1..c}.  The caller appends and
     calls st.keep()."""
     k = len(draft)
@@ -282,6 +305,10 @@ def verify(st: DecoderState, pending: int, draft, return_logits: bool = False):
     assert min(fed) >= 0, "the never-matching id may only be the last draft token"
     lg = st.forward(fed)
     o_hat = [argmax_lowest(lg[i]) for i in range(k)]
+    if beta > 1:
+        for i in range(k):
+            if gadpp_requirement(lg[i], int(draft[i]), beta, tau):
+                o_hat[i] = int(draft[i])
     c = k
     for i in range(k):
         if int(draft[i]) != o_hat[i]:
@@ -338,12 +365,13 @@ def draft_nat(drafter: Model, memory, prefix, k: int, mask_id: int):
 
 
 def gad(verifier: Model, src, k: int, max_len: int, eos: int, bos: int, drafter: Model | None = None,
-        mask_id: int | None = None, draft_override=None):
+        mask_id: int | None = None, draft_override=None, beta: int = 1, tau: float = 0.0):
     """Draft-then-verify iterations until [EOS] or max_len.
 
     The draft comes from the block drafter, or, if `draft_override` (a positional
     sequence D with D[p] proposed for output position p) is given, from D; when both
-    are given the drafter still runs and its output is discarded."""
+    are given the drafter still runs and its output is discarded.  beta > 1 verifies with the
+    GAD++ requirement (the output then need not be the greedy one)."""
     st = DecoderState(verifier, verifier.encode(src))
     mem_d = drafter.encode(src) if drafter is not None else None
     o, stats = [bos], Stats()
@@ -356,7 +384,7 @@ def gad(verifier: Model, src, k: int, max_len: int, eos: int, bos: int, drafter:
         if draft_override is not None:
             # D has no entry past its end: the block stops there (at least one row)
             draft = [int(t) for t in draft_override[j:j + kk]] or [NEVER]
-        o_hat, c = verify(st, o[-1], draft)
+        o_hat, c = verify(st, o[-1], draft, beta=beta, tau=tau)
         add = _truncate(o_hat[:c], j, max_len, eos)
         st.keep(st.length + len(add))
         o += add

@@ -240,3 +240,92 @@ def test_suffix_match_worked_cases():
     assert O.suffix_match([0, 5, 7], [0, 7, 8, 7, 9, -1]) is None     # "7" twice, "5 7" never
     assert O.suffix_match([0, 8, 7], [0, 7, 8, 7, 9, -1]) == 3        # "8 7" once
     assert O.suffix_match([0, 6], [0, 7, 8, -1]) is None
+
+
+# ------------------------------------------------------------ GAD++ requirement (Section 3.2.3)
+def test_gadpp_requirement_worked_cases():
+    """Hand-worked rows.  Scores 2.0 > 1.5 > 0.25 > -1.0: token 1 is ranked 2nd with gap 0.5,
+    token 2 is ranked 3rd with gap 1.75."""
+    row = np.array([2.0, 1.5, 0.25, -1.0])
+    assert O.gadpp_requirement(row, 1, beta=2, tau=1.0)
+    assert not O.gadpp_requirement(row, 1, beta=2, tau=0.25)      # in the top 2, gap too large
+    assert O.gadpp_requirement(row, 1, beta=2, tau=0.5)           # the gap bound is inclusive
+    assert not O.gadpp_requirement(row, 2, beta=2, tau=5.0)       # ranked 3rd
+    assert O.gadpp_requirement(row, 2, beta=3, tau=1.75)          # the rank bound is inclusive
+    assert not O.gadpp_requirement(row, 2, beta=3, tau=1.5)
+    assert O.gadpp_requirement(row, 0, beta=1, tau=0.0)           # the top-1 token always stands
+    assert not O.gadpp_requirement(row, O.NEVER, beta=4, tau=100.0)
+    # equal scores: a token that ties with the beta-th ranked one is in the top beta
+    tie = np.array([1.0, 0.5, 0.5, 0.5, -2.0])
+    assert all(O.gadpp_requirement(tie, t, beta=2, tau=1.0) for t in (1, 2, 3))
+    assert not O.gadpp_requirement(tie, 4, beta=4, tau=10.0)
+
+
+def test_gadpp_requirement_equals_the_log_likelihood_definition_and_the_count_form():
+    """Against the definition on log-likelihoods in float64 (log-softmax, ranking by a sort of
+    its own) on rows whose scores and gaps are exact in float32 (multiples of 1/8), so that the
+    precision of the decision plays no part; and against the count form the HIP path uses:
+    token within the top beta <=> fewer than beta scores are strictly greater."""
+    rng = np.random.default_rng(5)
+    for trial in range(300):
+        V = int(rng.integers(2, 12))
+        row = rng.integers(-24, 25, size=V) / 8.0                  # ties do occur
+        beta = int(rng.integers(1, V + 2))
+        tau = float(rng.integers(0, 40)) / 8.0
+        logp = row - (np.log(np.sum(np.exp(row - row.max()))) + row.max())
+        order = sorted(range(V), key=lambda t: -logp[t])
+        kth = logp[order[min(beta, V) - 1]]
+        for t in range(V):
+            want = bool(logp[t] >= kth - 1e-12 and logp[order[0]] - logp[t] <= tau + 1e-12)
+            assert O.gadpp_requirement(row, t, beta, tau) == want
+            count_form = int(np.sum(row > row[t])) < beta and row.max() - row[t] <= tau
+            assert O.gadpp_requirement(row, t, beta, tau) == bool(count_form)
+
+
+def test_gadpp_requirement_grows_with_beta_and_tau():
+    rng = np.random.default_rng(6)
+    row = rng.normal(size=40)
+    for t in range(40):
+        prev = False
+        for beta, tau in ((1, 0.0), (2, 0.5), (3, 1.0), (5, 3.0), (40, 100.0)):
+            now = O.gadpp_requirement(row, t, beta, tau)
+            assert now or not prev
+            prev = now
+        assert prev                                                 # beta = V, huge tau: everything stands
+
+
+def test_gadpp_special_cases_of_the_decode_loop():
+    """beta = 1 (or tau = 0) is the vanilla verification: greedy output.  beta = V with an
+    unbounded gap accepts every drafted token: the output is the draft, ceil(T/k) iterations."""
+    dims, ver = make("micro", 41)
+    src = src_for(dims, 8, 9)
+    g = O.greedy(ver, src, 12, EOS, BOS)
+    D = [int(t) for t in positional_draft(g, 0.4, 9, dims["vocab"])[0]]
+    ref, st_ref = O.gad(ver, src, 4, 12, EOS, BOS, draft_override=D)
+    assert ref == g
+    for beta, tau in ((1, 5.0), (7, 0.0)):
+        out, st = O.gad(ver, src, 4, 12, EOS, BOS, draft_override=D, beta=beta, tau=tau)
+        assert out == g and st.accepted == st_ref.accepted
+    Dn = [t if t != EOS else 5 for t in D][:12]                     # no EOS: nothing truncates the blocks
+    out, st = O.gad(ver, src, 4, 12, EOS, BOS, draft_override=Dn, beta=dims["vocab"], tau=1e9)
+    assert out == Dn and st.iterations == math.ceil(len(Dn) / 4)
+
+
+def test_gadpp_accepts_a_superset_and_bifurcates_at_the_first_failure():
+    """One verify call: o_hat equals the draft exactly where the requirement holds and the arg max
+    elsewhere; c is the first position where it fails."""
+    dims, ver = make("micro", 42)
+    src = src_for(dims, 10, 8)
+    g = O.greedy(ver, src, 10, EOS, BOS)
+    rng = np.random.default_rng(11)
+    st = O.DecoderState(ver, ver.encode(src))
+    draft = [int(t) for t in rng.integers(5, dims["vocab"], size=6)]
+    draft[0] = g[0]
+    o_hat, c, lg = O.verify(st, BOS, draft, return_logits=True, beta=3, tau=1.0)
+    met = [O.gadpp_requirement(lg[i], draft[i], 3, 1.0) for i in range(6)]
+    assert met[0]
+    for i in range(6):
+        assert o_hat[i] == (draft[i] if met[i] else O.argmax_lowest(lg[i]))
+    assert c == (met.index(False) + 1 if False in met else 6)
+    o_hat1, c1 = O.verify(O.DecoderState(ver, ver.encode(src)), BOS, draft)
+    assert c >= c1
