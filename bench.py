@@ -249,6 +249,24 @@ def main():
                                     "tokens_per_s": tk / t_gad, "greedy_tokens_per_s": tk / t_gr,
                                     "speedup_vs_greedy": t_gr / t_gad, "iterations": it,
                                     "mean_tokens_per_iteration": tk / max(1, it) / Bw}
+            # the same decode under the relaxed verification (GAD++, the paper's two presets): not
+            # greedy-identical, so only its rate and acceptance are reported (random-init scores
+            # put a substituted token far from the top, so few extra tokens stand; the figure shows
+            # what the second pass of the output projection costs)
+            for name, beta, tau in (("gadpp_3_1.0", 3, 1.0), ("gadpp_5_3.0", 5, 3.0)):
+                cx.set_gadpp(beta, tau)
+                cx.decode_gad(groups[0][0], cfgw["k"], use_drafter=True, draft_override=drafts[0], max_out=groups[0][1])
+                torch.cuda.synchronize()
+                tk2 = it2 = 0
+                t0 = time.perf_counter()
+                for (ss, mo), D in zip(groups, drafts):
+                    o, st = cx.decode_gad(ss, cfgw["k"], use_drafter=True, draft_override=D, max_out=mo)
+                    tk2 += sum(len(x) for x in o); it2 += st["iterations"]
+                torch.cuda.synchronize()
+                t2 = time.perf_counter() - t0
+                gad[f"workload{wl}"][name] = {"tokens_per_s": tk2 / t2, "iterations": it2,
+                                              "mean_tokens_per_iteration": tk2 / max(1, it2) / Bw}
+            cx.set_gadpp(1, 0.0)
             cx.close()
 
     # ---------------- measured peaks of this machine (context for the nominal ones) -------------------

@@ -213,6 +213,19 @@ enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 
+/* GAD++, the relaxed verification of Section 3.2.3 (its two inequalities).  With beta > 1, every
+ * later ad_verify (and the decode loops built on it) lets a drafted token stand where the
+ * verifier ranks it among its top `beta` candidates AND the top-1 log-likelihood exceeds the
+ * drafted token's by at most `tau`: verified[b][i] is then the drafted token instead of the arg
+ * max, and the bifurcation is the first position whose drafted token meets neither that nor the
+ * top-1 match.  Log-likelihood differences are taken as differences of the fp32 output scores
+ * (the normaliser cancels); "among the top beta" means fewer than beta tokens score strictly
+ * higher, so tokens that tie with the beta-th ranked one are in.  AD_NEVER is never accepted.
+ * The output is no longer the greedy one.  beta = 1 (the default) restores top-1 matching;
+ * tau is ignored then.  Costs a second pass of the output projection per call.
+ * AD_EINVAL: beta outside [1, vocab], tau negative or not finite. */
+int ad_set_gadpp(ad_ctx* ctx, int32_t beta, float tau);
+
 /* ---- host-only logic, exposed so that it can be tested without a GPU -------------------------- */
 
 /* The if-test of Algorithm 1: o = (o_0..o_j), x = guide with sentinels (x_0 = [BOS],

@@ -24,7 +24,7 @@ EXPORTS = [
     "ad_weights_pack",
     "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
-    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy",
+    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp",
 ]
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
@@ -99,6 +99,7 @@ def lib():
     L.ad_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.ad_calibration_copy.restype = C.c_int
     L.ad_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]; L.ad_set_option.restype = C.c_int
+    L.ad_set_gadpp.argtypes = [C.c_void_p, C.c_int32, C.c_float]; L.ad_set_gadpp.restype = C.c_int
     L.ad_get_option.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]; L.ad_get_option.restype = C.c_int
     L.ad_suffix_match.argtypes = [_I32P, C.c_int, _I32P, C.c_int, C.POINTER(C.c_int)]; L.ad_suffix_match.restype = C.c_int
     L.ad_host_simulate.argtypes = [C.c_int, _I32P, C.c_int, _I32P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -314,6 +315,9 @@ class Context:
                                     _p(out), _p(n), C.byref(st)), self.h)
         self.B = B
         return self._result(out, n, st)
+
+    def set_gadpp(self, beta, tau):
+        _check(self.L.ad_set_gadpp(self.h, int(beta), float(tau)), self.h)
 
     def set_option(self, option, value):
         _check(self.L.ad_set_option(self.h, option, value), self.h)

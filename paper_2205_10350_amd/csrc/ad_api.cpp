@@ -40,7 +40,7 @@ struct Plan {
   int l_cap = 0;        // rows of a sequence's self-attention cache
   int n_strips = 0;
   int max_pos = 0;
-  size_t pe, x, s, xa, q, att, tk, tv, f, xg, part_val, part_idx, o_hat, o_val, logits;
+  size_t pe, x, s, xa, q, att, tk, tv, f, xg, part_val, part_idx, o_hat, o_val, logits, draft_lp, draft_col;
   size_t cache_k, cache_v, cache_layer_stride;          // [NL][B*l_cap, d]
   size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
   size_t row_tok, row_pos, row_seq, row_dst, row_dst2, row_start, self_desc, cross_desc, mask_rows;
@@ -76,6 +76,8 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.part_idx = take((size_t)p.mv_cap * p.n_strips * 4);
   p.o_hat = take((size_t)p.mv_cap * 4);
   p.o_val = take((size_t)p.mv_cap * 4);
+  p.draft_lp = take((size_t)p.mv_cap * 4);
+  p.draft_col = take((size_t)p.mv_cap * 4);
   p.logits = take(c.debug_logits ? (size_t)p.mv_cap * c.vocab * 4 : 0);
   p.cache_layer_stride = align_up(B * p.l_cap * d * p.esz);
   p.cache_k = take(p.cache_layer_stride * c.dec_layers);
@@ -138,6 +140,8 @@ struct ad_ctx {
   // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
   const LnW* ln_pending = nullptr;
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
+  int gadpp_beta = 1;             // GAD++ (Section 3.2.3): 1 = plain top-1 verification
+  float gadpp_tau = 0.f;
   int fused_grid = 0, fused_stages = 0, fused_teams = 0;
   size_t fused_lds = 0;
   unsigned long long dev_base = 0, team_base[kMaxTeams] = {};
@@ -443,7 +447,10 @@ static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bo
 // The verify forward over the M packed rows the tables describe.  ev (optional) brackets the
 // output-projection kernel.
 // finish = false: the caller finishes the arg max itself (n_part partials per row are returned)
-static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr, bool finish = true) {
+// plain_rows = true: the last LayerNorm runs as a launch of its own, so the rows the output
+// projection multiplies are in memory (xa) for whoever multiplies them again
+static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr, bool finish = true,
+                          bool plain_rows = false) {
   const Plan& p = c->plan;
   const ModelW& w = c->w[AD_VERIFIER];
   embed_rows(c, w, M);
@@ -455,6 +462,7 @@ static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_
                      c->ws + p.mem_v[0] + l * p.mem_layer_stride);
     ffn_block(c, L.ffn, L.ln3, M);
   }
+  if (plain_rows) flush_ln(c, M);
   if (ev_a) (void)hipEventRecord(ev_a, c->stream);
   c->ln_vocab = c->ln_pending;
   c->ln_pending = nullptr;
@@ -736,7 +744,8 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   int32_t* h = c->pin;
   memcpy(h, k, (size_t)B * 4);
   for (int b = 0; b < B; ++b) memcpy(h + B + (size_t)b * km, draft + (size_t)b * km, (size_t)km * 4);
-  bool fused = c->fused_rows > 0 && M <= c->fused_rows;
+  const bool gadpp = c->gadpp_beta > 1;
+  bool fused = c->fused_rows > 0 && M <= c->fused_rows && !gadpp;
   // One launch per stage: the two small kernels that need k and the draft read them where they
   // are, in the pinned (device-visible) staging buffer, and the result is written there too: no
   // copy operations around the forward.  The persistent kernel works on device copies at
@@ -767,18 +776,40 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
       HIP_TRY(c, fused_verify_forward(c, k, M, B, true));
       HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     } else {
+      int* result_dst = mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result);
+      auto accept = [&](const float* pv, const int* pi, int stride, int n_part) {
+        launch_argmax_accept(pv, pi, stride, n_part, c->at<int>(p.o_hat), c->at<float>(p.o_val), k_src, draft_src, km,
+                             t.row_start, B, cf.eos, cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len),
+                             c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst, c->stream);
+      };
       auto launches = [&]() {
         assemble();
-        const int n_part = verify_forward(c, M, nullptr, nullptr, false);
-        launch_argmax_accept(c->at<float>(p.part_val), c->at<int>(p.part_idx), p.n_strips, n_part, c->at<int>(p.o_hat),
-                             c->at<float>(p.o_val), k_src, draft_src, km, t.row_start, B, cf.eos, cf.max_len,
-                             c->at<int>(p.max_out), c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished),
-                             c->at<int>(p.out), mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result), c->stream);
+        if (!gadpp) {
+          const int n_part = verify_forward(c, M, nullptr, nullptr, false);
+          accept(c->at<float>(p.part_val), c->at<int>(p.part_idx), p.n_strips, n_part);
+          return;
+        }
+        // GAD++ (Section 3.2.3): arg max as before; then the score of every row's drafted token,
+        // a second pass of the output projection that counts the columns scoring above it (the
+        // logits still never reach memory), the relaxed replacement of o_hat, and acceptance
+        const ModelW& w = c->w[AD_VERIFIER];
+        (void)verify_forward(c, M, nullptr, nullptr, true, true);
+        launch_draft_logit(cf.dtype, c->at<void>(p.xa), w.out_w, M, cf.vocab, cf.d_model, t.row_seq, t.row_start,
+                           draft_src, km, c->at<float>(p.draft_lp), c->at<int>(p.draft_col), c->stream);
+        Epi e{};
+        e.mode = EPI_COUNT; e.part_idx = c->at<int>(p.part_idx); e.n_strips = p.n_strips; e.thr = c->at<float>(p.draft_lp);
+        const int n_cnt = launch_gemm(cf.dtype, c->at<void>(p.xa), w.out_w, M, cf.vocab, cf.d_model, e, c->stream);
+        launch_gadpp_apply(c->at<int>(p.part_idx), p.n_strips, n_cnt, c->at<float>(p.draft_lp), c->at<int>(p.draft_col),
+                           c->at<float>(p.o_val), c->at<int>(p.o_hat), M, c->gadpp_beta, c->gadpp_tau, c->stream);
+        accept(c->at<float>(p.o_val), c->at<int>(p.o_hat), 1, 1);
       };
-      // every launch argument is a function of (rows, sequences, longest block) and
-      // of pointers fixed for the context's life
-      const unsigned long long key = shape_key(M, c->fw_max_rows, B, 0);
-      if (!mapped || !run_as_graph(c, key, launches)) launches();
+      // every launch argument is a function of (rows, sequences, longest block), of the GAD++
+      // setting and of pointers fixed for the context's life
+      const unsigned long long key = shape_key(M, c->fw_max_rows, B, gadpp ? 1 : 0);
+      unsigned tau_bits;
+      memcpy(&tau_bits, &c->gadpp_tau, 4);
+      const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;
+      if (!mapped || !run_as_graph(c, key, launches, more)) launches();
       if (!mapped) HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     }
     flags[0] = 0; flags[kBarPlacement - kBarAbort] = 1; flags[kBarPlacement - kBarAbort + 1] = 1;
@@ -974,6 +1005,15 @@ int ad_decode_gad(ad_ctx* c, const int32_t* src, const int32_t* src_len, int B, 
   rc = loop_gad(be, io, k, use_drafter != 0, draft_override ? &D : nullptr);
   if (rc != AD_OK) return rc;
   write_out(c, io, out, out_len, stats, t_enc);
+  return AD_OK;
+}
+
+int ad_set_gadpp(ad_ctx* c, int beta, float tau) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (beta < 1 || beta > c->cfg.vocab) return fail(c, AD_EINVAL, "beta outside [1, vocab]");
+  if (!(tau >= 0.f) || tau > 3.0e38f) return fail(c, AD_EINVAL, "tau must be finite and >= 0");
+  c->gadpp_beta = beta;
+  c->gadpp_tau = tau;
   return AD_OK;
 }
 

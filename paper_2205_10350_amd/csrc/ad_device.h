@@ -156,6 +156,14 @@ __device__ __forceinline__ void argmax_row16(float& v, int& i) {
   argmax_merge(v, i, dpp_move<0x141>(v), dpp_move_i<0x141>(i));
   argmax_merge(v, i, dpp_move<0x140>(v), dpp_move_i<0x140>(i));
 }
+// integer sum over each row of 16 lanes (every lane of the row gets it)
+__device__ __forceinline__ int row16_sum_i(int v) {
+  v += dpp_move_i<0xB1>(v);
+  v += dpp_move_i<0x4E>(v);
+  v += dpp_move_i<0x141>(v);
+  v += dpp_move_i<0x140>(v);
+  return v;
+}
 __device__ __forceinline__ void argmax_wave(float& v, int& i) {
   argmax_row16(v, i);
   float rv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
@@ -349,6 +357,21 @@ __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[
           stg<STC>(e.part_val + (size_t)m * e.n_strips + strip, v);
           stg<STC>(e.part_idx + (size_t)m * e.n_strips + strip, idx);
         }
+      }
+    }
+    return;
+  }
+  if (e.mode == EPI_COUNT) {
+    const int strip = n0 >> 4;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      if (t >= mt_used) break;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + t * 16 + kq * 4 + i;
+        const float th = e.thr[m < M ? m : M - 1];
+        const int cnt = row16_sum_i(acc[t][i] > th ? 1 : 0);
+        if (r == 0 && m < M) stg<STC>(e.part_idx + (size_t)m * e.n_strips + strip, cnt);
       }
     }
     return;

@@ -55,7 +55,9 @@ struct LnA {
 };
 
 // ---- GEMM epilogues ----------------------------------------------------------------------------
-enum EpiMode { EPI_QKV = 0, EPI_KV = 1, EPI_STORE = 2, EPI_RELU = 3, EPI_RESID = 4, EPI_ARGMAX = 5 };
+// EPI_COUNT (output projection only): per row, how many columns score strictly above the row's
+// threshold `thr`; integer partials go where EPI_ARGMAX puts its index partials.
+enum EpiMode { EPI_QKV = 0, EPI_KV = 1, EPI_STORE = 2, EPI_RELU = 3, EPI_RESID = 4, EPI_ARGMAX = 5, EPI_COUNT = 6 };
 struct Epi {
   int mode;
   int d;                  // model width (column split of QKV / KV)
@@ -69,6 +71,7 @@ struct Epi {
   int* part_idx;          // ARGMAX: [M, n_strips]
   int n_strips;
   float* logits;          // ARGMAX: optional full logits [M,N]
+  const float* thr;       // COUNT: [M] thresholds
 };
 
 // ---- persistent fused forward (ad_fused.hip) ---------------------------------------------------------
@@ -157,6 +160,15 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
 // second stage of the arg max: n_part partials per row, rows `stride` entries apart
 void launch_argmax_finish(const float* part_val, const int* part_idx, int M, int stride, int n_part, int* o_hat,
                           float* o_val, hipStream_t s);
+// GAD++ (Section 3.2.3).  Score of every row's drafted token, by the same dot-product chain the
+// output projection uses (bit-identical to the logit it computes for that column): lp[m], and the
+// drafted token col[m] (negative: the never-matching id).
+void launch_draft_logit(int dtype, const void* A, const void* W, int M, int N, int K, const int* row_seq,
+                        const int* row_start, const int* draft, int k_max, float* lp, int* col, hipStream_t s);
+// A row's drafted token replaces its arg max where fewer than `beta` columns score above it
+// (count partials of an EPI_COUNT launch) and top1 - lp <= tau.
+void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float* lp, const int* col,
+                        const float* o_val, int* o_hat, int M, int beta, float tau, hipStream_t s);
 void launch_gather_rows(int dtype, const void* src, const int* rows, int n, int d, void* dst, hipStream_t s);
 
 // Row assembly of a verify call: from k[B], draft[B,k_max], len[B], pending[B] builds the

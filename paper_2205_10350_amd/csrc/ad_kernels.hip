@@ -232,7 +232,8 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
 
 // AMAX: 0 = an ordinary epilogue, 1 = output projection with the running arg max, 2 = the same and the
 // logits are also stored (tests; only instantiated for MT = 1, SP = 1: a store inside the unit
-// loop makes the compiler wait for every weight fetch in flight at each unit)
+// loop makes the compiler wait for every weight fetch in flight at each unit), 3 = EPI_COUNT: per
+// row, the number of columns that score above the row's threshold
 template <int MT, int AMAX, int SP, bool ONE>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, Epi e, int strips_per_wg, int groups,
@@ -311,7 +312,15 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   float bv[NB];
   int bi[NB];
 #pragma unroll
-  for (int x = 0; x < NB; ++x) { bv[x] = -INFINITY; bi[x] = n_units > 0 ? (s_first << 4) + r : 0x7fffffff; }
+  for (int x = 0; x < NB; ++x) {
+    if constexpr (AMAX == 3) {   // bv = the row's threshold, bi = this lane's count
+      const int row = m0 + (x >> 2) * 16 + kq * 4 + (x & 3);
+      bv[x] = e.thr[row < M ? row : M - 1];
+      bi[x] = 0;
+    } else {
+      bv[x] = -INFINITY; bi[x] = n_units > 0 ? (s_first << 4) + r : 0x7fffffff;
+    }
+  }
   // MT = 4: the A fragments in flight across steps and units (see the unit)
   constexpr int AFB = MT < 4 ? 2 : 1;
   uint4 ar[AFB == 1 ? MT : 1];
@@ -417,8 +426,12 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
             for (int i = 0; i < 4; ++i) {
               const float v = acc[j][t][i];
               const bool better = v > bv[t * 4 + i];
-              bv[t * 4 + i] = better ? v : bv[t * 4 + i];
-              bi[t * 4 + i] = better ? n : bi[t * 4 + i];
+              if constexpr (AMAX == 3) {
+                bi[t * 4 + i] += better ? 1 : 0;
+              } else {
+                bv[t * 4 + i] = better ? v : bv[t * 4 + i];
+                bi[t * 4 + i] = better ? n : bi[t * 4 + i];
+              }
             }
           if constexpr (AMAX == 2) {
             for (int t = 0; t < MT; ++t)
@@ -447,7 +460,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     int* mi = (int*)(mv + 4 * ROWS);
 #pragma unroll
     for (int x = 0; x < MT * 4; ++x) {
-      argmax_row16(bv[x], bi[x]);
+      if constexpr (AMAX == 3) bi[x] = row16_sum_i(bi[x]);
+      else argmax_row16(bv[x], bi[x]);
       if (r == 0) {
         const int row = (x >> 2) * 16 + kq * 4 + (x & 3);
         mv[wave * ROWS + row] = bv[x];
@@ -456,12 +470,19 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     }
     __syncthreads();
     if ((int)threadIdx.x < ROWS && m0 + (int)threadIdx.x < M) {
-      float v = mv[threadIdx.x];
-      int idx = mi[threadIdx.x];
+      if constexpr (AMAX == 3) {
+        int cnt = mi[threadIdx.x];
 #pragma unroll
-      for (int w = 1; w < 4; ++w) argmax_merge(v, idx, mv[w * ROWS + threadIdx.x], mi[w * ROWS + threadIdx.x]);
-      e.part_val[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = v;
-      e.part_idx[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = idx;
+        for (int w = 1; w < 4; ++w) cnt += mi[w * ROWS + threadIdx.x];
+        e.part_idx[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = cnt;
+      } else {
+        float v = mv[threadIdx.x];
+        int idx = mi[threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) argmax_merge(v, idx, mv[w * ROWS + threadIdx.x], mi[w * ROWS + threadIdx.x]);
+        e.part_val[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = v;
+        e.part_idx[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = idx;
+      }
     }
   }
 }
@@ -517,11 +538,15 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
       return gx;
     }
   }
+  using I3 = std::integral_constant<int, 3>;
+  const bool count = e.mode == EPI_COUNT;
   if (K == 512) {
     if (amax) go(I1{}, std::true_type{});
+    else if (count) go(I3{}, std::true_type{});
     else go(I0{}, std::true_type{});
   } else {
     if (amax) go(I1{}, std::false_type{});
+    else if (count) go(I3{}, std::false_type{});
     else go(I0{}, std::false_type{});
   }
   return gx;
@@ -560,6 +585,11 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, c
       e.part_val[(size_t)m * e.n_strips + blockIdx.x] = v;
       e.part_idx[(size_t)m * e.n_strips + blockIdx.x] = idx;
     }
+    return;
+  }
+  if (e.mode == EPI_COUNT) {
+    const int cnt = row16_sum_i(n < N && acc > e.thr[m < M ? m : M - 1] ? 1 : 0);
+    if (tx == 0 && m < M) e.part_idx[(size_t)m * e.n_strips + blockIdx.x] = cnt;
     return;
   }
   if (m < M && n < N) epi_store<float>(e, m, n, N, acc);
@@ -951,6 +981,91 @@ void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part
                           hipStream_t s) {
   k_argmax_accept<<<B, 256, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
                                     max_out, len, pending, finished, out, result);
+}
+// ------------------------------------------------------------------------------------- GAD++ (Section 3.2.3)
+// The drafted token of packed row m: draft[b][i] for row i of sequence b.
+__device__ __forceinline__ int drafted_token(const int* __restrict__ row_seq, const int* __restrict__ row_start,
+                                             const int* __restrict__ draft, int k_max, int m) {
+  const int b = row_seq[m];
+  return draft[b * k_max + (m - row_start[b])];
+}
+// Score of each row's drafted token.  One wave per 16 rows: the MFMA tile whose column j holds
+// the weight row of row j's drafted token; its diagonal is what is asked for.  Operand layouts,
+// instruction and k order are those of the output projection, and an MFMA output element is a dot
+// product of its own, so lp[m] equals the logit that projection computes for (m, token), bit for bit.
+__global__ __launch_bounds__(64) void k_draft_logit_bf16(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                         int M, int N, int K, const int* __restrict__ row_seq,
+                                                         const int* __restrict__ row_start,
+                                                         const int* __restrict__ draft, int k_max,
+                                                         float* __restrict__ lp, int* __restrict__ col) {
+  const int lane = threadIdx.x, r = lane & 15, kq = lane >> 4;
+  const int m = min((int)blockIdx.x * 16 + r, M - 1);
+  const int tok = drafted_token(row_seq, row_start, draft, k_max, m);
+  const int c = min(max(tok, 0), N - 1);
+  const bf16_t* ap = A + (size_t)m * K + kq * 8;
+  const bf16_t* wp = W + (size_t)(c >> 4) * 16 * K + ((c & 15) + 16 * kq) * 8;   // tile (strip, step u) at + u * 512
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < K; k0 += 32) {
+    const bf16x8 a = __builtin_bit_cast(bf16x8, *(const uint4*)(ap + k0));
+    const bf16x8 b = __builtin_bit_cast(bf16x8, *(const uint4*)(wp + k0 * 16));
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+  }
+  // lane (r, kq) holds rows 4 kq .. 4 kq + 3 of column r: the diagonal element of row r sits in
+  // the lane with kq = r / 4
+  if (kq == (r >> 2) && (int)blockIdx.x * 16 + r < M) {
+    const int i = r & 3;
+    lp[m] = i == 0 ? acc[0] : i == 1 ? acc[1] : i == 2 ? acc[2] : acc[3];
+    col[m] = tok;
+  }
+}
+// fp32 path: the fused multiply-add chain of k_gemm_f32, k ascending.
+__global__ void k_draft_logit_f32(const float* __restrict__ A, const float* __restrict__ W, int M, int N, int K,
+                                  const int* __restrict__ row_seq, const int* __restrict__ row_start,
+                                  const int* __restrict__ draft, int k_max, float* __restrict__ lp,
+                                  int* __restrict__ col) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= M) return;
+  const int tok = drafted_token(row_seq, row_start, draft, k_max, m);
+  const int c = min(max(tok, 0), N - 1);
+  float acc = 0.f;
+  for (int k = 0; k < K; ++k) acc = fmaf(A[(size_t)m * K + k], W[(size_t)c * K + k], acc);
+  lp[m] = acc;
+  col[m] = tok;
+}
+void launch_draft_logit(int dtype, const void* A, const void* W, int M, int N, int K, const int* row_seq,
+                        const int* row_start, const int* draft, int k_max, float* lp, int* col, hipStream_t s) {
+  if (M <= 0) return;
+  if (dtype == AD_BF16)
+    k_draft_logit_bf16<<<(M + 15) / 16, 64, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, row_seq, row_start, draft,
+                                                    k_max, lp, col);
+  else
+    k_draft_logit_f32<<<(M + 63) / 64, 64, 0, s>>>((const float*)A, (const float*)W, M, N, K, row_seq, row_start, draft,
+                                                   k_max, lp, col);
+}
+// One wave per row: sums the row's count partials; the drafted token stands in for the arg max
+// if fewer than beta columns score above it and the top score exceeds its score by at most tau
+// (both inequalities of the GAD++ requirement, on fp32 scores: log-likelihood differences are
+// score differences).
+__global__ __launch_bounds__(256) void k_gadpp_apply(const int* __restrict__ part_cnt, int stride, int n_part,
+                                                     const float* __restrict__ lp, const int* __restrict__ col,
+                                                     const float* __restrict__ o_val, int* __restrict__ o_hat, int M,
+                                                     int beta, float tau) {
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (m >= M) return;
+  int cnt = 0;
+  for (int i = lane; i < n_part; i += 64) cnt += part_cnt[(size_t)m * stride + i];
+  cnt = row16_sum_i(cnt);
+  cnt = __builtin_amdgcn_readlane(cnt, 0) + __builtin_amdgcn_readlane(cnt, 16) + __builtin_amdgcn_readlane(cnt, 32) +
+        __builtin_amdgcn_readlane(cnt, 48);
+  if (lane == 0) {
+    const int tok = col[m];
+    if (tok >= 0 && cnt < beta && o_val[m] - lp[m] <= tau) o_hat[m] = tok;
+  }
+}
+void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float* lp, const int* col,
+                        const float* o_val, int* o_hat, int M, int beta, float tau, hipStream_t s) {
+  if (M <= 0) return;
+  k_gadpp_apply<<<(M + 3) / 4, 256, 0, s>>>(part_cnt, stride, n_part, lp, col, o_val, o_hat, M, beta, tau);
 }
 __global__ void k_reset_state(int* len, int* pending, int* finished, int B, int bos) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
