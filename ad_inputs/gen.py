@@ -21,6 +21,10 @@ DIMS = {
     "tiny": dict(enc_layers=2, dec_layers=2, d_model=128, n_heads=4, d_ffn=512, vocab=2000),
     "base": dict(enc_layers=6, dec_layers=6, d_model=512, n_heads=8, d_ffn=2048, vocab=32000),
     "big": dict(enc_layers=6, dec_layers=6, d_model=1024, n_heads=16, d_ffn=4096, vocab=32000),
+    # deep encoder, shallow decoder at the big width (the paper's second input-guided model) and a
+    # small model of the same asymmetry for parity tests
+    "deep_shallow": dict(enc_layers=12, dec_layers=2, d_model=1024, n_heads=16, d_ffn=4096, vocab=32000),
+    "tiny_deep": dict(enc_layers=3, dec_layers=1, d_model=128, n_heads=4, d_ffn=512, vocab=2000),
     # small shapes for brute-force tests of the invariant
     "nano": dict(enc_layers=1, dec_layers=1, d_model=16, n_heads=2, d_ffn=32, vocab=8),
     "micro": dict(enc_layers=1, dec_layers=2, d_model=32, n_heads=2, d_ffn=64, vocab=64),
@@ -38,6 +42,9 @@ CONFIGS = {
             src_len=("uniform", 20, 80), max_out=("src",), k=25, rate=0.3, seed=1003),
     4: dict(model="big", dtype="bf16", mode="positional", drafter=True, batch=8, n_sent=32,
             src_len=("fixed", 512), max_out=("fixed", 128), k=25, rate=0.3, seed=1004),
+    # input-guided decoding with the deep-encoder / shallow-decoder model, lengths as workload 1
+    5: dict(model="deep_shallow", dtype="bf16", mode="guide", batch=1, n_sent=64, src_len=("normal", 25, 8, 5, 64),
+            max_out=("src",), rate=0.1, seed=1005),
 }
 
 

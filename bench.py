@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bs32", action="store_true")
     ap.add_argument("--no-gad", action="store_true", help="skip the block-drafter workloads 3 and 4")
+    ap.add_argument("--no-next", action="store_true", help="skip the row/batch sweeps and the deep-encoder workload")
     ap.add_argument("--cpu-sentences", type=int, default=256)
     ap.add_argument("--sentences", type=int, default=0,
                     help="use only the first N sentences of the batch-1 workload (counter runs, where every "
@@ -149,7 +150,7 @@ def main():
         # algorithmic bytes).  Average launch duration = 50 launches back to back between two HIP
         # events on the kernel's stream / 50 (a single launch bracketed by two events inside a
         # forward reads 3-4 us more, the cost of the two event records: staged_vocab_kernel_us).
-        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<1, true, 1> (output projection + arg max)", "rows": M1,
+        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<1, 1, 1, true> (output projection + arg max)", "rows": M1,
                     "achieved": voc_bytes / (voc_b2b_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                     "frac": voc_bytes / (voc_b2b_us * 1e-6) / HBM_PEAK, "traffic": VOCAB_KERNEL_TRAFFIC_BYTES}
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,
@@ -204,7 +205,68 @@ def main():
                 "mfma_frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK,
                 "staged_launches_us": staged32_us, "staged_vocab_kernel_us": voc32_us,
                 "staged_vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
+    # ---------------- verify forward against block size and batch size (roofline against rows) -------
+    sweeps = None
+    if not args.no_next:
+        rng = np.random.default_rng(77)
+        src_len, blk = 25, 36
+        def point(Bs, rows_each):
+            ss = [rng.integers(5, V, size=src_len).astype(np.int32) for _ in range(Bs)]
+            ctx.encode(ad.AD_VERIFIER, ss, max_out=[64] * Bs)
+            ctx.verify([[int(t) for t in rng.integers(5, V, size=rows_each)] for _ in range(Bs)])
+            f_us, _, v_us = ctx.time_verify_forward(20, back_to_back=True)
+            Ms = Bs * rows_each
+            kvb = dims["dec_layers"] * 2 * 2 * dims["d_model"] * (Ms + Bs * src_len)
+            return {"batch": Bs, "rows": Ms, "forward_us": f_us, "vocab_kernel_us": v_us,
+                    "forward_hbm_frac": (2 * params + kvb) / (f_us * 1e-6) / HBM_PEAK,
+                    "forward_mfma_frac": 2.0 * Ms * params / (f_us * 1e-6) / MFMA_BF16_PEAK,
+                    "vocab_hbm_frac": 2 * V * dims["d_model"] / (v_us * 1e-6) / HBM_PEAK,
+                    "vocab_mfma_frac": 2.0 * Ms * V * dims["d_model"] / (v_us * 1e-6) / MFMA_BF16_PEAK}
+        sweeps = {"block_size_batch1": [point(1, kk) for kk in (1, 2, 4, 8, 10, 15, 20, 25, 30, 40, 64)],
+                  "batch_size_block36": [point(bb, blk) for bb in (1, 2, 4, 8, 16, 32)]}
     ctx.close()
+
+    # ---------------- input-guided decoding, deep encoder + shallow decoder (workload 5) --------------
+    deep = None
+    if not args.no_next:
+        cfg5 = CONFIGS[5]
+        dims5 = model_dims(cfg5["model"])
+        cx = ad.Context(ad.make_config(dims5, max_batch=1, max_src=64, max_len=64, k_max=K_MAX, dtype="bf16",
+                                       special=SPECIAL), init_weights(dims5, cfg5["seed"]))
+        s5, mo5 = draw_sources(cfg5, V)
+        g5 = []
+        cx.decode_greedy([s5[0]], max_out=[mo5[0]])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s_, m_ in zip(s5, mo5):
+            g5.append(cx.decode_greedy([s_], max_out=[m_])[0][0])
+        torch.cuda.synchronize()
+        t_g5 = time.perf_counter() - t0
+        gd5 = [edit_guide(g, cfg5["rate"], cfg5["seed"] + i, V) for i, g in enumerate(g5)]
+        for i in range(8):
+            cx.decode_iad([s5[i]], [gd5[i]], max_out=[mo5[i]])
+        torch.cuda.synchronize()
+        tk5 = it5 = 0
+        t0 = time.perf_counter()
+        for i in range(len(s5)):
+            o, st = cx.decode_iad([s5[i]], [gd5[i]], max_out=[mo5[i]])
+            assert o[0] == g5[i], "draft-and-verify output differs from greedy"
+            tk5 += len(o[0]); it5 += st["iterations"]
+        torch.cuda.synchronize()
+        t5 = time.perf_counter() - t0
+        j5 = int(np.argsort([len(x) for x in s5])[len(s5) // 2])
+        cx.encode(ad.AD_VERIFIER, [s5[j5]], max_out=[mo5[j5]])
+        d5 = (list(gd5[j5]) + [ad.AD_NEVER])[:int(mo5[j5])]
+        cx.verify([d5])
+        f5_us, _, v5_us = cx.time_verify_forward(50, back_to_back=True)
+        p5 = decoder_stream_params(dims5)
+        deep = {"model": "12 encoder + 2 decoder layers, d1024, 16 heads, FFN 4096, vocab 32000", "batch": 1,
+                "sentences": len(s5), "tokens_per_s": tk5 / t5, "greedy_tokens_per_s": tk5 / t_g5,
+                "speedup_vs_greedy": t_g5 / t5, "mean_tokens_per_forward": tk5 / max(1, it5),
+                "verify_rows": len(d5), "verify_forward_us": f5_us, "verify_algorithmic_MB": 2 * p5 / 1e6,
+                "verify_forward_hbm_frac": 2 * p5 / (f5_us * 1e-6) / HBM_PEAK, "vocab_kernel_us": v5_us,
+                "vocab_kernel_hbm_frac": 2 * V * dims5["d_model"] / (v5_us * 1e-6) / HBM_PEAK}
+        cx.close()
 
     # ---------------- draft-and-verify with the block drafter (workloads 3 and 4) ---------------------
     # The drafter forward runs and is timed inside every iteration; its output is replaced by a
@@ -315,7 +377,7 @@ def main():
         "tokens": toks, "verify_forwards": its, "rows_verified": rows,
         "mean_tokens_per_forward": toks / max(1, its),
         "greedy_tokens_per_s": greedy_tps, "speedup_vs_greedy": value / greedy_tps,
-        "verify_forward_bs1": verify_bs1, "bs32": bs32, "gad": gad,
+        "verify_forward_bs1": verify_bs1, "bs32": bs32, "gad": gad, "sweeps": sweeps, "deep_encoder": deep,
         "measured_copy_GBps": copy_gbps,
         "roofline": roofline, "cpu_baseline": cpu,
     }

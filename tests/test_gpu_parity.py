@@ -92,6 +92,7 @@ def _report(log):
 @pytest.mark.parametrize("name,dtype,seed,std", [
     ("tiny", "fp32", 1000, 0.02), ("tiny", "bf16", 1000, 0.02),
     ("tiny", "fp32", 31, 0.15), ("micro", "fp32", 32, 0.3), ("tiny", "bf16", 33, 0.15),
+    ("tiny_deep", "fp32", 34, 0.02), ("tiny_deep", "bf16", 35, 0.02),   # 3 encoder layers, 1 decoder layer
 ])
 def test_verify_logits_teacher_forced(name, dtype, seed, std):
     """One verify forward over the oracle's own greedy prefix: logits, arg max, accepted length.
@@ -125,7 +126,8 @@ def test_verify_logits_teacher_forced(name, dtype, seed, std):
         rig.close()
 
 
-@pytest.mark.parametrize("name,dtype,seed,B", [("tiny", "fp32", 1000, 1), ("tiny", "fp32", 5, 3), ("tiny", "bf16", 6, 3)])
+@pytest.mark.parametrize("name,dtype,seed,B", [("tiny", "fp32", 1000, 1), ("tiny", "fp32", 5, 3), ("tiny", "bf16", 6, 3),
+                                              ("tiny_deep", "fp32", 8, 2), ("tiny_deep", "bf16", 9, 2)])
 def test_decodes_are_greedy_identical_and_match_oracle(name, dtype, seed, B):
     """Workload 0 (tiny, fp32, k = 8, substitution rate 0.1) and batched variants: greedy,
     input-guided and draft-verify outputs are identical to each other and to the oracle; the
