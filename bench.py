@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bs32", action="store_true")
     ap.add_argument("--no-gad", action="store_true", help="skip the block-drafter workloads 3 and 4")
+    ap.add_argument("--no-graphs", action="store_true", help="launch every kernel eagerly (AD_OPT_GRAPHS = 0)")
     ap.add_argument("--no-next", action="store_true", help="skip the row/batch sweeps and the deep-encoder workload")
     ap.add_argument("--cpu-sentences", type=int, default=256)
     ap.add_argument("--sentences", type=int, default=0,
@@ -77,6 +78,8 @@ def main():
     K_MAX = 72
     conf = ad.make_config(dims, max_batch=32, max_src=64, max_len=64, k_max=K_MAX, dtype="bf16", special=SPECIAL)
     ctx = ad.Context(conf, w)
+    if args.no_graphs:
+        ctx.set_option(ad.AD_OPT_GRAPHS, 0)
     if args.calibration_copy:
         a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)

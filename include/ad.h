@@ -208,8 +208,12 @@ int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* 
  * launch-per-stage path the launches of an ad_verify call are captured into a HIP graph per call
  * shape (rows, sequences, longest block) on the shape's third appearance and replayed afterwards
  * (at most 512 shapes); the library switches it off by itself when the context's stream cannot be
- * captured (the null stream cannot).  AD_OPT_GRAPHS_CAPTURED (read only): graphs held. */
-enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4 };
+ * captured (the null stream cannot).  AD_OPT_GRAPHS_CAPTURED (read only): graphs held.
+ * AD_OPT_SPIN_WAIT (0/1, default 1): ad_verify returns as soon as the device has written the
+ * call's result into the (device-mapped) host staging buffer, which the calling thread watches,
+ * instead of waiting for the stream to drain; later calls are ordered behind the unfinished rest
+ * of the stream as usual.  After 50 ms without the result it waits for the stream. */
+enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 

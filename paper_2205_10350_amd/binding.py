@@ -30,6 +30,7 @@ AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
 AD_OPT_GRAPHS = 3
 AD_OPT_GRAPHS_CAPTURED = 4
+AD_OPT_SPIN_WAIT = 5
 
 
 class AdConfig(C.Structure):

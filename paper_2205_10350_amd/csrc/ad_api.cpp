@@ -140,6 +140,8 @@ struct ad_ctx {
   // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
   const LnW* ln_pending = nullptr;
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
+  int ticket = 0;                 // number of the last ad_verify call that waited by watching memory
+  bool spin_wait = true;
   int gadpp_beta = 1;             // GAD++ (Section 3.2.3): 1 = plain top-1 verification
   float gadpp_tau = 0.f;
   int fused_grid = 0, fused_stages = 0, fused_teams = 0;
@@ -449,11 +451,13 @@ static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bo
 // finish = false: the caller finishes the arg max itself (n_part partials per row are returned)
 // plain_rows = true: the last LayerNorm runs as a launch of its own, so the rows the output
 // projection multiplies are in memory (xa) for whoever multiplies them again
+// embedded = true: the rows are embedded already (x, xa)
 static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr, bool finish = true,
-                          bool plain_rows = false) {
+                          bool plain_rows = false, bool embedded = false) {
   const Plan& p = c->plan;
   const ModelW& w = c->w[AD_VERIFIER];
-  embed_rows(c, w, M);
+  if (embedded) c->ln_pending = nullptr;
+  else embed_rows(c, w, M);
   for (int l = 0; l < c->cfg.dec_layers; ++l) {
     const DecLayerW& L = w.dec[l];
     self_attn_block(c, L.self, L.ln1, M, c->ws + p.cache_k + l * p.cache_layer_stride,
@@ -771,21 +775,38 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   int32_t* res = c->pin + (size_t)B * (1 + km);
   int32_t* oh = res + 2 * B;
   unsigned long long* flags = (unsigned long long*)(c->pin + c->pin_ints - 2 * (kBarPlacement - kBarAbort + 2) - 2);
+  int32_t* ticket_in = oh + p.mv_cap;     // [1] then one slot per sequence
+  int32_t* ticket_out = ticket_in + 1;
+  bool watch = false;
   for (;;) {
     if (fused) {
       HIP_TRY(c, fused_verify_forward(c, k, M, B, true));
       HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
     } else {
       int* result_dst = mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result);
+      // The result lands in host memory the device writes directly; the call's ticket follows it,
+      // and the host watches for the ticket instead of waiting for the stream to drain (the end of
+      // the kernel, its completion signal and the runtime's wake-up are off the critical path).
+      watch = mapped && c->spin_wait && !verified;
+      if (watch) {
+        if (++c->ticket <= 0) c->ticket = 1;
+        *ticket_in = c->ticket;
+        for (int b = 0; b < B; ++b) ticket_out[b] = 0;   // whatever an earlier call left in these words
+      }
       auto accept = [&](const float* pv, const int* pi, int stride, int n_part) {
         launch_argmax_accept(pv, pi, stride, n_part, c->at<int>(p.o_hat), c->at<float>(p.o_val), k_src, draft_src, km,
                              t.row_start, B, cf.eos, cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len),
-                             c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst, c->stream);
+                             c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst,
+                             watch ? c->pin_dev + (ticket_in - c->pin) : nullptr,
+                             watch ? c->pin_dev + (ticket_out - c->pin) : nullptr, c->stream);
       };
       auto launches = [&]() {
-        assemble();
+        launch_assemble_embed_verify(cf.dtype, k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
+                                     c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, M, c->w[AD_VERIFIER].emb,
+                                     c->at<float>(p.pe), cf.d_model, sqrtf((float)cf.d_model), c->at<float>(p.x),
+                                     c->at<void>(p.xa), c->stream);
         if (!gadpp) {
-          const int n_part = verify_forward(c, M, nullptr, nullptr, false);
+          const int n_part = verify_forward(c, M, nullptr, nullptr, false, false, true);
           accept(c->at<float>(p.part_val), c->at<int>(p.part_idx), p.n_strips, n_part);
           return;
         }
@@ -793,7 +814,7 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
         // a second pass of the output projection that counts the columns scoring above it (the
         // logits still never reach memory), the relaxed replacement of o_hat, and acceptance
         const ModelW& w = c->w[AD_VERIFIER];
-        (void)verify_forward(c, M, nullptr, nullptr, true, true);
+        (void)verify_forward(c, M, nullptr, nullptr, true, true, true);
         launch_draft_logit(cf.dtype, c->at<void>(p.xa), w.out_w, M, cf.vocab, cf.d_model, t.row_seq, t.row_start,
                            draft_src, km, c->at<float>(p.draft_lp), c->at<int>(p.draft_col), c->stream);
         Epi e{};
@@ -818,8 +839,22 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
       HIP_TRY(c, hipMemcpyAsync(flags, c->at<unsigned long long>(p.bar) + kBarAbort,
                                 8 * (size_t)(kBarPlacement - kBarAbort + 2), hipMemcpyDeviceToHost, c->stream));
     if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    HIP_TRY(c, hipGetLastError());
+    bool seen = false;
+    if (watch && !fused) {
+      const int want = c->ticket;
+      const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(50);
+      for (unsigned spin = 1;; ++spin) {
+        int b = 0;
+        while (b < B && __atomic_load_n(ticket_out + b, __ATOMIC_ACQUIRE) == want) ++b;
+        if (b == B) { seen = true; break; }
+        if ((spin & 1023u) == 0 && std::chrono::steady_clock::now() > t_end) break;   // fall back to the stream
+        __builtin_ia32_pause();
+      }
+    }
+    if (!seen) {
+      HIP_TRY(c, hipStreamSynchronize(c->stream));
+      HIP_TRY(c, hipGetLastError());
+    }
     if (flags[0]) {
       // a barrier timed out: the decode state is undefined; switch the persistent path off
       c->fused_rows = 0;
@@ -1024,6 +1059,11 @@ int ad_set_option(ad_ctx* c, int option, int value) {
     c->graphs_on = value != 0;
     return AD_OK;
   }
+  if (option == AD_OPT_SPIN_WAIT) {
+    if (value != 0 && value != 1) return fail(c, AD_EINVAL, "AD_OPT_SPIN_WAIT must be 0 or 1");
+    c->spin_wait = value != 0;
+    return AD_OK;
+  }
   if (option != AD_OPT_FUSED_ROWS) return fail(c, AD_EINVAL, "unknown option");
   if (value < 0 || value > c->plan.mv_cap) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, max_batch * k_max]");
   if (value > 0 && c->fused_grid == 0) return fail(c, AD_ESTATE, "the persistent forward is unavailable for this context");
@@ -1037,6 +1077,7 @@ int ad_get_option(ad_ctx* c, int option, int* value) {
   else if (option == AD_OPT_FUSED_AVAILABLE) *value = c->fused_grid > 0 ? 1 : 0;
   else if (option == AD_OPT_GRAPHS) *value = c->graphs_on ? 1 : 0;
   else if (option == AD_OPT_GRAPHS_CAPTURED) *value = (int)c->graphs.size();
+  else if (option == AD_OPT_SPIN_WAIT) *value = c->spin_wait ? 1 : 0;
   else return fail(c, AD_EINVAL, "unknown option");
   return AD_OK;
 }

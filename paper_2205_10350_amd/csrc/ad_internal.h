@@ -180,12 +180,18 @@ struct VerifyTables {
 };
 void launch_assemble_verify(const int* k, const int* draft, int k_max, const int* len, const int* pending,
                             const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s);
+// the tables of launch_assemble_verify and the embedding of its M rows (x, xa) in one launch
+void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int k_max, const int* len,
+                                  const int* pending, const int* src_len, int B, int l_cap, int s_max, VerifyTables t,
+                                  int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,
+                                  hipStream_t s);
 // Longest-prefix match, acceptance, truncation and rollback for every sequence.
-// second stage of the arg max (as launch_argmax_finish) and acceptance in one launch
+// second stage of the arg max (as launch_argmax_finish) and acceptance in one launch; with
+// ticket_out set (host-visible memory), sequence b's slot receives *ticket_in after its result is written
 void launch_argmax_accept(const float* part_val, const int* part_idx, int stride, int n_part, int* o_hat, float* o_val,
                           const int* k, const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          hipStream_t s);
+                          const int* ticket_in, int* ticket_out, hipStream_t s);
 // Row tables for the encoder (rows = source tokens) and for the drafter (prefix + masks).
 void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
                              hipStream_t s);

@@ -835,6 +835,77 @@ void launch_assemble_verify(const int* k, const int* draft, int k_max, const int
                             const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s) {
   k_assemble_verify<<<1, 256, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t);
 }
+// The same tables and the embedding of the rows in one launch: workgroup m finds its row's
+// (sequence, block index) by the same scan and embeds it; workgroup 0 also writes the tables
+// the later kernels read.
+template <typename T>
+__global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __restrict__ k, const int* __restrict__ draft,
+                                                               int k_max, const int* __restrict__ len,
+                                                               const int* __restrict__ pending,
+                                                               const int* __restrict__ src_len, int B, int l_cap,
+                                                               int s_max, VerifyTables t, const T* __restrict__ emb,
+                                                               const float* __restrict__ pe, int d, float sqrt_d,
+                                                               float* __restrict__ x, T* __restrict__ xa) {
+  __shared__ int where[2];
+  const int m = blockIdx.x;
+  if (threadIdx.x == 0) {
+    int acc = 0, bb = 0, ii = 0;
+    for (int b = 0; b < B; ++b) {
+      const int kb = k[b];
+      if (m >= acc && m < acc + kb) { bb = b; ii = m - acc; }
+      acc += kb;
+    }
+    where[0] = bb; where[1] = ii;
+  }
+  __syncthreads();
+  {
+    const int b = where[0], i = where[1];
+    const int tok = i == 0 ? pending[b] : draft[b * k_max + i - 1];
+    const T* e = emb + (size_t)tok * d;
+    const float* p = pe + (size_t)(len[b] + i) * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+      const float v = embed_value(Store<T>::load(e + c), sqrt_d, p[c]);
+      x[(size_t)m * d + c] = v;
+      Store<T>::store(xa + (size_t)m * d + c, v);
+    }
+  }
+  if (blockIdx.x != 0) return;
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += k[b]; }
+    t.row_start[B] = acc;
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    SeqDesc s;
+    s.q_row0 = t.row_start[b]; s.nq = k[b]; s.kv_row0 = b * l_cap; s.nk_base = len[b]; s.causal = 1;
+    s.pad0 = s.pad1 = s.pad2 = 0;
+    t.self_desc[b] = s;
+    s.kv_row0 = b * s_max; s.nk_base = src_len[b]; s.causal = 0;
+    t.cross_desc[b] = s;
+  }
+  for (int b = 0; b < B; ++b) {
+    const int r0 = t.row_start[b], kb = k[b], L = len[b];
+    for (int i = threadIdx.x; i < kb; i += blockDim.x) {
+      t.row_tok[r0 + i] = i == 0 ? pending[b] : draft[b * k_max + i - 1];
+      t.row_pos[r0 + i] = L + i;
+      t.row_seq[r0 + i] = b;
+      t.row_dst[r0 + i] = b * l_cap + L + i;
+    }
+  }
+}
+void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int k_max, const int* len,
+                                  const int* pending, const int* src_len, int B, int l_cap, int s_max, VerifyTables t,
+                                  int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,
+                                  hipStream_t s) {
+  if (M <= 0) return;
+  if (dtype == AD_BF16)
+    k_assemble_embed_verify<bf16_t><<<M, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
+                                                      (const bf16_t*)emb, pe, d, sqrt_d, x, (bf16_t*)xa);
+  else
+    k_assemble_embed_verify<float><<<M, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
+                                                     (const float*)emb, pe, d, sqrt_d, x, (float*)xa);
+}
 
 // Encoder: rows = x_1..x_n of every sentence at positions 0..n-1, full self-attention over the
 // sentence's own rows (keys live in the packed temporary buffers, row_dst = identity); the
@@ -933,21 +1004,25 @@ void launch_draft_scatter(const int* o_hat, const int* finished, int B, int k, i
 // it is dead and overwritten by the next call.
 // One workgroup per sequence: its waves finish the arg max of the sequence's rows (argmax_row over
 // the partials, as k_argmax_finish does), then one thread accepts.
-__global__ __launch_bounds__(256) void k_argmax_accept(const float* __restrict__ pv, const int* __restrict__ pi, int stride,
+__global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict__ pv, const int* __restrict__ pi, int stride,
                                                        int n_part, int* __restrict__ o_hat, float* __restrict__ o_val,
                                                        const int* __restrict__ k, const int* __restrict__ draft, int k_max,
                                                        const int* __restrict__ row_start, int eos, int max_len,
                                                        const int* __restrict__ max_out, int* __restrict__ len,
                                                        int* __restrict__ pending, int* __restrict__ finished,
-                                                       int* __restrict__ out, int* __restrict__ result) {
+                                                       int* __restrict__ out, int* __restrict__ result,
+                                                       const int* __restrict__ ticket_in, int* __restrict__ ticket_out) {
   const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int kb = k[b];
   if (kb == 0) {
-    if (threadIdx.x == 0) { result[2 * b] = 0; result[2 * b + 1] = 0; }
+    if (threadIdx.x == 0) {
+      result[2 * b] = 0; result[2 * b + 1] = 0;
+      if (ticket_out) __hip_atomic_store(ticket_out + b, *ticket_in, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     return;
   }
   const int r0 = row_start[b];
-  for (int i = wave; i < kb; i += 4) {
+  for (int i = wave; i < kb; i += (int)(blockDim.x >> 6)) {
     const int m = r0 + i;
     float v;
     int idx;
@@ -976,13 +1051,16 @@ __global__ __launch_bounds__(256) void k_argmax_accept(const float* __restrict__
   finished[b] = (n > 0 && last == eos) || (L + n >= lim);
   result[2 * b] = n;
   result[2 * b + 1] = last;
+  // a host that waits for this call by watching memory: the call's ticket appears after the result
+  if (ticket_out) __hip_atomic_store(ticket_out + b, *ticket_in, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part, int* o_hat, float* o_val, const int* k,
                           const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          hipStream_t s) {
-  k_argmax_accept<<<B, 256, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
-                                    max_out, len, pending, finished, out, result);
+                          const int* ticket_in, int* ticket_out, hipStream_t s) {
+  // as many waves as the longest block has rows (up to 16): a wave finishes a row at a time
+  k_argmax_accept<<<B, 1024, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
+                                    max_out, len, pending, finished, out, result, ticket_in, ticket_out);
 }
 // ------------------------------------------------------------------------------------- GAD++ (Section 3.2.3)
 // The drafted token of packed row m: draft[b][i] for row i of sequence b.

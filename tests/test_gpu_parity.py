@@ -562,3 +562,32 @@ def test_graph_replays_equal_eager_launches(name, B):
             assert og == out_ref and oi == out_ref
     finally:
         rig.close()
+
+
+def test_waiting_on_the_mapped_result_equals_waiting_on_the_stream():
+    """AD_OPT_SPIN_WAIT only changes how the host learns that a verify call has finished: tokens,
+    accepted lengths and iteration structure are the same either way, also right after other
+    calls have left unrelated words in the staging buffer (an encode, an output read-back)."""
+    rig = Rig("tiny", "bf16", 77, B=3, k_max=8)
+    try:
+        srcs = _sources(rig.dims, 77, [9, 14, 11])
+        ref, _ = rig.ctx.decode_greedy(srcs, max_out=[20, 20, 20])
+        guides = [edit_guide(g, 0.2, 5 + i, rig.dims["vocab"]) for i, g in enumerate(ref)]
+        results = {}
+        for mode in (1, 0, 1):
+            rig.ctx.set_option(ad.AD_OPT_SPIN_WAIT, mode)
+            assert rig.ctx.get_option(ad.AD_OPT_SPIN_WAIT) == mode
+            out, st = rig.ctx.decode_iad(srcs, guides, max_out=[20, 20, 20])
+            assert out == ref
+            rig.ctx.encode(ad.AD_VERIFIER, srcs, max_out=[20, 20, 20])
+            trace = []
+            for step in range(4):
+                n, nx = rig.ctx.verify([list(g[sum(t[0][b] for t in trace):][:5]) or [ad.AD_NEVER] for b, g in enumerate(ref)])
+                trace.append((n.tolist(), nx.tolist()))
+                assert rig.ctx.output()[0] == ref[0][:sum(t[0][0] for t in trace)]
+            results.setdefault("trace", trace)
+            assert trace == results["trace"]
+            results.setdefault("iters", st["iterations"])
+            assert st["iterations"] == results["iters"]
+    finally:
+        rig.close()
