@@ -121,6 +121,8 @@ struct ad_ctx {
   char* ws = nullptr;
   hipStream_t stream = nullptr;
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr, ev3 = nullptr;
+  hipEvent_t ev_up = nullptr;     // the last ad_encode's upload has left the staging buffer
+  bool up_pending = false;
   int32_t* pin = nullptr;       // pinned staging, ints
   int32_t* pin_dev = nullptr;   // the same buffer as the device addresses it (null: not mapped, use copies)
   size_t pin_ints = 0;
@@ -551,7 +553,7 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   auto bail = [&](const char* what, hipError_t e) {
     std::string m = std::string(what) + ": " + hipGetErrorString(e);
     if (c->pin) (void)hipHostFree(c->pin);
-    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3})
+    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up})
       if (ev) (void)hipEventDestroy(ev);
     delete c;
     return fail(nullptr, AD_EDEVICE, m);
@@ -567,6 +569,7 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   if ((e = hipEventCreate(&c->ev1)) != hipSuccess) return bail("hipEventCreate", e);
   if ((e = hipEventCreate(&c->ev2)) != hipSuccess) return bail("hipEventCreate", e);
   if ((e = hipEventCreate(&c->ev3)) != hipSuccess) return bail("hipEventCreate", e);
+  if ((e = hipEventCreateWithFlags(&c->ev_up, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   // sinusoidal positions: PE(p, 2i) = sin(p / 10000^(2i/d)), PE(p, 2i+1) = cos(same)
   {
     const int d = cfg->d_model;
@@ -594,7 +597,7 @@ int ad_destroy(ad_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   if (c->pin) (void)hipHostFree(c->pin);
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
-  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3})
+  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up})
     if (ev) (void)hipEventDestroy(ev);
   delete c;
   return AD_OK;
@@ -657,8 +660,14 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   const ad_config& cf = c->cfg;
   const Plan& p = c->plan;
   const int d = cf.d_model, S = cf.max_src;
-  // one upload: src_len[B], max_out[B], src[B, max_src]
-  int32_t* h = c->pin;
+  // one upload: src_len[B], max_out[B], src[B, max_src], from a part of the staging buffer no
+  // other call writes: the call returns without waiting for the device (what follows on the
+  // stream is ordered behind it), so only the next ad_encode has to make sure the copy has left
+  int32_t* h = c->pin + (size_t)cf.max_batch * (4 + 2 * cf.k_max) + 4;   // past everything ad_verify stages
+  if (c->up_pending) {
+    HIP_TRY(c, hipEventSynchronize(c->ev_up));
+    c->up_pending = false;
+  }
   int M = 0;
   for (int b = 0; b < B; ++b) {
     h[b] = src_len[b];
@@ -668,6 +677,8 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   memcpy(h + 2 * B, src, (size_t)B * S * 4);
   int* dev = c->at<int>(p.src_dev);
   HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipEventRecord(c->ev_up, c->stream));
+  c->up_pending = true;
   HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.src_len[model]), dev, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
   VerifyTables t = tables(c);
   c->fw_nseq = B;
@@ -707,7 +718,6 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   };
   const unsigned long long key = (1ull << 63) | ((unsigned long long)model << 62) | shape_key(M, c->fw_max_rows, B, 0);
   if (!run_as_graph(c, key, launches)) launches();
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
   HIP_TRY(c, hipGetLastError());
   c->h_src_len[model].assign(src_len, src_len + B);
   c->encoded[model] = true;
