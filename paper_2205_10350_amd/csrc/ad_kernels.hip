@@ -835,9 +835,9 @@ void launch_assemble_verify(const int* k, const int* draft, int k_max, const int
                             const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s) {
   k_assemble_verify<<<1, 256, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t);
 }
-// The same tables and the embedding of the rows in one launch: workgroup m finds its row's
-// (sequence, block index) by the same scan and embeds it; workgroup 0 also writes the tables
-// the later kernels read.
+// The same tables and the embedding of the rows in one launch: workgroup 0 writes the tables
+// the later kernels read; workgroup m + 1 finds row m's (sequence, block index) by the same scan
+// and embeds it.
 template <typename T>
 __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __restrict__ k, const int* __restrict__ draft,
                                                                int k_max, const int* __restrict__ len,
@@ -847,18 +847,18 @@ __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __rest
                                                                const float* __restrict__ pe, int d, float sqrt_d,
                                                                float* __restrict__ x, T* __restrict__ xa) {
   __shared__ int where[2];
-  const int m = blockIdx.x;
-  if (threadIdx.x == 0) {
-    int acc = 0, bb = 0, ii = 0;
-    for (int b = 0; b < B; ++b) {
-      const int kb = k[b];
-      if (m >= acc && m < acc + kb) { bb = b; ii = m - acc; }
-      acc += kb;
+  if (blockIdx.x != 0) {
+    const int m = blockIdx.x - 1;
+    if (threadIdx.x == 0) {
+      int acc = 0, bb = 0, ii = 0;
+      for (int b = 0; b < B; ++b) {
+        const int kb = k[b];
+        if (m >= acc && m < acc + kb) { bb = b; ii = m - acc; }
+        acc += kb;
+      }
+      where[0] = bb; where[1] = ii;
     }
-    where[0] = bb; where[1] = ii;
-  }
-  __syncthreads();
-  {
+    __syncthreads();
     const int b = where[0], i = where[1];
     const int tok = i == 0 ? pending[b] : draft[b * k_max + i - 1];
     const T* e = emb + (size_t)tok * d;
@@ -868,8 +868,9 @@ __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __rest
       x[(size_t)m * d + c] = v;
       Store<T>::store(xa + (size_t)m * d + c, v);
     }
+    return;
   }
-  if (blockIdx.x != 0) return;
+  // workgroup 0: the tables
   if (threadIdx.x == 0) {
     int acc = 0;
     for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += k[b]; }
@@ -900,10 +901,10 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
                                   hipStream_t s) {
   if (M <= 0) return;
   if (dtype == AD_BF16)
-    k_assemble_embed_verify<bf16_t><<<M, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
+    k_assemble_embed_verify<bf16_t><<<M + 1, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
                                                       (const bf16_t*)emb, pe, d, sqrt_d, x, (bf16_t*)xa);
   else
-    k_assemble_embed_verify<float><<<M, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
+    k_assemble_embed_verify<float><<<M + 1, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
                                                      (const float*)emb, pe, d, sqrt_d, x, (float*)xa);
 }
 
@@ -1057,9 +1058,10 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
 void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part, int* o_hat, float* o_val, const int* k,
                           const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          const int* ticket_in, int* ticket_out, hipStream_t s) {
-  // as many waves as the longest block has rows (up to 16): a wave finishes a row at a time
-  k_argmax_accept<<<B, 1024, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
+                          const int* ticket_in, int* ticket_out, int max_rows, hipStream_t s) {
+  // as many waves as the longest block has rows (4 to 16): a wave finishes a row at a time
+  const int waves = std::min(16, std::max(4, max_rows));
+  k_argmax_accept<<<B, 64 * waves, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
                                     max_out, len, pending, finished, out, result, ticket_in, ticket_out);
 }
 // ------------------------------------------------------------------------------------- GAD++ (Section 3.2.3)
