@@ -40,6 +40,7 @@ struct Plan {
   int l_cap = 0;        // rows of a sequence's self-attention cache
   int n_strips = 0;
   int max_pos = 0;
+  size_t kv_w[2], kv_b[2];   // per model: cross-attention [wk; wv] of every decoder layer as one matrix, and its bias
   size_t pe, x, s, xa, q, att, tk, tv, f, xg, part_val, part_idx, o_hat, o_val, logits, draft_lp, draft_col;
   size_t cache_k, cache_v, cache_layer_stride;          // [NL][B*l_cap, d]
   size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
@@ -88,6 +89,8 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
     p.mem_k[i] = take(on ? p.mem_layer_stride * c.dec_layers : 0);
     p.mem_v[i] = take(on ? p.mem_layer_stride * c.dec_layers : 0);
     p.src_len[i] = take(B * 4);
+    p.kv_w[i] = take(on ? (size_t)c.dec_layers * 2 * d * d * p.esz : 0);
+    p.kv_b[i] = take(on ? (size_t)c.dec_layers * 2 * d * 4 : 0);
   }
   p.row_tok = take(m * 4); p.row_pos = take(m * 4); p.row_seq = take(m * 4); p.row_dst = take(m * 4); p.row_dst2 = take(m * 4);
   p.row_start = take((B + 1) * 4);
@@ -585,6 +588,17 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
       return bail("hipMemcpyAsync(pe)", e);
     if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail("hipStreamSynchronize", e);
   }
+  // the memory key/value projections of all decoder layers, side by side: one product per encode
+  for (int i = 0; i < (c->has_drafter ? 2 : 1); ++i) {
+    const size_t d = cfg->d_model, wb = 2 * d * d * plan.esz;
+    for (int l = 0; l < cfg->dec_layers; ++l) {
+      const AttnW& a = c->w[i].dec[l].cross;
+      if ((e = hipMemcpyAsync(c->ws + plan.kv_w[i] + l * wb, w_rows(c, a.wqkv, d, d), wb, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess ||
+          (e = hipMemcpyAsync(c->ws + plan.kv_b[i] + l * 2 * d * 4, a.bqkv + d, 2 * d * 4, hipMemcpyDeviceToDevice, c->stream)) != hipSuccess)
+        return bail("hipMemcpyAsync(memory projections)", e);
+    }
+  }
+  if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail("hipStreamSynchronize", e);
   c->h_len.assign(B, 0); c->h_finished.assign(B, 1); c->h_max_out.assign(B, 0);
   c->h_src_len[0].assign(B, 0); c->h_src_len[1].assign(B, 0);
   setup_fused(c);
@@ -700,16 +714,16 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
       gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
       ffn_block(c, L.ffn, L.ln2, M);
     }
-    // cross-attention keys and values of every decoder layer: memory . [wk; wv]^T + [bk; bv]
-    flush_ln(c, M);
-    for (int l = 0; l < cf.dec_layers; ++l) {
-      const AttnW& a = w.dec[l].cross;
+    // cross-attention keys and values of every decoder layer: memory . [wk; wv]^T + [bk; bv], the
+    // layers' matrices side by side (copied so at ad_create), the encoder's last LayerNorm applied
+    // while the rows are staged
+    {
       Epi e{};
-      e.mode = EPI_KV; e.d = d; e.bias = a.bqkv + d;
-      e.out1 = c->ws + p.mem_k[model] + l * p.mem_layer_stride;
-      e.out2 = c->ws + p.mem_v[model] + l * p.mem_layer_stride;
+      e.mode = EPI_KV; e.d = d; e.bias = c->at<float>(p.kv_b[model]);
+      e.out1 = c->ws + p.mem_k[model]; e.out2 = c->ws + p.mem_v[model];
+      e.layer_stride = p.mem_layer_stride;
       e.row_dst = t.row_dst2;
-      launch_gemm(cf.dtype, c->at<void>(p.xa), w_rows(c, a.wqkv, d, d), M, 2 * d, d, e, c->stream);
+      gemm_rows(c, c->ws + p.kv_w[model], M, cf.dec_layers * 2 * d, e);
     }
     if (model == AD_VERIFIER) {
       launch_reset_state(c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished), B, cf.bos, c->stream);

@@ -314,9 +314,11 @@ __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], 
     else if (n0 < 2 * d) { base = (T*)e.out1; col = n - d; by_dst = true; }
     else { base = (T*)e.out2; col = n - 2 * d; by_dst = true; }
   } else if (mode == EPI_KV) {
+    // columns [layer][key d | value d]: one product serves every layer's memory keys and values
     ld = d; by_dst = true;
-    if (n0 < d) base = (T*)e.out1;
-    else { base = (T*)e.out2; col = n - d; }
+    const int layer = n0 / (2 * d), c0 = n0 - layer * 2 * d;
+    if (c0 < d) { base = (T*)((char*)e.out1 + layer * e.layer_stride); col = n - layer * 2 * d; }
+    else { base = (T*)((char*)e.out2 + layer * e.layer_stride); col = n - layer * 2 * d - d; }
   } else if (mode == EPI_STORE || mode == EPI_RELU) {
     base = (T*)e.out0;
   }
@@ -394,9 +396,11 @@ __device__ __forceinline__ void epi_store(const Epi& e, int m, int n, int N, flo
       break;
     }
     case EPI_KV: {
-      const int d = e.d;
-      if (n < d) Store<T>::store((T*)e.out1 + (size_t)e.row_dst[m] * d + n, acc);
-      else Store<T>::store((T*)e.out2 + (size_t)e.row_dst[m] * d + (n - d), acc);
+      const int d = e.d, layer = n / (2 * d), c = n - layer * 2 * d;
+      T* kb = (T*)((char*)e.out1 + layer * e.layer_stride);
+      T* vb = (T*)((char*)e.out2 + layer * e.layer_stride);
+      if (c < d) Store<T>::store(kb + (size_t)e.row_dst[m] * d + c, acc);
+      else Store<T>::store(vb + (size_t)e.row_dst[m] * d + (c - d), acc);
       break;
     }
     case EPI_STORE: Store<T>::store((T*)e.out0 + (size_t)m * N + n, acc); break;

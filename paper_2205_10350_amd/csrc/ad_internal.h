@@ -72,6 +72,7 @@ struct Epi {
   int n_strips;
   float* logits;          // ARGMAX: optional full logits [M,N]
   const float* thr;       // COUNT: [M] thresholds
+  size_t layer_stride;    // KV with N = layers * 2d: bytes from one layer's key (value) buffer to the next
 };
 
 // ---- persistent fused forward (ad_fused.hip) ---------------------------------------------------------
