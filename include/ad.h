@@ -12,10 +12,16 @@
  * Conventions
  *  - Every `int32_t*` token / length buffer is HOST memory owned by the caller.
  *  - `verifier_w`, `drafter_w`, `workspace` are DEVICE pointers owned by the caller
- *    (allocate them with any allocator; they must outlive the context).  The library
- *    allocates no device memory, ever; after ad_create it allocates no memory at all.
+ *    (allocate them with any allocator; they must outlive the context and the weights must
+ *    not change while it lives: ad_create copies some of them into the workspace, side by
+ *    side).  The library allocates no device memory, ever; after ad_create it allocates no
+ *    memory at all.
  *  - `hip_stream` is a hipStream_t (NULL = the null stream).  All device work of a
- *    context is enqueued on it; calls return after that work has completed.
+ *    context is enqueued on it.  Calls that return results return once the results are
+ *    there; ad_encode returns as soon as its work is enqueued, and the tail of an ad_verify
+ *    call's device work may still be running when it returns its result (AD_OPT_SPIN_WAIT).
+ *    Work the caller enqueues on the same stream is ordered behind both; to touch the
+ *    workspace from another stream, synchronize with this one first.
  *  - Every function returns AD_OK or a negative AD_E* code and, on error, leaves the
  *    context as it was.  Nothing throws or aborts across this boundary.
  *    ad_last_error() gives a static or per-context message for the last failure.

@@ -376,6 +376,25 @@ def test_workload1_base_iad_batch1():
         rig.close()
 
 
+def test_workload5_deep_encoder_shallow_decoder_iad_batch1():
+    """Input-guided decoding with the 12 + 2 layer model at the big width (Section 4.1's second
+    model shape): teacher-forced logits of one sentence, greedy identity and iteration structure."""
+    cfg = CONFIGS[5]
+    rig = Rig("deep_shallow", "bf16", cfg["seed"], max_src=64, max_len=64, k_max=72)
+    try:
+        srcs, max_out = draw_sources(cfg, rig.dims["vocab"], n_sent=6)
+        _teacher_forced_base(rig, srcs, 1, "workload5")
+        for s, mo in zip(srcs, max_out):
+            out_g, _ = rig.ctx.decode_greedy([s], max_out=[mo])
+            guide = edit_guide(out_g[0], cfg["rate"], cfg["seed"], rig.dims["vocab"])
+            out_i, st = rig.ctx.decode_iad([s], [guide], max_out=[mo])
+            assert out_i == out_g and len(out_g[0]) == mo
+            _, acc, st_sim = ad.host_simulate(0, out_g[0], guide, k_max=72, max_out=int(mo))
+            assert st["iterations"] == st_sim["iterations"] and st["rows_verified"] == st_sim["rows_verified"]
+    finally:
+        rig.close()
+
+
 def test_workload2_base_iad_batch32():
     cfg = CONFIGS[2]
     rig = Rig("base", "bf16", CONFIGS[1]["seed"], B=32, max_src=64, max_len=64, k_max=72)
