@@ -552,7 +552,9 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   c->has_drafter = drafter_w != nullptr;
   if (c->has_drafter) c->w[1] = bind_weights(*cfg, drafter_w);
   const size_t B = cfg->max_batch;
-  c->pin_ints = (4 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 128 + 3) / 4 * 4;
+  // ad_verify's part [k | draft | result | o_hat | ticket + slots] <= B (6 + 2 k_max) + 8 ints, then ad_encode's
+  // [src_len | max_out | src], then the persistent forward's flag words at the very end
+  c->pin_ints = (8 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 160 + 3) / 4 * 4;
   auto bail = [&](const char* what, hipError_t e) {
     std::string m = std::string(what) + ": " + hipGetErrorString(e);
     if (c->pin) (void)hipHostFree(c->pin);
@@ -677,7 +679,7 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   // one upload: src_len[B], max_out[B], src[B, max_src], from a part of the staging buffer no
   // other call writes: the call returns without waiting for the device (what follows on the
   // stream is ordered behind it), so only the next ad_encode has to make sure the copy has left
-  int32_t* h = c->pin + (size_t)cf.max_batch * (4 + 2 * cf.k_max) + 4;   // past everything ad_verify stages
+  int32_t* h = c->pin + (size_t)cf.max_batch * (6 + 2 * cf.k_max) + 8;   // past everything ad_verify stages
   if (c->up_pending) {
     HIP_TRY(c, hipEventSynchronize(c->ev_up));
     c->up_pending = false;
@@ -799,9 +801,10 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   int32_t* res = c->pin + (size_t)B * (1 + km);
   int32_t* oh = res + 2 * B;
   unsigned long long* flags = (unsigned long long*)(c->pin + c->pin_ints - 2 * (kBarPlacement - kBarAbort + 2) - 2);
-  int32_t* ticket_in = oh + p.mv_cap;     // [1] then one slot per sequence
-  int32_t* ticket_out = ticket_in + 1;
-  bool watch = false;
+  // the call's ticket, then one 8-byte slot per sequence (8-byte aligned)
+  int32_t* ticket_in = c->pin + (((size_t)(oh - c->pin) + p.mv_cap + 1) & ~(size_t)1);
+  unsigned long long* ticket_out = (unsigned long long*)(ticket_in + 2);
+  bool watch = false, seen_ticket = false;
   for (;;) {
     if (fused) {
       HIP_TRY(c, fused_verify_forward(c, k, M, B, true));
@@ -813,7 +816,7 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
       // the kernel, its completion signal and the runtime's wake-up are off the critical path).
       watch = mapped && c->spin_wait && !verified;
       if (watch) {
-        if (++c->ticket <= 0) c->ticket = 1;
+        if (++c->ticket >= (1 << 18)) c->ticket = 1;
         *ticket_in = c->ticket;
         for (int b = 0; b < B; ++b) ticket_out[b] = 0;   // whatever an earlier call left in these words
       }
@@ -822,7 +825,8 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
                              t.row_start, B, cf.eos, cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len),
                              c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst,
                              watch ? c->pin_dev + (ticket_in - c->pin) : nullptr,
-                             watch ? c->pin_dev + (ticket_out - c->pin) : nullptr, c->fw_max_rows, c->stream);
+                             watch ? (unsigned long long*)(c->pin_dev + ((int32_t*)ticket_out - c->pin)) : nullptr,
+                             c->fw_max_rows, c->stream);
       };
       auto launches = [&]() {
         launch_assemble_embed_verify(cf.dtype, k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
@@ -864,13 +868,14 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
                                 8 * (size_t)(kBarPlacement - kBarAbort + 2), hipMemcpyDeviceToHost, c->stream));
     if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
     bool seen = false;
+    seen_ticket = false;
     if (watch && !fused) {
       const int want = c->ticket;
       const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(50);
       for (unsigned spin = 1;; ++spin) {
         int b = 0;
-        while (b < B && __atomic_load_n(ticket_out + b, __ATOMIC_ACQUIRE) == want) ++b;
-        if (b == B) { seen = true; break; }
+        while (b < B && (int)(__atomic_load_n(ticket_out + b, __ATOMIC_ACQUIRE) >> 46) == want) ++b;
+        if (b == B) { seen = seen_ticket = true; break; }
         if ((spin & 1023u) == 0 && std::chrono::steady_clock::now() > t_end) break;   // fall back to the stream
         __builtin_ia32_pause();
       }
@@ -898,8 +903,14 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
   c->last_k.assign(k, k + B);
   int r0 = 0;
   for (int b = 0; b < B; ++b) {
-    n_accept[b] = res[2 * b];
-    next_token[b] = res[2 * b + 1];
+    if (seen_ticket) {
+      const unsigned long long v = ticket_out[b];
+      n_accept[b] = (int)((v >> 32) & 0x3fff);
+      next_token[b] = (int)(unsigned)v;
+    } else {
+      n_accept[b] = res[2 * b];
+      next_token[b] = res[2 * b + 1];
+    }
     if (k[b]) {
       c->h_len[b] += n_accept[b];
       c->h_finished[b] = (n_accept[b] > 0 && next_token[b] == cf.eos) || c->h_len[b] >= c->h_max_out[b];

@@ -1012,13 +1012,14 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
                                                        const int* __restrict__ max_out, int* __restrict__ len,
                                                        int* __restrict__ pending, int* __restrict__ finished,
                                                        int* __restrict__ out, int* __restrict__ result,
-                                                       const int* __restrict__ ticket_in, int* __restrict__ ticket_out) {
+                                                       const int* __restrict__ ticket_in,
+                                                       unsigned long long* __restrict__ ticket_out) {
   const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int kb = k[b];
   if (kb == 0) {
     if (threadIdx.x == 0) {
       result[2 * b] = 0; result[2 * b + 1] = 0;
-      if (ticket_out) __hip_atomic_store(ticket_out + b, *ticket_in, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (ticket_out) __hip_atomic_store(ticket_out + b, (unsigned long long)*ticket_in << 46, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     return;
   }
@@ -1052,13 +1053,17 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
   finished[b] = (n > 0 && last == eos) || (L + n >= lim);
   result[2 * b] = n;
   result[2 * b + 1] = last;
-  // a host that waits for this call by watching memory: the call's ticket appears after the result
-  if (ticket_out) __hip_atomic_store(ticket_out + b, *ticket_in, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  // a host that waits for this call by watching memory: ticket (18 bits), accepted length (14) and
+  // next token (32) in ONE 8-byte store, so that seeing the ticket is seeing the result; no
+  // release fence (it would write the whole cache back)
+  if (ticket_out)
+    __hip_atomic_store(ticket_out + b, ((unsigned long long)*ticket_in << 46) | ((unsigned long long)n << 32) | (unsigned)last,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part, int* o_hat, float* o_val, const int* k,
                           const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          const int* ticket_in, int* ticket_out, int max_rows, hipStream_t s) {
+                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, hipStream_t s) {
   // as many waves as the longest block has rows (4 to 16): a wave finishes a row at a time
   const int waves = std::min(16, std::max(4, max_rows));
   k_argmax_accept<<<B, 64 * waves, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
