@@ -198,6 +198,15 @@ int ad_debug_logits(ad_ctx* ctx, float* logits, int rows_cap, int* rows);
 int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us,
                            double* vocab_back_to_back_us);
 
+/* The output-projection/arg-max kernel of the last ad_verify forward, `reps` launches back to back on
+ * the context's stream, launch r reading the matrix from copy r % n_copies of `w_copies` (DEVICE
+ * memory, the caller's: n_copies images of the verifier's "out.w" entry, copy_stride_bytes apart,
+ * a multiple of 16).  With copies that together exceed the GPU's last-level cache every launch
+ * streams its matrix from HBM; with one copy it may come from that cache.  Mean microseconds per
+ * launch by HIP events.  Results of the launches are discarded; decode state is not touched. */
+int ad_time_output_projection(ad_ctx* ctx, const void* w_copies, size_t copy_stride_bytes, int32_t n_copies,
+                              int32_t reps, double* us_per_launch);
+
 /* Measurement aid, no part of the method: copies `bytes` (a multiple of 16) from src to dst, both
  * device memory, with one plain kernel (16 bytes per lane per step) on `stream`.  A hardware
  * memory-traffic counter read for this launch, whose traffic is known (`bytes` read, `bytes`

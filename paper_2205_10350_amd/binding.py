@@ -24,7 +24,7 @@ EXPORTS = [
     "ad_weights_pack",
     "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
-    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp",
+    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp", "ad_time_output_projection",
 ]
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
@@ -101,6 +101,8 @@ def lib():
     L.ad_calibration_copy.restype = C.c_int
     L.ad_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]; L.ad_set_option.restype = C.c_int
     L.ad_set_gadpp.argtypes = [C.c_void_p, C.c_int32, C.c_float]; L.ad_set_gadpp.restype = C.c_int
+    L.ad_time_output_projection.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
+    L.ad_time_output_projection.restype = C.c_int
     L.ad_get_option.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int)]; L.ad_get_option.restype = C.c_int
     L.ad_suffix_match.argtypes = [_I32P, C.c_int, _I32P, C.c_int, C.POINTER(C.c_int)]; L.ad_suffix_match.restype = C.c_int
     L.ad_host_simulate.argtypes = [C.c_int, _I32P, C.c_int, _I32P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -327,6 +329,23 @@ class Context:
         v = C.c_int(0)
         _check(self.L.ad_get_option(self.h, option, C.byref(v)), self.h)
         return v.value
+
+    def time_output_projection(self, n_copies, reps=50):
+        """Mean microseconds per launch of the output-projection kernel over `n_copies` rotating
+        copies of the verifier's output matrix (made here, device to device)."""
+        torch = self._torch
+        layout, _ = weights_layout(self.cfg)
+        name, off, rows, cols, eb = next(e for e in layout if e[0] == "out.w")
+        nbytes = rows * cols * eb
+        stride = (nbytes + 255) // 256 * 256
+        buf = torch.empty(n_copies * stride, dtype=torch.uint8, device=self.w_ver.device)
+        for i in range(n_copies):
+            buf[i * stride:i * stride + nbytes].copy_(self.w_ver[off:off + nbytes])
+        torch.cuda.synchronize()
+        us = C.c_double(0)
+        _check(self.L.ad_time_output_projection(self.h, C.c_void_p(buf.data_ptr()), stride, n_copies, reps, C.byref(us)), self.h)
+        del buf
+        return us.value
 
     def debug_logits(self):
         cap = self.cfg.max_batch * self.cfg.k_max

@@ -268,14 +268,15 @@ static void embed_rows(ad_ctx* c, const ModelW& w, int M) {
 }
 
 // Output projection fused with the per-row arg max; `A` holds Mv rows.
-static int vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv, const LnW* ln_of_s = nullptr) {
+static int vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv, const LnW* ln_of_s = nullptr,
+                        const void* out_w = nullptr /* another copy of w.out_w (timing) */) {
   const Plan& p = c->plan;
   Epi e{};
   e.mode = EPI_ARGMAX; e.part_val = c->at<float>(p.part_val); e.part_idx = c->at<int>(p.part_idx);
   e.n_strips = p.n_strips; e.logits = c->cfg.debug_logits ? c->at<float>(p.logits) : nullptr;
   LnA ln{};
   if (ln_of_s) { ln.x = c->at<float>(p.s); ln.g = ln_of_s->g; ln.b = ln_of_s->b; ln.y = c->at<float>(p.x); }
-  return launch_gemm(c->cfg.dtype, A, w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream, ln);
+  return launch_gemm(c->cfg.dtype, A, out_w ? out_w : w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream, ln);
 }
 static void vocab_finish(ad_ctx* c, int Mv, int n_part) {
   const Plan& p = c->plan;
@@ -1202,6 +1203,29 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   HIP_TRY(c, hipGetLastError());
   *forward_us = tot;
   *vocab_kernel_us = voc;
+  return AD_OK;
+}
+
+int ad_time_output_projection(ad_ctx* c, const void* w_copies, size_t copy_stride_bytes, int n_copies, int reps,
+                              double* us_per_launch) {
+  if (!c) return fail(nullptr, AD_EINVAL, "null context");
+  if (!w_copies || n_copies < 1 || reps < 1 || !us_per_launch) return fail(c, AD_EINVAL, "bad argument");
+  const size_t need = (size_t)c->cfg.vocab * c->cfg.d_model * (c->cfg.dtype == AD_BF16 ? 2 : 4);
+  if (copy_stride_bytes < need || copy_stride_bytes % 16) return fail(c, AD_EINVAL, "copy stride smaller than the matrix or not a multiple of 16");
+  if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
+  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
+  verify_forward(c, c->last_M);   // the rows (and the pending LayerNorm) the projection works on
+  const ModelW& w = c->w[AD_VERIFIER];
+  auto copy = [&](int r) { return (const char*)w_copies + (size_t)(r % n_copies) * copy_stride_bytes; };
+  for (int r = 0; r < n_copies; ++r) (void)vocab_argmax(c, w, c->at<void>(c->plan.xa), c->last_M, c->ln_vocab, copy(r));
+  HIP_TRY(c, hipEventRecord(c->ev1, c->stream));
+  for (int r = 0; r < reps; ++r) (void)vocab_argmax(c, w, c->at<void>(c->plan.xa), c->last_M, c->ln_vocab, copy(r));
+  HIP_TRY(c, hipEventRecord(c->ev2, c->stream));
+  HIP_TRY(c, hipEventSynchronize(c->ev2));
+  float b = 0;
+  HIP_TRY(c, hipEventElapsedTime(&b, c->ev1, c->ev2));
+  HIP_TRY(c, hipGetLastError());
+  *us_per_launch = b * 1e3 / reps;
   return AD_OK;
 }
 
