@@ -211,29 +211,38 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
 #pragma unroll
     for (int i = 0; i < RB; ++i)
       if (i0 + i < n_rows) ln_load4<false, NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
+    // statistics of all rows of the batch first (independent reduction chains the scheduler can
+    // interleave), then the values, then, in the workgroups that keep them, the fp32 rows
+    float mean[RB], rstd[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) ln_stats4<NV>(xv[i0 + i < n_rows ? i : 0], K, mean[i], rstd[i]);
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
       if (i0 + i >= n_rows) break;
-      const int row = row0 + i0 + i, m = m0 + row;
-      float mean, rstd;
-      ln_stats4<NV>(xv[i], K, mean, rstd);
+      const int row = row0 + i0 + i;
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
         const int c = 4 * lane + 256 * j;
-        const float4 o = float4{ln_value(xv[i][j].x, mean, rstd, gv[j].x, bv[j].x), ln_value(xv[i][j].y, mean, rstd, gv[j].y, bv[j].y),
-                                ln_value(xv[i][j].z, mean, rstd, gv[j].z, bv[j].z), ln_value(xv[i][j].w, mean, rstd, gv[j].w, bv[j].w)};
+        const float4 o = float4{ln_value(xv[i][j].x, mean[i], rstd[i], gv[j].x, bv[j].x), ln_value(xv[i][j].y, mean[i], rstd[i], gv[j].y, bv[j].y),
+                                ln_value(xv[i][j].z, mean[i], rstd[i], gv[j].z, bv[j].z), ln_value(xv[i][j].w, mean[i], rstd[i], gv[j].w, bv[j].w)};
         const unsigned lo = (unsigned)f2bf(o.x) | ((unsigned)f2bf(o.y) << 16), hi = (unsigned)f2bf(o.z) | ((unsigned)f2bf(o.w) << 16);
         *(uint2*)(At + row * ld + c) = uint2{lo, hi};
-        if (store_y && m < M) *(float4*)(ln.y + (size_t)m * K + c) = o;
+        xv[i][j] = o;
+      }
+    }
+    if (store_y) {
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        const int m = m0 + row0 + i0 + i;
+        if (i0 + i < n_rows && m < M) {
+#pragma unroll
+          for (int j = 0; j < NV; ++j) *(float4*)(ln.y + (size_t)m * K + 4 * lane + 256 * j) = xv[i][j];
+        }
       }
     }
   }
 }
 
-// AMAX: 0 = an ordinary epilogue, 1 = output projection with the running arg max, 2 = the same and the
-// logits are also stored (tests; only instantiated for MT = 1, SP = 1: a store inside the unit
-// loop makes the compiler wait for every weight fetch in flight at each unit), 3 = EPI_COUNT: per
-// row, the number of columns that score above the row's threshold
 template <int MT, int AMAX, int SP, bool ONE>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, Epi e, int strips_per_wg, int groups,
@@ -289,8 +298,10 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   if (ln.x) {
     // rows to be normalised first (K = 512 or 1024): the statistics and values of the LayerNorm
     // kernel; the workgroups of strip group 0 also store the fp32 rows
-    if (K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, group == 0);
-    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, group == 0);
+    // (the output projection is the last consumer of its rows: nobody needs them in fp32)
+    const bool keep_y = group == 0 && AMAX == 0;
+    if (K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y);
+    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y);
   } else
   // a wave's loads of a 512-column slice are all issued before the first LDS store
   for (int h = 0; h < halves; ++h) {
