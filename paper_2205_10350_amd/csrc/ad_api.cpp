@@ -855,7 +855,8 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
       };
       // every launch argument is a function of (rows, sequences, longest block), of the GAD++
       // setting and of pointers fixed for the context's life
-      const unsigned long long key = shape_key(M, c->fw_max_rows, B, gadpp ? 1 : 0);
+      // (and of whether the acceptance kernel posts the ticket)
+      const unsigned long long key = shape_key(M, c->fw_max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0));
       unsigned tau_bits;
       memcpy(&tau_bits, &c->gadpp_tau, 4);
       const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;

@@ -469,11 +469,15 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     // rows of 16 lanes reduce by lane moves, the four waves through LDS
     float* mv = (float*)(At + ROWS * ld);   // [4 waves][ROWS]
     int* mi = (int*)(mv + 4 * ROWS);
+    // (all lane reductions first: independent chains; then one branch for the LDS writes)
 #pragma unroll
     for (int x = 0; x < MT * 4; ++x) {
       if constexpr (AMAX == 3) bi[x] = row16_sum_i(bi[x]);
       else argmax_row16(bv[x], bi[x]);
-      if (r == 0) {
+    }
+    if (r == 0) {
+#pragma unroll
+      for (int x = 0; x < MT * 4; ++x) {
         const int row = (x >> 2) * 16 + kq * 4 + (x & 3);
         mv[wave * ROWS + row] = bv[x];
         mi[wave * ROWS + row] = bi[x];
