@@ -827,7 +827,7 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
                              c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst,
                              watch ? c->pin_dev + (ticket_in - c->pin) : nullptr,
                              watch ? (unsigned long long*)(c->pin_dev + ((int32_t*)ticket_out - c->pin)) : nullptr,
-                             c->fw_max_rows, c->stream);
+                             c->fw_max_rows, M, c->stream);
       };
       auto launches = [&]() {
         launch_assemble_embed_verify(cf.dtype, k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),

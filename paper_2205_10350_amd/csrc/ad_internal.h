@@ -193,7 +193,8 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
 void launch_argmax_accept(const float* part_val, const int* part_idx, int stride, int n_part, int* o_hat, float* o_val,
                           const int* k, const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, hipStream_t s);
+                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, int M /* sum of k */,
+                          hipStream_t s);
 // Row tables for the encoder (rows = source tokens) and for the drafter (prefix + masks).
 void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
                              hipStream_t s);

@@ -860,21 +860,24 @@ __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __rest
                                                                const int* __restrict__ src_len, int B, int l_cap,
                                                                int s_max, VerifyTables t, const T* __restrict__ emb,
                                                                const float* __restrict__ pe, int d, float sqrt_d,
-                                                               float* __restrict__ x, T* __restrict__ xa) {
+                                                               float* __restrict__ x, T* __restrict__ xa, int M) {
+  // k lives in host memory (a trip over the bus); with one sequence it is the row count M
   __shared__ int where[2];
   if (blockIdx.x != 0) {
     const int m = blockIdx.x - 1;
-    if (threadIdx.x == 0) {
-      int acc = 0, bb = 0, ii = 0;
-      for (int b = 0; b < B; ++b) {
-        const int kb = k[b];
-        if (m >= acc && m < acc + kb) { bb = b; ii = m - acc; }
-        acc += kb;
+    if (B > 1) {
+      if (threadIdx.x == 0) {
+        int acc = 0, bb = 0, ii = 0;
+        for (int b = 0; b < B; ++b) {
+          const int kb = k[b];
+          if (m >= acc && m < acc + kb) { bb = b; ii = m - acc; }
+          acc += kb;
+        }
+        where[0] = bb; where[1] = ii;
       }
-      where[0] = bb; where[1] = ii;
+      __syncthreads();
     }
-    __syncthreads();
-    const int b = where[0], i = where[1];
+    const int b = B > 1 ? where[0] : 0, i = B > 1 ? where[1] : m;
     const int tok = i == 0 ? pending[b] : draft[b * k_max + i - 1];
     const T* e = emb + (size_t)tok * d;
     const float* p = pe + (size_t)(len[b] + i) * d;
@@ -888,20 +891,20 @@ __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __rest
   // workgroup 0: the tables
   if (threadIdx.x == 0) {
     int acc = 0;
-    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += k[b]; }
+    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += B > 1 ? k[b] : M; }
     t.row_start[B] = acc;
   }
   __syncthreads();
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
     SeqDesc s;
-    s.q_row0 = t.row_start[b]; s.nq = k[b]; s.kv_row0 = b * l_cap; s.nk_base = len[b]; s.causal = 1;
+    s.q_row0 = t.row_start[b]; s.nq = B > 1 ? k[b] : M; s.kv_row0 = b * l_cap; s.nk_base = len[b]; s.causal = 1;
     s.pad0 = s.pad1 = s.pad2 = 0;
     t.self_desc[b] = s;
     s.kv_row0 = b * s_max; s.nk_base = src_len[b]; s.causal = 0;
     t.cross_desc[b] = s;
   }
   for (int b = 0; b < B; ++b) {
-    const int r0 = t.row_start[b], kb = k[b], L = len[b];
+    const int r0 = t.row_start[b], kb = B > 1 ? k[b] : M, L = len[b];
     for (int i = threadIdx.x; i < kb; i += blockDim.x) {
       t.row_tok[r0 + i] = i == 0 ? pending[b] : draft[b * k_max + i - 1];
       t.row_pos[r0 + i] = L + i;
@@ -917,10 +920,10 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
   if (M <= 0) return;
   if (dtype == AD_BF16)
     k_assemble_embed_verify<bf16_t><<<M + 1, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
-                                                      (const bf16_t*)emb, pe, d, sqrt_d, x, (bf16_t*)xa);
+                                                      (const bf16_t*)emb, pe, d, sqrt_d, x, (bf16_t*)xa, M);
   else
     k_assemble_embed_verify<float><<<M + 1, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
-                                                     (const float*)emb, pe, d, sqrt_d, x, (float*)xa);
+                                                     (const float*)emb, pe, d, sqrt_d, x, (float*)xa, M);
 }
 
 // Encoder: rows = x_1..x_n of every sentence at positions 0..n-1, full self-attention over the
@@ -1028,9 +1031,9 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
                                                        int* __restrict__ pending, int* __restrict__ finished,
                                                        int* __restrict__ out, int* __restrict__ result,
                                                        const int* __restrict__ ticket_in,
-                                                       unsigned long long* __restrict__ ticket_out) {
+                                                       unsigned long long* __restrict__ ticket_out, int M) {
   const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int kb = k[b];
+  const int kb = gridDim.x == 1 ? M : k[b];   // k is in host memory; a lone sequence owns all M rows
   if (kb == 0) {
     if (threadIdx.x == 0) {
       result[2 * b] = 0; result[2 * b + 1] = 0;
@@ -1039,6 +1042,13 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
     return;
   }
   const int r0 = row_start[b];
+  // what the end of the kernel needs and nothing here depends on: requested now (the draft and
+  // the ticket sit in host memory, one trip over the bus each)
+  __shared__ int s_first, s_eos;
+  const int my_draft = (int)threadIdx.x < kb ? draft[b * k_max + threadIdx.x] : 0;
+  const int ticket = threadIdx.x == 0 && ticket_out ? *ticket_in : 0;
+  const int L = len[b], lim = max_out[b];
+  if (threadIdx.x == 0) { s_first = kb; s_eos = kb; }
   for (int i = wave; i < kb; i += (int)(blockDim.x >> 6)) {
     const int m = r0 + i;
     float v;
@@ -1050,19 +1060,21 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
     }
   }
   __syncthreads();   // the sequence's arg maxima are in memory, visible to the whole workgroup
-  if (threadIdx.x != 0) return;
-  int c = kb;
-  for (int i = 0; i < kb; ++i)
-    if (draft[b * k_max + i] != o_hat[r0 + i]) { c = i + 1; break; }
-  const int L = len[b], lim = max_out[b];
-  int n = 0, last = 0;
-  for (int i = 0; i < c; ++i) {
-    if (L + n >= lim) break;
-    last = o_hat[r0 + i];
-    out[b * max_len + L + n] = last;
-    ++n;
-    if (last == eos) break;
+  // first mismatch with the draft and first [EOS], every thread a row at a time
+  for (int i = threadIdx.x; i < kb; i += blockDim.x) {
+    const int t = o_hat[r0 + i];
+    const int dr = i == (int)threadIdx.x ? my_draft : draft[b * k_max + i];
+    if (dr != t) atomicMin(&s_first, i);
+    if (t == eos) atomicMin(&s_eos, i);
   }
+  __syncthreads();
+  // accepted block = o_hat_{1..c}, cut after the first [EOS] and at the output limit
+  const int c = s_first < kb ? s_first + 1 : kb;
+  int n = min(c, max(lim - L, 0));
+  if (s_eos < n) n = s_eos + 1;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) out[b * max_len + L + i] = o_hat[r0 + i];
+  if (threadIdx.x != 0) return;
+  const int last = n > 0 ? o_hat[r0 + n - 1] : 0;
   len[b] = L + n;
   if (n > 0) pending[b] = last;
   finished[b] = (n > 0 && last == eos) || (L + n >= lim);
@@ -1072,17 +1084,17 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
   // next token (32) in ONE 8-byte store, so that seeing the ticket is seeing the result; no
   // release fence (it would write the whole cache back)
   if (ticket_out)
-    __hip_atomic_store(ticket_out + b, ((unsigned long long)*ticket_in << 46) | ((unsigned long long)n << 32) | (unsigned)last,
+    __hip_atomic_store(ticket_out + b, ((unsigned long long)ticket << 46) | ((unsigned long long)n << 32) | (unsigned)last,
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part, int* o_hat, float* o_val, const int* k,
                           const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, hipStream_t s) {
+                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, int M, hipStream_t s) {
   // as many waves as the longest block has rows (4 to 16): a wave finishes a row at a time
   const int waves = std::min(16, std::max(4, max_rows));
   k_argmax_accept<<<B, 64 * waves, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
-                                    max_out, len, pending, finished, out, result, ticket_in, ticket_out);
+                                    max_out, len, pending, finished, out, result, ticket_in, ticket_out, M);
 }
 // ------------------------------------------------------------------------------------- GAD++ (Section 3.2.3)
 // The drafted token of packed row m: draft[b][i] for row i of sequence b.
