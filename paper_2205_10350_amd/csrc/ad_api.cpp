@@ -124,8 +124,8 @@ struct ad_ctx {
   char* ws = nullptr;
   hipStream_t stream = nullptr;
   hipEvent_t ev0 = nullptr, ev1 = nullptr, ev2 = nullptr, ev3 = nullptr;
-  hipEvent_t ev_up = nullptr;     // the last ad_encode's upload has left the staging buffer
-  bool up_pending = false;
+  hipEvent_t ev_up[2] = {nullptr, nullptr};   // per model: the last ad_encode's inputs have been read from the staging buffer
+  bool up_pending[2] = {false, false};
   int32_t* pin = nullptr;       // pinned staging, ints
   int32_t* pin_dev = nullptr;   // the same buffer as the device addresses it (null: not mapped, use copies)
   size_t pin_ints = 0;
@@ -554,12 +554,12 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   if (c->has_drafter) c->w[1] = bind_weights(*cfg, drafter_w);
   const size_t B = cfg->max_batch;
   // ad_verify's part [k | draft | result | o_hat | ticket + slots] <= B (6 + 2 k_max) + 8 ints, then ad_encode's
-  // [src_len | max_out | src], then the persistent forward's flag words at the very end
-  c->pin_ints = (8 * B + B * cfg->k_max * 2 + B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 160 + 3) / 4 * 4;
+  // [src_len | max_out | src] once per model, then the persistent forward's flag words at the very end
+  c->pin_ints = (12 * B + B * cfg->k_max * 2 + 2 * B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 160 + 3) / 4 * 4;
   auto bail = [&](const char* what, hipError_t e) {
     std::string m = std::string(what) + ": " + hipGetErrorString(e);
     if (c->pin) (void)hipHostFree(c->pin);
-    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up})
+    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1]})
       if (ev) (void)hipEventDestroy(ev);
     delete c;
     return fail(nullptr, AD_EDEVICE, m);
@@ -575,7 +575,8 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   if ((e = hipEventCreate(&c->ev1)) != hipSuccess) return bail("hipEventCreate", e);
   if ((e = hipEventCreate(&c->ev2)) != hipSuccess) return bail("hipEventCreate", e);
   if ((e = hipEventCreate(&c->ev3)) != hipSuccess) return bail("hipEventCreate", e);
-  if ((e = hipEventCreateWithFlags(&c->ev_up, hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  for (int i = 0; i < 2; ++i)
+    if ((e = hipEventCreateWithFlags(&c->ev_up[i], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
   // sinusoidal positions: PE(p, 2i) = sin(p / 10000^(2i/d)), PE(p, 2i+1) = cos(same)
   {
     const int d = cfg->d_model;
@@ -614,7 +615,7 @@ int ad_destroy(ad_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   if (c->pin) (void)hipHostFree(c->pin);
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
-  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up})
+  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1]})
     if (ev) (void)hipEventDestroy(ev);
   delete c;
   return AD_OK;
@@ -677,13 +678,16 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   const ad_config& cf = c->cfg;
   const Plan& p = c->plan;
   const int d = cf.d_model, S = cf.max_src;
-  // one upload: src_len[B], max_out[B], src[B, max_src], from a part of the staging buffer no
-  // other call writes: the call returns without waiting for the device (what follows on the
-  // stream is ordered behind it), so only the next ad_encode has to make sure the copy has left
-  int32_t* h = c->pin + (size_t)cf.max_batch * (6 + 2 * cf.k_max) + 8;   // past everything ad_verify stages
-  if (c->up_pending) {
-    HIP_TRY(c, hipEventSynchronize(c->ev_up));
-    c->up_pending = false;
+  // src_len[B], max_out[B], src[B, max_src] go into a part of the staging buffer that no other
+  // call writes (one part per model).  The device reads them there (mapped memory) or gets them by
+  // one copy; either way the call returns without waiting (what follows on the stream is ordered
+  // behind it), so only the next ad_encode of the same model has to make sure they have been read.
+  const size_t enc_ints = (size_t)cf.max_batch * (2 + S);
+  int32_t* h = c->pin + (size_t)cf.max_batch * (6 + 2 * cf.k_max) + 8 + (size_t)model * enc_ints;
+  const bool mapped = c->pin_dev != nullptr;
+  if (c->up_pending[model]) {
+    HIP_TRY(c, hipEventSynchronize(c->ev_up[model]));
+    c->up_pending[model] = false;
   }
   int M = 0;
   for (int b = 0; b < B; ++b) {
@@ -692,19 +696,24 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
     M += src_len[b];
   }
   memcpy(h + 2 * B, src, (size_t)B * S * 4);
-  int* dev = c->at<int>(p.src_dev);
-  HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
-  HIP_TRY(c, hipEventRecord(c->ev_up, c->stream));
-  c->up_pending = true;
-  HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.src_len[model]), dev, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream));
+  int* dev = mapped ? c->pin_dev + (h - c->pin) : c->at<int>(p.src_dev);
+  if (!mapped) {
+    HIP_TRY(c, hipMemcpyAsync(dev, h, (size_t)(2 * B + B * S) * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipEventRecord(c->ev_up[model], c->stream));
+    c->up_pending[model] = true;
+  }
   VerifyTables t = tables(c);
   c->fw_nseq = B;
   c->fw_max_rows = *std::max_element(src_len, src_len + B);
   // kernels and device-to-device copies of the encoder forward: replayed as a graph per call shape
   auto launches = [&]() {
-    launch_assemble_encoder(dev + 2 * B, S, dev, B, S, t, c->stream);
     const ModelW& w = c->w[model];
-    embed_rows(c, w, M);
+    const bool ver = model == AD_VERIFIER;
+    launch_assemble_embed_encoder(cf.dtype, dev + 2 * B, S, dev, dev + B, B, S, t, c->at<int>(p.src_len[model]),
+                                  c->at<int>(p.max_out), ver ? c->at<int>(p.len) : nullptr, c->at<int>(p.pending),
+                                  c->at<int>(p.finished), cf.bos, M, w.emb, c->at<float>(p.pe), d, sqrtf((float)d),
+                                  c->at<float>(p.x), c->at<void>(p.xa), c->stream);
+    c->ln_pending = nullptr;
     for (int l = 0; l < cf.enc_layers; ++l) {
       const EncLayerW& L = w.enc[l];
       // the sentence's own keys/values live in the packed temporaries: key row = packed row
@@ -728,13 +737,13 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
       e.row_dst = t.row_dst2;
       gemm_rows(c, c->ws + p.kv_w[model], M, cf.dec_layers * 2 * d, e);
     }
-    if (model == AD_VERIFIER) {
-      launch_reset_state(c->at<int>(p.len), c->at<int>(p.pending), c->at<int>(p.finished), B, cf.bos, c->stream);
-      (void)hipMemcpyAsync(c->at<int>(p.max_out), dev + B, (size_t)B * 4, hipMemcpyDeviceToDevice, c->stream);
-    }
   };
   const unsigned long long key = (1ull << 63) | ((unsigned long long)model << 62) | shape_key(M, c->fw_max_rows, B, 0);
   if (!run_as_graph(c, key, launches)) launches();
+  if (mapped) {
+    HIP_TRY(c, hipEventRecord(c->ev_up[model], c->stream));
+    c->up_pending[model] = true;
+  }
   HIP_TRY(c, hipGetLastError());
   c->h_src_len[model].assign(src_len, src_len + B);
   c->encoded[model] = true;

@@ -954,6 +954,83 @@ __global__ void k_assemble_encoder(const int* __restrict__ src, int max_src, con
     }
   }
 }
+// The encoder's tables, the embedding of its rows and the per-call device state in one launch
+// (src, src_len, max_out may live in host memory): workgroup 0 writes the tables, keeps the
+// source lengths and, for the verifier (len != null), the output limits and the start state of a
+// decode; workgroup m + 1 embeds row m.
+template <typename T>
+__global__ __launch_bounds__(128) void k_assemble_embed_encoder(const int* __restrict__ src, int max_src,
+                                                                const int* __restrict__ src_len,
+                                                                const int* __restrict__ max_out_in, int B, int s_max,
+                                                                VerifyTables t, int* __restrict__ src_len_out,
+                                                                int* __restrict__ max_out, int* __restrict__ len,
+                                                                int* __restrict__ pending, int* __restrict__ finished,
+                                                                int bos, const T* __restrict__ emb,
+                                                                const float* __restrict__ pe, int d, float sqrt_d,
+                                                                float* __restrict__ x, T* __restrict__ xa) {
+  __shared__ int where[2];
+  if (blockIdx.x != 0) {
+    const int m = blockIdx.x - 1;
+    if (threadIdx.x == 0) {
+      int acc = 0, bb = 0, ii = 0;
+      for (int b = 0; b < B; ++b) {
+        const int n = src_len[b];
+        if (m >= acc && m < acc + n) { bb = b; ii = m - acc; }
+        acc += n;
+      }
+      where[0] = bb; where[1] = ii;
+    }
+    __syncthreads();
+    const int b = where[0], i = where[1];
+    const T* e = emb + (size_t)src[b * max_src + i] * d;
+    const float* p = pe + (size_t)i * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+      const float v = embed_value(Store<T>::load(e + c), sqrt_d, p[c]);
+      x[(size_t)m * d + c] = v;
+      Store<T>::store(xa + (size_t)m * d + c, v);
+    }
+    return;
+  }
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += src_len[b]; }
+    t.row_start[B] = acc;
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    const int n = src_len[b];
+    SeqDesc s;
+    s.q_row0 = t.row_start[b]; s.nq = n; s.kv_row0 = t.row_start[b]; s.nk_base = n; s.causal = 0;
+    s.pad0 = s.pad1 = s.pad2 = 0;
+    t.self_desc[b] = s;
+    src_len_out[b] = n;
+    if (len) { max_out[b] = max_out_in[b]; len[b] = 0; pending[b] = bos; finished[b] = 0; }
+  }
+  for (int b = 0; b < B; ++b) {
+    const int r0 = t.row_start[b], n = src_len[b];
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      t.row_tok[r0 + i] = src[b * max_src + i];
+      t.row_pos[r0 + i] = i;
+      t.row_seq[r0 + i] = b;
+      t.row_dst[r0 + i] = r0 + i;            // own keys/values: packed temporaries
+      t.row_dst2[r0 + i] = b * s_max + i;    // where this row's memory key/value goes
+    }
+  }
+}
+void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const int* src_len, const int* max_out_in,
+                                   int B, int s_max, VerifyTables t, int* src_len_out, int* max_out, int* len,
+                                   int* pending, int* finished, int bos, int M, const void* emb, const float* pe, int d,
+                                   float sqrt_d, float* x, void* xa, hipStream_t s) {
+  if (M <= 0) return;
+  if (dtype == AD_BF16)
+    k_assemble_embed_encoder<bf16_t><<<M + 1, 128, 0, s>>>(src, max_src, src_len, max_out_in, B, s_max, t, src_len_out, max_out,
+                                                           len, pending, finished, bos, (const bf16_t*)emb, pe, d, sqrt_d, x,
+                                                           (bf16_t*)xa);
+  else
+    k_assemble_embed_encoder<float><<<M + 1, 128, 0, s>>>(src, max_src, src_len, max_out_in, B, s_max, t, src_len_out, max_out,
+                                                          len, pending, finished, bos, (const float*)emb, pe, d, sqrt_d, x,
+                                                          (float*)xa);
+}
 void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
                              hipStream_t s) {
   k_assemble_encoder<<<1, 256, 0, s>>>(src, max_src, src_len, B, s_max, t);
