@@ -196,18 +196,15 @@ void launch_argmax_accept(const float* part_val, const int* part_idx, int stride
                           const int* ticket_in, unsigned long long* ticket_out, int max_rows, int M /* sum of k */,
                           hipStream_t s);
 // Row tables for the encoder (rows = source tokens) and for the drafter (prefix + masks).
-// launch_assemble_encoder, the embedding of the M rows, the copy of src_len (and, with len set, of
+// the encoder's row tables, the embedding of the M rows, the copy of src_len (and, with len set, of
 // max_out and the start state of a decode) in one launch; the three inputs may be host memory
 void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const int* src_len, const int* max_out_in,
                                    int B, int s_max, VerifyTables t, int* src_len_out, int* max_out, int* len,
                                    int* pending, int* finished, int bos, int M, const void* emb, const float* pe, int d,
                                    float sqrt_d, float* x, void* xa, hipStream_t s);
-void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
-                             hipStream_t s);
 void launch_assemble_drafter(const int* out, int max_len, const int* len, const int* finished, const int* src_len,
                              int B, int k, int bos, int mask, int s_max, VerifyTables t, int* mask_rows,
                              hipStream_t s);
-void launch_reset_state(int* len, int* pending, int* finished, int B, int bos, hipStream_t s);
 void launch_draft_scatter(const int* o_hat, const int* finished, int B, int k, int k_max, int* draft_out,
                           hipStream_t s);
 

@@ -929,31 +929,6 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
 // Encoder: rows = x_1..x_n of every sentence at positions 0..n-1, full self-attention over the
 // sentence's own rows (keys live in the packed temporary buffers, row_dst = identity); the
 // cross_desc slot describes where the memory keys/values of each sentence go.
-__global__ void k_assemble_encoder(const int* __restrict__ src, int max_src, const int* __restrict__ src_len, int B,
-                                   int s_max, VerifyTables t) {
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += src_len[b]; }
-    t.row_start[B] = acc;
-  }
-  __syncthreads();
-  for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    SeqDesc s;
-    s.q_row0 = t.row_start[b]; s.nq = src_len[b]; s.kv_row0 = t.row_start[b]; s.nk_base = src_len[b]; s.causal = 0;
-    s.pad0 = s.pad1 = s.pad2 = 0;
-    t.self_desc[b] = s;
-  }
-  for (int b = 0; b < B; ++b) {
-    const int r0 = t.row_start[b], n = src_len[b];
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      t.row_tok[r0 + i] = src[b * max_src + i];
-      t.row_pos[r0 + i] = i;
-      t.row_seq[r0 + i] = b;
-      t.row_dst[r0 + i] = r0 + i;            // own keys/values: packed temporaries
-      t.row_dst2[r0 + i] = b * s_max + i;    // where this row's memory key/value goes
-    }
-  }
-}
 // The encoder's tables, the embedding of its rows and the per-call device state in one launch
 // (src, src_len, max_out may live in host memory): workgroup 0 writes the tables, keeps the
 // source lengths and, for the verifier (len != null), the output limits and the start state of a
@@ -1030,10 +1005,6 @@ void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const
     k_assemble_embed_encoder<float><<<M + 1, 128, 0, s>>>(src, max_src, src_len, max_out_in, B, s_max, t, src_len_out, max_out,
                                                           len, pending, finished, bos, (const float*)emb, pe, d, sqrt_d, x,
                                                           (float*)xa);
-}
-void launch_assemble_encoder(const int* src, int max_src, const int* src_len, int B, int s_max, VerifyTables t,
-                             hipStream_t s) {
-  k_assemble_encoder<<<1, 256, 0, s>>>(src, max_src, src_len, B, s_max, t);
 }
 
 // Drafter: rows = (o_0..o_j, [MASK] x k) at positions 0..j+k for every unfinished sequence
@@ -1257,14 +1228,6 @@ void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float
                         const float* o_val, int* o_hat, int M, int beta, float tau, hipStream_t s) {
   if (M <= 0) return;
   k_gadpp_apply<<<(M + 3) / 4, 256, 0, s>>>(part_cnt, stride, n_part, lp, col, o_val, o_hat, M, beta, tau);
-}
-__global__ void k_reset_state(int* len, int* pending, int* finished, int B, int bos) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  len[b] = 0; pending[b] = bos; finished[b] = 0;
-}
-void launch_reset_state(int* len, int* pending, int* finished, int B, int bos, hipStream_t s) {
-  k_reset_state<<<(B + 63) / 64, 64, 0, s>>>(len, pending, finished, B, bos);
 }
 
 }  // namespace ad
