@@ -959,6 +959,10 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   for (int b = 0; b < B; ++b)
     if (!c->h_finished[b]) c->fw_max_rows = std::max(c->fw_max_rows, c->h_len[b] + 1 + k);
   const int Mv = live * k;
+  int32_t* h = c->pin;
+  unsigned long long* slots = (unsigned long long*)c->pin;          // [B, k_max]
+  int32_t* ticket_in = c->pin + 2 * (size_t)B * km;                 // behind the slots
+  const bool watch = c->pin_dev != nullptr && c->spin_wait;
   // the drafter forward's launches (made one by one: the prefix is recomputed every iteration,
   // so a call shape seldom comes back and a graph per shape costs more to build than it saves)
   auto launches = [&]() {
@@ -976,15 +980,54 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     }
     flush_ln(c, M);
     launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
-    vocab_finish(c, Mv, vocab_argmax(c, w, c->at<void>(p.xg), Mv));
-    launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
+    const int n_part = vocab_argmax(c, w, c->at<void>(p.xg), Mv);
+    if (watch) {
+      // the drafted tokens go straight to the host: (ticket, token) per 8-byte slot of the mapped buffer
+      launch_argmax_draft(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, n_part, c->at<int>(p.o_hat),
+                          c->at<int>(p.finished), B, k, km, c->pin_dev + (ticket_in - c->pin),
+                          (unsigned long long*)c->pin_dev, c->stream);
+    } else {
+      vocab_finish(c, Mv, n_part);
+      launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
+    }
   };
+  if (watch) {
+    if (++c->ticket >= (1 << 18)) c->ticket = 1;
+    *ticket_in = c->ticket;
+    for (int b = 0; b < B; ++b)
+      if (!c->h_finished[b])
+        for (int i = 0; i < k; ++i) slots[(size_t)b * km + i] = 0;
+  }
   launches();
-  int32_t* h = c->pin;
-  HIP_TRY(c, hipMemcpyAsync(h, c->at<int>(p.draft_out), (size_t)B * km * 4, hipMemcpyDeviceToHost, c->stream));
-  HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipGetLastError());
-  memcpy(draft_out, h, (size_t)B * km * 4);
+  bool seen = false;
+  if (watch) {
+    // wait for the last slot of every live sequence first (it is written about when the others are),
+    // then make sure of all of them
+    const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(50);
+    seen = true;
+    for (int b = 0; b < B && seen; ++b) {
+      if (c->h_finished[b]) continue;
+      for (int i = k - 1; i >= 0 && seen; --i)
+        for (unsigned spin = 1; (int)(__atomic_load_n(slots + (size_t)b * km + i, __ATOMIC_ACQUIRE) >> 32) != c->ticket; ++spin) {
+          if ((spin & 1023u) == 0 && std::chrono::steady_clock::now() > t_end) { seen = false; break; }
+          __builtin_ia32_pause();
+        }
+    }
+    if (seen) {
+      for (int b = 0; b < B; ++b)
+        for (int i = 0; i < km; ++i)
+          draft_out[(size_t)b * km + i] = !c->h_finished[b] && i < k ? (int32_t)(unsigned)slots[(size_t)b * km + i] : AD_NEVER;
+    } else {
+      // fall back to the stream: the tokens are in o_hat; scatter them as the other path does
+      launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
+    }
+  }
+  if (!seen) {
+    HIP_TRY(c, hipMemcpyAsync(h, c->at<int>(p.draft_out), (size_t)B * km * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipGetLastError());
+    memcpy(draft_out, h, (size_t)B * km * 4);
+  }
   c->last_logit_rows = Mv;
   c->last_M = 0;   // the row tables now describe the drafter's rows
   return AD_OK;

@@ -170,6 +170,11 @@ void launch_draft_logit(int dtype, const void* A, const void* W, int M, int N, i
 // (count partials of an EPI_COUNT launch) and top1 - lp <= tau.
 void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float* lp, const int* col,
                         const float* o_val, int* o_hat, int M, int beta, float tau, hipStream_t s);
+// second stage of the arg max over the drafter's M = live * k mask rows; token i of the l-th unfinished
+// sequence b goes to the 8-byte slot [b * k_max + i] of `slots` (host-visible) as (*ticket_in << 32 | token)
+void launch_argmax_draft(const float* part_val, const int* part_idx, int M, int stride, int n_part, int* o_hat,
+                         const int* finished, int B, int k, int k_max, const int* ticket_in, unsigned long long* slots,
+                         hipStream_t s);
 void launch_gather_rows(int dtype, const void* src, const int* rows, int n, int d, void* dst, hipStream_t s);
 
 // Row assembly of a verify call: from k[B], draft[B,k_max], len[B], pending[B] builds the

@@ -803,6 +803,40 @@ void launch_argmax_finish(const float* pv, const int* pi, int M, int stride, int
   k_argmax_finish<<<(M + 3) / 4, 256, 0, s>>>(pv, pi, M, stride, n_part, o_hat, o_val);
 }
 
+// Second stage of the arg max for the drafter's mask rows, writing the drafted tokens where the host
+// reads them: row r = (l, i) is drafted token i of the l-th unfinished sequence b; its 8-byte slot
+// [b * k_max + i] of `slots` (host-visible memory) receives (ticket << 32 | token) in one store, so
+// that seeing the call's ticket in a slot is seeing its token.
+__global__ __launch_bounds__(256) void k_argmax_draft(const float* __restrict__ pv, const int* __restrict__ pi, int M,
+                                                      int stride, int n_part, int* __restrict__ o_hat,
+                                                      const int* __restrict__ finished, int B, int k, int k_max,
+                                                      const int* __restrict__ ticket_in,
+                                                      unsigned long long* __restrict__ slots) {
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (m >= M) return;
+  const int ticket = *ticket_in;
+  const int l = m / k, i = m - l * k;
+  int b = 0;
+  for (int seen = 0; b < B; ++b) {
+    if (finished[b]) continue;
+    if (seen == l) break;
+    ++seen;
+  }
+  float v;
+  int idx;
+  argmax_row(pv + (size_t)m * stride, pi + (size_t)m * stride, n_part, lane, v, idx);
+  if (lane == 0) {
+    o_hat[m] = idx;
+    __hip_atomic_store(slots + (size_t)b * k_max + i, ((unsigned long long)(unsigned)ticket << 32) | (unsigned)idx,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+void launch_argmax_draft(const float* pv, const int* pi, int M, int stride, int n_part, int* o_hat, const int* finished,
+                         int B, int k, int k_max, const int* ticket_in, unsigned long long* slots, hipStream_t s) {
+  if (M <= 0) return;
+  k_argmax_draft<<<(M + 3) / 4, 256, 0, s>>>(pv, pi, M, stride, n_part, o_hat, finished, B, k, k_max, ticket_in, slots);
+}
+
 template <typename T>
 __global__ void k_gather_rows(const T* __restrict__ src, const int* __restrict__ rows, int d, T* __restrict__ dst) {
   const int r = blockIdx.x;
