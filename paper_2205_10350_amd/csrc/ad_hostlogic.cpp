@@ -151,9 +151,11 @@ static int run_loop(Backend& be, LoopIO& io, int mode, int k_block, bool use_dra
       for (int b = 0; b < B; ++b) live = live || !finished(io, b);
       if (!live) break;
       double td = now_us();
+      io.stats.t_host_us += td - t0;
       int rc = be.draft(k_block, nat.data());
       if (rc != AD_OK) return rc;
-      io.stats.t_draft_us += now_us() - td;
+      t0 = now_us();
+      io.stats.t_draft_us += t0 - td;
       for (int b = 0; b < B; ++b)
         if (!finished(io, b)) io.stats.draft_rows += (int64_t)io.o[b].size() + k_block;
     }
