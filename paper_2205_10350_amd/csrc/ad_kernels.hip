@@ -639,6 +639,17 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
           // (measured at 33..64 rows of the wide output projection: 12-16 strips per workgroup, about 500
           // workgroups = one round on the chip, 9.0-9.6 us against 11-13 us with 8 strips)
           if (N <= 4096 || chunks > 2) per_wg = 4 * std::max(1, (n_strips * chunks + 4 * 512 - 1) / (4 * 512));
+          // wider K (measured at 400..700 rows of the d = 1024 shapes): at most 16 strips per workgroup while
+          // two workgroups fit a CU (more rounds beat longer workgroups); one round of 256 workgroups while
+          // the A tile leaves room for one only (K = 4096)
+          if (K > 512 && N <= 4096) {
+            if (astat_lds_bytes(1, K) * 2 <= 160 * 1024) {
+              per_wg = std::min(per_wg, 16);
+            } else {
+              per_wg = 4 * std::max(1, (n_strips * chunks + 4 * 256 - 1) / (4 * 256));
+              while (per_wg < n_strips && (n_strips + per_wg - 1) / per_wg * chunks > 256) per_wg += 4;
+            }
+          }
           return launch_astat<1, 1>(a, w, M, N, K, e, per_wg, s, ln);
         }
       } else {
