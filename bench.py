@@ -29,10 +29,10 @@ MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 
 
 # HBM bytes per launch of the output-projection kernel at the headline shape (base model, 17..32
-# rows), from two rocprofv3 --pmc runs of this file (FETCH_SIZE 16342.7 KiB x 2.000, WRITE_SIZE
-# 544.1 KiB x 1.0; factors from k_calibration_copy's readings for a 256 MiB copy in the same runs;
+# rows), from two rocprofv3 --pmc runs of this file (FETCH_SIZE 16336.9 KiB x 2.000, WRITE_SIZE
+# 482.7 KiB x 1.0; factors from k_calibration_copy's readings for a 256 MiB copy in the same runs;
 # profiles/bench_base_bs1_vocab_kernel_hbm_traffic.md)
-VOCAB_KERNEL_TRAFFIC_BYTES = int(16342.7 * 1024 * (262144.0 / 131083.0) + 544.1 * 1024)
+VOCAB_KERNEL_TRAFFIC_BYTES = int(16336.9 * 1024 * (262144.0 / 131083.0) + 482.7 * 1024)
 
 
 def decoder_stream_params(dims):
