@@ -41,10 +41,10 @@ struct Plan {
   int n_strips = 0;
   int max_pos = 0;
   size_t kv_w[2], kv_b[2];   // per model: cross-attention [wk; wv] of every decoder layer as one matrix, and its bias
-  size_t pe, x, s, xa, q, att, tk, tv, f, xg, part_val, part_idx, o_hat, o_val, logits, draft_lp, draft_col;
+  size_t pe, x, s, xa, q, att, tk, tv, f, part_val, part_idx, o_hat, o_val, logits, draft_lp, draft_col;
   size_t cache_k, cache_v, cache_layer_stride;          // [NL][B*l_cap, d]
   size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
-  size_t row_tok, row_pos, row_seq, row_dst, row_dst2, row_start, self_desc, cross_desc, mask_rows;
+  size_t row_tok, row_pos, row_seq, row_dst, row_dst2, row_start, self_desc, cross_desc;
   size_t len, pending, finished, max_out, src_len[2], out, result, k_dev, draft_dev, src_dev, draft_out;
   size_t stages, bar, stamps;   // fused forward: stage program, barrier words, optional stage clock stamps
   int stage_cap = 0;
@@ -72,7 +72,6 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.tk = take(m * d * p.esz);
   p.tv = take(m * d * p.esz);
   p.f = take(m * (size_t)c.d_ffn * p.esz);
-  p.xg = take((size_t)p.mv_cap * d * p.esz);
   p.part_val = take((size_t)p.mv_cap * p.n_strips * 4);
   p.part_idx = take((size_t)p.mv_cap * p.n_strips * 4);
   p.o_hat = take((size_t)p.mv_cap * 4);
@@ -94,9 +93,8 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   }
   p.row_tok = take(m * 4); p.row_pos = take(m * 4); p.row_seq = take(m * 4); p.row_dst = take(m * 4); p.row_dst2 = take(m * 4);
   p.row_start = take((B + 1) * 4);
-  p.self_desc = take(B * sizeof(SeqDesc));
-  p.cross_desc = take(B * sizeof(SeqDesc));
-  p.mask_rows = take((size_t)p.mv_cap * 4);
+  p.self_desc = take(2 * B * sizeof(SeqDesc));    // the drafter has two per sequence (mask rows, prefix rows)
+  p.cross_desc = take(2 * B * sizeof(SeqDesc));
   p.len = take(B * 4); p.pending = take(B * 4); p.finished = take(B * 4); p.max_out = take(B * 4);
   p.out = take(B * c.max_len * 4);
   p.result = take(B * 2 * 4 + 16);   // [B,2] results, then one int: the fused forward's abort flag copy
@@ -235,13 +233,18 @@ static void ffn_block(ad_ctx* c, const FfnW& f, const LnW& ln, int M) {
 
 // Self-attention block: q,k,v projection with the key/value rows written to (Kl, Vl) at
 // row_dst, attention, output projection + residual + LayerNorm.
-static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, void* Kl, void* Vl, int max_keys) {
+// head_rows > 0: from the attention on, only the first head_rows packed rows are needed (they are
+// the queries of the first head_nseq descriptors, at most head_max_rows each): keys and values are
+// still projected from all M rows.
+static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, void* Kl, void* Vl, int max_keys,
+                            int head_rows = 0, int head_nseq = 0, int head_max_rows = 0) {
   const Plan& p = c->plan;
   const int d = c->cfg.d_model, H = c->cfg.n_heads;
   VerifyTables t = tables(c);
   Epi e{};
   e.mode = EPI_QKV; e.d = d; e.bias = a.bqkv; e.out0 = c->at<void>(p.q); e.out1 = Kl; e.out2 = Vl; e.row_dst = t.row_dst;
   gemm_rows(c, a.wqkv, M, 3 * d, e);
+  if (head_rows > 0) { c->fw_nseq = head_nseq; c->fw_max_rows = head_max_rows; M = head_rows; }
   launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.self_desc, c->fw_nseq, c->fw_max_rows,
                    H, d / H, max_keys, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
@@ -945,7 +948,7 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   const ad_config& cf = c->cfg;
   const Plan& p = c->plan;
   if (k < 1 || k > cf.k_max) return fail(c, AD_EINVAL, "k outside [1, k_max]");
-  const int B = c->B, km = cf.k_max, d = cf.d_model;
+  const int B = c->B, km = cf.k_max;
   int M = 0, live = 0;
   for (int b = 0; b < B; ++b)
     if (!c->h_finished[b]) { M += c->h_len[b] + 1 + k; ++live; }
@@ -954,33 +957,41 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     return AD_OK;
   }
   VerifyTables t = tables(c);
-  c->fw_nseq = B;
-  c->fw_max_rows = 0;
+  int max_rows = k;
   for (int b = 0; b < B; ++b)
-    if (!c->h_finished[b]) c->fw_max_rows = std::max(c->fw_max_rows, c->h_len[b] + 1 + k);
+    if (!c->h_finished[b]) max_rows = std::max(max_rows, c->h_len[b] + 1);
   const int Mv = live * k;
   int32_t* h = c->pin;
   unsigned long long* slots = (unsigned long long*)c->pin;          // [B, k_max]
   int32_t* ticket_in = c->pin + 2 * (size_t)B * km;                 // behind the slots
   const bool watch = c->pin_dev != nullptr && c->spin_wait;
   // the drafter forward's launches (made one by one: the prefix is recomputed every iteration,
-  // so a call shape seldom comes back and a graph per shape costs more to build than it saves)
+  // so a call shape seldom comes back and a graph per shape costs more to build than it saves).
+  // The mask rows are the first Mv packed rows; two attention problems per sequence (mask rows and
+  // prefix rows as queries).  In the last layer only the mask rows go on after the key/value
+  // projection: nothing reads the prefix rows' outputs.
   auto launches = [&]() {
     launch_assemble_drafter(c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
-                            c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->at<int>(p.mask_rows),
-                            c->stream);
+                            c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->stream);
     const ModelW& w = c->w[AD_DRAFTER];
     embed_rows(c, w, M);
+    int rows = M;
+    c->fw_nseq = 2 * live;
+    c->fw_max_rows = max_rows;
     for (int l = 0; l < cf.dec_layers; ++l) {
       const DecLayerW& L = w.dec[l];
-      self_attn_block(c, L.self, L.ln1, M, c->at<void>(p.tk), c->at<void>(p.tv), cf.max_len + km);
-      cross_attn_block(c, L.cross, L.ln2, M, c->ws + p.mem_k[1] + l * p.mem_layer_stride,
+      if (l + 1 == cf.dec_layers) {
+        self_attn_block(c, L.self, L.ln1, M, c->at<void>(p.tk), c->at<void>(p.tv), cf.max_len + km, Mv, live, k);
+        rows = Mv;
+      } else {
+        self_attn_block(c, L.self, L.ln1, M, c->at<void>(p.tk), c->at<void>(p.tv), cf.max_len + km);
+      }
+      cross_attn_block(c, L.cross, L.ln2, rows, c->ws + p.mem_k[1] + l * p.mem_layer_stride,
                        c->ws + p.mem_v[1] + l * p.mem_layer_stride);
-      ffn_block(c, L.ffn, L.ln3, M);
+      ffn_block(c, L.ffn, L.ln3, rows);
     }
-    flush_ln(c, M);
-    launch_gather_rows(cf.dtype, c->at<void>(p.xa), c->at<int>(p.mask_rows), Mv, d, c->at<void>(p.xg), c->stream);
-    const int n_part = vocab_argmax(c, w, c->at<void>(p.xg), Mv);
+    flush_ln(c, Mv);
+    const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), Mv);
     if (watch) {
       // the drafted tokens go straight to the host: (ticket, token) per 8-byte slot of the mapped buffer
       launch_argmax_draft(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, n_part, c->at<int>(p.o_hat),

@@ -175,7 +175,6 @@ void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float
 void launch_argmax_draft(const float* part_val, const int* part_idx, int M, int stride, int n_part, int* o_hat,
                          const int* finished, int B, int k, int k_max, const int* ticket_in, unsigned long long* slots,
                          hipStream_t s);
-void launch_gather_rows(int dtype, const void* src, const int* rows, int n, int d, void* dst, hipStream_t s);
 
 // Row assembly of a verify call: from k[B], draft[B,k_max], len[B], pending[B] builds the
 // packed row tables and both attention descriptors.
@@ -207,9 +206,11 @@ void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const
                                    int B, int s_max, VerifyTables t, int* src_len_out, int* max_out, int* len,
                                    int* pending, int* finished, int bos, int M, const void* emb, const float* pe, int d,
                                    float sqrt_d, float* x, void* xa, hipStream_t s);
+// Drafter rows: the k mask rows of every unfinished sequence first (l-th unfinished sequence at
+// [l*k, l*k + k)), then the prefix rows; descriptors [0, live) = mask rows as queries,
+// [live, 2 live) = prefix rows (self_desc and cross_desc hold 2 B entries).
 void launch_assemble_drafter(const int* out, int max_len, const int* len, const int* finished, const int* src_len,
-                             int B, int k, int bos, int mask, int s_max, VerifyTables t, int* mask_rows,
-                             hipStream_t s);
+                             int B, int k, int bos, int mask, int s_max, VerifyTables t, hipStream_t s);
 void launch_draft_scatter(const int* o_hat, const int* finished, int B, int k, int k_max, int* draft_out,
                           hipStream_t s);
 

@@ -848,17 +848,6 @@ void launch_argmax_draft(const float* pv, const int* pi, int M, int stride, int 
   k_argmax_draft<<<(M + 3) / 4, 256, 0, s>>>(pv, pi, M, stride, n_part, o_hat, finished, B, k, k_max, ticket_in, slots);
 }
 
-template <typename T>
-__global__ void k_gather_rows(const T* __restrict__ src, const int* __restrict__ rows, int d, T* __restrict__ dst) {
-  const int r = blockIdx.x;
-  const T* sp = src + (size_t)rows[r] * d;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(size_t)r * d + c] = sp[c];
-}
-void launch_gather_rows(int dtype, const void* src, const int* rows, int n, int d, void* dst, hipStream_t s) {
-  if (n <= 0) return;
-  if (dtype == AD_BF16) k_gather_rows<bf16_t><<<n, 128, 0, s>>>((const bf16_t*)src, rows, d, (bf16_t*)dst);
-  else k_gather_rows<float><<<n, 128, 0, s>>>((const float*)src, rows, d, (float*)dst);
-}
 
 // ------------------------------------------------------------------------------------- row assembly
 // Verify call: sequence b feeds (pending_b, draft_b[0..k_b-2]) at positions len_b .. len_b+k_b-1
@@ -1056,40 +1045,53 @@ void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const
 // (Section 3.2, draft paragraph), bidirectional self-attention over the sequence's own rows.
 __global__ void k_assemble_drafter(const int* __restrict__ out, int max_len, const int* __restrict__ len,
                                    const int* __restrict__ finished, const int* __restrict__ src_len, int B, int k,
-                                   int bos, int mask, int s_max, VerifyTables t, int* __restrict__ mask_rows) {
+                                   int bos, int mask, int s_max, VerifyTables t) {
+  // Packed row order: the k mask rows of every unfinished sequence first (sequence l's at
+  // [l*k, l*k + k)), then the prefix rows, so that whatever only the mask rows need (everything
+  // after the last layer's key/value projection, the output projection) works on the first live*k
+  // rows.  A sequence's keys and values stay contiguous (prefix, then masks) through row_dst.
+  // Descriptors: entries [0, live) = mask rows as queries, [live, 2 live) = prefix rows.
+  __shared__ int s_live;
   if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += finished[b] ? 0 : len[b] + 1 + k; }
-    t.row_start[B] = acc;
+    int live = 0;
+    for (int b = 0; b < B; ++b) live += finished[b] ? 0 : 1;
+    int l = 0, kslot = 0, pre = live * k;
+    for (int b = 0; b < B; ++b) {
+      t.row_start[b] = kslot;
+      if (finished[b]) continue;
+      const int L = len[b];
+      SeqDesc s;
+      s.q_row0 = l * k; s.nq = k; s.kv_row0 = kslot; s.nk_base = L + 1 + k; s.causal = 0;
+      s.pad0 = b; s.pad1 = pre; s.pad2 = 0;     // pad0/pad1: the sequence and its first prefix row (used below)
+      t.self_desc[l] = s;
+      s.q_row0 = pre; s.nq = L + 1;
+      t.self_desc[live + l] = s;
+      s.kv_row0 = b * s_max; s.nk_base = src_len[b];
+      t.cross_desc[live + l] = s;
+      s.q_row0 = l * k; s.nq = k;
+      t.cross_desc[l] = s;
+      kslot += L + 1 + k; pre += L + 1; ++l;
+    }
+    t.row_start[B] = kslot;
+    s_live = live;
   }
   __syncthreads();
-  for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    const int n = finished[b] ? 0 : len[b] + 1 + k;
-    SeqDesc s;
-    s.q_row0 = t.row_start[b]; s.nq = n; s.kv_row0 = t.row_start[b]; s.nk_base = n; s.causal = 0;
-    s.pad0 = s.pad1 = s.pad2 = 0;
-    t.self_desc[b] = s;
-    s.kv_row0 = b * s_max; s.nk_base = src_len[b];
-    t.cross_desc[b] = s;
-  }
-  int live = 0;   // index of sequence b among the unfinished ones: its mask rows are [live*k, live*k+k)
-  for (int b = 0; b < B; ++b) {
-    if (finished[b]) continue;
-    const int r0 = t.row_start[b], L = len[b], n = L + 1 + k;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      t.row_tok[r0 + i] = i == 0 ? bos : (i <= L ? out[b * max_len + i - 1] : mask);
-      t.row_pos[r0 + i] = i;
-      t.row_seq[r0 + i] = b;
-      t.row_dst[r0 + i] = r0 + i;
-      if (i > L) mask_rows[live * k + (i - L - 1)] = r0 + i;
+  const int live = s_live;
+  for (int l = 0; l < live; ++l) {
+    const SeqDesc m = t.self_desc[l];
+    const int b = m.pad0, pre = m.pad1, L = m.nk_base - 1 - k, kslot = m.kv_row0;
+    for (int i = threadIdx.x; i < L + 1 + k; i += blockDim.x) {
+      const int row = i <= L ? pre + i : l * k + (i - L - 1);
+      t.row_tok[row] = i == 0 ? bos : (i <= L ? out[b * max_len + i - 1] : mask);
+      t.row_pos[row] = i;
+      t.row_seq[row] = b;
+      t.row_dst[row] = kslot + i;
     }
-    ++live;
   }
 }
 void launch_assemble_drafter(const int* out, int max_len, const int* len, const int* finished, const int* src_len,
-                             int B, int k, int bos, int mask, int s_max, VerifyTables t, int* mask_rows,
-                             hipStream_t s) {
-  k_assemble_drafter<<<1, 256, 0, s>>>(out, max_len, len, finished, src_len, B, k, bos, mask, s_max, t, mask_rows);
+                             int B, int k, int bos, int mask, int s_max, VerifyTables t, hipStream_t s) {
+  k_assemble_drafter<<<1, 256, 0, s>>>(out, max_len, len, finished, src_len, B, k, bos, mask, s_max, t);
 }
 
 // Drafted tokens of the unfinished sequences, back in [B, k_max] order (AD_NEVER elsewhere).
