@@ -301,6 +301,33 @@ def test_block_drafter_matches_oracle():
             rig.close()
 
 
+def test_block_drafter_skips_finished_sequences():
+    """Three sequences, the middle one finished (its output limit reached): the drafter's rows are
+    those of the other two (mask rows first, prefix rows behind), its drafts land in their slots and
+    the finished sequence gets the never-matching id."""
+    rig = Rig("tiny", "fp32", 23, B=3, drafter=True)
+    try:
+        srcs = _sources(rig.dims, 23, [12, 7, 15])
+        gs = [O.greedy(rig.tok, s, 32, rig.eos, BOS) for s in srcs]
+        rig.ctx.encode(ad.AD_VERIFIER, srcs, max_out=[32, 2, 32])
+        rig.ctx.encode(ad.AD_DRAFTER, srcs)
+        n, _ = rig.ctx.verify([gs[0][:3], gs[1][:2], gs[2][:5]])
+        assert n.tolist() == [3, 2, 5]
+        k = 4
+        dr = rig.ctx.draft_nat(k)
+        logits = rig.ctx.debug_logits()
+        assert logits.shape[0] == 2 * k
+        assert dr[1].tolist() == [ad.AD_NEVER] * k
+        for live, (i, p) in enumerate(((0, 3), (2, 5))):
+            toks = [BOS] + gs[i][:p] + [MASK] * k
+            ref = rig.dr.decode_full(rig.dr.encode(srcs[i]), toks, causal=False)[p + 1:]
+            got = logits[live * k:(live + 1) * k]
+            assert np.abs(got - ref).max() < TOL["fp32"]
+            assert dr[i].tolist() == [O.argmax_lowest(r) for r in ref]
+    finally:
+        rig.close()
+
+
 def test_argument_errors_on_device_context():
     rig = Rig("tiny", "fp32", 3, B=2, k_max=4, max_src=16, max_len=8)
     try:
