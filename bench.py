@@ -213,6 +213,10 @@ def main():
                 "iterations": its2, "rows_verified": rows2,
                 "verify_rows": M32, "verify_us": fwd32_us, "single_launch": bool(fused32), "verify_gflop": flops / 1e9,
                 "mfma_frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK,
+                # all iterations of the decode (rows shrink as the guides are consumed): flops of every row
+                # verified over the whole decode's wall time, encoder and host included
+                "decode_mean_rows": rows2 / max(1, its2),
+                "decode_mfma_frac": 2.0 * rows2 * params / dt2 / MFMA_BF16_PEAK,
                 "staged_launches_us": staged32_us, "staged_vocab_kernel_us": voc32_us,
                 "staged_vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
     # ---------------- verify forward against block size and batch size (roofline against rows) -------
@@ -385,7 +389,9 @@ def main():
                                "vocab 32000, source len ~N(25,8) in [5,64], guide = greedy output + edits 0.1",
                    "batch": 1, "sentences": n_sent, "k_max": K_MAX},
         "tokens": toks, "verify_forwards": its, "rows_verified": rows,
-        "mean_tokens_per_forward": toks / max(1, its),
+        "mean_tokens_per_forward": toks / max(1, its), "mean_rows_per_forward": rows / max(1, its),
+        # weights streamed by all verify forwards of the timed decode over its wall time (encoder, host included)
+        "decode_hbm_frac": its * 2.0 * params / dt / HBM_PEAK,
         "greedy_tokens_per_s": greedy_tps, "speedup_vs_greedy": value / greedy_tps,
         "verify_forward_bs1": verify_bs1, "bs32": bs32, "gad": gad, "sweeps": sweeps, "deep_encoder": deep,
         "measured_copy_GBps": copy_gbps,
