@@ -394,7 +394,7 @@ def main():
         "decode_hbm_frac": its * 2.0 * params / dt / HBM_PEAK,
         "greedy_tokens_per_s": greedy_tps, "speedup_vs_greedy": value / greedy_tps,
         "verify_forward_bs1": verify_bs1, "bs32": bs32, "gad": gad, "sweeps": sweeps, "deep_encoder": deep,
-        "measured_copy_GBps": copy_gbps,
+        "measured_copy_GBps": copy_gbps, "measured_mfma_bf16_TFLOPs": ad.calibration_mfma(),
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

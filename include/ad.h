@@ -214,6 +214,14 @@ int ad_time_output_projection(ad_ctx* ctx, const void* w_copies, size_t copy_str
  * Returns AD_OK or AD_EINVAL / AD_EDEVICE. */
 int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
 
+/* Measurement aid, no part of the method: the rate at which the whole chip accepts the bf16 matrix
+ * instruction the GEMMs and the attention are built on (v_mfma_f32_16x16x32_bf16, fp32 accumulate) when
+ * nothing else limits it: 512 workgroups of 4 waves issue iters x 8 independent ones each on fixed
+ * register operands, timed by HIP events on `stream`.  `scratch_dev`: at least 512 KiB of device
+ * memory (receives values nobody needs).  *tflops: dense TFLOP/s, the measured counterpart of the
+ * nominal peak.  Returns AD_OK or AD_EINVAL / AD_EDEVICE. */
+int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int32_t iters, void* stream, double* tflops);
+
 /* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
  * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; at most
  * max_batch * k_max).  Default 0: one launch per stage always, the faster path at every size

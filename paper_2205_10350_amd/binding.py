@@ -24,7 +24,7 @@ EXPORTS = [
     "ad_weights_pack",
     "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
-    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp", "ad_time_output_projection",
+    "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp", "ad_time_output_projection", "ad_calibration_mfma",
 ]
 AD_OPT_FUSED_ROWS = 0
 AD_OPT_FUSED_AVAILABLE = 1
@@ -99,6 +99,8 @@ def lib():
     L.ad_time_verify_forward.restype = C.c_int
     L.ad_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.ad_calibration_copy.restype = C.c_int
+    L.ad_calibration_mfma.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
+    L.ad_calibration_mfma.restype = C.c_int
     L.ad_set_option.argtypes = [C.c_void_p, C.c_int, C.c_int]; L.ad_set_option.restype = C.c_int
     L.ad_set_gadpp.argtypes = [C.c_void_p, C.c_int32, C.c_float]; L.ad_set_gadpp.restype = C.c_int
     L.ad_time_output_projection.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.POINTER(C.c_double)]
@@ -201,6 +203,17 @@ def calibration_copy(dst, src, stream=None):
     assert dst.numel() * dst.element_size() == nbytes
     st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
     _check(lib().ad_calibration_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(st)))
+
+
+def calibration_mfma(iters=4000, stream=None):
+    """Measured dense bf16 MFMA rate of the chip in TFLOP/s (register operands, nothing else in the way)."""
+    import torch
+    scratch = torch.empty(512 * 1024, dtype=torch.uint8, device="cuda")
+    st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
+    t = C.c_double(0)
+    _check(lib().ad_calibration_mfma(C.c_void_p(scratch.data_ptr()), scratch.numel(), iters, C.c_void_p(st), C.byref(t)))
+    torch.cuda.synchronize()
+    return t.value
 
 
 class Context:

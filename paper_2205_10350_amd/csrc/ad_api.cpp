@@ -1202,6 +1202,24 @@ int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* 
   return AD_OK;
 }
 
+int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int iters, void* stream, double* tflops) {
+  const int wgs = 512;   // two workgroups per CU on 256 CUs: two waves per SIMD
+  if (!scratch_dev || !tflops || iters < 1 || scratch_bytes < (size_t)wgs * 256 * 4)
+    return fail(nullptr, AD_EINVAL, "ad_calibration_mfma: null pointer, iters < 1 or scratch smaller than 512 KiB");
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  float ms = 0;
+  bool ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess &&
+            launch_calibration_mfma((float*)scratch_dev, wgs, 16, s) == hipSuccess && hipEventRecord(e0, s) == hipSuccess &&
+            launch_calibration_mfma((float*)scratch_dev, wgs, iters, s) == hipSuccess && hipEventRecord(e1, s) == hipSuccess &&
+            hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (!ok || ms <= 0) { (void)hipGetLastError(); return fail(nullptr, AD_EDEVICE, "ad_calibration_mfma: launch or timing failed"); }
+  *tflops = (double)wgs * 4 * iters * 8 * (2.0 * 16 * 16 * 32) / (ms * 1e-3) / 1e12;
+  return AD_OK;
+}
+
 int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* vocab_kernel_us,
                            double* vocab_back_to_back_us) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");

@@ -158,6 +158,8 @@ void launch_attention(int dtype, const void* q, const void* K, const void* V, vo
 void launch_layernorm(int dtype, const float* x, const float* g, const float* b, int M, int d, float* y,
                       void* ya, hipStream_t s);
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// workgroups x 4 waves x iters x 8 bf16 MFMAs (16x16x32) on fixed register operands; out: workgroups x 256 floats
+hipError_t launch_calibration_mfma(float* out, int workgroups, int iters, hipStream_t s);
 // second stage of the arg max: n_part partials per row, rows `stride` entries apart
 void launch_argmax_finish(const float* part_val, const int* part_idx, int M, int stride, int n_part, int* o_hat,
                           float* o_val, hipStream_t s);

@@ -794,6 +794,35 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------- MFMA issue-rate calibration
+// Every wave issues `iters` x 8 independent v_mfma_f32_16x16x32_bf16 on register operands that never
+// change: the rate the matrix cores accept this instruction at, whole chip (2 waves per SIMD).
+__global__ __launch_bounds__(256) void k_calibration_mfma(float* __restrict__ out, int iters) {
+  f32x4 c[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) c[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint4 av = uint4{0x3c003c00u + threadIdx.x, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+  const uint4 bv = uint4{0x3c003c00u, 0x3c003c00u + blockIdx.x, 0x3c003c00u, 0x3c003c00u};
+  const bf16x8 a = __builtin_bit_cast(bf16x8, av), b = __builtin_bit_cast(bf16x8, bv);
+  // (written out: left to itself the compiler shuttles the accumulators between register files in the loop)
+  for (int i = 0; i < iters; ++i)
+    asm volatile(
+        "v_mfma_f32_16x16x32_bf16 %0, %8, %9, %0\n v_mfma_f32_16x16x32_bf16 %1, %8, %9, %1\n"
+        "v_mfma_f32_16x16x32_bf16 %2, %8, %9, %2\n v_mfma_f32_16x16x32_bf16 %3, %8, %9, %3\n"
+        "v_mfma_f32_16x16x32_bf16 %4, %8, %9, %4\n v_mfma_f32_16x16x32_bf16 %5, %8, %9, %5\n"
+        "v_mfma_f32_16x16x32_bf16 %6, %8, %9, %6\n v_mfma_f32_16x16x32_bf16 %7, %8, %9, %7\n"
+        : "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3]), "+v"(c[4]), "+v"(c[5]), "+v"(c[6]), "+v"(c[7])
+        : "v"(a), "v"(b));
+  float r = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r += c[j][0] + c[j][1] + c[j][2] + c[j][3];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+}
+hipError_t launch_calibration_mfma(float* out, int workgroups, int iters, hipStream_t s) {
+  k_calibration_mfma<<<workgroups, 256, 0, s>>>(out, iters);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------- arg max, second stage
 __global__ __launch_bounds__(256) void k_argmax_finish(const float* __restrict__ pv, const int* __restrict__ pi,
                                                        int M, int stride, int n_part, int* __restrict__ o_hat,
