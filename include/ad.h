@@ -235,8 +235,13 @@ int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int32_t iters, 
  * AD_OPT_SPIN_WAIT (0/1, default 1): ad_verify returns as soon as the device has written the
  * call's result into the (device-mapped) host staging buffer, which the calling thread watches,
  * instead of waiting for the stream to drain; later calls are ordered behind the unfinished rest
- * of the stream as usual.  After 50 ms without the result it waits for the stream. */
-enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5 };
+ * of the stream as usual.  After 50 ms without the result it waits for the stream.
+ * AD_OPT_FUSE_CROSSQ (0/1, default 1): in the launch-per-stage path a decoder layer's
+ * cross-attention runs its query projection and the attention as one launch (bf16, head width 64,
+ * model width 512 or 1024; other shapes take two launches whatever the setting).  Same results bit
+ * for bit either way. */
+enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5,
+       AD_OPT_FUSE_CROSSQ = 6 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 

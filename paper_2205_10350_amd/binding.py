@@ -31,6 +31,7 @@ AD_OPT_FUSED_AVAILABLE = 1
 AD_OPT_GRAPHS = 3
 AD_OPT_GRAPHS_CAPTURED = 4
 AD_OPT_SPIN_WAIT = 5
+AD_OPT_FUSE_CROSSQ = 6
 
 
 class AdConfig(C.Structure):

@@ -145,6 +145,7 @@ struct ad_ctx {
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
   int ticket = 0;                 // number of the last ad_verify call that waited by watching memory
   bool spin_wait = true;
+  bool fuse_crossq = true;   // cross-attention: query projection + attention as one launch (AD_OPT_FUSE_CROSSQ)
   int gadpp_beta = 1;             // GAD++ (Section 3.2.3): 1 = plain top-1 verification
   float gadpp_tau = 0.f;
   int fused_grid = 0, fused_stages = 0, fused_teams = 0;
@@ -254,11 +255,23 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
   const Plan& p = c->plan;
   const int d = c->cfg.d_model, H = c->cfg.n_heads;
   VerifyTables t = tables(c);
-  Epi e{};
-  e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
-  gemm_rows(c, a.wqkv, M, d, e);
-  launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
-                   c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
+  // query projection (with the pending LayerNorm) and attention in one launch where the shape allows
+  LnA la{};
+  if (c->ln_pending) {
+    la.x = c->at<float>(p.s); la.g = c->ln_pending->g; la.b = c->ln_pending->b; la.y = c->at<float>(p.x);
+  }
+  if (c->fuse_crossq &&
+      launch_crossq_attention(c->cfg.dtype, la, c->at<void>(p.xa), a.wqkv, a.bqkv, Km, Vm,
+                              c->at<void>(p.att), t.cross_desc, c->fw_nseq, c->fw_max_rows, H, d / H, c->cfg.max_src,
+                              c->stream)) {
+    c->ln_pending = nullptr;
+  } else {
+    Epi e{};
+    e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
+    gemm_rows(c, a.wqkv, M, d, e);
+    launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
+                     c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
+  }
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
 
@@ -868,7 +881,7 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
       // every launch argument is a function of (rows, sequences, longest block), of the GAD++
       // setting and of pointers fixed for the context's life
       // (and of whether the acceptance kernel posts the ticket)
-      const unsigned long long key = shape_key(M, c->fw_max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0));
+      const unsigned long long key = shape_key(M, c->fw_max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0));
       unsigned tau_bits;
       memcpy(&tau_bits, &c->gadpp_tau, 4);
       const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;
@@ -1164,6 +1177,11 @@ int ad_set_option(ad_ctx* c, int option, int value) {
     c->spin_wait = value != 0;
     return AD_OK;
   }
+  if (option == AD_OPT_FUSE_CROSSQ) {
+    if (value != 0 && value != 1) return fail(c, AD_EINVAL, "AD_OPT_FUSE_CROSSQ must be 0 or 1");
+    c->fuse_crossq = value != 0;
+    return AD_OK;
+  }
   if (option != AD_OPT_FUSED_ROWS) return fail(c, AD_EINVAL, "unknown option");
   if (value < 0 || value > c->plan.mv_cap) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, max_batch * k_max]");
   if (value > 0 && c->fused_grid == 0) return fail(c, AD_ESTATE, "the persistent forward is unavailable for this context");
@@ -1178,6 +1196,7 @@ int ad_get_option(ad_ctx* c, int option, int* value) {
   else if (option == AD_OPT_GRAPHS) *value = c->graphs_on ? 1 : 0;
   else if (option == AD_OPT_GRAPHS_CAPTURED) *value = (int)c->graphs.size();
   else if (option == AD_OPT_SPIN_WAIT) *value = c->spin_wait ? 1 : 0;
+  else if (option == AD_OPT_FUSE_CROSSQ) *value = c->fuse_crossq ? 1 : 0;
   else return fail(c, AD_EINVAL, "unknown option");
   return AD_OK;
 }

@@ -675,6 +675,30 @@ __device__ __forceinline__ void attn_preload(const bf16_t* __restrict__ q, const
     }
   }
 }
+// The key half of attn_preload alone (the queries come from somewhere else).
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_preload_k(const bf16_t* __restrict__ Kb, const SeqDesc sd, int row_begin, int row_end,
+                                               int h, int d, int nk_all, uint4 (&kf)[4][DH / 32]) {
+  constexpr int KS = DH / 32;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
+  const int n_tiles = (row_end - row_begin + 15) >> 4;
+  if (wave >= n_tiles) return;
+  const int tile_end = min(row_begin + wave * 16 + 16, row_end);
+  const int nk_tile = sd.causal ? sd.nk_base + tile_end : sd.nk_base;
+  const int nt = (nk_tile + 15) >> 4;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (j < nt) {
+      const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) kf[j][s] = ldg16<COH>(kp + 32 * s);
+    }
+  }
+}
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_coop_scores_q(const uint4 (&qf)[DH / 32], const bf16_t* __restrict__ Kb, const SeqDesc sd,
+                                                   int h, int d, int nk_all, int nt, float* Sbuf, int lds_s);
 // One 16-row tile, many keys: the score products Q K^T are independent per key tile, so all waves
 // of the workgroup compute them together (wave w: key tiles w, w + waves, ..; one fetch latency
 // instead of one per group of tiles on a single wave) and leave the raw fp32 products in LDS,
@@ -683,8 +707,8 @@ template <int DH, bool COH>
 __device__ __forceinline__ void attn_coop_scores(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, const SeqDesc sd,
                                                  int row_begin, int row_end, int h, int d, int nk_all, int nt,
                                                  float* Sbuf, int lds_s) {
-  constexpr int KS = DH / 32, TB = 8;   // key tiles per batch of loads
-  const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  constexpr int KS = DH / 32;
+  const int lane = threadIdx.x & 63;
   const int r = lane & 15, kq = lane >> 4;
   uint4 qf[KS];
   {
@@ -692,6 +716,15 @@ __device__ __forceinline__ void attn_coop_scores(const bf16_t* __restrict__ q, c
 #pragma unroll
     for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
   }
+  attn_coop_scores_q<DH, COH>(qf, Kb, sd, h, d, nk_all, nt, Sbuf, lds_s);
+}
+// (the same with the tile's query fragments given)
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_coop_scores_q(const uint4 (&qf)[DH / 32], const bf16_t* __restrict__ Kb, const SeqDesc sd,
+                                                   int h, int d, int nk_all, int nt, float* Sbuf, int lds_s) {
+  constexpr int KS = DH / 32, TB = 8;   // key tiles per batch of loads
+  const int waves = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
   for (int b0 = wave; b0 < nt; b0 += waves * TB) {
     uint4 kf[TB][KS];
 #pragma unroll
@@ -716,6 +749,51 @@ __device__ __forceinline__ void attn_coop_scores(const bf16_t* __restrict__ q, c
     }
   }
 }
+// Values of one (sequence, head) transposed into LDS: Vt[c][t] = V[t][c], keys nk_all .. nkp - 1 as zeros.
+template <int DH, bool COH>
+__device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb, const SeqDesc sd, int h, int d, bf16_t* Vt,
+                                                  int ldv, int nkp, int nk_all) {
+  // Values transposed into LDS.  Many keys: 8 keys x 8 channels per step and thread: eight 16-byte loads
+  // (one key row piece each), an 8 x 8 transpose of 16-bit values in registers (byte permutes),
+  // eight 16-byte LDS stores (one channel row piece each).  Keys past the last needed one: zeros.
+  constexpr int G = DH / 8;   // 16-byte pieces per key row
+  const bf16_t* vg = Vb + (size_t)sd.kv_row0 * d + h * DH;
+  // few keys: one 16-byte piece per thread and step, eight 2-byte LDS stores (more threads in
+  // flight, which is what counts there); many keys: the transposing path below
+  if (nkp <= 128)
+  for (int i = threadIdx.x; i < nkp * G; i += blockDim.x) {
+    const int g = i / nkp, t = i - g * nkp;
+    uint4 v = uint4{0u, 0u, 0u, 0u};
+    if (t < nk_all) v = ldg16<COH>(vg + (size_t)t * d + g * 8);
+    bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
+    dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
+    dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
+    dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
+    dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
+  }
+  const int n_items = nkp <= 128 ? 0 : (nkp >> 3) * G;
+  for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
+    const int g = it % G, t0 = (it / G) << 3;
+    unsigned in[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint4 v = uint4{0u, 0u, 0u, 0u};
+      if (t0 + i < nk_all) v = ldg16<COH>(vg + (size_t)(t0 + i) * d + g * 8);
+      in[i][0] = v.x; in[i][1] = v.y; in[i][2] = v.z; in[i][3] = v.w;
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      // channel c of keys t0 .. t0+7: the low (c even) or high (c odd) half of dword c/2 of every key
+      unsigned o[4];
+#pragma unroll
+      for (int pr = 0; pr < 4; ++pr) {
+        const unsigned lo = in[2 * pr][c >> 1], hi = in[2 * pr + 1][c >> 1];
+        o[pr] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+      }
+      *(uint4*)(Vt + (size_t)(g * 8 + c) * ldv + t0) = uint4{o[0], o[1], o[2], o[3]};
+    }
+  }
+}
 template <int DH, bool COH, bool STC>
 __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
@@ -734,48 +812,7 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
   const bool coop = row_end - row_begin <= 16 && nt_all > 8 && waves >= 3;
   float* Sbuf = coop ? (float*)(Vt + DH * ldv + 16 * ldv) : nullptr;
   if (coop) attn_coop_scores<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, nt_all, Sbuf, nkp);
-  {
-    // Values transposed into LDS.  Many keys: 8 keys x 8 channels per step and thread: eight 16-byte loads
-    // (one key row piece each), an 8 x 8 transpose of 16-bit values in registers (byte permutes),
-    // eight 16-byte LDS stores (one channel row piece each).  Keys past the last needed one: zeros.
-    constexpr int G = DH / 8;   // 16-byte pieces per key row
-    const bf16_t* vg = Vb + (size_t)sd.kv_row0 * d + h * DH;
-    // few keys: one 16-byte piece per thread and step, eight 2-byte LDS stores (more threads in
-    // flight, which is what counts there); many keys: the transposing path below
-    if (nkp <= 128)
-    for (int i = threadIdx.x; i < nkp * G; i += blockDim.x) {
-      const int g = i / nkp, t = i - g * nkp;
-      uint4 v = uint4{0u, 0u, 0u, 0u};
-      if (t < nk_all) v = ldg16<COH>(vg + (size_t)t * d + g * 8);
-      bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
-      dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
-      dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
-      dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
-      dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
-    }
-    const int n_items = nkp <= 128 ? 0 : (nkp >> 3) * G;
-    for (int it = threadIdx.x; it < n_items; it += blockDim.x) {
-      const int g = it % G, t0 = (it / G) << 3;
-      unsigned in[8][4];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        uint4 v = uint4{0u, 0u, 0u, 0u};
-        if (t0 + i < nk_all) v = ldg16<COH>(vg + (size_t)(t0 + i) * d + g * 8);
-        in[i][0] = v.x; in[i][1] = v.y; in[i][2] = v.z; in[i][3] = v.w;
-      }
-#pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        // channel c of keys t0 .. t0+7: the low (c even) or high (c odd) half of dword c/2 of every key
-        unsigned o[4];
-#pragma unroll
-        for (int pr = 0; pr < 4; ++pr) {
-          const unsigned lo = in[2 * pr][c >> 1], hi = in[2 * pr + 1][c >> 1];
-          o[pr] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-        }
-        *(uint4*)(Vt + (size_t)(g * 8 + c) * ldv + t0) = uint4{o[0], o[1], o[2], o[3]};
-      }
-    }
-  }
+  attn_stage_values<DH, COH>(Vb, sd, h, d, Vt, ldv, nkp, nk_all);
   __syncthreads();
   if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);

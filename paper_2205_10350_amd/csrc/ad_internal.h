@@ -154,6 +154,12 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
 // one attention problem per descriptor (n_seq of them, at most max_rows query rows each)
 void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
                       int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s);
+// Cross-attention of a decoder layer with its query projection (and the pending LayerNorm of the
+// rows, `ln`, or the rows `A` as they are) in one launch; false = shape not covered (nothing
+// launched: use launch_gemm + launch_attention).
+bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void* W, const float* bias, const void* K,
+                             const void* V, void* out, const SeqDesc* desc, int n_seq, int max_rows, int H, int dh,
+                             int max_keys, hipStream_t s);
 // y = LayerNorm(x) * g + b -> y (fp32) and ya (storage type)
 void launch_layernorm(int dtype, const float* x, const float* g, const float* b, int M, int d, float* y,
                       void* ya, hipStream_t s);

@@ -726,6 +726,188 @@ void launch_attention(int dtype, const void* q, const void* K, const void* V, vo
   else attention_dispatch<float>(q, K, V, out, desc, n_seq, max_rows, H, dh, max_keys, s);
 }
 
+// ------------------------------------------------- cross-attention with its query projection
+// One workgroup per (sequence, head, chunk of 16 or 64 query rows), head width 64, model width 512 or
+// 1024, bf16.  The workgroup stages its rows in LDS (through the pending LayerNorm of the
+// previous sublayer, the statistics and values of the LayerNorm kernel; the workgroups of head 0
+// also keep the fp32 rows), multiplies them by the head's 64 columns of the query matrix (wave w:
+// the 16-column strip 4 * head + w; k ascending, 32 at a time, one accumulator per element, bias
+// added and the sum rounded to bf16 as the GEMM kernels' epilogue does: the same bits as a
+// projection launch), leaves the queries in LDS and goes on with the attention of those rows as
+// k_attention does.  What the attention needs that does not depend on the queries (the first key
+// tiles, the values when they are few) is requested at the very start, next to the weights, so
+// the kernel waits for memory once.  One launch and one trip through memory less per decoder layer.
+// LDS: [values, transposed][probability tiles | row tile (until the queries are there)][queries].
+constexpr int kCrossqQld = 64 + 16;   // query tile row stride (elements): 32 bytes past a multiple of 64
+static size_t crossq_lds_bytes(int nk_cap, int mt, int d) {
+  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
+  return (64 * ldv + std::max((size_t)64 * ldv, (size_t)mt * 16 * (d + 16)) + 64 * (size_t)kCrossqQld) * 2;
+}
+template <int NV>
+__global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* __restrict__ A,
+                                                          const bf16_t* __restrict__ W, const float* __restrict__ bias,
+                                                          const bf16_t* __restrict__ Kb, const bf16_t* __restrict__ Vb,
+                                                          bf16_t* __restrict__ out, const SeqDesc* __restrict__ desc,
+                                                          float scale, int chunk_rows) {
+  constexpr int K = 256 * NV, KS = K / 32, DH = 64, ld = K + 16, QLD = kCrossqQld, G = DH / 8;
+  extern __shared__ uint4 cq_lds[];
+  const SeqDesc sd = desc[blockIdx.x];
+  const int row_begin = blockIdx.z * chunk_rows;
+  if (row_begin >= sd.nq) return;
+  const int row_end = min(sd.nq, row_begin + chunk_rows);
+  const int h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int mt = (row_end - row_begin + 15) >> 4;
+  const int m0 = sd.q_row0 + row_begin, m_end = sd.q_row0 + row_end;   // packed rows of the chunk
+  const int n0 = h * DH + wave * 16;
+  const int nk_all = sd.causal ? sd.nk_base + row_end : sd.nk_base;
+  const int nkp = (nk_all + 31) & ~31, ldv = nkp + 16;
+  bf16_t* Vt = (bf16_t*)cq_lds;          // [DH][ldv]
+  bf16_t* Pall = Vt + DH * ldv;          // [4 waves][16][ldv]
+  bf16_t* At = Pall;                     // [16 * mt][K + 16]
+  bf16_t* Qt = Pall + max(64 * ldv, mt * 16 * ld);   // [64][QLD]
+  // the wave's strip of the query matrix
+  uint4 b[KS];
+  {
+    const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
+#pragma unroll
+    for (int u = 0; u < KS; ++u) b[u] = *(const uint4*)(wp + u * 512);
+  }
+  const float bn = bias ? bias[n0 + r] : 0.f;
+  uint4 kf_pre[4][DH / 32];
+  attn_preload_k<DH, false>(Kb, sd, row_begin, row_end, h, K, nk_all, kf_pre);
+  // up to 128 keys: the values (piece i = 8 channels of one key; addresses clamped, never under a
+  // branch of their own) wait in registers until the row tile is staged
+  const bool v_small = nkp <= 128;
+  uint4 vreg[4];
+  if (v_small) {
+    const bf16_t* vg = Vb + (size_t)sd.kv_row0 * K + h * DH;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int i = min((int)threadIdx.x + 256 * it, nkp * G - 1);
+      const int g = i / nkp, t = min(i - g * nkp, nk_all - 1);
+      vreg[it] = *(const uint4*)(vg + (size_t)t * K + g * 8);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
+  auto project = [&](auto mt_c) {
+    constexpr int MT = decltype(mt_c)::value;
+    constexpr int per_wave = MT * 4;
+    if (ln.x) {
+      astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, h == 0);
+    } else {
+      uint4 av[per_wave][K / 512];
+#pragma unroll
+      for (int i = 0; i < per_wave; ++i)
+#pragma unroll
+        for (int j = 0; j < K / 512; ++j)
+          av[i][j] = *(const uint4*)(A + (size_t)min(m0 + wave * per_wave + i, m_end - 1) * K + j * 512 + lane * 8);
+#pragma unroll
+      for (int i = 0; i < per_wave; ++i)
+#pragma unroll
+        for (int j = 0; j < K / 512; ++j) *(uint4*)(At + (wave * per_wave + i) * ld + j * 512 + lane * 8) = av[i][j];
+    }
+    __syncthreads();
+    const bf16_t* a_lane = At + r * ld + kq * 8;
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < KS; ++u) {
+      uint4 af[MT];
+#pragma unroll
+      for (int t = 0; t < MT; ++t) af[t] = *(const uint4*)(a_lane + t * 16 * ld + 32 * u);
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, b[u]), acc[t], 0, 0, 0);
+    }
+    // this lane: rows 16 t + 4 kq + i of the chunk, column 16 wave + r of the head
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = acc[t][i];
+        if (bias) v += bn;
+        Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
+      }
+  };
+  if (mt == 1) project(std::integral_constant<int, 1>{});
+  else if (mt == 2) project(std::integral_constant<int, 2>{});
+  else if (mt == 3) project(std::integral_constant<int, 3>{});
+  else project(std::integral_constant<int, 4>{});
+  // values into LDS, transposed (keys nk_all .. nkp - 1 as zeros)
+  if (v_small) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int i = threadIdx.x + 256 * it;
+      if (i < nkp * G) {
+        const int g = i / nkp, t = i - g * nkp;
+        const uint4 v = t < nk_all ? vreg[it] : uint4{0u, 0u, 0u, 0u};
+        bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
+        dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
+        dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
+        dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
+        dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
+      }
+    }
+  } else {
+    attn_stage_values<DH, false>(Vb, sd, h, K, Vt, ldv, nkp, nk_all);
+  }
+  __syncthreads();   // queries and values are in LDS; the row tile is no longer needed
+  // the rest is attn_block_mfma with the query fragments read from the LDS tile
+  const int n_tiles = mt;
+  uint4 qf_pre[DH / 32];
+  {
+    const int row = min(min(wave, n_tiles - 1) * 16 + r, row_end - row_begin - 1);
+#pragma unroll
+    for (int s2 = 0; s2 < DH / 32; ++s2) qf_pre[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
+  }
+  const int nt_all = (nk_all + 15) >> 4;
+  const bool coop = row_end - row_begin <= 16 && nt_all > 8;
+  float* Sbuf = coop ? (float*)(Pall + 16 * ldv) : nullptr;
+  if (coop) {
+    attn_coop_scores_q<DH, false>(qf_pre, Kb, sd, h, K, nk_all, nt_all, Sbuf, nkp);
+    __syncthreads();
+  }
+  bf16_t* Pw = Pall + wave * 16 * ldv;
+  const bf16_t* qnone = nullptr;   // every wave has at most one tile: its fragments are qf_pre
+  if (nkp <= 64) attn_tiles_mfma<DH, 4, false, false>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8, false, false>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else attn_tiles_mfma<DH, 16, false, false>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+}
+bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void* W, const float* bias, const void* K,
+                             const void* V, void* out, const SeqDesc* desc, int n_seq, int max_rows, int H, int dh,
+                             int max_keys, hipStream_t s) {
+  const int d = H * dh;
+  if (dtype != AD_BF16 || dh != 64 || (d != 512 && d != 1024)) return false;
+  // query rows per workgroup: 16 while that keeps the launch within about one workgroup per compute
+  // unit (a row tile per workgroup: the shortest staging), else 64
+  // (measured, base model: batch 1, 25 / 64 rows: forward 237 / 243 us with 16, 247 / 271 us with 64, 247 / 260 us as
+  // two launches; batch 32 x 36 rows: 535 us with 16, 487 us with 64, 500 us as two launches)
+  const int chunk = n_seq * H * ((max_rows + 15) / 16) <= 256 ? 16 : 64;
+  const int mt = (std::min(max_rows, chunk) + 15) / 16;
+  const size_t sh = crossq_lds_bytes(max_keys, mt, d);
+  if (sh > 160 * 1024) return false;
+  if (n_seq <= 0 || max_rows <= 0) return true;
+  dim3 g(n_seq, H, (max_rows + chunk - 1) / chunk);
+  const float scale = 1.0f / sqrtf((float)dh);
+  auto go = [&](auto nv_c) {
+    constexpr int NV = decltype(nv_c)::value;
+    static size_t set_for = 0;
+    if (sh > set_for) {
+      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+      set_for = sh;
+    }
+    k_crossq_attention<NV><<<g, 256, sh, s>>>(ln, (const bf16_t*)A, (const bf16_t*)W, bias, (const bf16_t*)K,
+                                              (const bf16_t*)V, (bf16_t*)out, desc, scale, chunk);
+  };
+  if (d == 512) go(std::integral_constant<int, 2>{});
+  else go(std::integral_constant<int, 4>{});
+  return true;
+}
+
 // ------------------------------------------------------------------------------------- LayerNorm
 // One wave per row; mean, then biased variance of the centred values, eps = 1e-5.
 template <typename T, int NV>

@@ -610,6 +610,48 @@ def test_graph_replays_equal_eager_launches(name, B):
         rig.close()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,B", [("base", 1), ("base", 3), ("big", 2)])
+def test_fused_cross_attention_launch_equals_projection_plus_attention(name, B):
+    """AD_OPT_FUSE_CROSSQ: the decoder layers' cross-attention as one launch (query projection inside)
+    against the two launches it replaces: logits, arg max, accepted lengths, outputs and the block
+    drafter's tokens bit for bit, on ragged blocks of more than 16 and more than 32 rows."""
+    rig = Rig(name, "bf16", 91, B=B, max_src=48, max_len=48, k_max=40, drafter=True)
+    try:
+        assert rig.ctx.get_option(ad.AD_OPT_FUSE_CROSSQ) == 1
+        V = rig.dims["vocab"]
+        srcs = _sources(rig.dims, 91, [41 - 9 * b for b in range(B)])
+        out_ref, _ = rig.ctx.decode_greedy(srcs)
+        d1 = [out_ref[b][:17 + 9 * b] for b in range(B)]                       # all accepted; 18 / 27 / 36 rows
+        d2 = [[(out_ref[b][len(d1[b])] - 5 + 1) % (V - 5) + 5] + out_ref[b][len(d1[b]) + 1:len(d1[b]) + 6]
+              for b in range(B)]                                               # wrong first token
+        res = {}
+        for mode in (0, 1):
+            rig.ctx.set_option(ad.AD_OPT_FUSE_CROSSQ, mode)
+            assert rig.ctx.get_option(ad.AD_OPT_FUSE_CROSSQ) == mode
+            rig.ctx.encode(ad.AD_VERIFIER, srcs); rig.ctx.encode(ad.AD_DRAFTER, srcs)
+            a = rig.ctx.verify(d1, want_verified=True)
+            la = rig.ctx.debug_logits().view(np.uint32).copy()
+            dr = rig.ctx.draft_nat(7).copy()
+            b_ = rig.ctx.verify(d2, want_verified=True)
+            lb = rig.ctx.debug_logits().view(np.uint32).copy()
+            res[mode] = (a, la, b_, lb, dr, rig.ctx.output())
+        (a0, la0, b0, lb0, dr0, o0), (a1, la1, b1, lb1, dr1, o1) = res[0], res[1]
+        for x, y in zip(a0 + b0, a1 + b1):
+            assert np.array_equal(x, y)
+        assert np.array_equal(la0, la1) and np.array_equal(lb0, lb1) and np.array_equal(dr0, dr1)
+        assert o0 == o1
+        assert a1[0].tolist() == [len(d) for d in d1] and b1[0].tolist() == [1] * B
+        # whole decodes (graph replays included) with either setting
+        guides = [edit_guide(g, 0.1, 3 + b, V) for b, g in enumerate(out_ref)]
+        for mode in (0, 1, 0, 1):
+            rig.ctx.set_option(ad.AD_OPT_FUSE_CROSSQ, mode)
+            oi, _ = rig.ctx.decode_iad(srcs, guides)
+            assert oi == out_ref
+    finally:
+        rig.close()
+
+
 def test_waiting_on_the_mapped_result_equals_waiting_on_the_stream():
     """AD_OPT_SPIN_WAIT only changes how the host learns that a verify call has finished: tokens,
     accepted lengths and iteration structure are the same either way, also right after other
