@@ -611,18 +611,21 @@ def test_graph_replays_equal_eager_launches(name, B):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("name,B", [("base", 1), ("base", 3), ("big", 2)])
+@pytest.mark.parametrize("name,B", [("base", 1), ("base", 3), ("big", 2), ("base", 8)])
 def test_fused_cross_attention_launch_equals_projection_plus_attention(name, B):
     """AD_OPT_FUSE_CROSSQ: the decoder layers' cross-attention as one launch (query projection inside)
     against the two launches it replaces: logits, arg max, accepted lengths, outputs and the block
     drafter's tokens bit for bit, on ragged blocks of more than 16 and more than 32 rows."""
-    rig = Rig(name, "bf16", 91, B=B, max_src=48, max_len=48, k_max=40, drafter=True)
+    rig = Rig(name, "bf16", 91, B=B, max_src=48, max_len=80, k_max=72, drafter=True)
     try:
         assert rig.ctx.get_option(ad.AD_OPT_FUSE_CROSSQ) == 1
         V = rig.dims["vocab"]
-        srcs = _sources(rig.dims, 91, [41 - 9 * b for b in range(B)])
+        srcs = _sources(rig.dims, 91, [41 - 4 * b for b in range(B)])
         out_ref, _ = rig.ctx.decode_greedy(srcs)
-        d1 = [out_ref[b][:17 + 9 * b] for b in range(B)]                       # all accepted; 18 / 27 / 36 rows
+        # all accepted; 18 / 27 / 36 rows, and with eight sequences blocks of 1 .. 71 rows (chunks of 64 query
+        # rows per workgroup instead of 16: the launch would exceed a workgroup per compute unit)
+        lens = [17 + 9 * b for b in range(B)] if B < 8 else [70, 3, 64, 17, 33, 1, 48, 65]
+        d1 = [out_ref[b][:min(lens[b], len(out_ref[b]) - 7)] for b in range(B)]
         d2 = [[(out_ref[b][len(d1[b])] - 5 + 1) % (V - 5) + 5] + out_ref[b][len(d1[b]) + 1:len(d1[b]) + 6]
               for b in range(B)]                                               # wrong first token
         res = {}
