@@ -1229,7 +1229,7 @@ int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int iters, void
   hipEvent_t e0 = nullptr, e1 = nullptr;
   float ms = 0;
   bool ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess &&
-            launch_calibration_mfma((float*)scratch_dev, wgs, 16, s) == hipSuccess && hipEventRecord(e0, s) == hipSuccess &&
+            launch_calibration_mfma((float*)scratch_dev, wgs, iters, s) == hipSuccess && hipEventRecord(e0, s) == hipSuccess &&
             launch_calibration_mfma((float*)scratch_dev, wgs, iters, s) == hipSuccess && hipEventRecord(e1, s) == hipSuccess &&
             hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
   if (e0) (void)hipEventDestroy(e0);
