@@ -33,6 +33,23 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, name), name
 
 
+def test_binding_constants_equal_the_header_enums():
+    """Every enumerator of include/ad.h that the binding names has the header's value, and the
+    binding names all of them."""
+    header = open(os.path.join(ROOT, "include", "ad.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    enums = {}
+    for body in re.findall(r"enum\s*\{(.*?)\}", header, flags=re.S):
+        for name, value in re.findall(r"(AD_[A-Z_0-9]+)\s*=\s*(-?\d+)", body):
+            enums[name] = int(value)
+    assert len(enums) >= 14 and "AD_OPT_FUSE_CROSSQ" in enums
+    import paper_2205_10350_amd.binding as B
+    for name, value in enums.items():
+        assert getattr(B, name) == value, name
+        assert getattr(ad, name) == value, name
+    assert ad.AD_NEVER == int(re.search(r"#define\s+AD_NEVER\s+\((-?\d+)\)", header).group(1))
+
+
 def test_config_check_rejects_bad_dimensions():
     assert ad.config_check(cfg_for()) == ad.AD_OK
     for bad in (dict(d_model=100), dict(d_ffn=100), dict(vocab=2001), dict(n_heads=3), dict(n_heads=16)):
