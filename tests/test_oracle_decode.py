@@ -2,6 +2,7 @@
 invariant by brute force, closed-form iteration structure, suffix matching.  CPU only."""
 import itertools
 import math
+import os
 
 import numpy as np
 import pytest
@@ -329,3 +330,68 @@ def test_gadpp_accepts_a_superset_and_bifurcates_at_the_first_failure():
     assert c == (met.index(False) + 1 if False in met else 6)
     o_hat1, c1 = O.verify(O.DecoderState(ver, ver.encode(src)), BOS, draft)
     assert c >= c1
+
+
+# ----------------------------------------------------------------------------------------------
+# Algorithm 1 against the decoding examples the paper prints (tests/golden/iad_case_study.txt).
+
+def _case_study():
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "iad_case_study.txt")
+    lines = [ln.split(":", 1)[1].split() for ln in open(path) if not ln.startswith("#") and ln.strip()]
+    return [([int(t) for t in lines[i]], [int(t) for t in lines[i + 1]], lines[i + 2]) for i in range(0, len(lines), 3)]
+
+
+class _KnowsTheOutput:
+    """Stand-in for the incremental decoder: fed a prefix that agrees with the known greedy
+    output it scores that output's next token highest, after a disagreement a token of its own."""
+    g, vocab, fed_rows = None, 0, None
+
+    def __init__(self, model, memory):
+        self.tokens, self.length = [], 0
+
+    def forward(self, tokens):
+        type(self).fed_rows.append(len(tokens))
+        self.tokens = self.tokens[:self.length] + [int(t) for t in tokens]
+        lg = np.zeros((len(tokens), self.vocab))
+        for i in range(len(tokens)):
+            n = self.length + i + 1                       # row i has seen o_0 .. o_{n-1}
+            ok = self.tokens[1:n] == self.g[:n - 1] and n - 1 < len(self.g)
+            lg[i, self.g[n - 1] if ok else self.vocab - 1] = 1.0
+        return lg
+
+    def keep(self, new_length):
+        self.length = new_length
+
+
+class _NoModel:
+    def encode(self, src):
+        return np.zeros((1, 1))
+
+
+@pytest.mark.parametrize("case", range(7))
+def test_algorithm_1_reproduces_the_papers_decoding_examples(case, monkeypatch):
+    """Section 4.1.2's table shows, for seven input / output pairs, which output words one
+    iteration accepted from a draft and which came from single autoregressive steps.  With the
+    output as the model's greedy continuation, the oracle's Algorithm 1 (suffix match included) and
+    the library's own loop must cut the output into exactly those iterations."""
+    x, o, blocks = _case_study()[case]
+    g = o + [EOS]
+    _KnowsTheOutput.g, _KnowsTheOutput.vocab, _KnowsTheOutput.fed_rows = g, max(x + o) + 2, []
+    monkeypatch.setattr(O, "DecoderState", _KnowsTheOutput)
+    out, st = O.iad(_NoModel(), [], x, len(g) + 4, EOS, BOS)
+    assert out == g
+    acc, rows = list(st.accepted), list(_KnowsTheOutput.fed_rows)
+    # the table does not show the end-of-sequence token: it rides on the last block or is a step of its own
+    if acc[-1] == 1:
+        acc, rows = acc[:-1], rows[:-1]
+    else:
+        acc[-1] -= 1
+    want = [int(b[1:]) for b in blocks]
+    assert acc == want
+    # an iteration with a draft from the input feeds several rows, an autoregressive step one
+    assert ["A" if r > 1 else "R" for r in rows] == [b[0] for b in blocks]
+    # the library's loop over the same stand-in
+    import paper_2205_10350_amd as ad
+    out_l, acc_l, _ = ad.host_simulate(0, np.array(g, dtype=np.int32), np.array(x, dtype=np.int32), k_max=64,
+                                       max_out=len(g) + 4, eos=EOS, bos=BOS)
+    assert out_l == g and acc_l == list(st.accepted)
