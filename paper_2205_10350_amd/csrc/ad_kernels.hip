@@ -727,7 +727,7 @@ void launch_attention(int dtype, const void* q, const void* K, const void* V, vo
 }
 
 // ------------------------------------------------- cross-attention with its query projection
-// One workgroup per (sequence, head, chunk of 16 or 64 query rows), head width 64, model width 512 or
+// One workgroup per (sequence, head, chunk of 16, 32 or 64 query rows), head width 64, model width 512 or
 // 1024, bf16.  The workgroup stages its rows in LDS (through the pending LayerNorm of the
 // previous sublayer, the statistics and values of the LayerNorm kernel; the workgroups of head 0
 // also keep the fp32 rows), multiplies them by the head's 64 columns of the query matrix (wave w:
@@ -883,10 +883,11 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   const int d = H * dh;
   if (dtype != AD_BF16 || dh != 64 || (d != 512 && d != 1024)) return false;
   // query rows per workgroup: 16 while that keeps the launch within about one workgroup per compute
-  // unit (a row tile per workgroup: the shortest staging), else 64
-  // (measured, base model: batch 1, 25 / 64 rows: forward 237 / 243 us with 16, 247 / 271 us with 64, 247 / 260 us as
-  // two launches; batch 32 x 36 rows: 535 us with 16, 487 us with 64, 500 us as two launches)
-  const int chunk = n_seq * H * ((max_rows + 15) / 16) <= 256 ? 16 : 64;
+  // unit (a row tile per workgroup: the shortest staging), else 32 under the same condition, else 64
+  // (measured forward times, base model, 16 / 32 / 64 rows per workgroup; batch x rows:
+  //  1 x 25: 237 / 248 / 247 us, 1 x 64: 243 / 254 / 271, 8 x 36: 288 / 298 / 306, 12 x 36: 354 / 332 / 342,
+  //  16 x 36: 434 / 409 / 418, 24 x 36: 477 / 455 / 431, 32 x 36: 535 / 514 / 487)
+  const int chunk = n_seq * H * ((max_rows + 15) / 16) <= 256 ? 16 : (n_seq * H * ((max_rows + 31) / 32) <= 256 ? 32 : 64);
   const int mt = (std::min(max_rows, chunk) + 15) / 16;
   const size_t sh = crossq_lds_bytes(max_keys, mt, d);
   if (sh > 160 * 1024) return false;

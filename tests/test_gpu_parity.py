@@ -622,7 +622,7 @@ def test_fused_cross_attention_launch_equals_projection_plus_attention(name, B):
         V = rig.dims["vocab"]
         srcs = _sources(rig.dims, 91, [41 - 4 * b for b in range(B)])
         out_ref, _ = rig.ctx.decode_greedy(srcs)
-        # all accepted; 18 / 27 / 36 rows, and with eight sequences blocks of 1 .. 71 rows (chunks of 64 query
+        # all accepted; 18 / 27 / 36 rows, and with eight sequences blocks of 1 .. 71 rows (chunks of 32 query
         # rows per workgroup instead of 16: the launch would exceed a workgroup per compute unit)
         lens = [17 + 9 * b for b in range(B)] if B < 8 else [70, 3, 64, 17, 33, 1, 48, 65]
         d1 = [out_ref[b][:min(lens[b], len(out_ref[b]) - 7)] for b in range(B)]
