@@ -650,7 +650,29 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
               while (per_wg < n_strips && (n_strips + per_wg - 1) / per_wg * chunks > 256) per_wg += 4;
             }
           }
-          return launch_astat<1, 1>(a, w, M, N, K, e, per_wg, s, ln);
+          // Nine or more strip groups are dealt round the eight XCDs (group g on XCD g % 8): a count that is
+          // no multiple of eight leaves some XCDs with one group more than the others, so strips per
+          // workgroup grow until the groups divide evenly (measured at 576..756 rows: forward 3-6 % shorter)
+          // (layer GEMMs only: the output projection has hundreds of groups, where one more or less per XCD
+          // does not matter, and its own measured rule above)
+          auto balanced = [&](int pw) {
+            if (e.mode == EPI_ARGMAX || e.mode == EPI_COUNT) return pw;
+            auto groups_of = [&](int x) { return (n_strips + x - 1) / x; };
+            while (groups_of(pw) > 8 && groups_of(pw) % 8 != 0) pw += 4;
+            return pw;
+          };
+          // 520 rows and more (layer GEMMs only): 32 rows per workgroup, so that the weights cross from L2 to
+          // the CUs half as often (every 16-row chunk reads the whole matrix: at 576 rows x N 1536 that is
+          // 55 MB per launch, more than the launch takes to do anything else); below that the shorter staging
+          // of a 16-row tile wins (measured: 504 rows 347 / 362 us forward with 16 / 32 rows, 576 rows 387 / 374,
+          // 648 rows 408 / 399, 756 rows 416 / 416)
+          if (M >= 520 && e.mode != EPI_ARGMAX && e.mode != EPI_COUNT && astat_lds_bytes(2, K) <= 150 * 1024) {
+            const int chunks2 = (M + 31) / 32;
+            int pw2 = 4 * std::max(1, (n_strips * chunks2 + 4 * 512 - 1) / (4 * 512));
+            if (K > 512 && astat_lds_bytes(2, K) * 2 <= 160 * 1024) pw2 = std::min(pw2, 16);
+            return launch_astat<2, 1>(a, w, M, N, K, e, balanced(pw2), s, ln);
+          }
+          return launch_astat<1, 1>(a, w, M, N, K, e, balanced(per_wg), s, ln);
         }
       } else {
         // rows per workgroup (16, 32 or 64, as far as the A tile fits in LDS) and strips per

@@ -215,6 +215,34 @@ def test_rows_do_not_depend_on_block_or_batch_shape():
         rig.close()
 
 
+@pytest.mark.gpu
+def test_rows_do_not_depend_on_the_row_regime_of_the_gemm_kernels():
+    """Base model, bit-exact: the logits of one sequence's 36-row block verified alone (16 rows per
+    workgroup), among 9 / 16 / 20 sequences (324 / 576 / 720 packed rows: 16-row chunks with more
+    strips per workgroup, 32 rows per workgroup) and among 30 (1080 rows: the many-row variants)."""
+    B = 30
+    rig = Rig("base", "bf16", 83, B=B, max_src=40, max_len=48, k_max=40)
+    try:
+        V = rig.dims["vocab"]
+        rng = np.random.default_rng(83)
+        srcs = _sources(rig.dims, 83, [12 + (7 * b) % 25 for b in range(B)])
+        blocks = [[int(t) for t in rng.integers(5, V, size=36)] for _ in range(B)]
+        rig.ctx.encode(ad.AD_VERIFIER, srcs[:1])
+        rig.ctx.verify(blocks[:1])
+        alone = rig.ctx.debug_logits().view(np.uint32).copy()
+        assert alone.shape[0] == 36
+        for n in (9, 16, 20, 30):
+            # sequence 0 sits in the middle of the batch
+            order = list(range(1, n // 2 + 1)) + [0] + list(range(n // 2 + 1, n))
+            rig.ctx.encode(ad.AD_VERIFIER, [srcs[i] for i in order])
+            rig.ctx.verify([blocks[i] for i in order])
+            lg = rig.ctx.debug_logits().view(np.uint32)
+            at = 36 * (n // 2)
+            assert np.array_equal(lg[at:at + 36], alone), n
+    finally:
+        rig.close()
+
+
 def test_ragged_batch_rollback_and_inactive_sequences():
     rig = Rig("tiny", "fp32", 9, B=4, k_max=12)
     try:
