@@ -626,13 +626,15 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
     const int tiles_x = (N / 16 + 7) / 8, tiles_y = (M + 127) / 128;
     if (K <= 4096 && K % 512 == 0) {
       const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
-      // Few rows (measured: up to 64 for the wide output projection, up to 768 for the layer
-      // GEMMs): latency decides, so 16 rows per workgroup, one strip per wave, workgroups of four
-      // strips until the chip is covered (at most about 512 workgroups for the layer GEMMs); more
-      // rows are more row chunks of the same shape.
+      // Few rows (measured: up to 64 for the wide output projection, up to 1024 for the layer
+      // GEMMs: forward at 792..1008 rows 420-438 us this way, 431-449 us by the cost model below; from
+      // 1080 rows the other way round, 520 against 489 us): latency decides, so 16 rows per workgroup
+      // (32 from 520 rows, see below), one strip per wave, workgroups of four strips until the chip is
+      // covered (at most about 512 workgroups for the layer GEMMs); more rows are more row chunks of
+      // the same shape.
       const int mt = 1;
       const bool want_logits = e.mode == EPI_ARGMAX && e.logits != nullptr;
-      if ((M <= 64 || (M <= 768 && N <= 4096) || want_logits) && astat_lds_bytes(mt, K) <= 150 * 1024) {
+      if ((M <= 64 || (M <= 1024 && N <= 4096) || want_logits) && astat_lds_bytes(mt, K) <= 150 * 1024) {
         {
           const int n_strips = N / 16, chunks = (M + 15) / 16;
           int per_wg = 4 * std::max(1, (n_strips + 4 * 384 - 1) / (4 * 384));

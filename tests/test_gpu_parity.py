@@ -218,7 +218,7 @@ def test_rows_do_not_depend_on_block_or_batch_shape():
 @pytest.mark.gpu
 def test_rows_do_not_depend_on_the_row_regime_of_the_gemm_kernels():
     """Base model, bit-exact: the logits of one sequence's 36-row block verified alone (16 rows per
-    workgroup), among 9 / 16 / 20 sequences (324 / 576 / 720 packed rows: 16-row chunks with more
+    workgroup), among 9 / 16 / 20 / 26 sequences (324 / 576 / 720 / 936 packed rows: 16-row chunks with more
     strips per workgroup, 32 rows per workgroup) and among 30 (1080 rows: the many-row variants)."""
     B = 30
     rig = Rig("base", "bf16", 83, B=B, max_src=40, max_len=48, k_max=40)
@@ -231,7 +231,7 @@ def test_rows_do_not_depend_on_the_row_regime_of_the_gemm_kernels():
         rig.ctx.verify(blocks[:1])
         alone = rig.ctx.debug_logits().view(np.uint32).copy()
         assert alone.shape[0] == 36
-        for n in (9, 16, 20, 30):
+        for n in (9, 16, 20, 26, 30):
             # sequence 0 sits in the middle of the batch
             order = list(range(1, n // 2 + 1)) + [0] + list(range(n // 2 + 1, n))
             rig.ctx.encode(ad.AD_VERIFIER, [srcs[i] for i in order])
