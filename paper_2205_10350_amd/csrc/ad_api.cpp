@@ -1003,8 +1003,10 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
                        c->ws + p.mem_v[1] + l * p.mem_layer_stride);
       ffn_block(c, L.ffn, L.ln3, rows);
     }
-    flush_ln(c, Mv);
-    const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), Mv);
+    // the last LayerNorm goes into the output projection's staging, as in the verify forward
+    const LnW* ln_last = c->ln_pending;
+    c->ln_pending = nullptr;
+    const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), Mv, ln_last);
     if (watch) {
       // the drafted tokens go straight to the host: (ticket, token) per 8-byte slot of the mapped buffer
       launch_argmax_draft(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, n_part, c->at<int>(p.o_hat),
