@@ -984,10 +984,12 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   // prefix rows as queries).  In the last layer only the mask rows go on after the key/value
   // projection: nothing reads the prefix rows' outputs.
   auto launches = [&]() {
-    launch_assemble_drafter(c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
-                            c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, c->stream);
     const ModelW& w = c->w[AD_DRAFTER];
-    embed_rows(c, w, M);
+    c->ln_pending = nullptr;
+    launch_assemble_embed_drafter(cf.dtype, c->at<int>(p.out), cf.max_len, c->at<int>(p.len), c->at<int>(p.finished),
+                                  c->at<int>(p.src_len[1]), B, k, cf.bos, cf.mask, cf.max_src, t, M, w.emb,
+                                  c->at<float>(p.pe), cf.d_model, sqrtf((float)cf.d_model), c->at<float>(p.x),
+                                  c->at<void>(p.xa), c->stream);
     int rows = M;
     c->fw_nseq = 2 * live;
     c->fw_max_rows = max_rows;

@@ -1329,6 +1329,109 @@ void launch_assemble_drafter(const int* out, int max_len, const int* len, const 
                              int B, int k, int bos, int mask, int s_max, VerifyTables t, hipStream_t s) {
   k_assemble_drafter<<<1, 256, 0, s>>>(out, max_len, len, finished, src_len, B, k, bos, mask, s_max, t);
 }
+// The same tables and the embedding of the M packed rows in one launch: workgroup 0 is
+// k_assemble_drafter, workgroup r + 1 finds row r's (token, position) itself from the decode state
+// (the packed order above: mask rows of the unfinished sequences first, then their prefixes) and
+// writes x[r] = E[token] * sqrt(d) + PE[position] as k_embed does.
+template <typename T>
+__global__ __launch_bounds__(256) void k_assemble_embed_drafter(const int* __restrict__ out, int max_len,
+                                                                const int* __restrict__ len,
+                                                                const int* __restrict__ finished,
+                                                                const int* __restrict__ src_len, int B, int k, int bos,
+                                                                int mask, int s_max, VerifyTables t,
+                                                                const T* __restrict__ emb, const float* __restrict__ pe,
+                                                                int d, float sqrt_d, float* __restrict__ x,
+                                                                T* __restrict__ xa) {
+  if (blockIdx.x == 0) {
+    __shared__ int s_live;
+    if (threadIdx.x == 0) {
+      int live = 0;
+      for (int b = 0; b < B; ++b) live += finished[b] ? 0 : 1;
+      int l = 0, kslot = 0, pre = live * k;
+      for (int b = 0; b < B; ++b) {
+        t.row_start[b] = kslot;
+        if (finished[b]) continue;
+        const int L = len[b];
+        SeqDesc sd;
+        sd.q_row0 = l * k; sd.nq = k; sd.kv_row0 = kslot; sd.nk_base = L + 1 + k; sd.causal = 0;
+        sd.pad0 = b; sd.pad1 = pre; sd.pad2 = 0;
+        t.self_desc[l] = sd;
+        sd.q_row0 = pre; sd.nq = L + 1;
+        t.self_desc[live + l] = sd;
+        sd.kv_row0 = b * s_max; sd.nk_base = src_len[b];
+        t.cross_desc[live + l] = sd;
+        sd.q_row0 = l * k; sd.nq = k;
+        t.cross_desc[l] = sd;
+        kslot += L + 1 + k; pre += L + 1; ++l;
+      }
+      t.row_start[B] = kslot;
+      s_live = live;
+    }
+    __syncthreads();
+    const int live = s_live;
+    for (int l = 0; l < live; ++l) {
+      const SeqDesc m = t.self_desc[l];
+      const int b = m.pad0, pre = m.pad1, L = m.nk_base - 1 - k, kslot = m.kv_row0;
+      for (int i = threadIdx.x; i < L + 1 + k; i += blockDim.x) {
+        const int row = i <= L ? pre + i : l * k + (i - L - 1);
+        t.row_tok[row] = i == 0 ? bos : (i <= L ? out[b * max_len + i - 1] : mask);
+        t.row_pos[row] = i;
+        t.row_seq[row] = b;
+        t.row_dst[row] = kslot + i;
+      }
+    }
+    return;
+  }
+  const int r = blockIdx.x - 1;
+  __shared__ int s_tok, s_pos;
+  if (threadIdx.x == 0) {
+    int live = 0;
+    for (int b = 0; b < B; ++b) live += finished[b] ? 0 : 1;
+    int tok = mask, pos = 0;
+    if (r < live * k) {
+      // mask row j of the l-th unfinished sequence: position L + 1 + j
+      const int l = r / k, j = r - l * k;
+      int seen = 0;
+      for (int b = 0; b < B; ++b) {
+        if (finished[b]) continue;
+        if (seen == l) { pos = len[b] + 1 + j; break; }
+        ++seen;
+      }
+    } else {
+      int pre = live * k;
+      for (int b = 0; b < B; ++b) {
+        if (finished[b]) continue;
+        const int L = len[b];
+        if (r < pre + L + 1) {
+          pos = r - pre;
+          tok = pos == 0 ? bos : out[b * max_len + pos - 1];
+          break;
+        }
+        pre += L + 1;
+      }
+    }
+    s_tok = tok; s_pos = pos;
+  }
+  __syncthreads();
+  const T* e = emb + (size_t)s_tok * d;
+  const float* pp = pe + (size_t)s_pos * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const float v = embed_value(Store<T>::load(e + c), sqrt_d, pp[c]);
+    x[(size_t)r * d + c] = v;
+    Store<T>::store(xa + (size_t)r * d + c, v);
+  }
+}
+void launch_assemble_embed_drafter(int dtype, const int* out, int max_len, const int* len, const int* finished,
+                                   const int* src_len, int B, int k, int bos, int mask, int s_max, VerifyTables t,
+                                   int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,
+                                   hipStream_t s) {
+  if (dtype == AD_BF16)
+    k_assemble_embed_drafter<bf16_t><<<M + 1, 256, 0, s>>>(out, max_len, len, finished, src_len, B, k, bos, mask, s_max, t,
+                                                           (const bf16_t*)emb, pe, d, sqrt_d, x, (bf16_t*)xa);
+  else
+    k_assemble_embed_drafter<float><<<M + 1, 256, 0, s>>>(out, max_len, len, finished, src_len, B, k, bos, mask, s_max, t,
+                                                          (const float*)emb, pe, d, sqrt_d, x, (float*)xa);
+}
 
 // Drafted tokens of the unfinished sequences, back in [B, k_max] order (AD_NEVER elsewhere).
 __global__ void k_draft_scatter(const int* __restrict__ o_hat, const int* __restrict__ finished, int B, int k,
