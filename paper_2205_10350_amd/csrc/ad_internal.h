@@ -217,9 +217,7 @@ void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const
 // Drafter rows: the k mask rows of every unfinished sequence first (l-th unfinished sequence at
 // [l*k, l*k + k)), then the prefix rows; descriptors [0, live) = mask rows as queries,
 // [live, 2 live) = prefix rows (self_desc and cross_desc hold 2 B entries).
-void launch_assemble_drafter(const int* out, int max_len, const int* len, const int* finished, const int* src_len,
-                             int B, int k, int bos, int mask, int s_max, VerifyTables t, hipStream_t s);
-// The same with the embedding of the M packed rows in the same launch (x, xa as launch_embed writes them).
+// (with the embedding of the M packed rows in the same launch: x, xa as launch_embed writes them)
 void launch_assemble_embed_drafter(int dtype, const int* out, int max_len, const int* len, const int* finished,
                                    const int* src_len, int B, int k, int bos, int mask, int s_max, VerifyTables t,
                                    int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,

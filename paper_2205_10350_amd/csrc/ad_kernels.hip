@@ -1279,60 +1279,14 @@ void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const
 
 // Drafter: rows = (o_0..o_j, [MASK] x k) at positions 0..j+k for every unfinished sequence
 // (Section 3.2, draft paragraph), bidirectional self-attention over the sequence's own rows.
-__global__ void k_assemble_drafter(const int* __restrict__ out, int max_len, const int* __restrict__ len,
-                                   const int* __restrict__ finished, const int* __restrict__ src_len, int B, int k,
-                                   int bos, int mask, int s_max, VerifyTables t) {
-  // Packed row order: the k mask rows of every unfinished sequence first (sequence l's at
-  // [l*k, l*k + k)), then the prefix rows, so that whatever only the mask rows need (everything
-  // after the last layer's key/value projection, the output projection) works on the first live*k
-  // rows.  A sequence's keys and values stay contiguous (prefix, then masks) through row_dst.
-  // Descriptors: entries [0, live) = mask rows as queries, [live, 2 live) = prefix rows.
-  __shared__ int s_live;
-  if (threadIdx.x == 0) {
-    int live = 0;
-    for (int b = 0; b < B; ++b) live += finished[b] ? 0 : 1;
-    int l = 0, kslot = 0, pre = live * k;
-    for (int b = 0; b < B; ++b) {
-      t.row_start[b] = kslot;
-      if (finished[b]) continue;
-      const int L = len[b];
-      SeqDesc s;
-      s.q_row0 = l * k; s.nq = k; s.kv_row0 = kslot; s.nk_base = L + 1 + k; s.causal = 0;
-      s.pad0 = b; s.pad1 = pre; s.pad2 = 0;     // pad0/pad1: the sequence and its first prefix row (used below)
-      t.self_desc[l] = s;
-      s.q_row0 = pre; s.nq = L + 1;
-      t.self_desc[live + l] = s;
-      s.kv_row0 = b * s_max; s.nk_base = src_len[b];
-      t.cross_desc[live + l] = s;
-      s.q_row0 = l * k; s.nq = k;
-      t.cross_desc[l] = s;
-      kslot += L + 1 + k; pre += L + 1; ++l;
-    }
-    t.row_start[B] = kslot;
-    s_live = live;
-  }
-  __syncthreads();
-  const int live = s_live;
-  for (int l = 0; l < live; ++l) {
-    const SeqDesc m = t.self_desc[l];
-    const int b = m.pad0, pre = m.pad1, L = m.nk_base - 1 - k, kslot = m.kv_row0;
-    for (int i = threadIdx.x; i < L + 1 + k; i += blockDim.x) {
-      const int row = i <= L ? pre + i : l * k + (i - L - 1);
-      t.row_tok[row] = i == 0 ? bos : (i <= L ? out[b * max_len + i - 1] : mask);
-      t.row_pos[row] = i;
-      t.row_seq[row] = b;
-      t.row_dst[row] = kslot + i;
-    }
-  }
-}
-void launch_assemble_drafter(const int* out, int max_len, const int* len, const int* finished, const int* src_len,
-                             int B, int k, int bos, int mask, int s_max, VerifyTables t, hipStream_t s) {
-  k_assemble_drafter<<<1, 256, 0, s>>>(out, max_len, len, finished, src_len, B, k, bos, mask, s_max, t);
-}
-// The same tables and the embedding of the M packed rows in one launch: workgroup 0 is
-// k_assemble_drafter, workgroup r + 1 finds row r's (token, position) itself from the decode state
-// (the packed order above: mask rows of the unfinished sequences first, then their prefixes) and
-// writes x[r] = E[token] * sqrt(d) + PE[position] as k_embed does.
+// Packed row order: the k mask rows of every unfinished sequence first (sequence l's at
+// [l*k, l*k + k)), then the prefix rows, so that whatever only the mask rows need (everything
+// after the last layer's key/value projection, the output projection) works on the first live*k
+// rows.  A sequence's keys and values stay contiguous (prefix, then masks) through row_dst.
+// Descriptors: entries [0, live) = mask rows as queries, [live, 2 live) = prefix rows.
+// One launch: workgroup 0 writes the tables and descriptors; workgroup r + 1 finds row r's (token,
+// position) itself from the decode state (no workgroup waits for another) and writes
+// x[r] = E[token] * sqrt(d) + PE[position] as k_embed does.
 template <typename T>
 __global__ __launch_bounds__(256) void k_assemble_embed_drafter(const int* __restrict__ out, int max_len,
                                                                 const int* __restrict__ len,
