@@ -846,13 +846,13 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
         *ticket_in = c->ticket;
         for (int b = 0; b < B; ++b) ticket_out[b] = 0;   // whatever an earlier call left in these words
       }
-      auto accept = [&](const float* pv, const int* pi, int stride, int n_part) {
+      auto accept = [&](const float* pv, const int* pi, int stride, int n_part, const GadppIn& gp = GadppIn{}) {
         launch_argmax_accept(pv, pi, stride, n_part, c->at<int>(p.o_hat), c->at<float>(p.o_val), k_src, draft_src, km,
                              t.row_start, B, cf.eos, cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len),
                              c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst,
                              watch ? c->pin_dev + (ticket_in - c->pin) : nullptr,
                              watch ? (unsigned long long*)(c->pin_dev + ((int32_t*)ticket_out - c->pin)) : nullptr,
-                             c->fw_max_rows, M, c->stream);
+                             c->fw_max_rows, M, c->stream, gp);
       };
       auto launches = [&]() {
         launch_assemble_embed_verify(cf.dtype, k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
@@ -874,9 +874,12 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
         Epi e{};
         e.mode = EPI_COUNT; e.part_idx = c->at<int>(p.part_idx); e.n_strips = p.n_strips; e.thr = c->at<float>(p.draft_lp);
         const int n_cnt = launch_gemm(cf.dtype, c->at<void>(p.xa), w.out_w, M, cf.vocab, cf.d_model, e, c->stream);
-        launch_gadpp_apply(c->at<int>(p.part_idx), p.n_strips, n_cnt, c->at<float>(p.draft_lp), c->at<int>(p.draft_col),
-                           c->at<float>(p.o_val), c->at<int>(p.o_hat), M, c->gadpp_beta, c->gadpp_tau, c->stream);
-        accept(c->at<float>(p.o_val), c->at<int>(p.o_hat), 1, 1);
+        // (the relaxed replacement of o_hat happens inside the acceptance kernel)
+        GadppIn gp;
+        gp.part_cnt = c->at<int>(p.part_idx); gp.stride = p.n_strips; gp.n_part = n_cnt;
+        gp.lp = c->at<float>(p.draft_lp); gp.col = c->at<int>(p.draft_col);
+        gp.beta = c->gadpp_beta; gp.tau = c->gadpp_tau;
+        accept(c->at<float>(p.o_val), c->at<int>(p.o_hat), 1, 1, gp);
       };
       // every launch argument is a function of (rows, sequences, longest block), of the GAD++
       // setting and of pointers fixed for the context's life

@@ -174,10 +174,6 @@ void launch_argmax_finish(const float* part_val, const int* part_idx, int M, int
 // drafted token col[m] (negative: the never-matching id).
 void launch_draft_logit(int dtype, const void* A, const void* W, int M, int N, int K, const int* row_seq,
                         const int* row_start, const int* draft, int k_max, float* lp, int* col, hipStream_t s);
-// A row's drafted token replaces its arg max where fewer than `beta` columns score above it
-// (count partials of an EPI_COUNT launch) and top1 - lp <= tau.
-void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float* lp, const int* col,
-                        const float* o_val, int* o_hat, int M, int beta, float tau, hipStream_t s);
 // second stage of the arg max over the drafter's M = live * k mask rows; token i of the l-th unfinished
 // sequence b goes to the 8-byte slot [b * k_max + i] of `slots` (host-visible) as (*ticket_in << 32 | token)
 void launch_argmax_draft(const float* part_val, const int* part_idx, int M, int stride, int n_part, int* o_hat,
@@ -198,6 +194,18 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
                                   const int* pending, const int* src_len, int B, int l_cap, int s_max, VerifyTables t,
                                   int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,
                                   hipStream_t s);
+// GAD++ inputs of the acceptance kernel (Section 3.2.3; part_cnt == nullptr: plain verification):
+// a row's drafted token `col` (score `lp`) replaces its arg max where fewer than `beta` columns
+// score above it (the counting pass's partials, n_part per row at `stride`) and the top score is
+// at most `tau` above it.
+struct GadppIn {
+  const int* part_cnt = nullptr;
+  int stride = 0, n_part = 0;
+  const float* lp = nullptr;
+  const int* col = nullptr;
+  int beta = 1;
+  float tau = 0.f;
+};
 // Longest-prefix match, acceptance, truncation and rollback for every sequence.
 // second stage of the arg max (as launch_argmax_finish) and acceptance in one launch; with
 // ticket_out set (host-visible memory), sequence b's 8-byte slot receives *ticket_in (18 bits), the accepted
@@ -206,7 +214,7 @@ void launch_argmax_accept(const float* part_val, const int* part_idx, int stride
                           const int* k, const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
                           const int* ticket_in, unsigned long long* ticket_out, int max_rows, int M /* sum of k */,
-                          hipStream_t s);
+                          hipStream_t s, const GadppIn& gp = GadppIn{});
 // Row tables for the encoder (rows = source tokens) and for the drafter (prefix + masks).
 // the encoder's row tables, the embedding of the M rows, the copy of src_len (and, with len set, of
 // max_out and the start state of a decode) in one launch; the three inputs may be host memory

@@ -1419,7 +1419,7 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
                                                        int* __restrict__ pending, int* __restrict__ finished,
                                                        int* __restrict__ out, int* __restrict__ result,
                                                        const int* __restrict__ ticket_in,
-                                                       unsigned long long* __restrict__ ticket_out, int M) {
+                                                       unsigned long long* __restrict__ ticket_out, int M, GadppIn gp) {
   const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int kb = gridDim.x == 1 ? M : k[b];   // k is in host memory; a lone sequence owns all M rows
   if (kb == 0) {
@@ -1442,6 +1442,18 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
     float v;
     int idx;
     argmax_row(pv + (size_t)m * stride, pi + (size_t)m * stride, n_part, lane, v, idx);
+    if (gp.part_cnt) {
+      // relaxed verification (both inequalities of the GAD++ requirement, on fp32 scores: log-likelihood
+      // differences are score differences): the drafted token stands in for the arg max if fewer than beta
+      // columns score above it and the top score exceeds its score by at most tau
+      int cnt = 0;
+      for (int j = lane; j < gp.n_part; j += 64) cnt += gp.part_cnt[(size_t)m * gp.stride + j];
+      cnt = row16_sum_i(cnt);
+      cnt = __builtin_amdgcn_readlane(cnt, 0) + __builtin_amdgcn_readlane(cnt, 16) + __builtin_amdgcn_readlane(cnt, 32) +
+            __builtin_amdgcn_readlane(cnt, 48);
+      const int tok = gp.col[m];
+      if (tok >= 0 && cnt < gp.beta && v - gp.lp[m] <= gp.tau) idx = tok;
+    }
     if (lane == 0) {
       o_hat[m] = idx;
       if (o_val) o_val[m] = v;
@@ -1478,11 +1490,12 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
 void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part, int* o_hat, float* o_val, const int* k,
                           const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,
                           const int* max_out, int* len, int* pending, int* finished, int* out, int* result,
-                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, int M, hipStream_t s) {
+                          const int* ticket_in, unsigned long long* ticket_out, int max_rows, int M, hipStream_t s,
+                          const GadppIn& gp) {
   // as many waves as the longest block has rows (4 to 16): a wave finishes a row at a time
   const int waves = std::min(16, std::max(4, max_rows));
   k_argmax_accept<<<B, 64 * waves, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
-                                    max_out, len, pending, finished, out, result, ticket_in, ticket_out, M);
+                                    max_out, len, pending, finished, out, result, ticket_in, ticket_out, M, gp);
 }
 // ------------------------------------------------------------------------------------- GAD++ (Section 3.2.3)
 // The drafted token of packed row m: draft[b][i] for row i of sequence b.
@@ -1543,31 +1556,6 @@ void launch_draft_logit(int dtype, const void* A, const void* W, int M, int N, i
   else
     k_draft_logit_f32<<<(M + 63) / 64, 64, 0, s>>>((const float*)A, (const float*)W, M, N, K, row_seq, row_start, draft,
                                                    k_max, lp, col);
-}
-// One wave per row: sums the row's count partials; the drafted token stands in for the arg max
-// if fewer than beta columns score above it and the top score exceeds its score by at most tau
-// (both inequalities of the GAD++ requirement, on fp32 scores: log-likelihood differences are
-// score differences).
-__global__ __launch_bounds__(256) void k_gadpp_apply(const int* __restrict__ part_cnt, int stride, int n_part,
-                                                     const float* __restrict__ lp, const int* __restrict__ col,
-                                                     const float* __restrict__ o_val, int* __restrict__ o_hat, int M,
-                                                     int beta, float tau) {
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (m >= M) return;
-  int cnt = 0;
-  for (int i = lane; i < n_part; i += 64) cnt += part_cnt[(size_t)m * stride + i];
-  cnt = row16_sum_i(cnt);
-  cnt = __builtin_amdgcn_readlane(cnt, 0) + __builtin_amdgcn_readlane(cnt, 16) + __builtin_amdgcn_readlane(cnt, 32) +
-        __builtin_amdgcn_readlane(cnt, 48);
-  if (lane == 0) {
-    const int tok = col[m];
-    if (tok >= 0 && cnt < beta && o_val[m] - lp[m] <= tau) o_hat[m] = tok;
-  }
-}
-void launch_gadpp_apply(const int* part_cnt, int stride, int n_part, const float* lp, const int* col,
-                        const float* o_val, int* o_hat, int M, int beta, float tau, hipStream_t s) {
-  if (M <= 0) return;
-  k_gadpp_apply<<<(M + 3) / 4, 256, 0, s>>>(part_cnt, stride, n_part, lp, col, o_val, o_hat, M, beta, tau);
 }
 
 }  // namespace ad
