@@ -14,8 +14,9 @@
  *  - `verifier_w`, `drafter_w`, `workspace` are DEVICE pointers owned by the caller
  *    (allocate them with any allocator; they must outlive the context and the weights must
  *    not change while it lives: ad_create copies some of them into the workspace, side by
- *    side).  The library allocates no device memory, ever; after ad_create it allocates no
- *    memory at all.
+ *    side).  The library allocates no device memory, ever.  ad_create allocates one
+ *    pinned, device-mapped host staging buffer and a few events; later calls may allocate host
+ *    memory for bookkeeping (the decode loops' token lists, a captured graph per call shape).
  *  - `hip_stream` is a hipStream_t (NULL = the null stream).  All device work of a
  *    context is enqueued on it.  Calls that return results return once the results are
  *    there; ad_encode returns as soon as its work is enqueued, and the tail of an ad_verify
@@ -222,13 +223,8 @@ int ad_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* 
  * nominal peak.  Returns AD_OK or AD_EINVAL / AD_EDEVICE. */
 int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int32_t iters, void* stream, double* tflops);
 
-/* Launch-style knob; results never depend on it.  AD_OPT_FUSED_ROWS: a verify call with at most
- * this many packed rows (sum of k[b]) runs as ONE persistent kernel (bf16 contexts only; at most
- * max_batch * k_max).  Default 0: one launch per stage always, the faster path at every size
- * measured.  Setting a positive value on a context where the persistent kernel is unavailable
- * (device, model shape) gives AD_ESTATE.  AD_OPT_FUSED_AVAILABLE (read only): 1 if it is
- * available.  AD_OPT_GRAPHS (0/1, default 1): in the
- * launch-per-stage path the launches of an ad_verify call are captured into a HIP graph per call
+/* Launch-style knobs; results never depend on them.  AD_OPT_GRAPHS (0/1, default 1): the
+ * launches of an ad_verify call are captured into a HIP graph per call
  * shape (rows, sequences, longest block) on the shape's third appearance and replayed afterwards
  * (at most 512 shapes); the library switches it off by itself when the context's stream cannot be
  * captured (the null stream cannot).  AD_OPT_GRAPHS_CAPTURED (read only): graphs held.
@@ -236,12 +232,11 @@ int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int32_t iters, 
  * call's result into the (device-mapped) host staging buffer, which the calling thread watches,
  * instead of waiting for the stream to drain; later calls are ordered behind the unfinished rest
  * of the stream as usual.  After 50 ms without the result it waits for the stream.
- * AD_OPT_FUSE_CROSSQ (0/1, default 1): in the launch-per-stage path a decoder layer's
+ * AD_OPT_FUSE_CROSSQ (0/1, default 1): a decoder layer's
  * cross-attention runs its query projection and the attention as one launch (bf16, head width 64,
  * model width 512 or 1024; other shapes take two launches whatever the setting).  Same results bit
  * for bit either way. */
-enum { AD_OPT_FUSED_ROWS = 0, AD_OPT_FUSED_AVAILABLE = 1, AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5,
-       AD_OPT_FUSE_CROSSQ = 6 };
+enum { AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5, AD_OPT_FUSE_CROSSQ = 6 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 

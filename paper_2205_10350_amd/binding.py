@@ -26,8 +26,6 @@ EXPORTS = [
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
     "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp", "ad_time_output_projection", "ad_calibration_mfma",
 ]
-AD_OPT_FUSED_ROWS = 0
-AD_OPT_FUSED_AVAILABLE = 1
 AD_OPT_GRAPHS = 3
 AD_OPT_GRAPHS_CAPTURED = 4
 AD_OPT_SPIN_WAIT = 5

@@ -6,7 +6,6 @@
 
 #include <algorithm>
 #include <chrono>
-#include <functional>
 #include <string>
 #include <map>
 #include <utility>
@@ -46,8 +45,6 @@ struct Plan {
   size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
   size_t row_tok, row_pos, row_seq, row_dst, row_dst2, row_start, self_desc, cross_desc;
   size_t len, pending, finished, max_out, src_len[2], out, result, k_dev, draft_dev, src_dev, draft_out;
-  size_t stages, bar, stamps;   // fused forward: stage program, barrier words, optional stage clock stamps
-  int stage_cap = 0;
 };
 
 static Plan make_plan(const ad_config& c, bool with_drafter) {
@@ -97,11 +94,7 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.cross_desc = take(2 * B * sizeof(SeqDesc));
   p.len = take(B * 4); p.pending = take(B * 4); p.finished = take(B * 4); p.max_out = take(B * 4);
   p.out = take(B * c.max_len * 4);
-  p.result = take(B * 2 * 4 + 16);   // [B,2] results, then one int: the fused forward's abort flag copy
-  p.stage_cap = 8 * c.dec_layers + 1;
-  p.stages = take((size_t)p.stage_cap * sizeof(Stage));
-  p.stamps = take((size_t)(8 * 64 + 64 + 4 * 64) * 8);   // stage clock stamps; also scratch for the placement probe
-  p.bar = take(8 * (size_t)kBarWords);   // barrier words of the persistent forward
+  p.result = take(B * 2 * 4);   // [B,2] results
   p.k_dev = take(B * 4 + B * c.k_max * 4);   // k[B] followed by draft[B, k_max]: one upload
   p.draft_dev = p.k_dev + B * 4;
   p.src_dev = take(B * 4 * 2 + B * c.max_src * 4);   // src_len[B], max_out[B], src[B, max_src]: one upload
@@ -109,6 +102,36 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.total = off;
   return p;
 }
+
+// Layout (in ints) of the pinned, device-mapped host staging buffer.  Every part has a place of
+// its own for the whole life of the context, sized for max_batch: what one call leaves behind
+// never lies where another call's words are watched.
+struct PinLayout {
+  size_t k, draft, result, o_hat;     // ad_verify: k[B], draft[B, k_max] in; result[B, 2], o_hat[mv_cap] out
+  size_t v_ticket, v_slots;           // ad_verify: the call's ticket (in), one 8-byte result word per sequence (out)
+  size_t d_ticket, d_slots;           // ad_draft_nat: ticket (in), one 8-byte (ticket, token) word per drafted token (out)
+  size_t d_copy;                      // ad_draft_nat without the watch: draft_out[B, k_max]
+  size_t enc[2];                      // ad_encode per model: src_len[B], max_out[B], src[B, max_src]
+  size_t out;                         // ad_output: out[B, max_len]
+  size_t total;
+};
+static PinLayout make_pin_layout(const ad_config& c, const Plan& p) {
+  PinLayout l{};
+  const size_t B = c.max_batch;
+  size_t off = 0;
+  auto take = [&](size_t ints) { size_t o = off; off = (off + ints + 3) & ~(size_t)3; return o; };   // 16-byte steps
+  l.k = take(B); l.draft = take(B * c.k_max); l.result = take(2 * B); l.o_hat = take(p.mv_cap);
+  l.v_ticket = take(4); l.v_slots = take(2 * B);
+  l.d_ticket = take(4); l.d_slots = take(2 * B * c.k_max);
+  l.d_copy = take(B * c.k_max);
+  for (int i = 0; i < 2; ++i) l.enc[i] = take(B * (2 + (size_t)c.max_src));
+  l.out = take(B * c.max_len);
+  l.total = off;
+  return l;
+}
+
+// where the output projection leaves its arg-max partials: [rows, stride] values and indices
+struct PartialBuf { float* val; int* idx; int stride; };
 
 }  // namespace ad
 
@@ -126,8 +149,8 @@ struct ad_ctx {
   bool up_pending[2] = {false, false};
   int32_t* pin = nullptr;       // pinned staging, ints
   int32_t* pin_dev = nullptr;   // the same buffer as the device addresses it (null: not mapped, use copies)
-  size_t pin_ints = 0;
-  std::string err;
+  PinLayout pl{};
+  char err[320] = "";
   // host mirror of the decode state
   int B = 0;
   bool encoded[2] = {false, false};
@@ -138,8 +161,6 @@ struct ad_ctx {
   // shape of the forward being launched: attention problems and the most query rows in one
   int fw_nseq = 0, fw_max_rows = 0;
   int last_nseq = 0, last_max_rows = 0;
-  // persistent fused forward (bf16)
-  int fused_rows = 0;            // largest M it takes; 0 = off
   // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
   const LnW* ln_pending = nullptr;
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
@@ -148,10 +169,6 @@ struct ad_ctx {
   bool fuse_crossq = true;   // cross-attention: query projection + attention as one launch (AD_OPT_FUSE_CROSSQ)
   int gadpp_beta = 1;             // GAD++ (Section 3.2.3): 1 = plain top-1 verification
   float gadpp_tau = 0.f;
-  int fused_grid = 0, fused_stages = 0, fused_teams = 0;
-  size_t fused_lds = 0;
-  unsigned long long dev_base = 0, team_base[kMaxTeams] = {};
-  bool last_fused = false;
   // One launch per stage: the launches of a verify call (row assembly, forward, acceptance) are
   // captured into a graph per call shape on the shape's third appearance and replayed after.
   bool graphs_on = true;
@@ -163,15 +180,21 @@ struct ad_ctx {
   template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
 };
 
-static int fail(ad_ctx* c, int code, const std::string& msg) {
-  if (c) c->err = msg;
-  set_global_error(msg.c_str());
+// (messages go into fixed buffers: reporting an error allocates nothing)
+static int fail(ad_ctx* c, int code, const char* msg) {
+  if (c) snprintf(c->err, sizeof(c->err), "%s", msg);
+  set_global_error(msg);
   return code;
 }
-#define HIP_TRY(ctx, expr)                                                                      \
-  do {                                                                                          \
-    hipError_t e_ = (expr);                                                                     \
-    if (e_ != hipSuccess) return fail(ctx, AD_EDEVICE, std::string(#expr ": ") + hipGetErrorString(e_)); \
+static int fail_hip(ad_ctx* c, const char* what, hipError_t e) {
+  char msg[300];
+  snprintf(msg, sizeof(msg), "%.200s: %.90s", what, hipGetErrorString(e));
+  return fail(c, AD_EDEVICE, msg);
+}
+#define HIP_TRY(ctx, expr)                                          \
+  do {                                                              \
+    hipError_t e_ = (expr);                                         \
+    if (e_ != hipSuccess) return fail_hip(ctx, #expr, e_);          \
   } while (0)
 
 static double now_us() {
@@ -285,187 +308,21 @@ static void embed_rows(ad_ctx* c, const ModelW& w, int M) {
 
 // Output projection fused with the per-row arg max; `A` holds Mv rows.
 static int vocab_argmax(ad_ctx* c, const ModelW& w, const void* A, int Mv, const LnW* ln_of_s = nullptr,
-                        const void* out_w = nullptr /* another copy of w.out_w (timing) */) {
+                        const void* out_w = nullptr /* another copy of w.out_w (timing) */,
+                        const PartialBuf* pb = nullptr /* null: the workspace's partial buffers */) {
   const Plan& p = c->plan;
   Epi e{};
-  e.mode = EPI_ARGMAX; e.part_val = c->at<float>(p.part_val); e.part_idx = c->at<int>(p.part_idx);
-  e.n_strips = p.n_strips; e.logits = c->cfg.debug_logits ? c->at<float>(p.logits) : nullptr;
+  e.mode = EPI_ARGMAX;
+  e.part_val = pb ? pb->val : c->at<float>(p.part_val); e.part_idx = pb ? pb->idx : c->at<int>(p.part_idx);
+  e.n_strips = pb ? pb->stride : p.n_strips; e.logits = c->cfg.debug_logits ? c->at<float>(p.logits) : nullptr;
   LnA ln{};
   if (ln_of_s) { ln.x = c->at<float>(p.s); ln.g = ln_of_s->g; ln.b = ln_of_s->b; ln.y = c->at<float>(p.x); }
   return launch_gemm(c->cfg.dtype, A, out_w ? out_w : w.out_w, Mv, c->cfg.vocab, c->cfg.d_model, e, c->stream, ln);
 }
-static void vocab_finish(ad_ctx* c, int Mv, int n_part) {
+static void vocab_finish(ad_ctx* c, int Mv, int n_part, const PartialBuf* pb = nullptr) {
   const Plan& p = c->plan;
-  launch_argmax_finish(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, n_part, c->at<int>(p.o_hat),
-                       c->at<float>(p.o_val), c->stream);
-}
-
-// Layer-phase stage program of the verify forward for the persistent kernel (pointers are fixed
-// for the life of the context; only the row tables' contents, the team shares, M and B change
-// per call).  The output projection, its arg max and acceptance are fixed parts of the kernel.
-static int build_verify_program(ad_ctx* c, std::vector<Stage>& prog) {
-  const Plan& p = c->plan;
-  const ad_config& cf = c->cfg;
-  const ModelW& w = c->w[AD_VERIFIER];
-  const int d = cf.d_model, F = cf.d_ffn;
-  VerifyTables t = tables(c);
-  auto gemm = [&](int a_mode, const void* a_src, const LnW* ln, const void* W, int N, int K, Epi e) {
-    Stage s{};
-    s.type = ST_GEMM; s.a_mode = a_mode; s.N = N; s.K = K; s.W = W; s.a_src = a_src;
-    if (ln) { s.ln_g = ln->g; s.ln_b = ln->b; }
-    s.x_out = (a_mode == A_LN || a_mode == A_EMBED) ? c->at<float>(p.x) : nullptr;
-    s.epi = e;
-    prog.push_back(s);
-  };
-  auto attn = [&](const void* K, const void* V, const SeqDesc* desc, int nk_cap) {
-    Stage s{};
-    s.type = ST_ATTN; s.q = c->at<void>(p.q); s.Kb = K; s.Vb = V; s.att_out = c->at<void>(p.att); s.desc = desc;
-    s.nk_cap = nk_cap;
-    prog.push_back(s);
-  };
-  auto resid = [&](const float* bias) {
-    Epi e{};
-    e.mode = EPI_RESID; e.bias = bias; e.out0 = c->at<float>(p.s); e.resid = c->at<float>(p.x);
-    return e;
-  };
-  for (int l = 0; l < cf.dec_layers; ++l) {
-    const DecLayerW& L = w.dec[l];
-    Epi e{};
-    e.mode = EPI_QKV; e.d = d; e.bias = L.self.bqkv; e.out0 = c->at<void>(p.q);
-    e.out1 = c->ws + p.cache_k + l * p.cache_layer_stride; e.out2 = c->ws + p.cache_v + l * p.cache_layer_stride;
-    e.row_dst = t.row_dst;
-    if (l == 0) gemm(A_EMBED, w.emb, nullptr, L.self.wqkv, 3 * d, d, e);
-    else gemm(A_LN, c->at<float>(p.s), &w.dec[l - 1].ln3, L.self.wqkv, 3 * d, d, e);
-    attn(e.out1, e.out2, t.self_desc, p.l_cap);
-    gemm(A_COPY, c->at<void>(p.att), nullptr, L.self.wo, d, d, resid(L.self.bo));
-    Epi q{};
-    q.mode = EPI_STORE; q.bias = L.cross.bqkv; q.out0 = c->at<void>(p.q);
-    gemm(A_LN, c->at<float>(p.s), &L.ln1, L.cross.wqkv, d, d, q);
-    attn(c->ws + p.mem_k[0] + l * p.mem_layer_stride, c->ws + p.mem_v[0] + l * p.mem_layer_stride, t.cross_desc,
-         cf.max_src);
-    gemm(A_COPY, c->at<void>(p.att), nullptr, L.cross.wo, d, d, resid(L.cross.bo));
-    Epi r{};
-    r.mode = EPI_RELU; r.bias = L.ffn.b1; r.out0 = c->at<void>(p.f);
-    gemm(A_LN, c->at<float>(p.s), &L.ln2, L.ffn.w1, F, d, r);
-    gemm(A_COPY, c->at<void>(p.f), nullptr, L.ffn.w2, d, F, resid(L.ffn.b2));
-  }
-  // every GEMM stage prefetches the next GEMM stage's weights; the last one the output projection's
-  for (size_t i = 0; i < prog.size(); ++i) {
-    prog[i].pf_stage = -1;
-    if (prog[i].type != ST_GEMM) continue;
-    prog[i].pf_stage = -2;
-    for (size_t j = i + 1; j < prog.size(); ++j)
-      if (prog[j].type == ST_GEMM) { prog[i].pf_stage = (int)j; break; }
-  }
-  Stage ln{};
-  ln.pf_stage = -1;
-  ln.type = ST_LN; ln.K = d; ln.a_src = c->at<float>(p.s);
-  ln.ln_g = w.dec[cf.dec_layers - 1].ln3.g; ln.ln_b = w.dec[cf.dec_layers - 1].ln3.b;
-  ln.epi.out0 = c->at<void>(p.xa);
-  prog.push_back(ln);
-  return (int)prog.size();
-}
-
-// Sets the persistent forward up if this context and device can run it; otherwise leaves it off.
-static void setup_fused(ad_ctx* c) {
-  c->fused_rows = 0;
-  c->fused_grid = 0;
-  if (c->cfg.dtype != AD_BF16) return;
-  const ad_config& cf = c->cfg;
-  const Plan& p = c->plan;
-  const int d = cf.d_model, F = cf.d_ffn;
-  // LayerNorm rows and A tiles are at most kFusedMaxWidth wide; wider GEMMs walk whole slices
-  if (d > kFusedMaxWidth || d % 32 || F % 32 || (F > kFusedMaxWidth && F % kFusedMaxWidth)) return;
-  const int dh_f = d / cf.n_heads;
-  if (dh_f != 16 && dh_f != 32 && dh_f != 64) return;   // the head widths the persistent kernel is built for
-  const size_t att_bytes = attn_lds_host(std::max(p.l_cap, cf.max_src), d / cf.n_heads, 2, kFusedWaves);
-  const size_t lds = kFusedLdsBytes;
-  if (att_bytes > lds || (size_t)cf.k_max * 4 > lds) return;
-  hipDeviceProp_t prop;
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { (void)hipGetLastError(); return; }
-  if (!prop.cooperativeLaunch) return;
-  if (fused_max_blocks_per_cu(lds) < 1) return;
-  const int grid = std::min(prop.multiProcessorCount, 64 * 16);
-  // where do the workgroups of such a launch land?  Team t = workgroups with index % n == t must
-  // share one XCD.
-  int* xcc_dev = c->at<int>(p.stamps);
-  std::vector<int> xcc(grid, -1);
-  if (launch_probe_placement(xcc_dev, grid, lds, c->stream) != hipSuccess ||
-      hipMemcpyAsync(xcc.data(), xcc_dev, (size_t)grid * 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
-      hipStreamSynchronize(c->stream) != hipSuccess) {
-    (void)hipGetLastError();
-    return;
-  }
-  const int n_teams = *std::max_element(xcc.begin(), xcc.end()) + 1;
-  if (n_teams < 1 || n_teams > kMaxTeams || grid < n_teams) return;
-  // round-robin from a starting XCD that may differ from launch to launch
-  for (int b = 0; b < grid; ++b)
-    if (xcc[b] != (b + xcc[0]) % n_teams) return;
-  std::vector<Stage> prog;
-  const int n = build_verify_program(c, prog);
-  if (n > p.stage_cap || n > kFusedMaxStages) return;
-  if (hipMemcpyAsync(c->ws + p.stages, prog.data(), prog.size() * sizeof(Stage), hipMemcpyHostToDevice, c->stream) != hipSuccess ||
-      hipMemsetAsync(c->ws + p.bar, 0, 8 * (size_t)kBarWords, c->stream) != hipSuccess || hipStreamSynchronize(c->stream) != hipSuccess) {
-    (void)hipGetLastError();
-    return;
-  }
-  c->fused_grid = grid;
-  c->fused_teams = n_teams;
-  c->fused_stages = n;
-  c->fused_lds = lds;
-  c->dev_base = 0;
-  for (int t = 0; t < kMaxTeams; ++t) c->team_base[t] = 0;
-  // Off unless asked for: one launch per stage is the faster path at every size measured (a
-  // kernel boundary costs no more than a device-wide barrier inside the persistent kernel, and
-  // the per-stage kernels pick their own grid).
-  c->fused_rows = 0;
-}
-
-// One launch: the whole verify forward for the rows the tables describe.  k[b] = rows of
-// sequence b; sequences go to the teams in contiguous runs of about M / n_teams rows.
-static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bool do_accept, bool stamps = false) {
-  const Plan& p = c->plan;
-  const ad_config& cf = c->cfg;
-  VerifyTables t = tables(c);
-  FusedArgs fa{};
-  fa.stages = c->at<Stage>(p.stages); fa.n_stages = c->fused_stages;
-  fa.M = M; fa.B = B; fa.d = cf.d_model; fa.H = cf.n_heads; fa.dh = cf.d_model / cf.n_heads; fa.V = cf.vocab;
-  fa.sqrt_d = sqrtf((float)cf.d_model); fa.pe = c->at<float>(p.pe);
-  fa.row_tok = t.row_tok; fa.row_pos = t.row_pos;
-  const int nt = c->fused_teams;
-  fa.n_teams = nt;
-  {
-    // sequence b goes to team floor(first row of b * n_teams / M): contiguous, balanced by rows
-    int b = 0, rows = 0;
-    for (int tm = 0; tm < nt; ++tm) {
-      fa.team_seq[tm] = b; fa.team_row[tm] = rows;
-      while (b < B && (tm == nt - 1 || (long long)rows * nt / M <= tm)) { rows += k[b]; ++b; }
-    }
-    fa.team_seq[nt] = B; fa.team_row[nt] = M;
-  }
-  for (int tm = 0; tm < nt; ++tm) fa.team_base[tm] = c->team_base[tm];
-  fa.bar = c->at<unsigned long long>(p.bar); fa.dev_base = c->dev_base; fa.zero = 0;
-  fa.out_w = c->w[AD_VERIFIER].out_w; fa.xa = c->at<void>(p.xa);
-  fa.logits = cf.debug_logits ? c->at<float>(p.logits) : nullptr;
-  fa.part_val = c->at<float>(p.part_val); fa.part_idx = c->at<int>(p.part_idx); fa.part_stride = p.n_strips;
-  fa.o_hat = c->at<int>(p.o_hat); fa.o_val = c->at<float>(p.o_val);
-  fa.do_accept = do_accept ? 1 : 0;
-  fa.k = c->at<int>(p.k_dev); fa.draft = c->at<int>(p.draft_dev); fa.row_start = t.row_start;
-  fa.max_out = c->at<int>(p.max_out); fa.k_max = cf.k_max; fa.eos = cf.eos; fa.max_len = cf.max_len;
-  fa.len = c->at<int>(p.len); fa.pending = c->at<int>(p.pending); fa.finished = c->at<int>(p.finished);
-  fa.out = c->at<int>(p.out); fa.result = c->at<int>(p.result);
-  fa.stamps = stamps ? c->at<unsigned long long>(p.stamps) : nullptr;
-  hipError_t e = launch_fused_forward(fa, c->fused_grid, c->fused_lds, c->stream);
-  if (e == hipSuccess) {
-    c->dev_base += 2;
-    for (int tm = 0; tm < nt; ++tm)
-      if (fa.team_row[tm + 1] > fa.team_row[tm]) {
-        const int T = (c->fused_grid - tm + nt - 1) / nt;
-        c->team_base[tm] += (unsigned long long)(c->fused_stages - 1) * T;
-      }
-  }
-  return e;
+  launch_argmax_finish(pb ? pb->val : c->at<float>(p.part_val), pb ? pb->idx : c->at<int>(p.part_idx), Mv,
+                       pb ? pb->stride : p.n_strips, n_part, c->at<int>(p.o_hat), c->at<float>(p.o_val), c->stream);
 }
 
 // The verify forward over the M packed rows the tables describe.  ev (optional) brackets the
@@ -475,7 +332,7 @@ static hipError_t fused_verify_forward(ad_ctx* c, const int* k, int M, int B, bo
 // projection multiplies are in memory (xa) for whoever multiplies them again
 // embedded = true: the rows are embedded already (x, xa)
 static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_t ev_b = nullptr, bool finish = true,
-                          bool plain_rows = false, bool embedded = false) {
+                          bool plain_rows = false, bool embedded = false, const PartialBuf* pb = nullptr) {
   const Plan& p = c->plan;
   const ModelW& w = c->w[AD_VERIFIER];
   if (embedded) c->ln_pending = nullptr;
@@ -492,9 +349,9 @@ static int verify_forward(ad_ctx* c, int M, hipEvent_t ev_a = nullptr, hipEvent_
   if (ev_a) (void)hipEventRecord(ev_a, c->stream);
   c->ln_vocab = c->ln_pending;
   c->ln_pending = nullptr;
-  const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), M, c->ln_vocab);
+  const int n_part = vocab_argmax(c, w, c->at<void>(p.xa), M, c->ln_vocab, nullptr, pb);
   if (ev_b) (void)hipEventRecord(ev_b, c->stream);
-  if (finish) vocab_finish(c, M, n_part);
+  if (finish) vocab_finish(c, M, n_part, pb);
   return n_part;
 }
 
@@ -540,7 +397,7 @@ static void write_out(ad_ctx* c, const LoopIO& io, int32_t* out, int32_t* out_le
 // =================================================================================================
 extern "C" {
 
-const char* ad_last_error(const ad_ctx* ctx) { return ctx ? ctx->err.c_str() : ad::global_error(); }
+const char* ad_last_error(const ad_ctx* ctx) { return ctx ? ctx->err : ad::global_error(); }
 
 size_t ad_workspace_bytes(const ad_config* cfg, int with_drafter) {
   if (ad_config_check(cfg) != AD_OK) return 0;
@@ -569,19 +426,21 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   c->has_drafter = drafter_w != nullptr;
   if (c->has_drafter) c->w[1] = bind_weights(*cfg, drafter_w);
   const size_t B = cfg->max_batch;
-  // ad_verify's part [k | draft | result | o_hat | ticket + slots] <= B (6 + 2 k_max) + 8 ints, then ad_encode's
-  // [src_len | max_out | src] once per model, then the persistent forward's flag words at the very end
-  c->pin_ints = (12 * B + B * cfg->k_max * 2 + 2 * B * cfg->max_src + B * cfg->max_len + plan.mv_cap + 160 + 3) / 4 * 4;
+  c->pl = make_pin_layout(*cfg, plan);
+  c->last_k.assign(B, 0);
   auto bail = [&](const char* what, hipError_t e) {
-    std::string m = std::string(what) + ": " + hipGetErrorString(e);
     if (c->pin) (void)hipHostFree(c->pin);
     for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1]})
       if (ev) (void)hipEventDestroy(ev);
     delete c;
-    return fail(nullptr, AD_EDEVICE, m);
+    return fail_hip(nullptr, what, e);
   };
   hipError_t e;
-  if ((e = hipHostMalloc((void**)&c->pin, c->pin_ints * 4, hipHostMallocMapped)) != hipSuccess) return bail("hipHostMalloc", e);
+  // mapped and coherent: the device reads words the host rewrites between graph replays and the
+  // host watches words the device writes in mid-stream, neither side may keep a stale copy
+  if ((e = hipHostMalloc((void**)&c->pin, c->pl.total * 4, hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
+    return bail("hipHostMalloc", e);
+  memset(c->pin, 0, c->pl.total * 4);
   {
     void* dp = nullptr;
     if (hipHostGetDevicePointer(&dp, c->pin, 0) == hipSuccess) c->pin_dev = (int32_t*)dp;
@@ -621,7 +480,6 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail("hipStreamSynchronize", e);
   c->h_len.assign(B, 0); c->h_finished.assign(B, 1); c->h_max_out.assign(B, 0);
   c->h_src_len[0].assign(B, 0); c->h_src_len[1].assign(B, 0);
-  setup_fused(c);
   *out = c;
   return AD_OK;
 }
@@ -637,6 +495,8 @@ int ad_destroy(ad_ctx* c) {
   return AD_OK;
 }
 
+}  // extern "C"
+
 // rows < 2^26, longest block < 2^14, sequences < 2^13, knob < 2^6 (the configuration check's
 // capacities): disjoint bit fields, bits 62 and 63 left to the caller
 static unsigned long long shape_key(int rows, int max_rows, int n_seq, int knob) {
@@ -648,19 +508,20 @@ static unsigned long long shape_key(int rows, int max_rows, int n_seq, int knob)
 // this call shape has one, capture + instantiate + launch on the shape's third appearance.
 // false = nothing was launched, the caller launches eagerly.  Any failure switches graphs off
 // for the context (a stream that cannot be captured, e.g. the null stream, is such a failure).
-static bool run_as_graph(ad_ctx* c, unsigned long long shape, const std::function<void()>& launches,
+template <typename F>
+static bool run_as_graph(ad_ctx* c, hipStream_t stream, unsigned long long shape, const F& launches,
                          unsigned long long more = 0) {
   if (!c->graphs_on) return false;
   const ad_ctx::GraphKey key(shape, more);
   auto it = c->graphs.find(key);
   if (it != c->graphs.end()) {
-    if (hipGraphLaunch(it->second, c->stream) == hipSuccess) return true;
+    if (hipGraphLaunch(it->second, stream) == hipSuccess) return true;
     (void)hipGetLastError();
     c->graphs_on = false;
     return false;
   }
   if (++c->graph_seen[key] < 3 || c->graphs.size() >= 512) return false;   // worth building once a shape keeps coming back
-  if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+  if (hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
     (void)hipGetLastError();
     c->graphs_on = false;
     return false;
@@ -668,7 +529,7 @@ static bool run_as_graph(ad_ctx* c, unsigned long long shape, const std::functio
   launches();
   hipGraph_t g = nullptr;
   hipGraphExec_t ge = nullptr;
-  hipError_t e = hipStreamEndCapture(c->stream, &g);
+  hipError_t e = hipStreamEndCapture(stream, &g);
   if (e == hipSuccess && g) e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
   if (g) (void)hipGraphDestroy(g);
   if (e != hipSuccess || !ge) {
@@ -677,11 +538,13 @@ static bool run_as_graph(ad_ctx* c, unsigned long long shape, const std::functio
     return false;
   }
   c->graphs[key] = ge;
-  if (hipGraphLaunch(ge, c->stream) == hipSuccess) return true;
+  if (hipGraphLaunch(ge, stream) == hipSuccess) return true;
   (void)hipGetLastError();
   c->graphs_on = false;
   return false;
 }
+
+extern "C" {
 
 int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, int B, const int32_t* max_out) {
   int rc = check_batch(c, src, src_len, B);
@@ -698,8 +561,7 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   // call writes (one part per model).  The device reads them there (mapped memory) or gets them by
   // one copy; either way the call returns without waiting (what follows on the stream is ordered
   // behind it), so only the next ad_encode of the same model has to make sure they have been read.
-  const size_t enc_ints = (size_t)cf.max_batch * (2 + S);
-  int32_t* h = c->pin + (size_t)cf.max_batch * (6 + 2 * cf.k_max) + 8 + (size_t)model * enc_ints;
+  int32_t* h = c->pin + c->pl.enc[model];
   const bool mapped = c->pin_dev != nullptr;
   if (c->up_pending[model]) {
     HIP_TRY(c, hipEventSynchronize(c->ev_up[model]));
@@ -755,7 +617,7 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
     }
   };
   const unsigned long long key = (1ull << 63) | ((unsigned long long)model << 62) | shape_key(M, c->fw_max_rows, B, 0);
-  if (!run_as_graph(c, key, launches)) launches();
+  if (!run_as_graph(c, c->stream, key, launches)) launches();
   if (mapped) {
     HIP_TRY(c, hipEventRecord(c->ev_up[model], c->stream));
     c->up_pending[model] = true;
@@ -774,15 +636,73 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   return AD_OK;
 }
 
-int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
-              int32_t* verified) {
+}  // extern "C"
+
+// What a verify call's launches need beyond the context: where the device reads k and the draft,
+// where the acceptance kernel puts the result, whether it posts the call's ticket, and where the
+// arg-max partials of the output projection live.
+struct VerifyLaunch {
+  const int* k_src;
+  const int* draft_src;
+  int* result_dst;
+  const int* ticket_in;              // device view, null: no ticket
+  unsigned long long* ticket_out;    // device view
+  float* part_val;
+  int* part_idx;
+  int part_stride;
+  int M, B;
+};
+// The launches of one verify call: row assembly + embedding, the forward, arg-max finish + acceptance.
+static void verify_launches(ad_ctx* c, const VerifyLaunch& v) {
+  const ad_config& cf = c->cfg;
+  const Plan& p = c->plan;
+  const int km = cf.k_max;
+  VerifyTables t = tables(c);
+  const bool gadpp = c->gadpp_beta > 1;
+  auto accept = [&](const float* pv, const int* pi, int stride, int n_part, const GadppIn& gp) {
+    launch_argmax_accept(pv, pi, stride, n_part, c->at<int>(p.o_hat), c->at<float>(p.o_val), v.k_src, v.draft_src, km,
+                         t.row_start, v.B, cf.eos, cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len),
+                         c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), v.result_dst, v.ticket_in,
+                         v.ticket_out, c->fw_max_rows, v.M, c->stream, gp);
+  };
+  launch_assemble_embed_verify(cf.dtype, v.k_src, v.draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
+                               c->at<int>(p.src_len[0]), v.B, p.l_cap, cf.max_src, t, v.M, c->w[AD_VERIFIER].emb,
+                               c->at<float>(p.pe), cf.d_model, sqrtf((float)cf.d_model), c->at<float>(p.x),
+                               c->at<void>(p.xa), c->stream);
+  PartialBuf pb{v.part_val, v.part_idx, v.part_stride};
+  if (!gadpp) {
+    const int n_part = verify_forward(c, v.M, nullptr, nullptr, false, false, true, &pb);
+    accept(v.part_val, v.part_idx, v.part_stride, n_part, GadppIn{});
+    return;
+  }
+  // GAD++ (Section 3.2.3): arg max as before; then the score of every row's drafted token,
+  // a second pass of the output projection that counts the columns scoring above it (the
+  // logits still never reach memory), the relaxed replacement of o_hat, and acceptance
+  const ModelW& w = c->w[AD_VERIFIER];
+  (void)verify_forward(c, v.M, nullptr, nullptr, true, true, true, &pb);
+  launch_draft_logit(cf.dtype, c->at<void>(p.xa), w.out_w, v.M, cf.vocab, cf.d_model, t.row_seq, t.row_start,
+                     v.draft_src, km, c->at<float>(p.draft_lp), c->at<int>(p.draft_col), c->stream);
+  Epi e{};
+  e.mode = EPI_COUNT; e.part_idx = v.part_idx; e.n_strips = v.part_stride; e.thr = c->at<float>(p.draft_lp);
+  const int n_cnt = launch_gemm(cf.dtype, c->at<void>(p.xa), w.out_w, v.M, cf.vocab, cf.d_model, e, c->stream);
+  // (the relaxed replacement of o_hat happens inside the acceptance kernel)
+  GadppIn gp;
+  gp.part_cnt = v.part_idx; gp.stride = v.part_stride; gp.n_part = n_cnt;
+  gp.lp = c->at<float>(p.draft_lp); gp.col = c->at<int>(p.draft_col);
+  gp.beta = c->gadpp_beta; gp.tau = c->gadpp_tau;
+  accept(c->at<float>(p.o_val), c->at<int>(p.o_hat), 1, 1, gp);
+}
+
+static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
+                       int32_t* verified) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
   if (!draft || !k || !n_accept || !next_token) return fail(c, AD_EINVAL, "null buffer");
   if (!c->encoded[AD_VERIFIER]) return fail(c, AD_ESTATE, "ad_verify before ad_encode(AD_VERIFIER)");
   const ad_config& cf = c->cfg;
   const Plan& p = c->plan;
+  const PinLayout& pl = c->pl;
   const int B = c->B, km = cf.k_max;
-  int M = 0;
+  int M = 0, max_rows = 0;
   for (int b = 0; b < B; ++b) {
     if (k[b] < 0 || k[b] > km) return fail(c, AD_EINVAL, "k[b] outside [0, k_max]");
     if (k[b] && c->h_finished[b]) return fail(c, AD_ESTATE, "k[b] > 0 for a finished sequence");
@@ -792,151 +712,88 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
         return fail(c, AD_EINVAL, "draft id outside the vocabulary (AD_NEVER is allowed last only)");
     }
     M += k[b];
+    max_rows = std::max(max_rows, (int)k[b]);
   }
   if (M == 0) {
     for (int b = 0; b < B; ++b) { n_accept[b] = 0; next_token[b] = 0; }
     return AD_OK;
   }
   int32_t* h = c->pin;
-  memcpy(h, k, (size_t)B * 4);
-  for (int b = 0; b < B; ++b) memcpy(h + B + (size_t)b * km, draft + (size_t)b * km, (size_t)km * 4);
-  const bool gadpp = c->gadpp_beta > 1;
-  bool fused = c->fused_rows > 0 && M <= c->fused_rows && !gadpp;
-  // One launch per stage: the two small kernels that need k and the draft read them where they
-  // are, in the pinned (device-visible) staging buffer, and the result is written there too: no
-  // copy operations around the forward.  The persistent kernel works on device copies at
-  // k_dev = [k | draft] laid out for max_batch.
+  memcpy(h + pl.k, k, (size_t)B * 4);
+  for (int b = 0; b < B; ++b) memcpy(h + pl.draft + (size_t)b * km, draft + (size_t)b * km, (size_t)km * 4);
+  // The two small kernels that need k and the draft read them where they are, in the pinned
+  // (device-visible) staging buffer, and the result is written there too: no copy operations
+  // around the forward.
   const bool mapped = c->pin_dev != nullptr;
-  const int* k_src = mapped ? c->pin_dev : nullptr;
-  const int* draft_src = mapped ? c->pin_dev + B : nullptr;
-  if (fused || !mapped) {
-    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + B, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
-    k_src = c->at<int>(p.k_dev);
-    draft_src = c->at<int>(p.draft_dev);
+  VerifyLaunch v{};
+  v.M = M; v.B = B;
+  if (mapped) {
+    v.k_src = c->pin_dev + pl.k; v.draft_src = c->pin_dev + pl.draft; v.result_dst = c->pin_dev + pl.result;
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h + pl.k, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + pl.draft, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
+    v.k_src = c->at<int>(p.k_dev); v.draft_src = c->at<int>(p.draft_dev); v.result_dst = c->at<int>(p.result);
   }
-  VerifyTables t = tables(c);
+  v.part_val = c->at<float>(p.part_val);
+  v.part_idx = c->at<int>(p.part_idx);
+  v.part_stride = p.n_strips;
   c->fw_nseq = B;
-  c->fw_max_rows = *std::max_element(k, k + B);
-  c->last_nseq = B; c->last_max_rows = c->fw_max_rows;
-  auto assemble = [&]() {
-    launch_assemble_verify(k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
-                           c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, c->stream);
-  };
-  if (fused) assemble();
-  int32_t* res = c->pin + (size_t)B * (1 + km);
-  int32_t* oh = res + 2 * B;
-  unsigned long long* flags = (unsigned long long*)(c->pin + c->pin_ints - 2 * (kBarPlacement - kBarAbort + 2) - 2);
-  // the call's ticket, then one 8-byte slot per sequence (8-byte aligned)
-  int32_t* ticket_in = c->pin + (((size_t)(oh - c->pin) + p.mv_cap + 1) & ~(size_t)1);
-  unsigned long long* ticket_out = (unsigned long long*)(ticket_in + 2);
-  bool watch = false, seen_ticket = false;
-  for (;;) {
-    if (fused) {
-      HIP_TRY(c, fused_verify_forward(c, k, M, B, true));
-      HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
-    } else {
-      int* result_dst = mapped ? c->pin_dev + (res - c->pin) : c->at<int>(p.result);
-      // The result lands in host memory the device writes directly; the call's ticket follows it,
-      // and the host watches for the ticket instead of waiting for the stream to drain (the end of
-      // the kernel, its completion signal and the runtime's wake-up are off the critical path).
-      watch = mapped && c->spin_wait && !verified;
-      if (watch) {
-        if (++c->ticket >= (1 << 18)) c->ticket = 1;
-        *ticket_in = c->ticket;
-        for (int b = 0; b < B; ++b) ticket_out[b] = 0;   // whatever an earlier call left in these words
-      }
-      auto accept = [&](const float* pv, const int* pi, int stride, int n_part, const GadppIn& gp = GadppIn{}) {
-        launch_argmax_accept(pv, pi, stride, n_part, c->at<int>(p.o_hat), c->at<float>(p.o_val), k_src, draft_src, km,
-                             t.row_start, B, cf.eos, cf.max_len, c->at<int>(p.max_out), c->at<int>(p.len),
-                             c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), result_dst,
-                             watch ? c->pin_dev + (ticket_in - c->pin) : nullptr,
-                             watch ? (unsigned long long*)(c->pin_dev + ((int32_t*)ticket_out - c->pin)) : nullptr,
-                             c->fw_max_rows, M, c->stream, gp);
-      };
-      auto launches = [&]() {
-        launch_assemble_embed_verify(cf.dtype, k_src, draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
-                                     c->at<int>(p.src_len[0]), B, p.l_cap, cf.max_src, t, M, c->w[AD_VERIFIER].emb,
-                                     c->at<float>(p.pe), cf.d_model, sqrtf((float)cf.d_model), c->at<float>(p.x),
-                                     c->at<void>(p.xa), c->stream);
-        if (!gadpp) {
-          const int n_part = verify_forward(c, M, nullptr, nullptr, false, false, true);
-          accept(c->at<float>(p.part_val), c->at<int>(p.part_idx), p.n_strips, n_part);
-          return;
-        }
-        // GAD++ (Section 3.2.3): arg max as before; then the score of every row's drafted token,
-        // a second pass of the output projection that counts the columns scoring above it (the
-        // logits still never reach memory), the relaxed replacement of o_hat, and acceptance
-        const ModelW& w = c->w[AD_VERIFIER];
-        (void)verify_forward(c, M, nullptr, nullptr, true, true, true);
-        launch_draft_logit(cf.dtype, c->at<void>(p.xa), w.out_w, M, cf.vocab, cf.d_model, t.row_seq, t.row_start,
-                           draft_src, km, c->at<float>(p.draft_lp), c->at<int>(p.draft_col), c->stream);
-        Epi e{};
-        e.mode = EPI_COUNT; e.part_idx = c->at<int>(p.part_idx); e.n_strips = p.n_strips; e.thr = c->at<float>(p.draft_lp);
-        const int n_cnt = launch_gemm(cf.dtype, c->at<void>(p.xa), w.out_w, M, cf.vocab, cf.d_model, e, c->stream);
-        // (the relaxed replacement of o_hat happens inside the acceptance kernel)
-        GadppIn gp;
-        gp.part_cnt = c->at<int>(p.part_idx); gp.stride = p.n_strips; gp.n_part = n_cnt;
-        gp.lp = c->at<float>(p.draft_lp); gp.col = c->at<int>(p.draft_col);
-        gp.beta = c->gadpp_beta; gp.tau = c->gadpp_tau;
-        accept(c->at<float>(p.o_val), c->at<int>(p.o_hat), 1, 1, gp);
-      };
-      // every launch argument is a function of (rows, sequences, longest block), of the GAD++
-      // setting and of pointers fixed for the context's life
-      // (and of whether the acceptance kernel posts the ticket)
-      const unsigned long long key = shape_key(M, c->fw_max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0));
-      unsigned tau_bits;
-      memcpy(&tau_bits, &c->gadpp_tau, 4);
-      const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;
-      if (!mapped || !run_as_graph(c, key, launches, more)) launches();
-      if (!mapped) HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
-    }
-    flags[0] = 0; flags[kBarPlacement - kBarAbort] = 1; flags[kBarPlacement - kBarAbort + 1] = 1;
-    const int place_word = kBarPlacement - kBarAbort + (int)(((c->dev_base >> 1) + 1) & 1);   // of the launch above
-    if (fused)
-      HIP_TRY(c, hipMemcpyAsync(flags, c->at<unsigned long long>(p.bar) + kBarAbort,
-                                8 * (size_t)(kBarPlacement - kBarAbort + 2), hipMemcpyDeviceToHost, c->stream));
-    if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
-    bool seen = false;
-    seen_ticket = false;
-    if (watch && !fused) {
-      const int want = c->ticket;
-      const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(50);
-      for (unsigned spin = 1;; ++spin) {
-        int b = 0;
-        while (b < B && (int)(__atomic_load_n(ticket_out + b, __ATOMIC_ACQUIRE) >> 46) == want) ++b;
-        if (b == B) { seen = seen_ticket = true; break; }
-        if ((spin & 1023u) == 0 && std::chrono::steady_clock::now() > t_end) break;   // fall back to the stream
-        __builtin_ia32_pause();
-      }
-    }
-    if (!seen) {
-      HIP_TRY(c, hipStreamSynchronize(c->stream));
-      HIP_TRY(c, hipGetLastError());
-    }
-    if (flags[0]) {
-      // a barrier timed out: the decode state is undefined; switch the persistent path off
-      c->fused_rows = 0;
-      c->encoded[AD_VERIFIER] = false;
-      return fail(c, AD_EDEVICE, "persistent forward: a barrier timed out (state lost, encode again)");
-    }
-    if (fused && (flags[place_word] & (flags[place_word] - 1)) != 0) {
-      // a team was spread over several XCDs: the kernel left the decode state alone;
-      // run this call, and all later ones, with one launch per stage
-      c->fused_rows = 0;
-      fused = false;
-      continue;
-    }
-    break;
+  c->fw_max_rows = max_rows;
+  c->last_nseq = B; c->last_max_rows = max_rows;
+  // The result lands in host memory the device writes directly, as ONE 8-byte word per sequence that
+  // carries the call's ticket, and the host watches for the ticket instead of waiting for the
+  // stream to drain (the end of the kernel, its completion signal and the runtime's wake-up are off
+  // the critical path).
+  int32_t* ticket_in = c->pin + pl.v_ticket;
+  unsigned long long* ticket_out = (unsigned long long*)(c->pin + pl.v_slots);
+  const bool watch = mapped && c->spin_wait && !verified;
+  if (watch) {
+    if (++c->ticket >= (1 << 18)) c->ticket = 1;
+    *ticket_in = c->ticket;
+    for (int b = 0; b < B; ++b) ticket_out[b] = 0;   // whatever an earlier call left in these words
+    v.ticket_in = c->pin_dev + pl.v_ticket;
+    v.ticket_out = (unsigned long long*)(c->pin_dev + pl.v_slots);
   }
-  c->last_fused = fused;
-  c->last_k.assign(k, k + B);
+  // every launch argument is a function of (rows, sequences, longest block), of the GAD++
+  // setting, of whether the acceptance kernel posts the ticket, and of pointers fixed for the
+  // context's life
+  const bool gadpp = c->gadpp_beta > 1;
+  bool launched = false;
+  if (mapped) {
+    const unsigned long long key = shape_key(M, max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0));
+    unsigned tau_bits;
+    memcpy(&tau_bits, &c->gadpp_tau, 4);
+    const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;
+    launched = run_as_graph(c, c->stream, key, [&]() { verify_launches(c, v); }, more);
+  }
+  if (!launched) verify_launches(c, v);
+  int32_t* res = c->pin + pl.result;
+  int32_t* oh = c->pin + pl.o_hat;
+  if (!mapped) HIP_TRY(c, hipMemcpyAsync(res, c->at<int>(p.result), (size_t)B * 8, hipMemcpyDeviceToHost, c->stream));
+  if (verified) HIP_TRY(c, hipMemcpyAsync(oh, c->at<int>(p.o_hat), (size_t)M * 4, hipMemcpyDeviceToHost, c->stream));
+  bool seen = false;
+  if (watch) {
+    const int want = c->ticket;
+    const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(50);
+    for (unsigned spin = 1;; ++spin) {
+      int b = 0;
+      while (b < B && (int)(__atomic_load_n(ticket_out + b, __ATOMIC_ACQUIRE) >> 46) == want) ++b;
+      if (b == B) { seen = true; break; }
+      if ((spin & 1023u) == 0 && std::chrono::steady_clock::now() > t_end) break;   // fall back to the stream
+      __builtin_ia32_pause();
+    }
+  }
+  if (!seen) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipGetLastError());
+  }
   int r0 = 0;
   for (int b = 0; b < B; ++b) {
-    if (seen_ticket) {
-      const unsigned long long v = ticket_out[b];
-      n_accept[b] = (int)((v >> 32) & 0x3fff);
-      next_token[b] = (int)(unsigned)v;
+    if (watch) {
+      // (after the fall-back to the stream the words are there as well: the kernel has finished)
+      const unsigned long long w = __atomic_load_n(ticket_out + b, __ATOMIC_ACQUIRE);
+      n_accept[b] = (int)((w >> 32) & 0x3fff);
+      next_token[b] = (int)(unsigned)w;
     } else {
       n_accept[b] = res[2 * b];
       next_token[b] = res[2 * b + 1];
@@ -948,11 +805,19 @@ int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_acce
     if (verified) {
       for (int i = 0; i < km; ++i) verified[(size_t)b * km + i] = i < k[b] ? oh[r0 + i] : AD_NEVER;
     }
+    c->last_k[b] = k[b];
     r0 += k[b];
   }
   c->last_M = M;
   c->last_logit_rows = M;
   return AD_OK;
+}
+
+extern "C" {
+
+int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
+              int32_t* verified) {
+  return verify_call(c, draft, k, n_accept, next_token, verified);
 }
 
 int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
@@ -977,9 +842,9 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   for (int b = 0; b < B; ++b)
     if (!c->h_finished[b]) max_rows = std::max(max_rows, c->h_len[b] + 1);
   const int Mv = live * k;
-  int32_t* h = c->pin;
-  unsigned long long* slots = (unsigned long long*)c->pin;          // [B, k_max]
-  int32_t* ticket_in = c->pin + 2 * (size_t)B * km;                 // behind the slots
+  int32_t* h = c->pin + c->pl.d_copy;
+  unsigned long long* slots = (unsigned long long*)(c->pin + c->pl.d_slots);   // [B, k_max]
+  int32_t* ticket_in = c->pin + c->pl.d_ticket;
   const bool watch = c->pin_dev != nullptr && c->spin_wait;
   // the drafter forward's launches (made one by one: the prefix is recomputed every iteration,
   // so a call shape seldom comes back and a graph per shape costs more to build than it saves).
@@ -1015,8 +880,8 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     if (watch) {
       // the drafted tokens go straight to the host: (ticket, token) per 8-byte slot of the mapped buffer
       launch_argmax_draft(c->at<float>(p.part_val), c->at<int>(p.part_idx), Mv, p.n_strips, n_part, c->at<int>(p.o_hat),
-                          c->at<int>(p.finished), B, k, km, c->pin_dev + (ticket_in - c->pin),
-                          (unsigned long long*)c->pin_dev, c->stream);
+                          c->at<int>(p.finished), B, k, km, c->pin_dev + c->pl.d_ticket,
+                          (unsigned long long*)(c->pin_dev + c->pl.d_slots), c->stream);
     } else {
       vocab_finish(c, Mv, n_part);
       launch_draft_scatter(c->at<int>(p.o_hat), c->at<int>(p.finished), B, k, km, c->at<int>(p.draft_out), c->stream);
@@ -1069,11 +934,12 @@ int ad_output(ad_ctx* c, int32_t* out, int32_t* out_len) {
   if (!out || !out_len) return fail(c, AD_EINVAL, "null buffer");
   if (!c->encoded[AD_VERIFIER]) return fail(c, AD_ESTATE, "no decode in progress");
   const int B = c->B, L = c->cfg.max_len;
-  HIP_TRY(c, hipMemcpyAsync(c->pin, c->at<int>(c->plan.out), (size_t)B * L * 4, hipMemcpyDeviceToHost, c->stream));
+  const int32_t* ho = c->pin + c->pl.out;
+  HIP_TRY(c, hipMemcpyAsync(c->pin + c->pl.out, c->at<int>(c->plan.out), (size_t)B * L * 4, hipMemcpyDeviceToHost, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   for (int b = 0; b < B; ++b) {
     out_len[b] = c->h_len[b];
-    for (int i = 0; i < L; ++i) out[(size_t)b * L + i] = i < c->h_len[b] ? c->pin[(size_t)b * L + i] : c->cfg.pad;
+    for (int i = 0; i < L; ++i) out[(size_t)b * L + i] = i < c->h_len[b] ? ho[(size_t)b * L + i] : c->cfg.pad;
   }
   return AD_OK;
 }
@@ -1189,18 +1055,12 @@ int ad_set_option(ad_ctx* c, int option, int value) {
     c->fuse_crossq = value != 0;
     return AD_OK;
   }
-  if (option != AD_OPT_FUSED_ROWS) return fail(c, AD_EINVAL, "unknown option");
-  if (value < 0 || value > c->plan.mv_cap) return fail(c, AD_EINVAL, "AD_OPT_FUSED_ROWS must be in [0, max_batch * k_max]");
-  if (value > 0 && c->fused_grid == 0) return fail(c, AD_ESTATE, "the persistent forward is unavailable for this context");
-  c->fused_rows = value;
-  return AD_OK;
+  return fail(c, AD_EINVAL, "unknown option");
 }
 int ad_get_option(ad_ctx* c, int option, int* value) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
   if (!value) return fail(c, AD_EINVAL, "null pointer");
-  if (option == AD_OPT_FUSED_ROWS) *value = c->fused_rows;
-  else if (option == AD_OPT_FUSED_AVAILABLE) *value = c->fused_grid > 0 ? 1 : 0;
-  else if (option == AD_OPT_GRAPHS) *value = c->graphs_on ? 1 : 0;
+  if (option == AD_OPT_GRAPHS) *value = c->graphs_on ? 1 : 0;
   else if (option == AD_OPT_GRAPHS_CAPTURED) *value = (int)c->graphs.size();
   else if (option == AD_OPT_SPIN_WAIT) *value = c->spin_wait ? 1 : 0;
   else if (option == AD_OPT_FUSE_CROSSQ) *value = c->fuse_crossq ? 1 : 0;
@@ -1253,32 +1113,6 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
   double tot = 0, voc = 0;
   c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
-  if (c->last_fused && c->fused_rows > 0) {
-    // one kernel: the whole forward (arg max included, acceptance skipped)
-    const int* k = c->last_k.data();
-    HIP_TRY(c, fused_verify_forward(c, k, c->last_M, c->last_nseq, false));
-    for (int r = 0; r < reps; ++r) {
-      HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
-      HIP_TRY(c, fused_verify_forward(c, k, c->last_M, c->last_nseq, false));
-      HIP_TRY(c, hipEventRecord(c->ev3, c->stream));
-      HIP_TRY(c, hipEventSynchronize(c->ev3));
-      float a = 0;
-      HIP_TRY(c, hipEventElapsedTime(&a, c->ev0, c->ev3));
-      tot += a * 1e3;
-    }
-    *forward_us = tot / reps;
-    *vocab_kernel_us = 0;
-    if (vocab_back_to_back_us) *vocab_back_to_back_us = 0;
-    unsigned long long flags[kBarPlacement - kBarAbort + 2];
-    const int place_word = kBarPlacement - kBarAbort + (int)(((c->dev_base >> 1) + 1) & 1);   // of the last launch
-    HIP_TRY(c, hipMemcpyAsync(flags, c->at<unsigned long long>(c->plan.bar) + kBarAbort, sizeof(flags), hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (flags[0] || (flags[place_word] & (flags[place_word] - 1)) != 0) {
-      c->fused_rows = 0;
-      return fail(c, AD_EDEVICE, "persistent forward: barrier time-out or misplaced workgroup while timing");
-    }
-    return AD_OK;
-  }
   verify_forward(c, c->last_M);   // warm
   // the whole forward, reps times back to back between two events
   HIP_TRY(c, hipEventRecord(c->ev0, c->stream));

@@ -1,6 +1,7 @@
 // Host-only logic: configuration checks, weight layout, the suffix match of Algorithm 1 and
 // the decode loops (greedy, input-guided, draft-verify) written against an abstract
 // verifier so that the very same loops run over the GPU and over a model-free stand-in.
+#include <stdio.h>
 #include <string.h>
 
 #include <algorithm>
@@ -11,9 +12,10 @@
 
 namespace ad {
 
-static thread_local std::string g_error;
-void set_global_error(const char* msg) { g_error = msg ? msg : ""; }
-const char* global_error() { return g_error.c_str(); }
+// (a fixed buffer: reporting an error allocates nothing)
+static thread_local char g_error[320] = "";
+void set_global_error(const char* msg) { snprintf(g_error, sizeof(g_error), "%s", msg ? msg : ""); }
+const char* global_error() { return g_error; }
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

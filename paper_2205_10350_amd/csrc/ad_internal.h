@@ -75,72 +75,6 @@ struct Epi {
   size_t layer_stride;    // KV with N = layers * 2d: bytes from one layer's key (value) buffer to the next
 };
 
-// ---- persistent fused forward (ad_fused.hip) ---------------------------------------------------------
-// Layer-phase stage kinds: a GEMM with its left operand staged through LDS, the block attention,
-// and the last LayerNorm (rows in the storage type for the output projection).
-enum StageType { ST_GEMM = 0, ST_ATTN = 1, ST_LN = 2 };
-// where a GEMM stage takes its left operand from: LayerNorm of fp32 rows / embedding of the row
-// tokens / plain copy of storage-type rows
-enum AMode { A_LN = 0, A_EMBED = 1, A_COPY = 2 };
-struct Stage {
-  int type;
-  int a_mode, N, K;          // GEMM; LN: K = row width
-  const void* W;
-  const void* a_src;         // GEMM: see AMode; LN: fp32 rows
-  const float *ln_g, *ln_b;
-  float* x_out;              // A_LN / A_EMBED: the team's first workgroup also stores the fp32 rows here
-  Epi epi;                   // LN: out0 = storage-type rows
-  const void *q, *Kb, *Vb;   // ATTN
-  void* att_out;
-  const SeqDesc* desc;
-  int nk_cap;
-  int pf_stage;              // GEMM: stage whose weights idle waves prefetch into the L2 (-2: the output projection, -1: none)
-};
-constexpr int kFusedWaves = 4;            // waves per workgroup of the persistent kernel
-// LDS plan of the persistent kernel (dynamic part): [A tile | weight slots | arg-max merge slots].
-// The A tile holds 64 rows x (512 + 8) bf16 or 32 rows x (1024 + 8) bf16; the weight slots hold
-// B-operand tiles fetched ahead of a stage.  The attention stage overlays the whole range.
-constexpr int kFusedATileBytes = 64 * (512 + 8) * 2;
-constexpr int kFusedWSlotBytes = 64 * 1024;
-constexpr int kFusedLdsBytes = kFusedATileBytes + kFusedWSlotBytes + 2 * kFusedWaves * 64 * 4;
-constexpr int kFusedMaxStages = 64;       // layer-phase stages the kernel keeps in LDS
-constexpr int kFusedMaxWidth = 1024;      // widest LayerNorm row / GEMM K slice
-constexpr int kMaxTeams = 16;
-// barrier words (64-bit words, 128 bytes apart)
-constexpr int kBarDevTop = 0, kBarDevPhase = 16, kBarAbort = 32, kBarPlacement = 48, kBarDevGroup = 64,
-              kBarTeam = kBarDevGroup + 16 * 64, kBarWords = kBarTeam + 16 * kMaxTeams;
-struct FusedArgs {
-  const Stage* stages;            // layer-phase program
-  int n_stages;
-  int M, B, d, H, dh, V;
-  float sqrt_d;
-  const float* pe;
-  const int *row_tok, *row_pos;
-  // teams: team t = workgroups with index % n_teams == t; it owns packed rows
-  // [team_row[t], team_row[t+1]) = sequences [team_seq[t], team_seq[t+1])
-  int n_teams;
-  int team_row[kMaxTeams + 1], team_seq[kMaxTeams + 1];
-  unsigned long long team_base[kMaxTeams];   // arrivals at team t's barrier counter before this launch
-  unsigned long long* bar;        // barrier words
-  unsigned long long dev_base;    // device-wide barriers completed before this launch
-  unsigned long long zero;        // 0, opaque to the compiler (polling read-modify-write)
-  // output projection
-  const void* out_w;
-  const void* xa;                 // [M, d] storage-type rows after the last LayerNorm
-  float* logits;                  // nullable [M, V]
-  float* part_val; int* part_idx; int part_stride;   // [M, part_stride]: one partial per (row, workgroup)
-  // finish stage
-  int* o_hat; float* o_val;
-  int do_accept;
-  const int *k, *draft, *row_start, *max_out;
-  int k_max, eos, max_len;
-  int *len, *pending, *finished, *out, *result;
-  unsigned long long* stamps;     // nullable: workgroup 0 records the 100 MHz clock at every stage start
-};
-int fused_max_blocks_per_cu(size_t lds_bytes);
-hipError_t launch_probe_placement(int* xcc_dev, int grid, size_t lds_bytes, hipStream_t s);
-hipError_t launch_fused_forward(const FusedArgs& fa, int grid, size_t lds_bytes, hipStream_t s);
-
 // ---- launchers (ad_kernels.hip).  dtype: AD_F32 / AD_BF16 selects storage + arithmetic ---------
 void launch_embed(int dtype, const void* emb, const float* pe, const int* tok, const int* pos, int M,
                   int d, float sqrt_d, float* x, void* xa, hipStream_t s);
@@ -187,9 +121,7 @@ struct VerifyTables {
   int* row_dst2;   // [M] encoder only: row of the memory key/value buffers
   SeqDesc *self_desc, *cross_desc;                          // [B]
 };
-void launch_assemble_verify(const int* k, const int* draft, int k_max, const int* len, const int* pending,
-                            const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s);
-// the tables of launch_assemble_verify and the embedding of its M rows (x, xa) in one launch
+// those tables and the embedding of the M rows (x, xa) in one launch
 void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int k_max, const int* len,
                                   const int* pending, const int* src_len, int B, int l_cap, int s_max, VerifyTables t,
                                   int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,

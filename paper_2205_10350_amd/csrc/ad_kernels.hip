@@ -1088,41 +1088,9 @@ void launch_argmax_draft(const float* pv, const int* pi, int M, int stride, int 
 // ------------------------------------------------------------------------------------- row assembly
 // Verify call: sequence b feeds (pending_b, draft_b[0..k_b-2]) at positions len_b .. len_b+k_b-1
 // (Section 3.2, the verifier equation conditions row i on the accepted prefix and the first
-// i-1 drafted tokens).  One block; thread 0 scans, all threads fill.
-__global__ void k_assemble_verify(const int* __restrict__ k, const int* __restrict__ draft, int k_max,
-                                  const int* __restrict__ len, const int* __restrict__ pending,
-                                  const int* __restrict__ src_len, int B, int l_cap, int s_max, VerifyTables t) {
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += k[b]; }
-    t.row_start[B] = acc;
-  }
-  __syncthreads();
-  for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    SeqDesc s;
-    s.q_row0 = t.row_start[b]; s.nq = k[b]; s.kv_row0 = b * l_cap; s.nk_base = len[b]; s.causal = 1;
-    s.pad0 = s.pad1 = s.pad2 = 0;
-    t.self_desc[b] = s;
-    s.kv_row0 = b * s_max; s.nk_base = src_len[b]; s.causal = 0;
-    t.cross_desc[b] = s;
-  }
-  for (int b = 0; b < B; ++b) {
-    const int r0 = t.row_start[b], kb = k[b], L = len[b];
-    for (int i = threadIdx.x; i < kb; i += blockDim.x) {
-      t.row_tok[r0 + i] = i == 0 ? pending[b] : draft[b * k_max + i - 1];
-      t.row_pos[r0 + i] = L + i;
-      t.row_seq[r0 + i] = b;
-      t.row_dst[r0 + i] = b * l_cap + L + i;
-    }
-  }
-}
-void launch_assemble_verify(const int* k, const int* draft, int k_max, const int* len, const int* pending,
-                            const int* src_len, int B, int l_cap, int s_max, VerifyTables t, hipStream_t s) {
-  k_assemble_verify<<<1, 256, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t);
-}
-// The same tables and the embedding of the rows in one launch: workgroup 0 writes the tables
-// the later kernels read; workgroup m + 1 finds row m's (sequence, block index) by the same scan
-// and embeds it.
+// i-1 drafted tokens).  The row tables and the embedding of the rows in one launch: workgroup 0
+// writes the tables the later kernels read; workgroup m + 1 finds row m's (sequence, block index)
+// by the same scan and embeds it.
 template <typename T>
 __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __restrict__ k, const int* __restrict__ draft,
                                                                int k_max, const int* __restrict__ len,
@@ -1424,8 +1392,8 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
   const int kb = gridDim.x == 1 ? M : k[b];   // k is in host memory; a lone sequence owns all M rows
   if (kb == 0) {
     if (threadIdx.x == 0) {
-      result[2 * b] = 0; result[2 * b + 1] = 0;
       if (ticket_out) __hip_atomic_store(ticket_out + b, (unsigned long long)*ticket_in << 46, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      else { result[2 * b] = 0; result[2 * b + 1] = 0; }
     }
     return;
   }
@@ -1478,14 +1446,17 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict_
   len[b] = L + n;
   if (n > 0) pending[b] = last;
   finished[b] = (n > 0 && last == eos) || (L + n >= lim);
-  result[2 * b] = n;
-  result[2 * b + 1] = last;
   // a host that waits for this call by watching memory: ticket (18 bits), accepted length (14) and
   // next token (32) in ONE 8-byte store, so that seeing the ticket is seeing the result; no
-  // release fence (it would write the whole cache back)
-  if (ticket_out)
+  // release fence (it would write the whole cache back).  Nothing else is written to host memory
+  // then: a plain store could still be on its way when the host, having seen the ticket, goes on.
+  if (ticket_out) {
     __hip_atomic_store(ticket_out + b, ((unsigned long long)ticket << 46) | ((unsigned long long)n << 32) | (unsigned)last,
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  } else {
+    result[2 * b] = n;
+    result[2 * b + 1] = last;
+  }
 }
 void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part, int* o_hat, float* o_val, const int* k,
                           const int* draft, int k_max, const int* row_start, int B, int eos, int max_len,

@@ -522,55 +522,6 @@ def test_workload4_big_gad_batch8():
 
 
 # ----------------------------------------------------------------------------------------------
-# The persistent single-launch forward (few rows, bf16) against the launch-per-stage path.
-
-@pytest.mark.parametrize("name,B", [("tiny", 1), ("tiny", 3), ("base", 1), ("base", 4)])
-def test_persistent_forward_is_bit_identical_to_staged_launches(name, B):
-    rig = Rig(name, "bf16", 55, B=B, max_src=40, max_len=40, k_max=24)
-    try:
-        assert rig.ctx.get_option(ad.AD_OPT_FUSED_ROWS) == 0          # one launch per stage unless asked otherwise
-        assert rig.ctx.get_option(ad.AD_OPT_FUSED_AVAILABLE) == 1, "persistent forward unavailable on this device"
-        full = B * 24
-        rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, full)
-        srcs = _sources(rig.dims, 55, [30 - 7 * b for b in range(B)])
-        rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
-        out_ref, st_ref = rig.ctx.decode_greedy(srcs)
-        rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, full)
-        out_f, st_f = rig.ctx.decode_greedy(srcs)
-        assert out_f == out_ref
-        # ragged blocks through both paths: logits, arg max, accepted lengths, output
-        V = rig.dims["vocab"]
-        drafts1 = [out_ref[b][:3 + 5 * b] for b in range(B)]
-        drafts2 = [[(t - 5 + 1) % (V - 5) + 5 for t in out_ref[b][3 + 5 * b:3 + 5 * b + 2]] + out_ref[b][5 + 5 * b:12 + 5 * b]
-                   for b in range(B)]
-        res = {}
-        for rows in (0, full):
-            rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, rows)
-            rig.ctx.encode(ad.AD_VERIFIER, srcs)
-            a = rig.ctx.verify(drafts1, want_verified=True)
-            la = rig.ctx.debug_logits()
-            b_ = rig.ctx.verify(drafts2, want_verified=True)
-            lb = rig.ctx.debug_logits()
-            res[rows] = (a, la, b_, lb, rig.ctx.output())
-        (a0, la0, b0, lb0, o0), (a1, la1, b1, lb1, o1) = res[0], res[full]
-        for x, y in zip(a0 + b0, a1 + b1):
-            assert np.array_equal(x, y)
-        assert np.array_equal(la0.view(np.uint32), la1.view(np.uint32))
-        assert np.array_equal(lb0.view(np.uint32), lb1.view(np.uint32))
-        assert o0 == o1
-        assert a1[0].tolist() == [len(d) for d in drafts1] and b1[0].tolist() == [1] * B
-        # whole decodes: input-guided with edits, identical outputs and iteration structure
-        guides = [edit_guide(g, 0.1, 3 + b, V) for b, g in enumerate(out_ref)]
-        rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
-        oi0, si0 = rig.ctx.decode_iad(srcs, guides)
-        rig.ctx.set_option(ad.AD_OPT_FUSED_ROWS, full)
-        oi1, si1 = rig.ctx.decode_iad(srcs, guides)
-        assert oi0 == oi1 == out_ref and si0["rows_verified"] == si1["rows_verified"]
-    finally:
-        rig.close()
-
-
-# ----------------------------------------------------------------------------------------------
 # Graph replay of a verify call's launches against the same launches made one by one.
 
 @pytest.mark.gpu
