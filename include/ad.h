@@ -14,9 +14,11 @@
  *  - `verifier_w`, `drafter_w`, `workspace` are DEVICE pointers owned by the caller
  *    (allocate them with any allocator; they must outlive the context and the weights must
  *    not change while it lives: ad_create copies some of them into the workspace, side by
- *    side).  The library allocates no device memory, ever.  ad_create allocates one
+ *    side).  The library allocates no device memory, ever (its one device-side object of its
+ *    own is the fixed 4 MiB static array ad_verify_static works in).  ad_create allocates one
  *    pinned, device-mapped host staging buffer and a few events; later calls may allocate host
- *    memory for bookkeeping (the decode loops' token lists, a captured graph per call shape).
+ *    memory for bookkeeping (the decode loops' token lists, a captured graph per call shape);
+ *    ad_verify_static allocates nothing at all.
  *  - `hip_stream` is a hipStream_t (NULL = the null stream).  All device work of a
  *    context is enqueued on it.  Calls that return results return once the results are
  *    there; ad_encode returns as soon as its work is enqueued, and the tail of an ad_verify
@@ -144,6 +146,21 @@ int ad_encode(ad_ctx* ctx, int model, const int32_t* src, const int32_t* src_len
  * AD_EINVAL for k[b] > k_max, ids outside the vocabulary, AD_NEVER not last. */
 int ad_verify(ad_ctx* ctx, const int32_t* draft, const int32_t* k,
               int32_t* n_accept, int32_t* next_token, int32_t* verified);
+
+/* ad_verify for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, same results and same effect on the decode
+ * state as ad_verify.  The call allocates nothing, on the device or on the host: its kernels are
+ * launched one by one (no graph is built or replayed) and the one scratch buffer they need
+ * beyond the context's workspace, the per-workgroup arg-max partials of the output projection,
+ * lives in a 4 MiB array the library holds statically on every GPU it runs on (until the process
+ * ends).  Limit: rows x (vocab / 16) x 8 bytes <= 4 MiB, rows = sum of k[b] (262 rows at vocab
+ * 32000); more gives AD_EINVAL and leaves the context as it was.  All contexts on one GPU share
+ * that array and it keeps the last call's contents (every word a call reads it has written
+ * before, so nothing needs clearing): calls that overlap in time on one GPU race, also from
+ * different contexts or streams; serialise them.  AD_ESTATE if the array's address could not be
+ * obtained on this device. */
+int ad_verify_static(ad_ctx* ctx, const int32_t* draft, const int32_t* k,
+                     int32_t* n_accept, int32_t* next_token, int32_t* verified);
 
 /* Block drafter (Section 3.2, draft paragraph; Section 3.2.1): decoder input
  * (o_0..o_j, [MASK] x k) at positions 0..j+k with bidirectional self-attention and

@@ -22,7 +22,7 @@ AD_NEVER = -1
 EXPORTS = [
     "ad_config_check", "ad_workspace_bytes", "ad_weights_count", "ad_weights_bytes", "ad_weights_entry",
     "ad_weights_pack",
-    "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_draft_nat", "ad_output",
+    "ad_create", "ad_destroy", "ad_last_error", "ad_encode", "ad_verify", "ad_verify_static", "ad_draft_nat", "ad_output",
     "ad_decode_greedy", "ad_decode_iad", "ad_decode_gad", "ad_debug_logits", "ad_time_verify_forward",
     "ad_suffix_match", "ad_host_simulate", "ad_set_option", "ad_get_option", "ad_calibration_copy", "ad_set_gadpp", "ad_time_output_projection", "ad_calibration_mfma",
 ]
@@ -81,6 +81,7 @@ def lib():
     L.ad_last_error.argtypes = [C.c_void_p]; L.ad_last_error.restype = C.c_char_p
     L.ad_encode.argtypes = [C.c_void_p, C.c_int, _I32P, _I32P, C.c_int, _I32P]; L.ad_encode.restype = C.c_int
     L.ad_verify.argtypes = [C.c_void_p, _I32P, _I32P, _I32P, _I32P, _I32P]; L.ad_verify.restype = C.c_int
+    L.ad_verify_static.argtypes = [C.c_void_p, _I32P, _I32P, _I32P, _I32P, _I32P]; L.ad_verify_static.restype = C.c_int
     L.ad_draft_nat.argtypes = [C.c_void_p, C.c_int, _I32P]; L.ad_draft_nat.restype = C.c_int
     L.ad_output.argtypes = [C.c_void_p, _I32P, _I32P]; L.ad_output.restype = C.c_int
     sp = C.POINTER(AdStats)
@@ -269,13 +270,15 @@ class Context:
         if model == AD_VERIFIER:
             self.B = len(srcs)
 
-    def verify(self, drafts, want_verified=False):
-        """drafts: list of B token lists (empty = sit out).  Returns n_accept, next, [verified]."""
+    def verify(self, drafts, want_verified=False, static=False):
+        """drafts: list of B token lists (empty = sit out).  Returns n_accept, next, [verified].
+        static=True calls ad_verify_static, the variant that allocates nothing."""
         km = self.cfg.k_max
         d, k = self._pad_rows(drafts, km)
         n = np.zeros(self.B, dtype=np.int32); nx = np.zeros(self.B, dtype=np.int32)
         ver = np.zeros((self.B, km), dtype=np.int32) if want_verified else None
-        _check(self.L.ad_verify(self.h, _p(d), _p(k), _p(n), _p(nx), _p(ver)), self.h)
+        fn = self.L.ad_verify_static if static else self.L.ad_verify
+        _check(fn(self.h, _p(d), _p(k), _p(n), _p(nx), _p(ver)), self.h)
         return (n, nx, ver) if want_verified else (n, nx)
 
     def draft_nat(self, k):

@@ -133,6 +133,25 @@ static PinLayout make_pin_layout(const ad_config& c, const Plan& p) {
 // where the output projection leaves its arg-max partials: [rows, stride] values and indices
 struct PartialBuf { float* val; int* idx; int stride; };
 
+// The static scratch array of ad_verify_static (arg-max partials: values in the first half, indices
+// in the second).  Every GPU the library runs on holds its own copy at its own address; the name
+// below is a host-side stand-in, so host code only ever uses the address hipGetSymbolAddress
+// reports for the current device (looked up once per device in ad_create).
+constexpr size_t kStaticScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char ad_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+static void* static_scratch_for_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(ad_static_scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace ad
 
 using namespace ad;
@@ -150,6 +169,7 @@ struct ad_ctx {
   int32_t* pin = nullptr;       // pinned staging, ints
   int32_t* pin_dev = nullptr;   // the same buffer as the device addresses it (null: not mapped, use copies)
   PinLayout pl{};
+  void* scratch_dev = nullptr;  // this device's address of the static scratch array (ad_verify_static)
   char err[320] = "";
   // host mirror of the decode state
   int B = 0;
@@ -441,6 +461,8 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   if ((e = hipHostMalloc((void**)&c->pin, c->pl.total * 4, hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
     return bail("hipHostMalloc", e);
   memset(c->pin, 0, c->pl.total * 4);
+  // this device's copy of the static scratch array (ad_verify_static); looked up once per device
+  c->scratch_dev = static_scratch_for_current_device();
   {
     void* dp = nullptr;
     if (hipHostGetDevicePointer(&dp, c->pin, 0) == hipSuccess) c->pin_dev = (int32_t*)dp;
@@ -640,7 +662,7 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
 
 // What a verify call's launches need beyond the context: where the device reads k and the draft,
 // where the acceptance kernel puts the result, whether it posts the call's ticket, and where the
-// arg-max partials of the output projection live.
+// arg-max partials of the output projection live (the workspace's, or the static scratch array).
 struct VerifyLaunch {
   const int* k_src;
   const int* draft_src;
@@ -693,8 +715,11 @@ static void verify_launches(ad_ctx* c, const VerifyLaunch& v) {
   accept(c->at<float>(p.o_val), c->at<int>(p.o_hat), 1, 1, gp);
 }
 
+// ad_verify and its no-allocation variant.  static_scratch: the arg-max partials go to the
+// library's static device array, every launch is made eagerly (no graph is built or replayed) and
+// nothing on the way allocates.
 static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
-                       int32_t* verified) {
+                       int32_t* verified, bool static_scratch) {
   if (!c) return fail(nullptr, AD_EINVAL, "null context");
   if (!draft || !k || !n_accept || !next_token) return fail(c, AD_EINVAL, "null buffer");
   if (!c->encoded[AD_VERIFIER]) return fail(c, AD_ESTATE, "ad_verify before ad_encode(AD_VERIFIER)");
@@ -713,6 +738,11 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
     }
     M += k[b];
     max_rows = std::max(max_rows, (int)k[b]);
+  }
+  if (static_scratch) {
+    if (!c->scratch_dev) return fail(c, AD_ESTATE, "the static scratch array is unavailable on this device");
+    if ((size_t)M * p.n_strips * 8 > kStaticScratchBytes)
+      return fail(c, AD_EINVAL, "ad_verify_static: rows x (vocab / 16) x 8 bytes exceed the static scratch array (4 MiB)");
   }
   if (M == 0) {
     for (int b = 0; b < B; ++b) { n_accept[b] = 0; next_token[b] = 0; }
@@ -734,8 +764,13 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
     HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + pl.draft, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));
     v.k_src = c->at<int>(p.k_dev); v.draft_src = c->at<int>(p.draft_dev); v.result_dst = c->at<int>(p.result);
   }
-  v.part_val = c->at<float>(p.part_val);
-  v.part_idx = c->at<int>(p.part_idx);
+  if (static_scratch) {
+    v.part_val = (float*)c->scratch_dev;
+    v.part_idx = (int*)((char*)c->scratch_dev + kStaticScratchBytes / 2);
+  } else {
+    v.part_val = c->at<float>(p.part_val);
+    v.part_idx = c->at<int>(p.part_idx);
+  }
   v.part_stride = p.n_strips;
   c->fw_nseq = B;
   c->fw_max_rows = max_rows;
@@ -759,7 +794,7 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
   // context's life
   const bool gadpp = c->gadpp_beta > 1;
   bool launched = false;
-  if (mapped) {
+  if (mapped && !static_scratch) {
     const unsigned long long key = shape_key(M, max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0));
     unsigned tau_bits;
     memcpy(&tau_bits, &c->gadpp_tau, 4);
@@ -817,7 +852,12 @@ extern "C" {
 
 int ad_verify(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
               int32_t* verified) {
-  return verify_call(c, draft, k, n_accept, next_token, verified);
+  return verify_call(c, draft, k, n_accept, next_token, verified, false);
+}
+
+int ad_verify_static(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_t* n_accept, int32_t* next_token,
+                     int32_t* verified) {
+  return verify_call(c, draft, k, n_accept, next_token, verified, true);
 }
 
 int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
