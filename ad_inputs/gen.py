@@ -25,6 +25,8 @@ DIMS = {
     # small model of the same asymmetry for parity tests
     "deep_shallow": dict(enc_layers=12, dec_layers=2, d_model=1024, n_heads=16, d_ffn=4096, vocab=32000),
     "tiny_deep": dict(enc_layers=3, dec_layers=1, d_model=128, n_heads=4, d_ffn=512, vocab=2000),
+    # heads of width 128 (the widest the attention kernels take)
+    "wide_head": dict(enc_layers=2, dec_layers=2, d_model=256, n_heads=2, d_ffn=512, vocab=2000),
     # small shapes for brute-force tests of the invariant
     "nano": dict(enc_layers=1, dec_layers=1, d_model=16, n_heads=2, d_ffn=32, vocab=8),
     "micro": dict(enc_layers=1, dec_layers=2, d_model=32, n_heads=2, d_ffn=64, vocab=64),

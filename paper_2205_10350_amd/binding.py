@@ -6,8 +6,11 @@ There is no fallback: if the library is missing this module raises on import of 
 """
 from __future__ import annotations
 
+import atexit
 import ctypes as C
 import os
+import sys
+import weakref
 
 import numpy as np
 
@@ -216,8 +219,25 @@ def calibration_mfma(iters=4000, stream=None):
     return t.value
 
 
+# Contexts that are still open.  They are closed by an atexit hook, i.e. at the very start of the
+# interpreter's shutdown, while the HIP runtime, torch and any profiler tool are still fully
+# alive: ad_destroy synchronizes the stream and destroys graphs and events, which must not happen
+# from a finalizer that runs after those libraries have begun to tear themselves down.
+_live = weakref.WeakSet()
+
+
+@atexit.register
+def _close_all():
+    for ctx in list(_live):
+        try:
+            ctx.close()
+        except Exception:
+            pass
+
+
 class Context:
-    """One ad_ctx with its device memory.  Methods mirror the C entry points."""
+    """One ad_ctx with its device memory.  Methods mirror the C entry points.  Also a context
+    manager: `with Context(...) as ctx:` closes it on the way out."""
 
     def __init__(self, cfg: AdConfig, verifier_params: dict, drafter_params: dict | None = None, device="cuda:0"):
         import torch
@@ -241,13 +261,27 @@ class Context:
                                 C.c_void_p(self.stream.cuda_stream), C.byref(h)))
         self.h = h
         self.B = 0
+        _live.add(self)
 
     def close(self):
         if getattr(self, "h", None):
             self.L.ad_destroy(self.h)
             self.h = None
+        _live.discard(self)
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+        return False
 
     def __del__(self):
+        # never from interpreter shutdown: by then the atexit hook has closed every context, and a
+        # context it could not reach is left to the process's end rather than to a HIP call
+        # made while the runtime is going away
+        if sys.is_finalizing():
+            return
         try:
             self.close()
         except Exception:

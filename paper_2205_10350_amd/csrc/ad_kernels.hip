@@ -92,95 +92,6 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   strip_epilogue<bf16_t, MT>(e, acc, MT, m0, n0, M, N, lane);
 }
 
-// ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows
-// The same product for M >= 128 rows, where the weight-streaming kernel above would re-read
-// every operand from the L2: 128 x 128 output tile per workgroup, four waves of 64 x 64
-// (4 x 4 MFMA tiles each), k walked 32 at a time through a three-stage LDS ring.  Both operands
-// reach LDS by loads that write it directly, one 1 KB operand fragment per instruction, already
-// in the order the MFMA reads back (A: lane l = row l%16, k-group l/16 of a 16-row tile; B: the
-// stored weight tile as is).  Per step a wave issues four such loads (two A tiles, two B strips)
-// and reads eight fragments for sixteen MFMAs.  Each output element still sums k ascending 32
-// at a time into one accumulator: bit-identical to the kernel above.
-// The ring's stages are separate arrays and the k loop is unrolled by the ring size, so that the
-// compiler can tell a stage being filled from the stage being read (it would otherwise wait for
-// every outstanding fill before each LDS read).
-template <int STEP_MOD>
-__device__ __forceinline__ void tiled_issue(char* st, const bf16_t* const (&ga)[2], const bf16_t* const (&gb)[2], int step,
-                                            int wave) {
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    __builtin_amdgcn_global_load_lds((const AD_GLOBAL void*)(ga[j] + step * 32),
-                                     (__attribute__((address_space(3))) void*)(st + (2 * wave + j) * 1024), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const AD_GLOBAL void*)(gb[j] + step * 512),
-                                     (__attribute__((address_space(3))) void*)(st + 8192 + (2 * wave + j) * 1024), 16, 0, 0);
-  }
-}
-__device__ __forceinline__ void tiled_compute(const char* st, int wm, int wn, int lane, f32x4 (&acc)[4][4]) {
-  uint4 af[4], bf[4];
-#pragma unroll
-  for (int t = 0; t < 4; ++t) af[t] = *(const uint4*)(st + (wm * 4 + t) * 1024 + lane * 16);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) bf[j] = *(const uint4*)(st + 8192 + (wn * 4 + j) * 1024 + lane * 16);
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-      acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, bf[j]),
-                                                         acc[j][t], 0, 0, 0);
-}
-__global__ __launch_bounds__(256, 2) void k_gemm_bf16_tiled(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                            int M, int N, int K, Epi e) {
-  __shared__ __attribute__((aligned(1024))) char ring0[16 * 1024];   // [A | B][fragment][1 KB]
-  __shared__ __attribute__((aligned(1024))) char ring1[16 * 1024];
-  __shared__ __attribute__((aligned(1024))) char ring2[16 * 1024];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
-  const int n_strips = N >> 4;
-  const int strip0 = blockIdx.x * 8, m0 = blockIdx.y * 128;
-  const int nk = K >> 5;
-  // this wave's share of the loads of a step: A tiles 2*wave, 2*wave+1; B strips 2*wave, 2*wave+1
-  // (rows past M and strips past N are clamped to valid ones: never stored, but every wave
-  // issues exactly four loads per step, which the waits below count on)
-  const bf16_t* ga[2];
-  const bf16_t* gb[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int row = min(m0 + (2 * wave + j) * 16 + (lane & 15), M - 1);
-    ga[j] = A + (size_t)row * K + (lane >> 4) * 8;
-    const int strip = min(strip0 + 2 * wave + j, n_strips - 1);
-    gb[j] = W + (size_t)(strip << 4) * K + lane * 8;
-  }
-  f32x4 acc[4][4];   // [strip j][row tile t]
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int t = 0; t < 4; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  tiled_issue<0>(ring0, ga, gb, 0, wave);
-  if (nk > 1) tiled_issue<1>(ring1, ga, gb, 1, wave);
-  // Step k: its fragments have landed (this wave's; the barrier covers the others') while step
-  // k+1's four loads may still be in flight; the stage of step k+2 was read in step k-1, which
-  // every wave has finished once it is past the barrier.
-#define AD_TILED_STEP(KK, CUR, NXT2)                                                  \
-  if ((KK) < nk) {                                                                    \
-    if ((KK) + 1 < nk) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");               \
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                             \
-    __builtin_amdgcn_s_barrier();                                                     \
-    if ((KK) + 2 < nk) tiled_issue<0>(NXT2, ga, gb, (KK) + 2, wave);                  \
-    tiled_compute(CUR, wm, wn, lane, acc);                                            \
-  }
-  for (int k = 0; k < nk; k += 3) {
-    AD_TILED_STEP(k, ring0, ring2)
-    AD_TILED_STEP(k + 1, ring1, ring0)
-    AD_TILED_STEP(k + 2, ring2, ring1)
-  }
-#undef AD_TILED_STEP
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int strip = strip0 + wn * 4 + j;
-    if (strip < n_strips) strip_epilogue<bf16_t, 4>(e, acc[j], 4, m0 + wm * 64, strip << 4, M, N, lane);
-  }
-}
-
 // ------------------------------------------------------------------------------------- bf16 MFMA GEMM, many rows, K a multiple of 512
 // A stays put, weights stream: a workgroup stages MT*16 rows of A (all K) in LDS once and then
 // walks a run of 16-column strips, each wave SP strips at a time (two where rows are many and
@@ -623,7 +534,6 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
   if (ln.x && a_written) *a_written = false;
   if (dtype == AD_BF16) {
     const int nb = (N / 16 + 3) / 4;
-    const int tiles_x = (N / 16 + 7) / 8, tiles_y = (M + 127) / 128;
     if (K <= 4096 && K % 512 == 0) {
       const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
       // Few rows (measured: up to 64 for the wide output projection, up to 1024 for the layer
@@ -687,10 +597,6 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
         if (c2 <= c1) return launch_astat<2, 2>(a, w, M, N, K, e, pw[1], s, ln);
         return launch_astat<1, 2>(a, w, M, N, K, e, pw[0], s, ln);
       }
-    }
-    if (M >= 128 && tiles_x * tiles_y >= 96) {
-      k_gemm_bf16_tiled<<<dim3(tiles_x, tiles_y), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);
-      return N / 16;
     }
     if (M <= 16)
       k_gemm_bf16<1><<<dim3(nb, 1), 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)W, M, N, K, e);
