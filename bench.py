@@ -10,10 +10,11 @@ verify forward with fused output projection / arg max, prefix match, accept, rol
 until the output is complete.  Value = emitted tokens per second over the timed steps; every
 emitted sequence is checked to be identical to greedy decoding on the same kernels.
 
-Also reported in the same JSON line: the verify forward's share of the HBM roofline at batch
-1 and of the bf16 MFMA roofline at batch 32 (first-iteration shape), the roofline of the
-dominant kernel (output projection + arg max, a weight-streaming HBM-bound kernel), and the
-CPU oracle timed on this machine's host cores on a bounded sample.
+Also reported in the same JSON line: `roofline`, the verify forward at batch 1 against the HBM
+roofline (its algorithmic bytes over its measured duration), `roofline_bs32`, the verify forward
+at batch 32 (first-iteration shape) against the bf16 MFMA roofline, the figures of the largest
+single kernel (output projection + arg max) under `vocab_kernel`, and the CPU oracle timed on
+this machine's host cores on a bounded sample.
 """
 import argparse
 import json
@@ -31,7 +32,8 @@ MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 # HBM bytes per launch of the output-projection kernel at the headline shape (base model, 17..32
 # rows), from two rocprofv3 --pmc runs of this file (FETCH_SIZE 16336.9 KiB x 2.000, WRITE_SIZE
 # 482.7 KiB x 1.0; factors from k_calibration_copy's readings for a 256 MiB copy in the same runs;
-# profiles/bench_base_bs1_vocab_kernel_hbm_traffic.md)
+# profiles/bench_base_bs1_vocab_kernel_hbm_traffic.md): a figure of an earlier counter run, quoted
+# under `vocab_kernel.traffic_from_profile`, not a reading of this run
 VOCAB_KERNEL_TRAFFIC_BYTES = int(16336.9 * 1024 * (262144.0 / 131083.0) + 482.7 * 1024)
 
 
@@ -109,6 +111,13 @@ def main():
 
     for i in range(args.warmup):
         step(i)
+    # Every call shape of the timed sentences is replayed from a captured graph in the timed region
+    # whatever --warmup says: a graph is built on a shape's third appearance, so each timed sentence
+    # is decoded three times beforehand (untimed).
+    if not args.no_graphs:
+        for rep in range(3):
+            for i in range(min(args.steps, n_sent)):
+                step(i)
     torch.cuda.synchronize()
     toks = its = rows = 0
     t0 = time.perf_counter()
@@ -127,51 +136,44 @@ def main():
     draft = (list(guides[j]) + [ad.AD_NEVER])[:int(max_out[j])]
     ctx.verify([draft])
     M1 = len(draft)
-    fwd_us, voc_us = ctx.time_verify_forward(50)
     params = decoder_stream_params(dims)
     kv_bytes = dims["dec_layers"] * 2 * 2 * dims["d_model"] * (M1 + len(srcs[j]))
     fwd_bytes = 2 * params + kv_bytes
-    fused_rows = ctx.get_option(ad.AD_OPT_FUSED_ROWS)
-    fused = fused_rows >= M1
-    # the same forward as one launch per stage, for the output-projection kernel's own figure
-    ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
-    ctx.encode(ad.AD_VERIFIER, [srcs[j]], max_out=[max_out[j]])
-    ctx.verify([draft])
-    staged_us, voc_us, voc_b2b_us = ctx.time_verify_forward(50, back_to_back=True)
-    # the same kernel reading its matrix from 12 rotating copies (393 MB, more than the 256 MB last-level
-    # cache holds): every launch streams from HBM.  In the decode loop the base model's 77 MB of weights
-    # stay in that cache from one forward to the next, which is what the back-to-back figure measures.
+    fwd_us, voc_us, voc_b2b_us = ctx.time_verify_forward(50, back_to_back=True)
+    # the output-projection kernel reading its matrix from 12 rotating copies (393 MB, more than the
+    # 256 MB last-level cache holds): every launch streams from HBM.  In the decode loop the base
+    # model's 77 MB of weights stay in that cache from one forward to the next, which is what the
+    # back-to-back figure measures.
     voc_cold_us = ctx.time_output_projection(12, 48)
-    ctx.set_option(ad.AD_OPT_FUSED_ROWS, fused_rows)
     # output projection + arg max: the [V, d] bf16 matrix once, the M x d bf16 rows once, the
     # per-row partial maxima written once
     voc_bytes = 2 * V * dims["d_model"] + 2 * M1 * dims["d_model"] + 8 * M1 * ((V // 16 + 7) // 8)
-    if fused:
-        # dominant kernel = the persistent forward itself (one launch per verify call).  Algorithmic
-        # bytes per launch: every decoder weight the forward streams, once, plus the KV rows read.
-        roofline = {"bound": "hbm", "kernel": "k_fused_forward (whole verify forward, one launch)", "rows": M1,
-                    "achieved": fwd_bytes / (fwd_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                    "frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "traffic": None}
-    else:
-        # dominant kernel by bytes: the output projection + arg max (42 % of the forward's
-        # algorithmic bytes).  Average launch duration = 50 launches back to back between two HIP
-        # events on the kernel's stream / 50 (a single launch bracketed by two events inside a
-        # forward reads 3-4 us more, the cost of the two event records: staged_vocab_kernel_us).
-        roofline = {"bound": "hbm", "kernel": "k_gemm_bf16_astat<1, 1, 1, true> (output projection + arg max)", "rows": M1,
-                    "achieved": voc_bytes / (voc_b2b_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                    "frac": voc_bytes / (voc_b2b_us * 1e-6) / HBM_PEAK, "traffic": VOCAB_KERNEL_TRAFFIC_BYTES,
-                    "weights_resident_in": "256 MB last-level cache between launches (as in the decode loop)",
-                    "cold_us": voc_cold_us, "cold_achieved": voc_bytes / (voc_cold_us * 1e-6) / 1e9,
-                    "cold_frac": voc_bytes / (voc_cold_us * 1e-6) / HBM_PEAK}
+    n_launches = 3 + dims["dec_layers"] * 7   # embedding, seven per decoder layer, output projection, arg-max finish
+    # The path's roofline: one verify forward (embedding, six decoder layers, output projection with
+    # the fused arg max and its finish) at the first-iteration shape of a typical sentence.
+    # achieved = algorithmic bytes (every decoder weight the forward streams, once, plus the key /
+    # value rows read) over the forward's duration: HIP events on the library's stream around 50
+    # forwards launched back to back, / 50.
+    roofline = {"bound": "hbm", "kernel": f"verify forward, base model, batch 1 ({n_launches} launches per forward)",
+                "rows": M1, "us": fwd_us, "algorithmic_bytes": fwd_bytes,
+                "achieved": fwd_bytes / (fwd_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "traffic": None}
+    # the largest single kernel of that forward (42 % of its algorithmic bytes), context only.
+    # `frac` = the matrix streamed from HBM on every launch; the figure with the matrix resident in
+    # the last-level cache between launches (as it is in the decode loop) under its own name
+    vocab_kernel = {"kernel": "k_gemm_bf16_astat<1, 1, 1, true> (output projection + arg max)", "rows": M1,
+                    "algorithmic_bytes": voc_bytes, "us": voc_cold_us,
+                    "achieved": voc_bytes / (voc_cold_us * 1e-6) / 1e9, "frac": voc_bytes / (voc_cold_us * 1e-6) / HBM_PEAK,
+                    "llc_resident_us": voc_b2b_us, "llc_resident_achieved": voc_bytes / (voc_b2b_us * 1e-6) / 1e9,
+                    "llc_resident_frac_of_hbm_peak": voc_bytes / (voc_b2b_us * 1e-6) / HBM_PEAK,
+                    "bracketed_in_forward_us": voc_us,
+                    "traffic_from_profile": VOCAB_KERNEL_TRAFFIC_BYTES}
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,
-                  "hbm_frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "single_launch": bool(fused),
-                  "staged_launches_us": staged_us, "staged_vocab_kernel_us": voc_us,
-                  "staged_vocab_kernel_back_to_back_us": voc_b2b_us,
-                  "staged_vocab_kernel_back_to_back_hbm_frac": voc_bytes / (voc_b2b_us * 1e-6) / HBM_PEAK,
-                  "staged_vocab_kernel_hbm_frac": voc_bytes / (voc_us * 1e-6) / HBM_PEAK}
+                  "hbm_frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "launches": n_launches}
 
     # ---------------- batch 32 ---------------------------------------------------------------------
     bs32 = None
+    roofline_bs32 = None
     if not args.no_bs32:
         srcs2, max_out2 = draw_sources(cfg2, V)
         B = cfg2["batch"]
@@ -200,25 +202,22 @@ def main():
         drafts = [(list(g) + [ad.AD_NEVER])[:int(m)] for g, m in zip(gd2[0], mo)]
         ctx.verify(drafts)
         M32 = sum(len(d) for d in drafts)
-        fwd32_us, _ = ctx.time_verify_forward(20)
-        fused32 = ctx.get_option(ad.AD_OPT_FUSED_ROWS) >= M32
-        # the same forward as one launch per stage (the output-projection kernel can be timed alone there)
-        ctx.set_option(ad.AD_OPT_FUSED_ROWS, 0)
-        ctx.encode(ad.AD_VERIFIER, ss, max_out=mo)
-        ctx.verify(drafts)
-        staged32_us, voc32_us = ctx.time_verify_forward(20)
-        ctx.set_option(ad.AD_OPT_FUSED_ROWS, fused_rows)
+        fwd32_us, voc32_us = ctx.time_verify_forward(20)
         flops = 2.0 * M32 * params
         bs32 = {"tokens_per_s": toks2 / dt2, "greedy_tokens_per_s": sum(len(x) for o in g2 for x in o) / t_g2,
                 "iterations": its2, "rows_verified": rows2,
-                "verify_rows": M32, "verify_us": fwd32_us, "single_launch": bool(fused32), "verify_gflop": flops / 1e9,
+                "verify_rows": M32, "verify_us": fwd32_us, "verify_gflop": flops / 1e9,
                 "mfma_frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK,
                 # all iterations of the decode (rows shrink as the guides are consumed): flops of every row
                 # verified over the whole decode's wall time, encoder and host included
                 "decode_mean_rows": rows2 / max(1, its2),
                 "decode_mfma_frac": 2.0 * rows2 * params / dt2 / MFMA_BF16_PEAK,
-                "staged_launches_us": staged32_us, "staged_vocab_kernel_us": voc32_us,
-                "staged_vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
+                "vocab_kernel_us": voc32_us,
+                "vocab_kernel_mfma_frac": 2.0 * M32 * V * dims["d_model"] / (voc32_us * 1e-6) / MFMA_BF16_PEAK}
+        roofline_bs32 = {"bound": "mfma", "kernel": f"verify forward, base model, batch 32 ({n_launches} launches per forward)",
+                         "rows": M32, "us": fwd32_us, "algorithmic_flops": flops,
+                         "achieved": flops / (fwd32_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                         "frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK, "traffic": None}
     # ---------------- verify forward against block size and batch size (roofline against rows) -------
     sweeps = None
     if not args.no_next:
@@ -364,24 +363,34 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ad_oracle as O
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count()
+        from threadpoolctl import threadpool_info, threadpool_limits
+        pools = threadpool_info()
+        cores = max([p.get("num_threads", 1) for p in pools] + [1])
+        blas = ", ".join(sorted({f"{p.get('internal_api', '?')} {p.get('version', '')}".strip() for p in pools
+                                 if p.get("user_api") == "blas"})) or "numpy's BLAS"
         m = O.Model(dims, w, np.float32, max_pos=160)
         n_cpu = min(args.cpu_sentences, n_sent)
         og = [O.greedy(m, srcs[i], int(max_out[i]), SPECIAL["eos"], SPECIAL["bos"]) for i in range(n_cpu)]
         ogd = [edit_guide(g, cfg1["rate"], cfg1["seed"] + i, V) for i, g in enumerate(og)]
-        t0 = time.perf_counter()
-        ctoks = 0
-        for i in range(n_cpu):
-            o, _ = O.iad(m, srcs[i], ogd[i], int(max_out[i]), SPECIAL["eos"], SPECIAL["bos"], k_max=K_MAX)
-            ctoks += len(o)
-        cdt = time.perf_counter() - t0
+
+        def run_cpu(n):
+            t0 = time.perf_counter()
+            ct = 0
+            for i in range(n):
+                o, _ = O.iad(m, srcs[i], ogd[i], int(max_out[i]), SPECIAL["eos"], SPECIAL["bos"], k_max=K_MAX)
+                ct += len(o)
+            return ct, time.perf_counter() - t0
+
+        ctoks, cdt = run_cpu(n_cpu)
+        # the same oracle with the BLAS held to one thread, on a quarter of the sample
+        n_one = max(1, n_cpu // 4)
+        with threadpool_limits(limits=1):
+            c1toks, c1dt = run_cpu(n_one)
         cpu = {"value": ctoks / cdt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"first {n_cpu} sentences of the batch-1 workload, numpy float32 oracle, input-guided "
-                         f"decoding incl. encoder ({cdt:.1f} s)"}
+               "value_1_thread": c1toks / c1dt,
+               "sample": f"first {n_cpu} sentences of the batch-1 workload, numpy float32 oracle on {blas} with "
+                         f"{cores} threads, input-guided decoding incl. encoder ({cdt:.1f} s); one-thread figure on the "
+                         f"first {n_one} sentences ({c1dt:.1f} s)"}
 
     line = {
         "metric": "greedy_identical_tokens_per_s", "value": value, "unit": "tokens/s", "n_gpus": 1,
@@ -389,7 +398,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "Transformer-base IAD batch 1 (configs[1]): 6+6 layers, d512, 8 heads, FFN 2048, "
                                "vocab 32000, source len ~N(25,8) in [5,64], guide = greedy output + edits 0.1",
-                   "batch": 1, "sentences": n_sent, "k_max": K_MAX},
+                   "batch": 1, "sentences": min(args.steps, n_sent), "k_max": K_MAX},
         "tokens": toks, "verify_forwards": its, "rows_verified": rows,
         "mean_tokens_per_forward": toks / max(1, its), "mean_rows_per_forward": rows / max(1, its),
         # weights streamed by all verify forwards of the timed decode over its wall time (encoder, host included)
@@ -397,7 +406,8 @@ def main():
         "greedy_tokens_per_s": greedy_tps, "speedup_vs_greedy": value / greedy_tps,
         "verify_forward_bs1": verify_bs1, "bs32": bs32, "gad": gad, "sweeps": sweeps, "deep_encoder": deep,
         "measured_copy_GBps": copy_gbps, "measured_mfma_bf16_TFLOPs": mfma_tflops,
-        "roofline": roofline, "cpu_baseline": cpu,
+        "vocab_kernel": vocab_kernel,
+        "roofline": roofline, "roofline_bs32": roofline_bs32, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
 
