@@ -252,8 +252,14 @@ int ad_calibration_mfma(void* scratch_dev, size_t scratch_bytes, int32_t iters, 
  * AD_OPT_FUSE_CROSSQ (0/1, default 1): a decoder layer's
  * cross-attention runs its query projection and the attention as one launch (bf16, head width 64,
  * model width 512 or 1024; other shapes take two launches whatever the setting).  Same results bit
- * for bit either way. */
-enum { AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5, AD_OPT_FUSE_CROSSQ = 6 };
+ * for bit either way.
+ * AD_OPT_OVERLAP_ENCODERS (0/1, default 1 in contexts with a drafter whose stream is not the null
+ * stream; elsewhere 0 and switching it on gives AD_ESTATE): ad_encode(AD_DRAFTER) that follows
+ * ad_encode(AD_VERIFIER) runs on a second stream of the library's own (default priority), in a
+ * second block of activation buffers, beside the verifier's encoder instead of behind it; the
+ * first ad_draft_nat makes the context's stream wait for it.  Same results bit for bit. */
+enum { AD_OPT_GRAPHS = 3, AD_OPT_GRAPHS_CAPTURED = 4, AD_OPT_SPIN_WAIT = 5, AD_OPT_FUSE_CROSSQ = 6,
+       AD_OPT_OVERLAP_ENCODERS = 7 };
 int ad_set_option(ad_ctx* ctx, int option, int value);
 int ad_get_option(ad_ctx* ctx, int option, int* value);
 

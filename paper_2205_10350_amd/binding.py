@@ -33,6 +33,7 @@ AD_OPT_GRAPHS = 3
 AD_OPT_GRAPHS_CAPTURED = 4
 AD_OPT_SPIN_WAIT = 5
 AD_OPT_FUSE_CROSSQ = 6
+AD_OPT_OVERLAP_ENCODERS = 7
 
 
 class AdConfig(C.Structure):

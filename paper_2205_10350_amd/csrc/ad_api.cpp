@@ -40,6 +40,10 @@ struct Plan {
   int n_strips = 0;
   int max_pos = 0;
   size_t kv_w[2], kv_b[2];   // per model: cross-attention [wk; wv] of every decoder layer as one matrix, and its bias
+  // [act_begin, act_end): what one forward pass works in (rows, row tables, descriptors); with a
+  // drafter a second block of the same layout lies act2_shift bytes further on, for the drafter's
+  // encoder running beside the verifier's on a stream of its own
+  size_t act_begin = 0, act_end = 0, act2_shift = 0;
   size_t pe, x, s, xa, q, att, tk, tv, f, part_val, part_idx, o_hat, o_val, logits, draft_lp, draft_col;
   size_t cache_k, cache_v, cache_layer_stride;          // [NL][B*l_cap, d]
   size_t mem_k[2], mem_v[2], mem_layer_stride;          // per model: [NL][B*max_src, d]
@@ -61,6 +65,7 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   p.pe = take((size_t)p.max_pos * d * 4);
+  p.act_begin = off;
   p.x = take(m * d * 4);
   p.s = take(m * d * 4);
   p.xa = take(m * d * p.esz);
@@ -69,6 +74,17 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
   p.tk = take(m * d * p.esz);
   p.tv = take(m * d * p.esz);
   p.f = take(m * (size_t)c.d_ffn * p.esz);
+  p.row_tok = take(m * 4); p.row_pos = take(m * 4); p.row_seq = take(m * 4); p.row_dst = take(m * 4); p.row_dst2 = take(m * 4);
+  p.row_start = take((B + 1) * 4);
+  p.self_desc = take(2 * B * sizeof(SeqDesc));    // the drafter has two per sequence (mask rows, prefix rows)
+  p.cross_desc = take(2 * B * sizeof(SeqDesc));
+  p.act_end = off;
+  if (with_drafter) {
+    // the second block needs room for an encoder forward only: the same layout scaled would do, the
+    // same size is simpler
+    p.act2_shift = p.act_end - p.act_begin;
+    off += p.act2_shift;
+  }
   p.part_val = take((size_t)p.mv_cap * p.n_strips * 4);
   p.part_idx = take((size_t)p.mv_cap * p.n_strips * 4);
   p.o_hat = take((size_t)p.mv_cap * 4);
@@ -88,10 +104,6 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
     p.kv_w[i] = take(on ? (size_t)c.dec_layers * 2 * d * d * p.esz : 0);
     p.kv_b[i] = take(on ? (size_t)c.dec_layers * 2 * d * 4 : 0);
   }
-  p.row_tok = take(m * 4); p.row_pos = take(m * 4); p.row_seq = take(m * 4); p.row_dst = take(m * 4); p.row_dst2 = take(m * 4);
-  p.row_start = take((B + 1) * 4);
-  p.self_desc = take(2 * B * sizeof(SeqDesc));    // the drafter has two per sequence (mask rows, prefix rows)
-  p.cross_desc = take(2 * B * sizeof(SeqDesc));
   p.len = take(B * 4); p.pending = take(B * 4); p.finished = take(B * 4); p.max_out = take(B * 4);
   p.out = take(B * c.max_len * 4);
   p.result = take(B * 2 * 4);   // [B,2] results
@@ -197,7 +209,16 @@ struct ad_ctx {
   std::map<GraphKey, int> graph_seen;
   std::vector<int> last_k;       // k[b] of the last verify call
 
-  template <typename T> T* at(size_t off) const { return (T*)(ws + off); }
+  // the drafter's encoder beside the verifier's: a stream of the library's own (default priority),
+  // the second activation block, and the two events that order it against the context's stream
+  hipStream_t stream2 = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_enc2 = nullptr;
+  bool overlap_encoders = false, fork_recorded = false, enc2_pending = false;
+  size_t act_shift = 0;          // 0, or plan.act2_shift while a forward works in the second block
+
+  template <typename T> T* at(size_t off) const {
+    return (T*)(ws + off + ((off >= plan.act_begin && off < plan.act_end) ? act_shift : 0));
+  }
 };
 
 // (messages go into fixed buffers: reporting an error allocates nothing)
@@ -450,8 +471,9 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   c->last_k.assign(B, 0);
   auto bail = [&](const char* what, hipError_t e) {
     if (c->pin) (void)hipHostFree(c->pin);
-    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1]})
+    for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1], c->ev_fork, c->ev_enc2})
       if (ev) (void)hipEventDestroy(ev);
+    if (c->stream2) (void)hipStreamDestroy(c->stream2);
     delete c;
     return fail_hip(nullptr, what, e);
   };
@@ -474,6 +496,18 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
   if ((e = hipEventCreate(&c->ev3)) != hipSuccess) return bail("hipEventCreate", e);
   for (int i = 0; i < 2; ++i)
     if ((e = hipEventCreateWithFlags(&c->ev_up[i], hipEventDisableTiming)) != hipSuccess) return bail("hipEventCreate", e);
+  if (c->has_drafter && c->stream != nullptr) {
+    // the drafter's encoder runs beside the verifier's (both are needed before the first draft and
+    // neither depends on the other): a second stream at the default priority; if it cannot be had
+    // the two encoders simply run one after the other on the context's stream
+    if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) == hipSuccess &&
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess &&
+        hipEventCreateWithFlags(&c->ev_enc2, hipEventDisableTiming) == hipSuccess) {
+      c->overlap_encoders = true;
+    } else {
+      (void)hipGetLastError();
+    }
+  }
   // sinusoidal positions: PE(p, 2i) = sin(p / 10000^(2i/d)), PE(p, 2i+1) = cos(same)
   {
     const int d = cfg->d_model;
@@ -508,11 +542,13 @@ int ad_create(const ad_config* cfg, const void* verifier_w, const void* drafter_
 
 int ad_destroy(ad_ctx* c) {
   if (!c) return AD_EINVAL;
+  if (c->stream2) (void)hipStreamSynchronize(c->stream2);
   (void)hipStreamSynchronize(c->stream);
   if (c->pin) (void)hipHostFree(c->pin);
   for (auto& kv : c->graphs) (void)hipGraphExecDestroy(kv.second);
-  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1]})
+  for (hipEvent_t ev : {c->ev0, c->ev1, c->ev2, c->ev3, c->ev_up[0], c->ev_up[1], c->ev_fork, c->ev_enc2})
     if (ev) (void)hipEventDestroy(ev);
+  if (c->stream2) (void)hipStreamDestroy(c->stream2);
   delete c;
   return AD_OK;
 }
@@ -579,6 +615,26 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
   const ad_config& cf = c->cfg;
   const Plan& p = c->plan;
   const int d = cf.d_model, S = cf.max_src;
+  // The two encoders of a draft-then-verify decode side by side (their forwards are independent and
+  // both are needed before the first draft): the verifier's encode marks the point of the
+  // context's stream it starts at; the drafter's encode that follows runs on the library's second
+  // stream, in the second activation block, behind that mark only (i.e. behind everything that
+  // read the drafter's previous memory, not behind the verifier's encoder), and the first
+  // ad_draft_nat makes the context's stream wait for it.
+  struct SideGuard {   // the context's stream / activation block for the length of this call
+    ad_ctx* c; hipStream_t main; bool on;
+    ~SideGuard() { if (on) { c->stream = main; c->act_shift = 0; } }
+  } side{c, c->stream, false};
+  if (c->overlap_encoders && model == AD_VERIFIER) {
+    HIP_TRY(c, hipEventRecord(c->ev_fork, c->stream));
+    c->fork_recorded = true;
+  } else if (c->overlap_encoders && model == AD_DRAFTER && c->fork_recorded) {
+    HIP_TRY(c, hipStreamWaitEvent(c->stream2, c->ev_fork, 0));
+    c->fork_recorded = false;
+    side.on = true;
+    c->stream = c->stream2;
+    c->act_shift = p.act2_shift;
+  }
   // src_len[B], max_out[B], src[B, max_src] go into a part of the staging buffer that no other
   // call writes (one part per model).  The device reads them there (mapped memory) or gets them by
   // one copy; either way the call returns without waiting (what follows on the stream is ordered
@@ -638,8 +694,12 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
       gemm_rows(c, c->ws + p.kv_w[model], M, cf.dec_layers * 2 * d, e);
     }
   };
-  const unsigned long long key = (1ull << 63) | ((unsigned long long)model << 62) | shape_key(M, c->fw_max_rows, B, 0);
+  const unsigned long long key = (1ull << 63) | ((unsigned long long)model << 62) | shape_key(M, c->fw_max_rows, B, side.on ? 1 : 0);
   if (!run_as_graph(c, c->stream, key, launches)) launches();
+  if (side.on) {
+    HIP_TRY(c, hipEventRecord(c->ev_enc2, c->stream));
+    c->enc2_pending = true;
+  }
   if (mapped) {
     HIP_TRY(c, hipEventRecord(c->ev_up[model], c->stream));
     c->up_pending[model] = true;
@@ -870,6 +930,11 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
   const Plan& p = c->plan;
   if (k < 1 || k > cf.k_max) return fail(c, AD_EINVAL, "k outside [1, k_max]");
   const int B = c->B, km = cf.k_max;
+  if (c->enc2_pending) {
+    // the drafter's memory comes from the second stream
+    HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_enc2, 0));
+    c->enc2_pending = false;
+  }
   int M = 0, live = 0;
   for (int b = 0; b < B; ++b)
     if (!c->h_finished[b]) { M += c->h_len[b] + 1 + k; ++live; }
@@ -1095,6 +1160,13 @@ int ad_set_option(ad_ctx* c, int option, int value) {
     c->fuse_crossq = value != 0;
     return AD_OK;
   }
+  if (option == AD_OPT_OVERLAP_ENCODERS) {
+    if (value != 0 && value != 1) return fail(c, AD_EINVAL, "AD_OPT_OVERLAP_ENCODERS must be 0 or 1");
+    if (value && !c->stream2) return fail(c, AD_ESTATE, "no second stream (no drafter, or the context runs on the null stream)");
+    c->overlap_encoders = value != 0;
+    c->fork_recorded = false;
+    return AD_OK;
+  }
   return fail(c, AD_EINVAL, "unknown option");
 }
 int ad_get_option(ad_ctx* c, int option, int* value) {
@@ -1104,6 +1176,7 @@ int ad_get_option(ad_ctx* c, int option, int* value) {
   else if (option == AD_OPT_GRAPHS_CAPTURED) *value = (int)c->graphs.size();
   else if (option == AD_OPT_SPIN_WAIT) *value = c->spin_wait ? 1 : 0;
   else if (option == AD_OPT_FUSE_CROSSQ) *value = c->fuse_crossq ? 1 : 0;
+  else if (option == AD_OPT_OVERLAP_ENCODERS) *value = c->overlap_encoders ? 1 : 0;
   else return fail(c, AD_EINVAL, "unknown option");
   return AD_OK;
 }

@@ -212,3 +212,49 @@ def test_decodes_without_logits_equal_oracle_tokens():
     finally:
         dbg.close()
         prod.close()
+
+
+@pytest.mark.parametrize("name,B", [("tiny", 2), ("base", 1), ("base", 3)])
+def test_drafter_encoder_beside_the_verifier_encoder_equals_one_after_the_other(name, B):
+    """The two encoders of a draft-then-verify decode on two streams (the drafter's in a second
+    block of activation buffers) against the same two forwards back to back on one stream: the
+    drafter's logits and tokens bit for bit, whole decodes token for token, over several sentences in
+    a row (the next sentence's drafter encoder must wait for the previous sentence's drafts)."""
+    rig = Rig(name, "bf16", 77, B=B, max_src=48, max_len=40, k_max=8, drafter=True)
+    try:
+        assert rig.ctx.get_option(ad.AD_OPT_OVERLAP_ENCODERS) == 1
+        V = rig.dims["vocab"]
+        sents = [_sources(rig.dims, 770 + i, [40 - 5 * b - i for b in range(B)]) for i in range(4)]
+        res = {}
+        for overlap in (0, 1):
+            rig.ctx.set_option(ad.AD_OPT_OVERLAP_ENCODERS, overlap)
+            got = []
+            for rep in range(2):            # twice: the second pass replays the encoders' graphs
+                for srcs in sents:
+                    rig.ctx.encode(ad.AD_VERIFIER, srcs)
+                    rig.ctx.encode(ad.AD_DRAFTER, srcs)
+                    d1 = rig.ctx.draft_nat(8)
+                    l1 = rig.ctx.debug_logits()
+                    n, nx = rig.ctx.verify([list(map(int, d1[b])) for b in range(B)])
+                    d2 = rig.ctx.draft_nat(5)
+                    l2 = rig.ctx.debug_logits()
+                    out, st = rig.ctx.decode_gad(srcs, 8, use_drafter=True)
+                    got.append((d1.copy(), l1, n.copy(), nx.copy(), d2.copy(), l2, out, st["iterations"]))
+            res[overlap] = got
+        for a, b in zip(res[0], res[1]):
+            assert np.array_equal(a[0], b[0]) and np.array_equal(a[4], b[4])
+            assert np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+            assert np.array_equal(a[5].view(np.uint32), b[5].view(np.uint32))
+            assert np.array_equal(a[2], b[2]) and np.array_equal(a[3], b[3])
+            assert a[6] == b[6] and a[7] == b[7]
+        # and the drafter's first block against the oracle (the memory the second stream produced)
+        rig.ctx.set_option(ad.AD_OPT_OVERLAP_ENCODERS, 1)
+        srcs = sents[0]
+        rig.ctx.encode(ad.AD_VERIFIER, srcs); rig.ctx.encode(ad.AD_DRAFTER, srcs)
+        rig.ctx.draft_nat(8)
+        got = rig.ctx.debug_logits()
+        for i, s in enumerate(srcs):
+            want = rig.dr.decode_full(rig.dr.encode(s), [BOS] + [SPECIAL["mask"]] * 8, causal=False)[1:]
+            assert np.abs(got[8 * i:8 * i + 8] - want).max() < rig.tol
+    finally:
+        rig.close()
