@@ -107,9 +107,13 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
 // EPI_ARGMAX: one (value, column) partial per (row, workgroup) instead of one per strip.
 // A tile rows [row0, row0 + n_rows) of a workgroup from fp32 rows through LayerNorm (width
 // 256 * NV, the 16-byte rule of ln_load4 / ln_stats4), RB rows in flight at a time.
-template <int NV, int RB>
+// after_first_loads(): called once, when the wave's first batch of row loads has been issued:
+// whatever the caller wants in flight behind them.  Loads return in issue order, so what is
+// needed first (the rows: everything waits for the tile) is requested first.
+struct NoOp { __device__ __forceinline__ void operator()() const {} };
+template <int NV, int RB, typename F = NoOp>
 __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld, int row0, int n_rows, int m0, int M,
-                                               int lane, bool store_y) {
+                                               int lane, bool store_y, const F& after_first_loads = F{}) {
   constexpr int K = 256 * NV;
   float4 gv[NV], bv[NV];
 #pragma unroll
@@ -122,6 +126,7 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
 #pragma unroll
     for (int i = 0; i < RB; ++i)
       if (i0 + i < n_rows) ln_load4<false, NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
+    if (i0 == 0) after_first_loads();
     // statistics of all rows of the batch first (independent reduction chains the scheduler can
     // interleave), then the values, then, in the workgroups that keep them, the fp32 rows
     float mean[RB], rstd[RB];
@@ -196,23 +201,43 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
       w[j] = W + ((size_t)(min(s0 + j, s_end - 1) << 4) * K + (size_t)k0 * 16 + lane * 8);
   };
   uint4 b[SP][16];
-  {
+  // Unit 0 is requested right behind the wave's first row loads and is in flight while the rows are
+  // staged.  (Loads return in issue order: requested the other way round, the rows, which the
+  // whole workgroup waits for at the barrier below, would arrive behind 16 * SP KB of weights.)
+  auto prefetch0 = [&]() {
     const bf16_t* w[SP];
     unit_ptrs(0, w);
 #pragma unroll
     for (int u = 0; u < 16; ++u)
 #pragma unroll
       for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(w[j] + u * 512);
-  }
-  __builtin_amdgcn_sched_barrier(0);   // unit 0 is in flight while the rows are staged
+  };
+  // (The widest variants have no registers for the rows' staging values on top of the addresses
+  // this order keeps alive: they request the weights first, as the loop order has it.)
+  constexpr bool ROWS_FIRST = !(SP == 2 && MT >= 2);
+  if constexpr (!ROWS_FIRST) prefetch0();
+  auto behind_rows = [&]() { if constexpr (ROWS_FIRST) prefetch0(); };
   // stage the rows (past M: the last valid row, computed and never stored)
   if (ln.x) {
     // rows to be normalised first (K = 512 or 1024): the statistics and values of the LayerNorm
     // kernel; the workgroups of strip group 0 also store the fp32 rows
     // (the output projection is the last consumer of its rows: nobody needs them in fp32)
     const bool keep_y = group == 0 && AMAX == 0;
-    if (K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y);
-    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y);
+    if (K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
+    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
+  } else if (MT == 1 && !ONE && halves == 4) {
+    // few rows of K = 2048: every slice's loads before the weights
+    uint4 av[4][4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        av[h][i] = *(const uint4*)(A + (size_t)min(m0 + wave * 4 + i, M - 1) * K + h * 512 + lane * 8);
+    behind_rows();
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *(uint4*)(At + (wave * 4 + i) * ld + h * 512 + lane * 8) = av[h][i];
   } else
   // a wave's loads of a 512-column slice are all issued before the first LDS store
   for (int h = 0; h < halves; ++h) {
@@ -220,6 +245,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
 #pragma unroll
     for (int i = 0; i < MT * 4; ++i)
       av[i] = *(const uint4*)(A + (size_t)min(m0 + wave * MT * 4 + i, M - 1) * K + h * 512 + lane * 8);
+    if (h == 0) behind_rows();
 #pragma unroll
     for (int i = 0; i < MT * 4; ++i) *(uint4*)(At + (wave * MT * 4 + i) * ld + h * 512 + lane * 8) = av[i];
   }
