@@ -35,6 +35,13 @@ MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 # profiles/bench_base_bs1_vocab_kernel_hbm_traffic.md): a figure of an earlier counter run, quoted
 # under `vocab_kernel.traffic_from_profile`, not a reading of this run
 VOCAB_KERNEL_TRAFFIC_BYTES = int(16336.9 * 1024 * (262144.0 / 131083.0) + 482.7 * 1024)
+# HBM bytes of one verify forward of the base model at batch 1, 25 rows: the sum over its 45 launches of
+# FETCH_SIZE (49938.6 KiB x 2.000) and WRITE_SIZE (3566.2 KiB x 1.000) per dispatch, two rocprofv3 --pmc
+# runs of `bench.py --profile-forward 1 25 --calibration-copy`
+# (profiles/verify_forward_base_bs1_25rows_hbm_traffic.md).  A figure of that counter run, not a reading
+# of this one; the row count of the forward timed below may differ by a few rows, which moves it by
+# well under 1 % (weights are 98 % of it).
+VERIFY_FORWARD_TRAFFIC_BYTES = int(49938.6 * 1024 * (262144.0 / 131086.6) + 3566.2 * 1024)
 
 
 def decoder_stream_params(dims):
@@ -61,6 +68,10 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one plain 256 MiB device copy (k_calibration_copy): the known-size "
                          "launch a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE reading is scaled by")
+    ap.add_argument("--profile-forward", type=int, nargs=2, metavar=("BATCH", "ROWS"), default=None,
+                    help="run only the verify forward of the base model at BATCH sequences x ROWS rows "
+                         "(200 back-to-back forwards after one verify call) and print its time: the command "
+                         "the per-shape rocprofv3 summaries under profiles/ are made with")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
@@ -88,6 +99,19 @@ def main():
         ad.calibration_copy(b, a)
         torch.cuda.synchronize()
         del a, b
+
+    if args.profile_forward:
+        Bp, Rp = args.profile_forward
+        assert 1 <= Bp <= 32 and 1 <= Rp <= K_MAX, "--profile-forward: 1..32 sequences, 1..72 rows each"
+        rng = np.random.default_rng(7)
+        srcs_p = [rng.integers(5, V, size=25).astype(np.int32) for _ in range(Bp)]
+        ctx.encode(ad.AD_VERIFIER, srcs_p, max_out=[64] * Bp)
+        ctx.verify([[int(t) for t in rng.integers(5, V, size=Rp)] for _ in range(Bp)])
+        f_us, v_us, v_b2b = ctx.time_verify_forward(200, back_to_back=True)
+        print(json.dumps({"profile_forward": {"batch": Bp, "rows": Bp * Rp, "forward_us": f_us,
+                                              "vocab_kernel_in_forward_us": v_us, "vocab_kernel_back_to_back_us": v_b2b}}))
+        ctx.close()
+        return
 
     # ---------------- batch 1: the headline workload ------------------------------------------
     n_sent = cfg1["n_sent"]
@@ -157,7 +181,9 @@ def main():
     roofline = {"bound": "hbm", "kernel": f"verify forward, base model, batch 1 ({n_launches} launches per forward)",
                 "rows": M1, "us": fwd_us, "algorithmic_bytes": fwd_bytes,
                 "achieved": fwd_bytes / (fwd_us * 1e-6) / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "traffic": None}
+                "frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "traffic": VERIFY_FORWARD_TRAFFIC_BYTES,
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --profile-forward 1 25 "
+                                  "--calibration-copy`, summed over the forward's launches (profiles/)"}
     # the largest single kernel of that forward (42 % of its algorithmic bytes), context only.
     # `frac` = the matrix streamed from HBM on every launch; the figure with the matrix resident in
     # the last-level cache between launches (as it is in the decode loop) under its own name
