@@ -504,6 +504,69 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
   return gx;
 }
 
+// ---------------------------------------------------------------- few rows, K of several 512-slices
+// C = A . W^T for up to 64 rows when K is 1024, 2048 or 4096 and no LayerNorm is pending (FFN2, the
+// attention output projections of the wide model).  The A-in-LDS kernel above walks a strip's
+// 512-slices one after the other in one wave, a round trip to memory per slice.  Here a workgroup
+// owns one 16-column strip of one 16-row chunk and its wave w owns the slices w, w + 4, ...: every
+// wave requests its slice of the rows (into an LDS tile of its own: no barrier before the first
+// MFMA; fragments requested straight from the row-major rows, 16 rows x 64 bytes per wave
+// instruction, measured 1 us slower per launch) and of the weights at once, so the workgroup waits
+// for memory once.  The sum itself stays one chain: the accumulators go from
+// wave to wave through LDS in slice order (k ascending, 32 at a time, one accumulator per element:
+// the same bits as every other GEMM kernel here), and the wave of the last slice runs the epilogue.
+// a 512-slice of 16 rows into a wave's LDS tile (one row per wave instruction, 16 bytes per lane)
+// and of a strip's weights into registers; all requests before the first LDS store
+__device__ __forceinline__ void kchain_request(const bf16_t* __restrict__ A, const bf16_t* __restrict__ wp, bf16_t* At,
+                                               int m0, int M, int K, int slice, int lane, uint4 (&b)[16]) {
+  constexpr int LD = 512 + 16;
+  uint4 av[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) av[i] = *(const uint4*)(A + (size_t)min(m0 + i, M - 1) * K + slice * 512 + lane * 8);
+#pragma unroll
+  for (int u = 0; u < 16; ++u) b[u] = *(const uint4*)(wp + (size_t)slice * 8192 + u * 512);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) *(uint4*)(At + i * LD + lane * 8) = av[i];
+}
+template <int NS>
+__global__ __launch_bounds__(256) void k_gemm_bf16_kchain(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                         int M, int N, int K, Epi e, int n_strips) {
+  constexpr int LD = 512 + 16;               // row stride of a wave's tile (elements): see the kernel above
+  __shared__ uint4 tiles[4 * 16 * LD / 8];   // [wave][16 rows][LD]: each wave stages its own slice, no barrier
+  __shared__ f32x4 hand[64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int strip = blockIdx.x % n_strips, m0 = (blockIdx.x / n_strips) * 16, n0 = strip << 4;
+  bf16_t* At = (bf16_t*)tiles + wave * 16 * LD;
+  const bf16_t* a_lane = At + r * LD + kq * 8;
+  const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
+  uint4 b[16];
+  if (wave < NS) kchain_request(A, wp, At, m0, M, K, wave, lane, b);
+  constexpr int LAST = (NS - 1) & 3;
+  EpiRegs<1> g;
+  if (wave == LAST) epi_preload<1>(e, 1, m0, n0, M, N, lane, g);
+  f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+  for (int p = 0; p < NS; ++p) {
+    if (wave == (p & 3)) {
+      if (p > 0) acc[0] = hand[lane];
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, *(const uint4*)(a_lane + 32 * u)), __builtin_bit_cast(bf16x8, b[u]), acc[0], 0, 0, 0);
+      if (p + 1 < NS) hand[lane] = acc[0];
+      if (p + 4 < NS) kchain_request(A, wp, At, m0, M, K, p + 4, lane, b);
+    }
+    if (p + 1 < NS) __syncthreads();
+  }
+  if (wave == LAST) epi_apply<bf16_t, 1>(e, acc, g, 1, m0, n0, M, N, lane);
+}
+static void launch_kchain(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epi& e, hipStream_t s) {
+  const int n_strips = N / 16, grid = n_strips * ((M + 15) / 16);
+  if (K == 1024) k_gemm_bf16_kchain<2><<<grid, 256, 0, s>>>(A, W, M, N, K, e, n_strips);
+  else if (K == 2048) k_gemm_bf16_kchain<4><<<grid, 256, 0, s>>>(A, W, M, N, K, e, n_strips);
+  else k_gemm_bf16_kchain<8><<<grid, 256, 0, s>>>(A, W, M, N, K, e, n_strips);
+}
+
 // ------------------------------------------------------------------------------------- fp32 GEMM
 // Plain fp32 path: one thread per output element, k ascending, fused multiply-add.
 __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, const float* __restrict__ W, int M,
@@ -562,6 +625,11 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
     const int nb = (N / 16 + 3) / 4;
     if (K <= 4096 && K % 512 == 0) {
       const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
+      // up to 64 rows of a K of several slices, as they are: the slices side by side in the waves
+      if (M <= 64 && !ln.x && (K == 1024 || K == 2048 || K == 4096) && e.mode != EPI_ARGMAX && e.mode != EPI_COUNT) {
+        launch_kchain(a, w, M, N, K, e, s);
+        return N / 16;
+      }
       // Few rows (measured: up to 64 for the wide output projection, up to 1024 for the layer
       // GEMMs: forward at 792..1008 rows 420-438 us this way, 431-449 us by the cost model below; from
       // 1080 rows the other way round, 520 against 489 us): latency decides, so 16 rows per workgroup
@@ -699,6 +767,55 @@ static size_t crossq_lds_bytes(int nk_cap, int mt, int d) {
   const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
   return (64 * ldv + std::max((size_t)64 * ldv, (size_t)mt * 16 * (d + 16)) + 64 * (size_t)kCrossqQld) * 2;
 }
+// The query projection of k_crossq_attention for MT row tiles: stage the chunk's rows in LDS (through
+// the pending LayerNorm, or as they are), multiply by the wave's strip `b` of the query matrix,
+// leave the queries (bias added, rounded) in the LDS tile Qt.  (A function with the arrays as
+// reference parameters, not a lambda that captures them: captured arrays end up in scratch memory.)
+template <int NV, int MT>
+__device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, bf16_t* Qt,
+                                               const uint4 (&b)[8 * NV], bool has_bias, float bn, int m0, int m_end,
+                                               bool keep_rows) {
+  constexpr int K = 256 * NV, KS = K / 32, ld = K + 16, QLD = kCrossqQld, per_wave = MT * 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  if (ln.x) {
+    astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, keep_rows);
+  } else {
+    uint4 av[per_wave][K / 512];
+#pragma unroll
+    for (int i = 0; i < per_wave; ++i)
+#pragma unroll
+      for (int j = 0; j < K / 512; ++j)
+        av[i][j] = *(const uint4*)(A + (size_t)min(m0 + wave * per_wave + i, m_end - 1) * K + j * 512 + lane * 8);
+#pragma unroll
+    for (int i = 0; i < per_wave; ++i)
+#pragma unroll
+      for (int j = 0; j < K / 512; ++j) *(uint4*)(At + (wave * per_wave + i) * ld + j * 512 + lane * 8) = av[i][j];
+  }
+  __syncthreads();
+  const bf16_t* a_lane = At + r * ld + kq * 8;
+  f32x4 acc[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int u = 0; u < KS; ++u) {
+    uint4 af[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) af[t] = *(const uint4*)(a_lane + t * 16 * ld + 32 * u);
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, b[u]), acc[t], 0, 0, 0);
+  }
+  // this lane: rows 16 t + 4 kq + i of the chunk, column 16 wave + r of the head
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float v = acc[t][i];
+      if (has_bias) v += bn;
+      Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
+    }
+}
 template <int NV>
 __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* __restrict__ A,
                                                           const bf16_t* __restrict__ W, const float* __restrict__ bias,
@@ -748,51 +865,10 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
   }
   __builtin_amdgcn_sched_barrier(0);
   // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
-  auto project = [&](auto mt_c) {
-    constexpr int MT = decltype(mt_c)::value;
-    constexpr int per_wave = MT * 4;
-    if (ln.x) {
-      astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, h == 0);
-    } else {
-      uint4 av[per_wave][K / 512];
-#pragma unroll
-      for (int i = 0; i < per_wave; ++i)
-#pragma unroll
-        for (int j = 0; j < K / 512; ++j)
-          av[i][j] = *(const uint4*)(A + (size_t)min(m0 + wave * per_wave + i, m_end - 1) * K + j * 512 + lane * 8);
-#pragma unroll
-      for (int i = 0; i < per_wave; ++i)
-#pragma unroll
-        for (int j = 0; j < K / 512; ++j) *(uint4*)(At + (wave * per_wave + i) * ld + j * 512 + lane * 8) = av[i][j];
-    }
-    __syncthreads();
-    const bf16_t* a_lane = At + r * ld + kq * 8;
-    f32x4 acc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int u = 0; u < KS; ++u) {
-      uint4 af[MT];
-#pragma unroll
-      for (int t = 0; t < MT; ++t) af[t] = *(const uint4*)(a_lane + t * 16 * ld + 32 * u);
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, b[u]), acc[t], 0, 0, 0);
-    }
-    // this lane: rows 16 t + 4 kq + i of the chunk, column 16 wave + r of the head
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float v = acc[t][i];
-        if (bias) v += bn;
-        Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
-      }
-  };
-  if (mt == 1) project(std::integral_constant<int, 1>{});
-  else if (mt == 2) project(std::integral_constant<int, 2>{});
-  else if (mt == 3) project(std::integral_constant<int, 3>{});
-  else project(std::integral_constant<int, 4>{});
+  if (mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else if (mt == 2) crossq_project<NV, 2>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else if (mt == 3) crossq_project<NV, 3>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else crossq_project<NV, 4>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   // values into LDS, transposed (keys nk_all .. nkp - 1 as zeros)
   if (v_small) {
 #pragma unroll
