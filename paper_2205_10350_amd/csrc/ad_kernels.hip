@@ -505,7 +505,7 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
 }
 
 // ---------------------------------------------------------------- few rows, K of several 512-slices
-// C = A . W^T for up to 64 rows when K is 1024, 2048 or 4096 and no LayerNorm is pending (FFN2, the
+// C = A . W^T for up to 160 rows when K is 1024, 2048 or 4096 and no LayerNorm is pending (FFN2, the
 // attention output projections of the wide model).  The A-in-LDS kernel above walks a strip's
 // 512-slices one after the other in one wave, a round trip to memory per slice.  Here a workgroup
 // owns one 16-column strip of one 16-row chunk and its wave w owns the slices w, w + 4, ...: every
@@ -625,8 +625,11 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
     const int nb = (N / 16 + 3) / 4;
     if (K <= 4096 && K % 512 == 0) {
       const bf16_t *a = (const bf16_t*)A, *w = (const bf16_t*)W;
-      // up to 64 rows of a K of several slices, as they are: the slices side by side in the waves
-      if (M <= 64 && !ln.x && (K == 1024 || K == 2048 || K == 4096) && e.mode != EPI_ARGMAX && e.mode != EPI_COUNT) {
+      // up to 160 rows of a K of several slices, as they are: the slices side by side in the waves
+      // (measured, forward with this kernel up to 64 / 128 / 256 rows: base model 144 rows 253 / 253 / 249 us,
+      // 288 rows 285 / 286 / 285 us (293 us with a limit of 512); wide model 100 rows 365 / 352 / 352 us, 200 rows
+      // 430 / 430 / 477 us)
+      if (M <= 160 && !ln.x && (K == 1024 || K == 2048 || K == 4096) && e.mode != EPI_ARGMAX && e.mode != EPI_COUNT) {
         launch_kchain(a, w, M, N, K, e, s);
         return N / 16;
       }
