@@ -211,8 +211,7 @@ int ad_debug_logits(ad_ctx* ctx, float* logits, int rows_cap, int* rows);
  * vocab_kernel_us = its output-projection/arg-max kernel, mean over `reps` forwards of one launch
  * bracketed by two events (what a kernel trace reports for it); vocab_back_to_back_us (may be
  * null) = the same kernel, `reps` launches back to back divided by reps (launch overheads of
- * consecutive launches overlap).  Both kernel figures are 0 when the forward ran as one
- * persistent kernel.  For roofline measurements. */
+ * consecutive launches overlap).  For roofline measurements. */
 int ad_time_verify_forward(ad_ctx* ctx, int reps, double* forward_us, double* vocab_kernel_us,
                            double* vocab_back_to_back_us);
 

@@ -1,6 +1,6 @@
-// Device functions shared by the stand-alone kernels and the persistent fused forward.
-// Everything that decides a value's bits (reduction orders, rounding points, fused
-// multiply-adds) lives here exactly once, so that both launch styles give bit-identical rows.
+// Device functions shared by the kernels.  Everything that decides a value's bits (reduction
+// orders, rounding points, fused multiply-adds) lives here exactly once, so that a row's result does
+// not depend on which kernel computes it.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -19,15 +19,8 @@ __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsig
 __device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest, ties to even (the hardware conversion)
   return __builtin_bit_cast(bf16_t, (__bf16)f);
 }
-// Memory access policy.  COH = false: ordinary cached accesses (data produced by an earlier
-// launch, or weights).  COH = true: the access carries the device-scope cache policy (relaxed
-// device-scope atomics: ordinary vector loads/stores that miss the compute unit's L1; a store
-// writes through to memory).  The persistent kernel uses coherent LOADS for everything another
-// workgroup wrote earlier in the same launch.  Workgroups of one XCD share that XCD's L2, so data
-// exchanged inside an XCD needs plain stores only; data that crosses XCDs is stored coherently.
-// All of these address device (global) memory; the explicit address space keeps the compiler
-// from falling back to the slower flat instructions when it cannot see where a pointer came from
-// (pointers loaded from a stage program in memory).
+// Memory accesses name the global address space explicitly: that keeps the compiler from falling
+// back to the slower flat instructions when it cannot see where a pointer came from.
 #define AD_GLOBAL __attribute__((address_space(1)))
 // (class types are moved as raw 16-, 8-, 4- or 2-byte pieces: their copy constructors take
 // generic references, which would undo the address space)
@@ -57,57 +50,18 @@ template <typename V> __device__ __forceinline__ void gstore(V* p, V v) {
 #pragma unroll
   for (int i = 0; i < R::kCount; ++i) gp[i] = raw.v[i];
 }
-template <bool COH, typename V> __device__ __forceinline__ V ldg(const V* p) {
-  if constexpr (COH) {
-    if constexpr (sizeof(V) == 2) {
-      const unsigned short u = __hip_atomic_load((const AD_GLOBAL unsigned short*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return __builtin_bit_cast(V, u);
-    } else if constexpr (sizeof(V) == 4) {
-      const unsigned u = __hip_atomic_load((const AD_GLOBAL unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return __builtin_bit_cast(V, u);
-    } else {
-      static_assert(sizeof(V) == 8, "coherent loads: 2, 4 or 8 bytes");
-      const unsigned long long u = __hip_atomic_load((const AD_GLOBAL unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      return __builtin_bit_cast(V, u);
-    }
-  } else {
-    return gload(p);
-  }
-}
-template <bool COH, typename V> __device__ __forceinline__ void stg(V* p, V v) {
-  if constexpr (COH) {
-    if constexpr (sizeof(V) == 2) {
-      __hip_atomic_store((AD_GLOBAL unsigned short*)p, __builtin_bit_cast(unsigned short, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else if constexpr (sizeof(V) == 4) {
-      __hip_atomic_store((AD_GLOBAL unsigned*)p, __builtin_bit_cast(unsigned, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      static_assert(sizeof(V) == 8, "coherent stores: 2, 4 or 8 bytes");
-      __hip_atomic_store((AD_GLOBAL unsigned long long*)p, __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-  } else {
-    gstore(p, v);
-  }
-}
-// 16 bytes (16-byte aligned): coherent = two 8-byte halves
-template <bool COH> __device__ __forceinline__ uint4 ldg16(const void* p) {
-  if constexpr (COH) {
-    const unsigned long long lo = __hip_atomic_load((const AD_GLOBAL unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long hi = __hip_atomic_load((const AD_GLOBAL unsigned long long*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return uint4{(unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32)};
-  } else {
-    return gload((const uint4*)p);
-  }
-}
+// 16 bytes (16-byte aligned)
+__device__ __forceinline__ uint4 ldg16(const void* p) { return gload((const uint4*)p); }
 
 template <typename T> struct Store;
 template <> struct Store<float> {
-  template <bool COH = false> static __device__ __forceinline__ float load(const float* p) { return ldg<COH>(p); }
-  template <bool COH = false> static __device__ __forceinline__ void store(float* p, float v) { stg<COH>(p, v); }
+  static __device__ __forceinline__ float load(const float* p) { return gload(p); }
+  static __device__ __forceinline__ void store(float* p, float v) { gstore(p, v); }
   static __device__ __forceinline__ float round(float v) { return v; }
 };
 template <> struct Store<bf16_t> {
-  template <bool COH = false> static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(ldg<COH>(p)); }
-  template <bool COH = false> static __device__ __forceinline__ void store(bf16_t* p, float v) { stg<COH>(p, f2bf(v)); }
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf2f(gload(p)); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { gstore(p, f2bf(v)); }
   static __device__ __forceinline__ float round(float v) { return bf2f(f2bf(v)); }
 };
 
@@ -180,12 +134,12 @@ __device__ __forceinline__ float embed_value(float e, float sqrt_d, float pe) { 
 // LayerNorm statistics of one row by one wave: lane l owns elements l, l+64, ... (kept in
 // registers, NJ per lane: d <= 64*NJ); mean, then the biased variance of the centred values;
 // eps = 1e-5.  NJ only bounds the register array: the arithmetic depends on d alone.
-template <bool COH = false, int NJ = 32, bool EXACT = false>   // EXACT: d == 64 * NJ, no bounds tests
+template <int NJ = 32, bool EXACT = false>   // EXACT: d == 64 * NJ, no bounds tests
 __device__ __forceinline__ void ln_load(const float* __restrict__ xr, int d, int lane, float (&xv)[NJ]) {
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int c = lane + 64 * j;
-    xv[j] = (EXACT || c < d) ? ldg<COH>(xr + c) : 0.f;
+    xv[j] = (EXACT || c < d) ? gload(xr + c) : 0.f;
   }
 }
 template <int NJ = 32, bool EXACT = false>
@@ -208,11 +162,11 @@ __device__ __forceinline__ void ln_stats(const float (&xv)[NJ], int d, int lane,
 // consecutive elements at 4*l + 256*j, j < NV = d / 256 (ln_vector_width says which rule a width
 // takes; every kernel follows it, so a row's statistics never depend on the kernel).
 __host__ __device__ inline int ln_vector_width(int d) { return (d == 256 || d == 512 || d == 1024 || d == 2048) ? d / 256 : 0; }
-template <bool COH, int NV>
+template <int NV>
 __device__ __forceinline__ void ln_load4(const float* __restrict__ xr, int lane, float4 (&xv)[NV]) {
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    const uint4 u = ldg16<COH>(xr + 4 * lane + 256 * j);
+    const uint4 u = ldg16(xr + 4 * lane + 256 * j);
     xv[j] = float4{__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w)};
   }
 }
@@ -234,10 +188,9 @@ __device__ __forceinline__ void ln_stats4(const float4 (&xv)[NV], int d, float& 
   }
   rstd = __builtin_amdgcn_rsqf(fmaf(wave_sum(v), inv_d, 1e-5f));   // hardware reciprocal square root (1 ulp)
 }
-template <bool COH = false>
 __device__ __forceinline__ void ln_load_stats(const float* __restrict__ xr, int d, int lane, float (&xv)[32],
                                               float& mean, float& rstd) {
-  ln_load<COH, 32>(xr, d, lane, xv);
+  ln_load<32>(xr, d, lane, xv);
   ln_stats<32>(xv, d, lane, mean, rstd);
 }
 __device__ __forceinline__ float ln_value(float x, float mean, float rstd, float g, float b) {
@@ -253,7 +206,7 @@ template <int MT> struct EpiRegs {
   float bias;
   unsigned aux[MT * 4];   // destination row (QKV / KV) or the residual value's bits (RESID): never both
 };
-template <int MT, bool LDC = false>
+template <int MT>
 __device__ __forceinline__ void epi_preload(const Epi& e, int mt_used, int m0, int n0, int M, int N, int lane,
                                             EpiRegs<MT>& g) {
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
@@ -278,13 +231,13 @@ __device__ __forceinline__ void epi_preload(const Epi& e, int mt_used, int m0, i
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + t * 16 + kq * 4 + i;
-        if (full || (t < mt_used && m < M)) g.aux[t * 4 + i] = __float_as_uint(ldg<LDC>(e.resid + (size_t)m * N + n));
+        if (full || (t < mt_used && m < M)) g.aux[t * 4 + i] = __float_as_uint(gload(e.resid + (size_t)m * N + n));
       }
   }
 }
 // value = acc + bias, then the mode's operation.  A strip of 16 columns lies inside one of the
 // q / k / v column ranges (d is a multiple of 16), so the destination is uniform over the wave.
-template <typename T, int MT, bool STC = false>
+template <typename T, int MT>
 __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], const EpiRegs<MT>& g, int mt_used,
                                           int m0, int n0, int M, int N, int lane) {
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
@@ -300,7 +253,7 @@ __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], 
         const int m = m0 + t * 16 + kq * 4 + i;
         float v = acc[t][i];
         if (has_bias) v += g.bias;
-        if (full || (t < mt_used && m < M)) stg<STC>(out + (size_t)m * N, v + __uint_as_float(g.aux[t * 4 + i]));
+        if (full || (t < mt_used && m < M)) gstore(out + (size_t)m * N, v + __uint_as_float(g.aux[t * 4 + i]));
       }
     return;
   }
@@ -332,14 +285,14 @@ __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], 
       if (has_bias) v += g.bias;
       if (mode == EPI_RELU) v = fmaxf(v, 0.f);
       const size_t row = by_dst ? (size_t)g.aux[t * 4 + i] : (size_t)m;
-      if (full || (t < mt_used && m < M)) Store<T>::template store<STC>(base + row * ld, v);
+      if (full || (t < mt_used && m < M)) Store<T>::store(base + row * ld, v);
     }
 }
 
 // Epilogue of one 16-column strip held in MFMA C layout (lane l: column n0 + l%16, rows
 // m0 + 4*(l/16) + i of tile t).  For EPI_ARGMAX the 16 lanes of a row reduce to one
 // (value, index) partial.
-template <typename T, int MT, bool LDC = false, bool STC = false>
+template <typename T, int MT>
 __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[MT], int mt_used, int m0, int n0,
                                                int M, int N, int lane) {
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
@@ -356,8 +309,8 @@ __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[
         if (e.logits && m < M) gstore(e.logits + (size_t)m * N + n, v);
         argmax_row16(v, idx);
         if (r == 0 && m < M) {
-          stg<STC>(e.part_val + (size_t)m * e.n_strips + strip, v);
-          stg<STC>(e.part_idx + (size_t)m * e.n_strips + strip, idx);
+          gstore(e.part_val + (size_t)m * e.n_strips + strip, v);
+          gstore(e.part_idx + (size_t)m * e.n_strips + strip, idx);
         }
       }
     }
@@ -373,14 +326,14 @@ __device__ __forceinline__ void strip_epilogue(const Epi& e, const f32x4 (&acc)[
         const int m = m0 + t * 16 + kq * 4 + i;
         const float th = e.thr[m < M ? m : M - 1];
         const int cnt = row16_sum_i(acc[t][i] > th ? 1 : 0);
-        if (r == 0 && m < M) stg<STC>(e.part_idx + (size_t)m * e.n_strips + strip, cnt);
+        if (r == 0 && m < M) gstore(e.part_idx + (size_t)m * e.n_strips + strip, cnt);
       }
     }
     return;
   }
   EpiRegs<MT> g;
-  epi_preload<MT, LDC>(e, mt_used, m0, n0, M, N, lane, g);
-  epi_apply<T, MT, STC>(e, acc, g, mt_used, m0, n0, M, N, lane);
+  epi_preload<MT>(e, mt_used, m0, n0, M, N, lane, g);
+  epi_apply<T, MT>(e, acc, g, mt_used, m0, n0, M, N, lane);
 }
 
 // Epilogue of a single element (fp32 GEMM path).
@@ -411,7 +364,6 @@ __device__ __forceinline__ void epi_store(const Epi& e, int m, int n, int N, flo
 }
 
 // Second stage of the arg max for one row by one wave; partials are loaded eight at a time.
-template <bool COH = false>
 __device__ __forceinline__ void argmax_row(const float* __restrict__ pv, const int* __restrict__ pi, int n_strips,
                                            int lane, float& v, int& idx) {
   v = -INFINITY;
@@ -422,8 +374,8 @@ __device__ __forceinline__ void argmax_row(const float* __restrict__ pv, const i
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int t = t0 + 64 * u;
-      pvv[u] = t < n_strips ? ldg<COH>(pv + t) : -INFINITY;
-      pii[u] = t < n_strips ? ldg<COH>(pi + t) : 0x7fffffff;
+      pvv[u] = t < n_strips ? gload(pv + t) : -INFINITY;
+      pii[u] = t < n_strips ? gload(pi + t) : 0x7fffffff;
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) argmax_merge(v, idx, pvv[u], pii[u]);
@@ -493,7 +445,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 // Every step treats a query row independently of the other rows of its tile and of how many
 // tiles or keys the call covers (keys a row does not see contribute exact zeros), so a row's
 // result does not depend on the shape of the block it is verified in.
-template <int DH, int NT, bool COH, bool STC>
+template <int DH, int NT>
 __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
                                 const SeqDesc sd, int row_begin, int row_end, int h, int d, float scale,
                                 const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all,
@@ -519,7 +471,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
     } else {
       const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row0 + r, row_end - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
+      for (int s = 0; s < KS; ++s) qf[s] = ldg16(qp + 32 * s);
     }
     // this lane: rows row0 + 4*kq + i, key 16*(tile) + r
     int nkr[4];
@@ -552,7 +504,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
               } else {
                 const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * jc + r, nk_all - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) kf[j][s] = ldg16<COH>(kp + 32 * s);
+                for (int s = 0; s < KS; ++s) kf[j][s] = ldg16(kp + 32 * s);
               }
             }
           }
@@ -641,7 +593,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       if (row < row_end) {
         bf16_t* op = out + (size_t)(sd.q_row0 + row) * d + h * DH + r;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) Store<bf16_t>::template store<STC>(op + 16 * c, O[c][i] / l[i]);
+        for (int c = 0; c < CT; ++c) Store<bf16_t>::store(op + 16 * c, O[c][i] / l[i]);
       }
     }
   };
@@ -650,7 +602,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
 }
 // Query fragments and the first four key tiles of the wave's first 16-row tile (what
 // attn_tiles_mfma takes as qf_pre / kf_pre): same addresses, same clamping.
-template <int DH, bool COH>
+template <int DH>
 __device__ __forceinline__ void attn_preload(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, const SeqDesc sd,
                                              int row_begin, int row_end, int h, int d, int nk_all,
                                              uint4 (&qf)[DH / 32], uint4 (&kf)[4][DH / 32]) {
@@ -665,18 +617,18 @@ __device__ __forceinline__ void attn_preload(const bf16_t* __restrict__ q, const
   const int nt = (nk_tile + 15) >> 4;
   const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row0 + r, row_end - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-  for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
+  for (int s = 0; s < KS; ++s) qf[s] = ldg16(qp + 32 * s);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     if (j < nt) {
       const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) kf[j][s] = ldg16<COH>(kp + 32 * s);
+      for (int s = 0; s < KS; ++s) kf[j][s] = ldg16(kp + 32 * s);
     }
   }
 }
 // The key half of attn_preload alone (the queries come from somewhere else).
-template <int DH, bool COH>
+template <int DH>
 __device__ __forceinline__ void attn_preload_k(const bf16_t* __restrict__ Kb, const SeqDesc sd, int row_begin, int row_end,
                                                int h, int d, int nk_all, uint4 (&kf)[4][DH / 32]) {
   constexpr int KS = DH / 32;
@@ -692,18 +644,18 @@ __device__ __forceinline__ void attn_preload_k(const bf16_t* __restrict__ Kb, co
     if (j < nt) {
       const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * j + r, nk_all - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) kf[j][s] = ldg16<COH>(kp + 32 * s);
+      for (int s = 0; s < KS; ++s) kf[j][s] = ldg16(kp + 32 * s);
     }
   }
 }
-template <int DH, bool COH>
+template <int DH>
 __device__ __forceinline__ void attn_coop_scores_q(const uint4 (&qf)[DH / 32], const bf16_t* __restrict__ Kb, const SeqDesc sd,
                                                    int h, int d, int nk_all, int nt, float* Sbuf, int lds_s);
 // One 16-row tile, many keys: the score products Q K^T are independent per key tile, so all waves
 // of the workgroup compute them together (wave w: key tiles w, w + waves, ..; one fetch latency
 // instead of one per group of tiles on a single wave) and leave the raw fp32 products in LDS,
 // [16 rows][lds_s]; the tile's wave then goes on exactly as if it had computed them itself.
-template <int DH, bool COH>
+template <int DH>
 __device__ __forceinline__ void attn_coop_scores(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, const SeqDesc sd,
                                                  int row_begin, int row_end, int h, int d, int nk_all, int nt,
                                                  float* Sbuf, int lds_s) {
@@ -714,12 +666,12 @@ __device__ __forceinline__ void attn_coop_scores(const bf16_t* __restrict__ q, c
   {
     const bf16_t* qp = q + (size_t)(sd.q_row0 + min(row_begin + r, row_end - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[s] = ldg16<COH>(qp + 32 * s);
+    for (int s = 0; s < KS; ++s) qf[s] = ldg16(qp + 32 * s);
   }
-  attn_coop_scores_q<DH, COH>(qf, Kb, sd, h, d, nk_all, nt, Sbuf, lds_s);
+  attn_coop_scores_q<DH>(qf, Kb, sd, h, d, nk_all, nt, Sbuf, lds_s);
 }
 // (the same with the tile's query fragments given)
-template <int DH, bool COH>
+template <int DH>
 __device__ __forceinline__ void attn_coop_scores_q(const uint4 (&qf)[DH / 32], const bf16_t* __restrict__ Kb, const SeqDesc sd,
                                                    int h, int d, int nk_all, int nt, float* Sbuf, int lds_s) {
   constexpr int KS = DH / 32, TB = 8;   // key tiles per batch of loads
@@ -733,7 +685,7 @@ __device__ __forceinline__ void attn_coop_scores_q(const uint4 (&qf)[DH / 32], c
       const int jc = min(b0 + jj * waves, nt - 1);
       const bf16_t* kp = Kb + (size_t)(sd.kv_row0 + min(16 * jc + r, nk_all - 1)) * d + h * DH + kq * 8;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16<COH>(kp + 32 * s);
+      for (int s = 0; s < KS; ++s) kf[jj][s] = ldg16(kp + 32 * s);
     }
 #pragma unroll
     for (int jj = 0; jj < TB; ++jj) {
@@ -750,7 +702,7 @@ __device__ __forceinline__ void attn_coop_scores_q(const uint4 (&qf)[DH / 32], c
   }
 }
 // Values of one (sequence, head) transposed into LDS: Vt[c][t] = V[t][c], keys nk_all .. nkp - 1 as zeros.
-template <int DH, bool COH>
+template <int DH>
 __device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb, const SeqDesc sd, int h, int d, bf16_t* Vt,
                                                   int ldv, int nkp, int nk_all) {
   // Values transposed into LDS.  Many keys: 8 keys x 8 channels per step and thread: eight 16-byte loads
@@ -764,7 +716,7 @@ __device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb,
   for (int i = threadIdx.x; i < nkp * G; i += blockDim.x) {
     const int g = i / nkp, t = i - g * nkp;
     uint4 v = uint4{0u, 0u, 0u, 0u};
-    if (t < nk_all) v = ldg16<COH>(vg + (size_t)t * d + g * 8);
+    if (t < nk_all) v = ldg16(vg + (size_t)t * d + g * 8);
     bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
     dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
     dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
@@ -778,7 +730,7 @@ __device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb,
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       uint4 v = uint4{0u, 0u, 0u, 0u};
-      if (t0 + i < nk_all) v = ldg16<COH>(vg + (size_t)(t0 + i) * d + g * 8);
+      if (t0 + i < nk_all) v = ldg16(vg + (size_t)(t0 + i) * d + g * 8);
       in[i][0] = v.x; in[i][1] = v.y; in[i][2] = v.z; in[i][3] = v.w;
     }
 #pragma unroll
@@ -794,7 +746,7 @@ __device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb,
     }
   }
 }
-template <int DH, bool COH, bool STC>
+template <int DH>
 __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
                                 int row_begin, int row_end, int h, int d, float scale, unsigned* lds, int nk_all) {
@@ -805,28 +757,28 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
   // the first tile's operands of the score product are requested before the values are staged:
   // the two fetch latencies overlap
   uint4 qf_pre[DH / 32], kf_pre[4][DH / 32];
-  attn_preload<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, qf_pre, kf_pre);
+  attn_preload<DH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, qf_pre, kf_pre);
   // a single row tile against more than 128 keys: the waves share the score products; the buffer
   // lies over the probability tiles of the waves that have no rows
   const int nt_all = (nk_all + 15) >> 4;
   const bool coop = row_end - row_begin <= 16 && nt_all > 8 && waves >= 3;
   float* Sbuf = coop ? (float*)(Vt + DH * ldv + 16 * ldv) : nullptr;
-  if (coop) attn_coop_scores<DH, COH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, nt_all, Sbuf, nkp);
-  attn_stage_values<DH, COH>(Vb, sd, h, d, Vt, ldv, nkp, nk_all);
+  if (coop) attn_coop_scores<DH>(q, Kb, sd, row_begin, row_end, h, d, nk_all, nt_all, Sbuf, nkp);
+  attn_stage_values<DH>(Vb, sd, h, d, Vt, ldv, nkp, nk_all);
   __syncthreads();
-  if (nkp <= 64) attn_tiles_mfma<DH, 4, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else if (nkp <= 128) attn_tiles_mfma<DH, 8, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else attn_tiles_mfma<DH, 16, COH, STC>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  if (nkp <= 64) attn_tiles_mfma<DH, 4>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else attn_tiles_mfma<DH, 16>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   __syncthreads();   // LDS is free for the next call
 }
 
-template <typename T, int DH, bool COH = false, bool STC = false>
+template <typename T, int DH>
 __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, const T* __restrict__ Vb,
                            T* __restrict__ out, const SeqDesc sd, int row_begin, int row_end, int h, int d,
                            float scale, unsigned* lds, int nk_cap) {
   if constexpr (sizeof(T) == 2 && DH % 32 == 0) {
     const int nk_need = sd.causal ? sd.nk_base + row_end : sd.nk_base;
-    attn_block_mfma<DH, COH, STC>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
+    attn_block_mfma<DH>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
     return;
   }
   constexpr int RD = DH * (int)sizeof(T) / 4;   // dwords per key row
@@ -850,8 +802,8 @@ __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __r
         const int i = base + u * nt;
         if (i < n) {
           const int t = i / RD, w = i - t * RD;
-          kv[u] = ldg<COH>(kg + t * gs + w);
-          vv[u] = ldg<COH>(vg + t * gs + w);
+          kv[u] = gload(kg + t * gs + w);
+          vv[u] = gload(vg + t * gs + w);
         }
       }
 #pragma unroll
@@ -872,7 +824,7 @@ __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __r
         const int i = base + u * nt;
         if (i < nq) {
           const int rr = i / DH, c = i - rr * DH;
-          qv[u] = Store<T>::template load<COH>(q + (size_t)(sd.q_row0 + row_begin + rr) * d + h * DH + c);
+          qv[u] = Store<T>::load(q + (size_t)(sd.q_row0 + row_begin + rr) * d + h * DH + c);
         }
       }
 #pragma unroll
@@ -942,7 +894,7 @@ __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __r
         for (int j = 0; j < 8; ++j)
           if (t0 + j < nk) a = fmaf(pt[j], vt[j], a);
       }
-      Store<T>::template store<STC>(out + (size_t)m * d + h * DH + c, a / l);
+      Store<T>::store(out + (size_t)m * d + h * DH + c, a / l);
     }
     __builtin_amdgcn_wave_barrier();
   }

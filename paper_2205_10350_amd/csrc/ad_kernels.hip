@@ -125,7 +125,7 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
     float4 xv[RB][NV];
 #pragma unroll
     for (int i = 0; i < RB; ++i)
-      if (i0 + i < n_rows) ln_load4<false, NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
+      if (i0 + i < n_rows) ln_load4<NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
     if (i0 == 0) after_first_loads();
     // statistics of all rows of the batch first (independent reduction chains the scheduler can
     // interleave), then the values, then, in the workgroups that keep them, the fp32 rows
@@ -852,7 +852,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
   }
   const float bn = bias ? bias[n0 + r] : 0.f;
   uint4 kf_pre[4][DH / 32];
-  attn_preload_k<DH, false>(Kb, sd, row_begin, row_end, h, K, nk_all, kf_pre);
+  attn_preload_k<DH>(Kb, sd, row_begin, row_end, h, K, nk_all, kf_pre);
   // up to 128 keys: the values (piece i = 8 channels of one key; addresses clamped, never under a
   // branch of their own) wait in registers until the row tile is staged
   const bool v_small = nkp <= 128;
@@ -888,7 +888,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
       }
     }
   } else {
-    attn_stage_values<DH, false>(Vb, sd, h, K, Vt, ldv, nkp, nk_all);
+    attn_stage_values<DH>(Vb, sd, h, K, Vt, ldv, nkp, nk_all);
   }
   __syncthreads();   // queries and values are in LDS; the row tile is no longer needed
   // the rest is attn_block_mfma with the query fragments read from the LDS tile
@@ -903,14 +903,14 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
   const bool coop = row_end - row_begin <= 16 && nt_all > 8;
   float* Sbuf = coop ? (float*)(Pall + 16 * ldv) : nullptr;
   if (coop) {
-    attn_coop_scores_q<DH, false>(qf_pre, Kb, sd, h, K, nk_all, nt_all, Sbuf, nkp);
+    attn_coop_scores_q<DH>(qf_pre, Kb, sd, h, K, nk_all, nt_all, Sbuf, nkp);
     __syncthreads();
   }
   bf16_t* Pw = Pall + wave * 16 * ldv;
   const bf16_t* qnone = nullptr;   // every wave has at most one tile: its fragments are qf_pre
-  if (nkp <= 64) attn_tiles_mfma<DH, 4, false, false>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else if (nkp <= 128) attn_tiles_mfma<DH, 8, false, false>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else attn_tiles_mfma<DH, 16, false, false>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  if (nkp <= 64) attn_tiles_mfma<DH, 4>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else attn_tiles_mfma<DH, 16>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
 }
 bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void* W, const float* bias, const void* K,
                              const void* V, void* out, const SeqDesc* desc, int n_seq, int max_rows, int H, int dh,
@@ -952,7 +952,7 @@ __device__ __forceinline__ void layernorm_row4(const float* __restrict__ xr, con
                                                T* __restrict__ yar) {
   float4 xv[NV];
   float mean, rstd;
-  ln_load4<false, NV>(xr, lane, xv);
+  ln_load4<NV>(xr, lane, xv);
   ln_stats4<NV>(xv, d, mean, rstd);
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
