@@ -133,6 +133,35 @@ def test_heads_of_width_128(dtype):
         rig.close()
 
 
+def test_rows_of_the_wide_model_do_not_depend_on_the_gemm_kernel_the_row_count_selects():
+    """Big model (d 1024, FFN 4096), bit-exact: the logits of one sequence's 25-row block verified
+    alone (the attention output projections and FFN2 run in the kernel that puts a strip's
+    512-slices side by side in the waves) and in the middle of 8 sequences (200 packed rows: the
+    kernel that walks the slices one after the other, several strips per workgroup)."""
+    dims = model_dims("big")
+    w = init_weights(dims, 411)
+    ctx = ad.Context(ad.make_config(dims, max_batch=8, max_src=40, max_len=40, k_max=32, dtype="bf16", special=SPECIAL,
+                                    debug_logits=True), w)
+    try:
+        V = dims["vocab"]
+        rng = np.random.default_rng(411)
+        srcs = [rng.integers(5, V, size=int(n)).astype(np.int32) for n in rng.integers(10, 40, size=8)]
+        blocks = [[int(t) for t in rng.integers(5, V, size=25)] for _ in range(8)]
+        ctx.encode(ad.AD_VERIFIER, srcs[:1])
+        ctx.verify(blocks[:1])
+        alone = ctx.debug_logits().view(np.uint32).copy()
+        assert alone.shape[0] == 25
+        for n in (3, 8):   # 75 rows: still the first kernel, several row chunks; 200 rows: the other
+            order = list(range(1, n // 2 + 1)) + [0] + list(range(n // 2 + 1, n))
+            ctx.encode(ad.AD_VERIFIER, [srcs[i] for i in order])
+            ctx.verify([blocks[i] for i in order])
+            lg = ctx.debug_logits().view(np.uint32)
+            at = 25 * (n // 2)
+            assert np.array_equal(lg[at:at + 25], alone), n
+    finally:
+        ctx.close()
+
+
 def _ctx_pair(name, seed, **cap):
     """Two contexts over the same weights: one keeps the logits (its output projection stores
     them), the other runs the shipped epilogue that never writes them."""
