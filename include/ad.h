@@ -16,7 +16,8 @@
  *    not change while it lives: ad_create copies some of them into the workspace, side by
  *    side).  The library allocates no device memory, ever (its one device-side object of its
  *    own is the fixed 4 MiB static array ad_verify_static works in).  ad_create allocates one
- *    pinned, device-mapped host staging buffer and a few events; later calls may allocate host
+ *    pinned, device-mapped host staging buffer, a few events and, with a drafter, one more stream
+ *    of default priority (AD_OPT_OVERLAP_ENCODERS); later calls may allocate host
  *    memory for bookkeeping (the decode loops' token lists, a captured graph per call shape);
  *    ad_verify_static allocates nothing at all.
  *  - `hip_stream` is a hipStream_t (NULL = the null stream).  All device work of a
