@@ -819,7 +819,7 @@ __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __re
       Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
     }
 }
-template <int NV>
+template <int NV, bool SMALL>
 __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* __restrict__ A,
                                                           const bf16_t* __restrict__ W, const float* __restrict__ bias,
                                                           const bf16_t* __restrict__ Kb, const bf16_t* __restrict__ Vb,
@@ -855,7 +855,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
   attn_preload_k<DH>(Kb, sd, row_begin, row_end, h, K, nk_all, kf_pre);
   // up to 128 keys: the values (piece i = 8 channels of one key; addresses clamped, never under a
   // branch of their own) wait in registers until the row tile is staged
-  const bool v_small = nkp <= 128;
+  const bool v_small = SMALL || nkp <= 128;
   uint4 vreg[4];
   if (v_small) {
     const bf16_t* vg = Vb + (size_t)sd.kv_row0 * K + h * DH;
@@ -868,7 +868,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
   }
   __builtin_amdgcn_sched_barrier(0);
   // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
-  if (mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  if (SMALL || mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   else if (mt == 2) crossq_project<NV, 2>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   else if (mt == 3) crossq_project<NV, 3>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   else crossq_project<NV, 4>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
@@ -900,7 +900,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
     for (int s2 = 0; s2 < DH / 32; ++s2) qf_pre[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
   }
   const int nt_all = (nk_all + 15) >> 4;
-  const bool coop = row_end - row_begin <= 16 && nt_all > 8;
+  const bool coop = !SMALL && row_end - row_begin <= 16 && nt_all > 8;
   float* Sbuf = coop ? (float*)(Pall + 16 * ldv) : nullptr;
   if (coop) {
     attn_coop_scores_q<DH>(qf_pre, Kb, sd, h, K, nk_all, nt_all, Sbuf, nkp);
@@ -908,7 +908,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* 
   }
   bf16_t* Pw = Pall + wave * 16 * ldv;
   const bf16_t* qnone = nullptr;   // every wave has at most one tile: its fragments are qf_pre
-  if (nkp <= 64) attn_tiles_mfma<DH, 4>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  if (SMALL || nkp <= 64) attn_tiles_mfma<DH, 4>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   else if (nkp <= 128) attn_tiles_mfma<DH, 8>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   else attn_tiles_mfma<DH, 16>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
 }
@@ -929,18 +929,24 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   if (n_seq <= 0 || max_rows <= 0) return true;
   dim3 g(n_seq, H, (max_rows + chunk - 1) / chunk);
   const float scale = 1.0f / sqrtf((float)dh);
-  auto go = [&](auto nv_c) {
+  // one row tile per workgroup and at most 64 keys (the bounds the caller gives promise both): a
+  // variant that holds that one path only (a quarter of the code)
+  const bool small = mt == 1 && max_keys <= 64;
+  auto go = [&](auto nv_c, auto small_c) {
     constexpr int NV = decltype(nv_c)::value;
+    constexpr bool SMALL = decltype(small_c)::value;
     static size_t set_for = 0;
     if (sh > set_for) {
-      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, SMALL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       set_for = sh;
     }
-    k_crossq_attention<NV><<<g, 256, sh, s>>>(ln, (const bf16_t*)A, (const bf16_t*)W, bias, (const bf16_t*)K,
-                                              (const bf16_t*)V, (bf16_t*)out, desc, scale, chunk);
+    k_crossq_attention<NV, SMALL><<<g, 256, sh, s>>>(ln, (const bf16_t*)A, (const bf16_t*)W, bias, (const bf16_t*)K,
+                                                     (const bf16_t*)V, (bf16_t*)out, desc, scale, chunk);
   };
-  if (d == 512) go(std::integral_constant<int, 2>{});
-  else go(std::integral_constant<int, 4>{});
+  using I2 = std::integral_constant<int, 2>;
+  using I4 = std::integral_constant<int, 4>;
+  if (d == 512) { if (small) go(I2{}, std::true_type{}); else go(I2{}, std::false_type{}); }
+  else { if (small) go(I4{}, std::true_type{}); else go(I4{}, std::false_type{}); }
   return true;
 }
 
