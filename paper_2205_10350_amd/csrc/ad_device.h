@@ -206,12 +206,14 @@ template <int MT> struct EpiRegs {
   float bias;
   unsigned aux[MT * 4];   // destination row (QKV / KV) or the residual value's bits (RESID): never both
 };
-template <int MT>
+// EM: the epilogue mode where the caller knows it at compile time (the mode's branches then fold
+// away), -1: e.mode decides at run time.
+template <int MT, int EM = -1>
 __device__ __forceinline__ void epi_preload(const Epi& e, int mt_used, int m0, int n0, int M, int N, int lane,
                                             EpiRegs<MT>& g) {
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
   g.bias = e.bias ? gload(e.bias + n) : 0.f;
-  const int mode = e.mode;
+  const int mode = EM < 0 ? e.mode : EM;
   const bool want_dst = (mode == EPI_QKV && n0 >= e.d) || mode == EPI_KV, want_res = mode == EPI_RESID;
   // all MT tiles inside the matrix: no per-row tests (the common case away from the last rows)
   const bool full = mt_used == MT && m0 + MT * 16 <= M;
@@ -237,11 +239,11 @@ __device__ __forceinline__ void epi_preload(const Epi& e, int mt_used, int m0, i
 }
 // value = acc + bias, then the mode's operation.  A strip of 16 columns lies inside one of the
 // q / k / v column ranges (d is a multiple of 16), so the destination is uniform over the wave.
-template <typename T, int MT>
+template <typename T, int MT, int EM = -1>
 __device__ __forceinline__ void epi_apply(const Epi& e, const f32x4 (&acc)[MT], const EpiRegs<MT>& g, int mt_used,
                                           int m0, int n0, int M, int N, int lane) {
   const int r = lane & 15, kq = lane >> 4, n = n0 + r;
-  const int mode = e.mode, d = e.d;
+  const int mode = EM < 0 ? e.mode : EM, d = e.d;
   const bool has_bias = e.bias != nullptr;
   const bool full = mt_used == MT && m0 + MT * 16 <= M;
   if (mode == EPI_RESID) {

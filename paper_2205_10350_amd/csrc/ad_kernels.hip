@@ -159,7 +159,7 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
   }
 }
 
-template <int MT, int AMAX, int SP, bool ONE>
+template <int MT, int AMAX, int SP, bool ONE, int LNMODE = -1, int EM = -1>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, Epi e, int strips_per_wg, int groups,
                                                             int chunks, LnA ln) {
@@ -218,12 +218,14 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   if constexpr (!ROWS_FIRST) prefetch0();
   auto behind_rows = [&]() { if constexpr (ROWS_FIRST) prefetch0(); };
   // stage the rows (past M: the last valid row, computed and never stored)
-  if (ln.x) {
+  // (LNMODE 0 / 1: the caller knows at compile time that no LayerNorm / a LayerNorm is pending)
+  const bool has_ln = LNMODE < 0 ? ln.x != nullptr : LNMODE == 1;
+  if (has_ln) {
     // rows to be normalised first (K = 512 or 1024): the statistics and values of the LayerNorm
     // kernel; the workgroups of strip group 0 also store the fp32 rows
     // (the output projection is the last consumer of its rows: nobody needs them in fp32)
     const bool keep_y = group == 0 && AMAX == 0;
-    if (K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
+    if (ONE || K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
     else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
   } else if (MT == 1 && !ONE && halves == 4) {
     // few rows of K = 2048: every slice's loads before the weights
@@ -302,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
       if (last) {
 #pragma unroll
         for (int j = 0; j < SP; ++j)
-          if (s0 + j < s_end) epi_preload<MT>(e, MT, m0, (s0 + j) << 4, M, N, lane, g[j]);
+          if (s0 + j < s_end) epi_preload<MT, EM>(e, MT, m0, (s0 + j) << 4, M, N, lane, g[j]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
       } else if constexpr (PRE) {
 #pragma unroll
         for (int j = 0; j < SP; ++j)
-          if (s0 + j < s_end) epi_apply<bf16_t, MT>(e, acc[j], g[j], MT, m0e, (s0 + j) << 4, M, N, lane);
+          if (s0 + j < s_end) epi_apply<bf16_t, MT, EM>(e, acc[j], g[j], MT, m0e, (s0 + j) << 4, M, N, lane);
       } else {
 #pragma unroll
         for (int j = 0; j < SP; ++j)
@@ -495,7 +497,27 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
   if (K == 512) {
     if (amax) go(I1{}, std::true_type{});
     else if (count) go(I3{}, std::true_type{});
-    else go(I0{}, std::true_type{});
+    else if constexpr (MT == 1 && SP == 1) {
+      // the layer GEMMs of the few-row regime: the pending LayerNorm (or none) and the epilogue mode as
+      // compile-time constants, a kernel per combination that occurs (run-time branches around loads in
+      // flight make the compiler wait for all of them: 0.1-0.2 us per launch)
+      auto hot = [&](auto ln_c, auto em_c) {
+        constexpr int LNM = decltype(ln_c)::value, EMV = decltype(em_c)::value;
+        static size_t set_hot = 0;
+        if (lds > set_hot) {
+          (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+          set_hot = lds;
+        }
+        k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
+      };
+      using L0 = std::integral_constant<int, 0>;
+      using L1 = std::integral_constant<int, 1>;
+      if (ln.x && e.mode == EPI_QKV) hot(L1{}, std::integral_constant<int, EPI_QKV>{});
+      else if (ln.x && e.mode == EPI_RELU) hot(L1{}, std::integral_constant<int, EPI_RELU>{});
+      else if (!ln.x && e.mode == EPI_RESID) hot(L0{}, std::integral_constant<int, EPI_RESID>{});
+      else if (!ln.x && e.mode == EPI_QKV) hot(L0{}, std::integral_constant<int, EPI_QKV>{});
+      else go(I0{}, std::true_type{});
+    } else go(I0{}, std::true_type{});
   } else {
     if (amax) go(I1{}, std::false_type{});
     else if (count) go(I3{}, std::false_type{});
