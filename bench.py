@@ -36,12 +36,12 @@ MFMA_BF16_PEAK = 2.5e15  # FLOP/s dense bf16, MI355X published
 # under `vocab_kernel.traffic_from_profile`, not a reading of this run
 VOCAB_KERNEL_TRAFFIC_BYTES = int(16336.9 * 1024 * (262144.0 / 131083.0) + 482.7 * 1024)
 # HBM bytes of one verify forward of the base model at batch 1, 25 rows: the sum over its 45 launches of
-# FETCH_SIZE (49938.6 KiB x 2.000) and WRITE_SIZE (3566.2 KiB x 1.000) per dispatch, two rocprofv3 --pmc
+# FETCH_SIZE (48909.7 KiB x 2.000) and WRITE_SIZE (3566.1 KiB x 1.000) per dispatch, two rocprofv3 --pmc
 # runs of `bench.py --profile-forward 1 25 --calibration-copy`
 # (profiles/verify_forward_base_bs1_25rows_hbm_traffic.md).  A figure of that counter run, not a reading
 # of this one; the row count of the forward timed below may differ by a few rows, which moves it by
 # well under 1 % (weights are 98 % of it).
-VERIFY_FORWARD_TRAFFIC_BYTES = int(49938.6 * 1024 * (262144.0 / 131086.6) + 3566.2 * 1024)
+VERIFY_FORWARD_TRAFFIC_BYTES = int(48909.7 * 1024 * (262144.0 / 131084.9) + 3566.1 * 1024)
 
 
 def decoder_stream_params(dims):
