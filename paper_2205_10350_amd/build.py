@@ -9,8 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libad_mi355x.so")
 SOURCES = ["ad_hostlogic.cpp", "ad_api.cpp", "ad_kernels.hip"]
+# -amdgpu-mfma-vgpr-form: MFMA results go to ordinary vector registers, not to the accumulation
+# registers and back through copies before every vector instruction that reads them (masks, maxima,
+# epilogues): 1-2 % of the forward, no spills.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
 
 

@@ -528,13 +528,14 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
           }
         }
       }
+      // (a key tile that does not exist needs no test of its own: its keys' indices are at least
+      // 16 nt, which no row of the tile sees)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int j = 0; j < NT; ++j) {
+        const int key = 16 * (ch * NT + j) + r;
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-          const int jg = ch * NT + j;
-          S[j][i] = (jg < nt && 16 * jg + r < nkr[i]) ? S[j][i] * scale : -INFINITY;
-        }
+        for (int i = 0; i < 4; ++i) S[j][i] = key < nkr[i] ? S[j][i] * scale : -INFINITY;
+      }
     };
     f32x4 S[NT];
     float mx[4], sum[4], l[4];
