@@ -12,8 +12,11 @@ SOURCES = ["ad_hostlogic.cpp", "ad_api.cpp", "ad_kernels.hip"]
 # -amdgpu-mfma-vgpr-form: MFMA results go to ordinary vector registers, not to the accumulation
 # registers and back through copies before every vector instruction that reads them (masks, maxima,
 # epilogues): 1-2 % of the forward, no spills.
+# -amdgpu-kernarg-preload-count=16: the first 64 bytes of a kernel's arguments are in scalar registers
+# when a wave starts instead of being loaded (in two or three dependent steps) by its first
+# instructions; the kernels order their arguments for it: 4-6 % of the forward.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
 
 

@@ -159,10 +159,13 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
   }
 }
 
+// (Argument order, here and in the other kernels of a forward: the first 64 bytes of a kernel's arguments are in
+// scalar registers when a wave starts (kernel-argument preload); what the prologue needs first, the sizes that decide
+// the workgroup's place and the pointers of the first loads, comes first, the epilogue's description last.)
 template <int MT, int AMAX, int SP, bool ONE, int LNMODE = -1, int EM = -1>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                            int M, int N, int K, Epi e, int strips_per_wg, int groups,
-                                                            int chunks, LnA ln) {
+                                                            int M, int N, int K, int strips_per_wg, int groups,
+                                                            int chunks, LnA ln, Epi e) {
   constexpr int ROWS = MT * 16;
   extern __shared__ uint4 astat_lds[];
   bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 16]
@@ -479,7 +482,7 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
       (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, AMAX, SP, ONE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       set_for = lds;
     }
-    k_gemm_bf16_astat<MT, AMAX, SP, ONE><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
+    k_gemm_bf16_astat<MT, AMAX, SP, ONE><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln, e);
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -508,7 +511,7 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
           (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
           set_hot = lds;
         }
-        k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV><<<grid, 256, lds, s>>>(A, W, M, N, K, e, per_wg, gx, chunks, ln);
+        k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln, e);
       };
       using L0 = std::integral_constant<int, 0>;
       using L1 = std::integral_constant<int, 1>;
@@ -552,7 +555,7 @@ __device__ __forceinline__ void kchain_request(const bf16_t* __restrict__ A, con
 }
 template <int NS>
 __global__ __launch_bounds__(256) void k_gemm_bf16_kchain(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                         int M, int N, int K, Epi e, int n_strips) {
+                                                         int M, int N, int K, int n_strips, Epi e) {
   constexpr int LD = 512 + 16;               // row stride of a wave's tile (elements): see the kernel above
   __shared__ uint4 tiles[4 * 16 * LD / 8];   // [wave][16 rows][LD]: each wave stages its own slice, no barrier
   __shared__ f32x4 hand[64];
@@ -584,9 +587,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16_kchain(const bf16_t* __restri
 }
 static void launch_kchain(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epi& e, hipStream_t s) {
   const int n_strips = N / 16, grid = n_strips * ((M + 15) / 16);
-  if (K == 1024) k_gemm_bf16_kchain<2><<<grid, 256, 0, s>>>(A, W, M, N, K, e, n_strips);
-  else if (K == 2048) k_gemm_bf16_kchain<4><<<grid, 256, 0, s>>>(A, W, M, N, K, e, n_strips);
-  else k_gemm_bf16_kchain<8><<<grid, 256, 0, s>>>(A, W, M, N, K, e, n_strips);
+  if (K == 1024) k_gemm_bf16_kchain<2><<<grid, 256, 0, s>>>(A, W, M, N, K, n_strips, e);
+  else if (K == 2048) k_gemm_bf16_kchain<4><<<grid, 256, 0, s>>>(A, W, M, N, K, n_strips, e);
+  else k_gemm_bf16_kchain<8><<<grid, 256, 0, s>>>(A, W, M, N, K, n_strips, e);
 }
 
 // ------------------------------------------------------------------------------------- fp32 GEMM
@@ -842,11 +845,11 @@ __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __re
     }
 }
 template <int NV, bool SMALL>
-__global__ __launch_bounds__(256) void k_crossq_attention(LnA ln, const bf16_t* __restrict__ A,
-                                                          const bf16_t* __restrict__ W, const float* __restrict__ bias,
-                                                          const bf16_t* __restrict__ Kb, const bf16_t* __restrict__ Vb,
-                                                          bf16_t* __restrict__ out, const SeqDesc* __restrict__ desc,
-                                                          float scale, int chunk_rows) {
+__global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
+                                                          const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
+                                                          const bf16_t* __restrict__ Vb, LnA ln,
+                                                          const bf16_t* __restrict__ A, const float* __restrict__ bias,
+                                                          bf16_t* __restrict__ out) {
   constexpr int K = 256 * NV, KS = K / 32, DH = 64, ld = K + 16, QLD = kCrossqQld, G = DH / 8;
   extern __shared__ uint4 cq_lds[];
   const SeqDesc sd = desc[blockIdx.x];
@@ -962,8 +965,8 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
       (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, SMALL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       set_for = sh;
     }
-    k_crossq_attention<NV, SMALL><<<g, 256, sh, s>>>(ln, (const bf16_t*)A, (const bf16_t*)W, bias, (const bf16_t*)K,
-                                                     (const bf16_t*)V, (bf16_t*)out, desc, scale, chunk);
+    k_crossq_attention<NV, SMALL><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
+                                                     ln, (const bf16_t*)A, bias, (bf16_t*)out);
   };
   using I2 = std::integral_constant<int, 2>;
   using I4 = std::integral_constant<int, 4>;
@@ -1132,12 +1135,12 @@ void launch_argmax_draft(const float* pv, const int* pi, int M, int stride, int 
 // by the same scan and embeds it.
 template <typename T>
 __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __restrict__ k, const int* __restrict__ draft,
-                                                               int k_max, const int* __restrict__ len,
-                                                               const int* __restrict__ pending,
-                                                               const int* __restrict__ src_len, int B, int l_cap,
-                                                               int s_max, VerifyTables t, const T* __restrict__ emb,
-                                                               const float* __restrict__ pe, int d, float sqrt_d,
-                                                               float* __restrict__ x, T* __restrict__ xa, int M) {
+                                                               const int* __restrict__ len,
+                                                               const int* __restrict__ pending, const T* __restrict__ emb,
+                                                               const float* __restrict__ pe, float* __restrict__ x,
+                                                               T* __restrict__ xa, int k_max, int B, int d, float sqrt_d,
+                                                               int M, int l_cap, int s_max,
+                                                               const int* __restrict__ src_len, VerifyTables t) {
   // k lives in host memory (a trip over the bus); with one sequence it is the row count M
   __shared__ int where[2];
   if (blockIdx.x != 0) {
@@ -1196,11 +1199,11 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
                                   hipStream_t s) {
   if (M <= 0) return;
   if (dtype == AD_BF16)
-    k_assemble_embed_verify<bf16_t><<<M + 1, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
-                                                      (const bf16_t*)emb, pe, d, sqrt_d, x, (bf16_t*)xa, M);
+    k_assemble_embed_verify<bf16_t><<<M + 1, 128, 0, s>>>(k, draft, len, pending, (const bf16_t*)emb, pe, x, (bf16_t*)xa, k_max,
+                                                      B, d, sqrt_d, M, l_cap, s_max, src_len, t);
   else
-    k_assemble_embed_verify<float><<<M + 1, 128, 0, s>>>(k, draft, k_max, len, pending, src_len, B, l_cap, s_max, t,
-                                                     (const float*)emb, pe, d, sqrt_d, x, (float*)xa, M);
+    k_assemble_embed_verify<float><<<M + 1, 128, 0, s>>>(k, draft, len, pending, (const float*)emb, pe, x, (float*)xa, k_max, B,
+                                                     d, sqrt_d, M, l_cap, s_max, src_len, t);
 }
 
 // Encoder: rows = x_1..x_n of every sentence at positions 0..n-1, full self-attention over the
@@ -1418,15 +1421,15 @@ void launch_draft_scatter(const int* o_hat, const int* finished, int B, int k, i
 // it is dead and overwritten by the next call.
 // One workgroup per sequence: its waves finish the arg max of the sequence's rows (argmax_row over
 // the partials, as k_argmax_finish does), then one thread accepts.
-__global__ __launch_bounds__(1024) void k_argmax_accept(const float* __restrict__ pv, const int* __restrict__ pi, int stride,
-                                                       int n_part, int* __restrict__ o_hat, float* __restrict__ o_val,
-                                                       const int* __restrict__ k, const int* __restrict__ draft, int k_max,
-                                                       const int* __restrict__ row_start, int eos, int max_len,
-                                                       const int* __restrict__ max_out, int* __restrict__ len,
+__global__ __launch_bounds__(1024) void k_argmax_accept(const int* __restrict__ k, const int* __restrict__ draft,
+                                                       const int* __restrict__ ticket_in, const int* __restrict__ row_start,
+                                                       const float* __restrict__ pv, const int* __restrict__ pi,
+                                                       int* __restrict__ len, int M, int k_max, int stride, int n_part,
+                                                       const int* __restrict__ max_out, int* __restrict__ o_hat,
+                                                       float* __restrict__ o_val, int eos, int max_len,
                                                        int* __restrict__ pending, int* __restrict__ finished,
                                                        int* __restrict__ out, int* __restrict__ result,
-                                                       const int* __restrict__ ticket_in,
-                                                       unsigned long long* __restrict__ ticket_out, int M, GadppIn gp) {
+                                                       unsigned long long* __restrict__ ticket_out, GadppIn gp) {
   const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int kb = gridDim.x == 1 ? M : k[b];   // k is in host memory; a lone sequence owns all M rows
   if (kb == 0) {
@@ -1504,8 +1507,8 @@ void launch_argmax_accept(const float* pv, const int* pi, int stride, int n_part
                           const GadppIn& gp) {
   // as many waves as the longest block has rows (4 to 16): a wave finishes a row at a time
   const int waves = std::min(16, std::max(4, max_rows));
-  k_argmax_accept<<<B, 64 * waves, 0, s>>>(pv, pi, stride, n_part, o_hat, o_val, k, draft, k_max, row_start, eos, max_len,
-                                    max_out, len, pending, finished, out, result, ticket_in, ticket_out, M, gp);
+  k_argmax_accept<<<B, 64 * waves, 0, s>>>(k, draft, ticket_in, row_start, pv, pi, len, M, k_max, stride, n_part, max_out,
+                                    o_hat, o_val, eos, max_len, pending, finished, out, result, ticket_out, gp);
 }
 // ------------------------------------------------------------------------------------- GAD++ (Section 3.2.3)
 // The drafted token of packed row m: draft[b][i] for row i of sequence b.
