@@ -165,7 +165,13 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
 template <int MT, int AMAX, int SP, bool ONE, int LNMODE = -1, int EM = -1>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, int strips_per_wg, int groups,
-                                                            int chunks, LnA ln, Epi e) {
+                                                            int chunks, const float* __restrict__ ln_x,
+                                                            const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+                                                            float* __restrict__ ln_y, Epi e) {
+  // (the pending LayerNorm as four plain pointers: a structure among the arguments ends the run of
+  // arguments that are preloaded into scalar registers)
+  LnA ln;
+  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
   constexpr int ROWS = MT * 16;
   extern __shared__ uint4 astat_lds[];
   bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 16]
@@ -482,7 +488,7 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
       (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, AMAX, SP, ONE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       set_for = lds;
     }
-    k_gemm_bf16_astat<MT, AMAX, SP, ONE><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln, e);
+    k_gemm_bf16_astat<MT, AMAX, SP, ONE><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln.x, ln.g, ln.b, ln.y, e);
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -511,7 +517,7 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
           (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
           set_hot = lds;
         }
-        k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln, e);
+        k_gemm_bf16_astat<1, 0, 1, true, LNM, EMV><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln.x, ln.g, ln.b, ln.y, e);
       };
       using L0 = std::integral_constant<int, 0>;
       using L1 = std::integral_constant<int, 1>;
@@ -847,9 +853,12 @@ __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __re
 template <int NV, bool SMALL>
 __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
                                                           const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
-                                                          const bf16_t* __restrict__ Vb, LnA ln,
-                                                          const bf16_t* __restrict__ A, const float* __restrict__ bias,
-                                                          bf16_t* __restrict__ out) {
+                                                          const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
+                                                          const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+                                                          float* __restrict__ ln_y, const bf16_t* __restrict__ A,
+                                                          const float* __restrict__ bias, bf16_t* __restrict__ out) {
+  LnA ln;
+  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
   constexpr int K = 256 * NV, KS = K / 32, DH = 64, ld = K + 16, QLD = kCrossqQld, G = DH / 8;
   extern __shared__ uint4 cq_lds[];
   const SeqDesc sd = desc[blockIdx.x];
@@ -966,7 +975,7 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
       set_for = sh;
     }
     k_crossq_attention<NV, SMALL><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
-                                                     ln, (const bf16_t*)A, bias, (bf16_t*)out);
+                                                     ln.x, ln.g, ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
   };
   using I2 = std::integral_constant<int, 2>;
   using I4 = std::integral_constant<int, 4>;
