@@ -162,8 +162,9 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
 // (Argument order, here and in the other kernels of a forward: the first 64 bytes of a kernel's arguments are in
 // scalar registers when a wave starts (kernel-argument preload); what the prologue needs first, the sizes that decide
 // the workgroup's place and the pointers of the first loads, comes first, the epilogue's description last.)
-template <int MT, int AMAX, int SP, bool ONE, int LNMODE = -1, int EM = -1>
-__global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+// NW waves per workgroup (4, 8 or 16): a wave stages MT*16/NW rows and owns every NW-th run of SP strips.
+template <int MT, int AMAX, int SP, bool ONE, int LNMODE = -1, int EM = -1, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 16 ? 4 : 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, int strips_per_wg, int groups,
                                                             int chunks, const float* __restrict__ ln_x,
                                                             const float* __restrict__ ln_g, const float* __restrict__ ln_b,
@@ -172,7 +173,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   // arguments that are preloaded into scalar registers)
   LnA ln;
   ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
-  constexpr int ROWS = MT * 16;
+  constexpr int ROWS = MT * 16, RPW = ROWS / NW;   // rows a wave stages
+  static_assert(ROWS % NW == 0, "rows per workgroup must divide among the waves");
   extern __shared__ uint4 astat_lds[];
   bf16_t* At = (bf16_t*)astat_lds;          // [ROWS][K + 16]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -198,13 +200,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   const bf16_t* a_lane = At + r * ld + kq * 8;
   const int s_begin = group * strips_per_wg, s_end = min(n_strips, s_begin + strips_per_wg);
   const int s_first = s_begin + SP * wave;
-  const int n_units = s_first < s_end ? ((s_end - s_first + 4 * SP - 1) / (4 * SP)) * halves : 0;
+  const int n_units = s_first < s_end ? ((s_end - s_first + NW * SP - 1) / (NW * SP)) * halves : 0;
   // this lane's fragment addresses of unit q (clamped: the refill after the last unit re-reads it;
   // a wave without strips reads the workgroup's first strip and never uses it)
   auto unit_ptrs = [&](int q, const bf16_t* (&w)[SP]) {
     q = max(0, min(q, n_units - 1));
     const int p = q / halves, k0 = (q - p * halves) << 9;
-    const int s0 = n_units > 0 ? s_first + 4 * SP * p : s_begin;
+    const int s0 = n_units > 0 ? s_first + NW * SP * p : s_begin;
 #pragma unroll
     for (int j = 0; j < SP; ++j)
       w[j] = W + ((size_t)(min(s0 + j, s_end - 1) << 4) * K + (size_t)k0 * 16 + lane * 8);
@@ -234,9 +236,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     // kernel; the workgroups of strip group 0 also store the fp32 rows
     // (the output projection is the last consumer of its rows: nobody needs them in fp32)
     const bool keep_y = group == 0 && AMAX == 0;
-    if (ONE || K == 512) astat_stage_ln<2, (SP == 1 ? 8 : 4)>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
-    else astat_stage_ln<4, 4>(ln, At, ld, wave * MT * 4, MT * 4, m0, M, lane, keep_y, behind_rows);
-  } else if (MT == 1 && !ONE && halves == 4) {
+    if (ONE || K == 512) astat_stage_ln<2, (SP == 1 && RPW >= 8 ? 8 : RPW >= 4 ? 4 : RPW)>(ln, At, ld, wave * RPW, RPW, m0, M, lane, keep_y, behind_rows);
+    else astat_stage_ln<4, (RPW >= 4 ? 4 : RPW)>(ln, At, ld, wave * RPW, RPW, m0, M, lane, keep_y, behind_rows);
+  } else if (MT == 1 && NW == 4 && !ONE && halves == 4) {
     // few rows of K = 2048: every slice's loads before the weights
     uint4 av[4][4];
 #pragma unroll
@@ -252,13 +254,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   } else
   // a wave's loads of a 512-column slice are all issued before the first LDS store
   for (int h = 0; h < halves; ++h) {
-    uint4 av[MT * 4];
+    uint4 av[RPW];
 #pragma unroll
-    for (int i = 0; i < MT * 4; ++i)
-      av[i] = *(const uint4*)(A + (size_t)min(m0 + wave * MT * 4 + i, M - 1) * K + h * 512 + lane * 8);
+    for (int i = 0; i < RPW; ++i)
+      av[i] = *(const uint4*)(A + (size_t)min(m0 + wave * RPW + i, M - 1) * K + h * 512 + lane * 8);
     if (h == 0) behind_rows();
 #pragma unroll
-    for (int i = 0; i < MT * 4; ++i) *(uint4*)(At + (wave * MT * 4 + i) * ld + h * 512 + lane * 8) = av[i];
+    for (int i = 0; i < RPW; ++i) *(uint4*)(At + (wave * RPW + i) * ld + h * 512 + lane * 8) = av[i];
   }
   __syncthreads();
   f32x4 acc_x[SP][MT];   // lives across the units of a strip when K has several 512-slices
@@ -293,7 +295,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
     constexpr bool REFILL = decltype(refill_c)::value;
     const int p = q / halves, k0 = (q - p * halves) << 9;
     const bool last = k0 + 512 == K;
-    const int s0 = s_first + 4 * SP * p;
+    const int s0 = s_first + NW * SP * p;
     const bf16_t* wn[SP];
     unit_ptrs(q + 1, wn);
     // ONE (K = 512): a unit is a whole dot product; its accumulators are the unit's own
@@ -414,9 +416,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
   for (int q = 0; q + 1 < n_units; ++q) unit(std::true_type{}, q);
   if (n_units > 0) unit(std::false_type{}, n_units - 1);
   if constexpr (AMAX) {
-    // rows of 16 lanes reduce by lane moves, the four waves through LDS
-    float* mv = (float*)(At + ROWS * ld);   // [4 waves][ROWS]
-    int* mi = (int*)(mv + 4 * ROWS);
+    // rows of 16 lanes reduce by lane moves, the waves through LDS
+    float* mv = (float*)(At + ROWS * ld);   // [NW waves][ROWS]
+    int* mi = (int*)(mv + NW * ROWS);
     // (all lane reductions first: independent chains; then one branch for the LDS writes)
 #pragma unroll
     for (int x = 0; x < MT * 4; ++x) {
@@ -436,13 +438,13 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
       if constexpr (AMAX == 3) {
         int cnt = mi[threadIdx.x];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) cnt += mi[w * ROWS + threadIdx.x];
+        for (int w = 1; w < NW; ++w) cnt += mi[w * ROWS + threadIdx.x];
         e.part_idx[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = cnt;
       } else {
         float v = mv[threadIdx.x];
         int idx = mi[threadIdx.x];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) argmax_merge(v, idx, mv[w * ROWS + threadIdx.x], mi[w * ROWS + threadIdx.x]);
+        for (int w = 1; w < NW; ++w) argmax_merge(v, idx, mv[w * ROWS + threadIdx.x], mi[w * ROWS + threadIdx.x]);
         e.part_val[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = v;
         e.part_idx[(size_t)(m0 + threadIdx.x) * e.n_strips + group] = idx;
       }
@@ -453,7 +455,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_astat(const bf16_t* __rest
 // XCD runs its workgroups in rounds of (32 CUs x workgroups per CU); a workgroup costs a fixed
 // part (launch, staging the rows, drain) plus its units.  Strips per workgroup are a multiple of
 // eight (four waves, two strips each).
-static size_t astat_lds_bytes(int mt, int K) { return (size_t)mt * 16 * (K + 16) * 2 + 4 * (size_t)mt * 16 * 8; }
+static size_t astat_lds_bytes(int mt, int K, int nw = 4) { return (size_t)mt * 16 * (K + 16) * 2 + nw * (size_t)mt * 16 * 8; }
 static float astat_plan(int mt, int M, int N, int K, bool with_ln, int* per_wg_out) {
   const int chunks = (M + mt * 16 - 1) / (mt * 16), n_strips = N / 16, halves = K / 512;
   const size_t lds = astat_lds_bytes(mt, K);
@@ -473,11 +475,11 @@ static float astat_plan(int mt, int M, int N, int K, bool with_ln, int* per_wg_o
   }
   return best;
 }
-template <int MT, int SP>
+template <int MT, int SP, int NW = 4>
 static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, const Epi& e, int per_wg, hipStream_t s,
                         const LnA& ln) {
   const int chunks = (M + MT * 16 - 1) / (MT * 16), n_strips = N / 16;
-  const size_t lds = astat_lds_bytes(MT, K);
+  const size_t lds = astat_lds_bytes(MT, K, NW);
   const int gx = (n_strips + per_wg - 1) / per_wg;
   const int grid = (gx >= 8 ? (gx + 7) / 8 * 8 : gx) * chunks;
   auto go = [&](auto amax_c, auto one_c) {
@@ -485,16 +487,16 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
     constexpr bool ONE = decltype(one_c)::value;
     static size_t set_for = 0;
     if (lds > set_for) {
-      (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, AMAX, SP, ONE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, AMAX, SP, ONE, -1, -1, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       set_for = lds;
     }
-    k_gemm_bf16_astat<MT, AMAX, SP, ONE><<<grid, 256, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln.x, ln.g, ln.b, ln.y, e);
+    k_gemm_bf16_astat<MT, AMAX, SP, ONE, -1, -1, NW><<<grid, 64 * NW, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln.x, ln.g, ln.b, ln.y, e);
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
   const bool amax = e.mode == EPI_ARGMAX;
-  if constexpr (MT == 1 && SP == 1) {
+  if constexpr (MT == 1 && SP == 1 && NW == 4) {
     if (amax && e.logits) {   // launch_gemm sends every request for logits here
       if (K == 512) go(I2{}, std::true_type{});
       else go(I2{}, std::false_type{});
@@ -503,10 +505,15 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
   }
   using I3 = std::integral_constant<int, 3>;
   const bool count = e.mode == EPI_COUNT;
+  if constexpr (NW != 4) {   // the wide workgroups serve the layer GEMMs only
+    if (K == 512) go(I0{}, std::true_type{});
+    else go(I0{}, std::false_type{});
+    return gx;
+  } else
   if (K == 512) {
     if (amax) go(I1{}, std::true_type{});
     else if (count) go(I3{}, std::true_type{});
-    else if constexpr (MT == 1 && SP == 1) {
+    else if constexpr (MT == 1 && SP == 1 && NW == 4) {
       // the layer GEMMs of the few-row regime: the pending LayerNorm (or none) and the epilogue mode as
       // compile-time constants, a kernel per combination that occurs (run-time branches around loads in
       // flight make the compiler wait for all of them: 0.1-0.2 us per launch)
@@ -672,6 +679,21 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
       // the same shape.
       const int mt = 1;
       const bool want_logits = e.mode == EPI_ARGMAX && e.logits != nullptr;
+      // 520 rows and more of the d = 512 layer GEMMs: 32 rows per workgroup in workgroups of 16 or 8 waves, one
+      // strip and one unit per 512-slice for each wave, while the launch stays within one round of the chip
+      // (a wave stages 2 or 4 rows instead of 8, and every wave's weights are requested at once; measured at
+      // 1152 rows: QKV with the LayerNorm 12.4 -> 9.6 us, attention output projections 7.0 -> 5.5 us, FFN2
+      // 12.9 -> 11.0 us; forward at 576 / 720 / 864 / 1008 / 1152 rows 372 / 411 / 425 / 453 / 517 ->
+      // 362 / 393 / 401 / 417 / 458 us, at 432 rows 321 -> 350 us the other way; FFN1's 128 strips would need
+      // two rounds and gained nothing in any shape tried; K = 1024: drafter forward of the wide model at 626
+      // rows 983 -> 1073 us, so those shapes keep the rules below)
+      if (M >= 520 && e.mode != EPI_ARGMAX && e.mode != EPI_COUNT) {
+        const int n_strips = N / 16, chunks2 = (M + 31) / 32;
+        if (K == 512 && n_strips >= 64 && n_strips % 16 == 0 && (n_strips / 16) * chunks2 <= 256)
+          return launch_astat<2, 1, 16>(a, w, M, N, K, e, 16, s, ln);
+        if ((K == 512 || K == 2048) && !ln.x && n_strips % 8 == 0 && (n_strips / 8) * chunks2 <= 256)
+          return launch_astat<2, 1, 8>(a, w, M, N, K, e, 8, s, ln);
+      }
       if ((M <= 64 || (M <= 1024 && N <= 4096) || want_logits) && astat_lds_bytes(mt, K) <= 150 * 1024) {
         {
           const int n_strips = N / 16, chunks = (M + 15) / 16;

@@ -243,7 +243,8 @@ def test_rows_do_not_depend_on_block_or_batch_shape():
 def test_rows_do_not_depend_on_the_row_regime_of_the_gemm_kernels():
     """Base model, bit-exact: the logits of one sequence's 36-row block verified alone (16 rows per
     workgroup), among 9 / 16 / 20 / 26 sequences (324 / 576 / 720 / 936 packed rows: 16-row chunks with more
-    strips per workgroup, 32 rows per workgroup) and among 30 (1080 rows: the many-row variants)."""
+    strips per workgroup; from 520 rows 32 rows per workgroup in workgroups of 8 and 16 waves) and among 30
+    (1080 rows: the many-row variants)."""
     B = 30
     rig = Rig("base", "bf16", 83, B=B, max_src=40, max_len=48, k_max=40)
     try:
