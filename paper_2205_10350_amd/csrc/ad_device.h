@@ -538,7 +538,7 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       }
     };
     f32x4 S[NT];
-    float mx[4], sum[4], l[4];
+    float mx[4], l[4];
     // exact row maximum: one pass over all key tiles (more than NT of them: the scores are
     // computed again, tile group by tile group, in the pass below)
     {
@@ -551,12 +551,26 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
           for (int j = 0; j < NT; ++j) m[i] = fmaxf(m[i], S[j][i]);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { mx[i] = row16_max(m[i]); sum[i] = 0.f; }
+      for (int i = 0; i < 4; ++i) mx[i] = row16_max(m[i]);
     }
-    f32x4 O[CT];
+    // More than 128 keys (NT = 16), head width up to 64: the keys are taken in super-blocks of 128, super-block sb adds
+    // into accumulator sb % 4 (output sums and denominators alike, ascending inside an accumulator), and the four are
+    // combined as (a0 + a1) + (a2 + a3) at the end.  The order depends on the key index alone, so the kernel that gives
+    // the four accumulators to four waves (attn_split_keys) produces the same bits; with at most 128 keys there is one
+    // chain.  (Wider heads: one chain; no kernel splits their keys, and four accumulator sets would not fit the registers.)
+    constexpr int NA = NT == 16 && DH <= 64 ? 4 : 1;
+    f32x4 O[NA][CT];
+    float psum[NA][4];
 #pragma unroll
-    for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int ch = 0; ch < max(nch, 1); ++ch) {
+    for (int a = 0; a < NA; ++a) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) O[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) psum[a][i] = 0.f;
+    }
+    // group ch of NT key tiles; PAR = ch % 2 at compile time (a group of 16 tiles is the two super-blocks 2 ch, 2 ch + 1)
+    auto group = [&](auto par_c, int ch) {
+      constexpr int PAR = decltype(par_c)::value;
       if (nch > 1) scores(ch, S);
       const int tiles_here = 2 * nb - ch * NT;   // tiles of this group the output product reads (an odd count is padded with zeros)
       // Slot i of a lane holds row row0 + 4*kq + i.  All four slots are computed, tile by tile, as
@@ -570,33 +584,48 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
           for (int i = 0; i < 4; ++i) {
             // e^x as 2^(x log2 e) on the hardware exponential; 2^(-inf) = 0 for the keys the row does not see
             const float pv = __builtin_amdgcn_exp2f((S[j][i] - mx[i]) * 1.44269504088896340736f);
-            sum[i] += pv;
+            psum[NA == 1 ? 0 : (2 * PAR + (j >> 3)) & 3][i] += pv;
             Pw[(4 * kq + i) * ldv + r + 16 * j] = f2bf(pv);
           }
         }
       }
       __builtin_amdgcn_wave_barrier();
-      const int kb_end = min(nb, (ch + 1) * (NT / 2));
-      for (int kb = ch * (NT / 2); kb < kb_end; ++kb) {
-        const uint4 pa = *(const uint4*)(Pw + r * ldv + 32 * (kb - ch * (NT / 2)) + 8 * kq);
-        uint4 vb[CT];
 #pragma unroll
-        for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vt + (16 * c + r) * ldv + 32 * kb + 8 * kq);
+      for (int half = 0; half < (NA == 1 ? 1 : 2); ++half) {
+        const int kb_begin = ch * (NT / 2) + (NA == 1 ? 0 : 4 * half);
+        const int kb_end = min(nb, NA == 1 ? (ch + 1) * (NT / 2) : kb_begin + 4);
+        f32x4 (&Oa)[CT] = O[NA == 1 ? 0 : (2 * PAR + half) & 3];
+        for (int kb = kb_begin; kb < kb_end; ++kb) {
+          const uint4 pa = *(const uint4*)(Pw + r * ldv + 32 * (kb - ch * (NT / 2)) + 8 * kq);
+          uint4 vb[CT];
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
-          O[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), O[c], 0, 0, 0);
+          for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vt + (16 * c + r) * ldv + 32 * kb + 8 * kq);
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+            Oa[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), Oa[c], 0, 0, 0);
+        }
       }
       __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the next group and the wave's next rows
+    };
+    for (int ch = 0; ch < max(nch, 1); ch += 2) {
+      group(std::integral_constant<int, 0>{}, ch);
+      if (ch + 1 < nch) group(std::integral_constant<int, 1>{}, ch + 1);
+    }
+    if constexpr (NA == 4) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) O[0][c] = (O[0][c] + O[1][c]) + (O[2][c] + O[3][c]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) psum[0][i] = (psum[0][i] + psum[1][i]) + (psum[2][i] + psum[3][i]);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) l[i] = row16_sum(sum[i]);
+    for (int i = 0; i < 4; ++i) l[i] = row16_sum(psum[0][i]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = row0 + 4 * kq + i;
       if (row < row_end) {
         bf16_t* op = out + (size_t)(sd.q_row0 + row) * d + h * DH + r;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) Store<bf16_t>::store(op + 16 * c, O[c][i] / l[i]);
+        for (int c = 0; c < CT; ++c) Store<bf16_t>::store(op + 16 * c, O[0][c][i] / l[i]);
       }
     }
   };
@@ -747,6 +776,180 @@ __device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb,
       }
       *(uint4*)(Vt + (size_t)(g * 8 + c) * ldv + t0) = uint4{o[0], o[1], o[2], o[3]};
     }
+  }
+}
+// One 16-row tile against many keys (head width 64, four waves): wave w owns the key super-blocks (128 keys each)
+// w, w + 4, ... from the scores to the output product, i.e. accumulator w of the order attn_tiles_mfma<64, 16>
+// states, so the bits are the same whichever of the two serves a row.  Per wave: scores of its keys (key fragments
+// straight from memory), row maxima exchanged through LDS (exact, so their order cannot matter), exponentials,
+// probabilities into the wave's own LDS tile, its 128 values transposed into its own LDS tile (no other wave
+// touches either: no workgroup barrier), output product; then the four partial outputs and per-lane denominators
+// go through LDS and wave c combines and stores channel block c.
+// LDS per wave: values [64][kSplitLd] then probabilities [16][kSplitLd]; exchange area: see attn_split_lds_bytes.
+constexpr int kSplitLd = 128 + 16;                                   // row stride (elements): 32 bytes past a multiple of 64
+constexpr int kSplitWaveElems = (64 + 16) * kSplitLd;                // bf16 elements of a wave's two tiles
+constexpr int kSplitXchBytes = 4 * 16 * 4 + 4 * 64 * 16 + 4 * 4 * 64 * 16;   // maxima, denominators, partial outputs
+__host__ __device__ inline size_t attn_split_lds_bytes() { return 4 * (size_t)kSplitWaveElems * 2 + kSplitXchBytes; }
+// the key fragments of the eight tiles of super-block sb (indices clamped to the last key)
+__device__ __forceinline__ void split_request_keys(const bf16_t* __restrict__ Kb, const SeqDesc sd, int h, int d, int nk_all,
+                                                   int sb, uint4 (&kf)[8][2]) {
+  const int lane = threadIdx.x & 63, r = lane & 15, kq = lane >> 4;
+  const bf16_t* kbase = Kb + (size_t)sd.kv_row0 * d + h * 64 + kq * 8;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const bf16_t* kp = kbase + (size_t)min(128 * sb + 16 * j + r, nk_all - 1) * d;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) kf[j][s2] = ldg16(kp + 32 * s2);
+  }
+}
+// the raw values of super-block sb: two 8-key x 8-channel items per lane (transposed later)
+__device__ __forceinline__ void split_request_values(const bf16_t* __restrict__ Vb, const SeqDesc sd, int h, int d, int nk_all,
+                                                     int sb, uint4 (&vraw)[2][8]) {
+  const int lane = threadIdx.x & 63;
+  const bf16_t* vbase = Vb + (size_t)sd.kv_row0 * d + h * 64;
+#pragma unroll
+  for (int b2 = 0; b2 < 2; ++b2) {
+    const int it = lane + 64 * b2, g = it & 7, t0 = 128 * sb + ((it >> 3) << 3);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vraw[b2][i] = ldg16(vbase + (size_t)min(t0 + i, nk_all - 1) * d + g * 8);
+  }
+}
+// kf0, vraw: the key fragments and raw values of the wave's first super-block (sb = wave), requested by the caller
+__device__ __forceinline__ void attn_split_keys(const uint4 (&qf)[2], const uint4 (&kf0)[8][2], uint4 (&vraw)[2][8],
+                                                const bf16_t* __restrict__ Kb, const bf16_t* __restrict__ Vb,
+                                                bf16_t* __restrict__ out, const SeqDesc sd, int row_begin, int row_end, int h,
+                                                int d, float scale, int nk_all, bf16_t* lds_waves, float* xch) {
+  constexpr int DH = 64, KS = 2, CT = 4, LD = kSplitLd;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
+  bf16_t* Vw = lds_waves + wave * kSplitWaveElems;   // [64][LD]: Vw[c][t] = V[128 sb + t][c]
+  bf16_t* Pw = Vw + 64 * LD;                          // [16][LD]
+  float* xmax = xch;                                  // [4 waves][16 rows]
+  float* xsum = xch + 64;                             // [4 waves][64 lanes][4]
+  f32x4* xout = (f32x4*)(xch + 64 + 1024);            // [4 waves][4 channel blocks][64 lanes]
+  const int n_sb = (nk_all + 127) >> 7;
+  int nkr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) nkr[i] = sd.causal ? sd.nk_base + row_begin + 4 * kq + i + 1 : sd.nk_base;
+  // the eight score tiles of super-block sb from its key fragments: S[j][i] = row 4 kq + i, key 128 sb + 16 j + r
+  auto scores = [&](int sb, const uint4 (&kf)[8][2], f32x4 (&S)[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      S[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s2 = 0; s2 < KS; ++s2)
+        S[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[s2]), __builtin_bit_cast(bf16x8, kf[j][s2]), S[j], 0, 0, 0);
+      const int key = 128 * sb + 16 * j + r;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) S[j][i] = key < nkr[i] ? S[j][i] * scale : -INFINITY;
+    }
+  };
+  f32x4 S[8];
+  const bool mine = wave < n_sb;
+  const bool single = wave + 4 >= n_sb;   // at most one super-block: its scores stay in registers
+  float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  if (mine) {
+    scores(wave, kf0, S);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m[i] = fmaxf(m[i], S[j][i]);
+    for (int sb = wave + 4; sb < n_sb; sb += 4) {
+      uint4 kf[8][2];
+      f32x4 S2[8];
+      split_request_keys(Kb, sd, h, d, nk_all, sb, kf);
+      scores(sb, kf, S2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m[i] = fmaxf(m[i], S2[j][i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) m[i] = row16_max(m[i]);
+  if (r == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xmax[wave * 16 + 4 * kq + i] = m[i];
+  }
+  __syncthreads();
+  float mx[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    mx[i] = fmaxf(fmaxf(xmax[4 * kq + i], xmax[16 + 4 * kq + i]), fmaxf(xmax[32 + 4 * kq + i], xmax[48 + 4 * kq + i]));
+  f32x4 O[CT];
+  float psum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (mine) {
+    for (int sb = wave; sb < n_sb; sb += 4) {
+      if (sb != wave) {
+        uint4 kf[8][2];
+        split_request_keys(Kb, sd, h, d, nk_all, sb, kf);
+        split_request_values(Vb, sd, h, d, nk_all, sb, vraw);
+        scores(sb, kf, S);
+      } else if (!single) {
+        scores(sb, kf0, S);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pv = __builtin_amdgcn_exp2f((S[j][i] - mx[i]) * 1.44269504088896340736f);
+          psum[i] += pv;
+          Pw[(4 * kq + i) * LD + r + 16 * j] = f2bf(pv);
+        }
+      // values: 8 x 8 transposes in registers, 16-byte stores; keys past the last one as zeros
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const int it = lane + 64 * b2, g = it & 7, tl = (it >> 3) << 3, t0 = 128 * sb + tl;
+        unsigned in[8][4];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bool there = t0 + i < nk_all;
+          in[i][0] = there ? vraw[b2][i].x : 0u; in[i][1] = there ? vraw[b2][i].y : 0u;
+          in[i][2] = there ? vraw[b2][i].z : 0u; in[i][3] = there ? vraw[b2][i].w : 0u;
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          unsigned o[4];
+#pragma unroll
+          for (int pr = 0; pr < 4; ++pr) {
+            const unsigned lo = in[2 * pr][c >> 1], hi = in[2 * pr + 1][c >> 1];
+            o[pr] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+          }
+          *(uint4*)(Vw + (size_t)(g * 8 + c) * LD + tl) = uint4{o[0], o[1], o[2], o[3]};
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) {
+        const uint4 pa = *(const uint4*)(Pw + r * LD + 32 * kb + 8 * kq);
+        uint4 vb[CT];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vw + (16 * c + r) * LD + 32 * kb + 8 * kq);
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          O[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), O[c], 0, 0, 0);
+      }
+      __builtin_amdgcn_wave_barrier();   // the tiles are reused by the wave's next super-block
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < CT; ++c) xout[(wave * 4 + c) * 64 + lane] = O[c];
+  *(f32x4*)(xsum + (wave * 64 + lane) * 4) = f32x4{psum[0], psum[1], psum[2], psum[3]};
+  __syncthreads();
+  // wave c: channel block c of the tile
+  const f32x4 o = (xout[(0 * 4 + wave) * 64 + lane] + xout[(1 * 4 + wave) * 64 + lane]) +
+                  (xout[(2 * 4 + wave) * 64 + lane] + xout[(3 * 4 + wave) * 64 + lane]);
+  const f32x4 sm = (*(const f32x4*)(xsum + (0 * 64 + lane) * 4) + *(const f32x4*)(xsum + (1 * 64 + lane) * 4)) +
+                   (*(const f32x4*)(xsum + (2 * 64 + lane) * 4) + *(const f32x4*)(xsum + (3 * 64 + lane) * 4));
+  float l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) l[i] = row16_sum(sm[i]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = row_begin + 4 * kq + i;
+    if (row < row_end) Store<bf16_t>::store(out + (size_t)(sd.q_row0 + row) * d + h * DH + 16 * wave + r, o[i] / l[i]);
   }
 }
 template <int DH>

@@ -828,12 +828,10 @@ static size_t crossq_lds_bytes(int nk_cap, int mt, int d) {
 // leave the queries (bias added, rounded) in the LDS tile Qt.  (A function with the arrays as
 // reference parameters, not a lambda that captures them: captured arrays end up in scratch memory.)
 template <int NV, int MT>
-__device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, bf16_t* Qt,
-                                               const uint4 (&b)[8 * NV], bool has_bias, float bn, int m0, int m_end,
-                                               bool keep_rows) {
-  constexpr int K = 256 * NV, KS = K / 32, ld = K + 16, QLD = kCrossqQld, per_wave = MT * 4;
+__device__ __forceinline__ void crossq_stage(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, int m0, int m_end,
+                                             bool keep_rows) {
+  constexpr int K = 256 * NV, ld = K + 16, per_wave = MT * 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, kq = lane >> 4;
   if (ln.x) {
     astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, keep_rows);
   } else {
@@ -849,6 +847,12 @@ __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __re
       for (int j = 0; j < K / 512; ++j) *(uint4*)(At + (wave * per_wave + i) * ld + j * 512 + lane * 8) = av[i][j];
   }
   __syncthreads();
+}
+template <int NV, int MT>
+__device__ __forceinline__ void crossq_multiply(const bf16_t* At, bf16_t* Qt, const uint4 (&b)[8 * NV], bool has_bias, float bn) {
+  constexpr int K = 256 * NV, KS = K / 32, ld = K + 16, QLD = kCrossqQld;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
   const bf16_t* a_lane = At + r * ld + kq * 8;
   f32x4 acc[MT];
 #pragma unroll
@@ -871,6 +875,13 @@ __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __re
       if (has_bias) v += bn;
       Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
     }
+}
+template <int NV, int MT>
+__device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, bf16_t* Qt,
+                                               const uint4 (&b)[8 * NV], bool has_bias, float bn, int m0, int m_end,
+                                               bool keep_rows) {
+  crossq_stage<NV, MT>(ln, A, At, m0, m_end, keep_rows);
+  crossq_multiply<NV, MT>(At, Qt, b, has_bias, bn);
 }
 template <int NV, bool SMALL>
 __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
@@ -968,6 +979,62 @@ __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restr
   else if (nkp <= 128) attn_tiles_mfma<DH, 8>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   else attn_tiles_mfma<DH, 16>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
 }
+// The same for one row tile per workgroup against many keys (long sources): after the projection the four waves
+// split the keys (attn_split_keys: wave w owns the 128-key super-blocks w, w + 4, ...), instead of one wave walking
+// all of them behind a workgroup-wide staging of the values.  LDS: [4 waves: values, probabilities | row tile (until
+// the queries are there)][exchange area][queries].
+template <int NV>
+__global__ __launch_bounds__(256) void k_crossq_attention_split(const SeqDesc* __restrict__ desc, float scale,
+                                                                const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
+                                                                const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
+                                                                const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+                                                                float* __restrict__ ln_y, const bf16_t* __restrict__ A,
+                                                                const float* __restrict__ bias, bf16_t* __restrict__ out) {
+  LnA ln;
+  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
+  constexpr int K = 256 * NV, KS = K / 32, DH = 64, QLD = kCrossqQld;
+  extern __shared__ uint4 cqs_lds[];
+  const int h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int n0 = h * DH + wave * 16;
+  // the wave's strip of the query matrix first: its address depends on the head alone, not on the
+  // sequence's descriptor, which is a trip to memory of its own
+  uint4 b[KS];
+  {
+    const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
+#pragma unroll
+    for (int u = 0; u < KS; ++u) b[u] = *(const uint4*)(wp + u * 512);
+  }
+  const float bn = bias ? bias[n0 + r] : 0.f;
+  __builtin_amdgcn_sched_barrier(0);
+  const SeqDesc sd = desc[blockIdx.x];
+  const int row_begin = blockIdx.z * 16;
+  if (row_begin >= sd.nq) return;
+  const int row_end = min(sd.nq, row_begin + 16);
+  const int m0 = sd.q_row0 + row_begin, m_end = sd.q_row0 + row_end;
+  bf16_t* lds_waves = (bf16_t*)cqs_lds;
+  bf16_t* At = lds_waves;                                          // [16][K + 16]
+  float* xch = (float*)(lds_waves + 4 * kSplitWaveElems);
+  bf16_t* Qt = (bf16_t*)((char*)xch + kSplitXchBytes);             // [16][QLD]
+  const int nk_all = sd.causal ? sd.nk_base + row_end : sd.nk_base;
+  // the wave's first keys are requested once the rows are staged (the staging's registers are free
+  // again), its first values once the product has used up the weights
+  crossq_stage<NV, 1>(ln, A, At, m0, m_end, h == 0);
+  uint4 kf0[8][2], vraw0[2][8];
+  split_request_keys(Kb, sd, h, K, nk_all, wave, kf0);
+  crossq_multiply<NV, 1>(At, Qt, b, bias != nullptr, bn);
+  split_request_values(Vb, sd, h, K, nk_all, wave, vraw0);
+  __syncthreads();   // the queries are in LDS; the row tile is no longer needed
+  uint4 qf[2];
+  {
+    const int row = min(r, row_end - row_begin - 1);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) qf[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
+  }
+  attn_split_keys(qf, kf0, vraw0, Kb, Vb, out, sd, row_begin, row_end, h, K, scale, nk_all, lds_waves, xch);
+}
+static size_t crossq_split_lds_bytes() { return attn_split_lds_bytes() + 16 * (size_t)kCrossqQld * 2; }
 bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void* W, const float* bias, const void* K,
                              const void* V, void* out, const SeqDesc* desc, int n_seq, int max_rows, int H, int dh,
                              int max_keys, hipStream_t s) {
@@ -980,6 +1047,26 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   //  16 x 36: 434 / 409 / 418, 24 x 36: 477 / 455 / 431, 32 x 36: 535 / 514 / 487)
   const int chunk = n_seq * H * ((max_rows + 15) / 16) <= 256 ? 16 : (n_seq * H * ((max_rows + 31) / 32) <= 256 ? 32 : 64);
   const int mt = (std::min(max_rows, chunk) + 15) / 16;
+  // one row tile per workgroup and more than 128 keys: the waves split the keys
+  if (mt == 1 && max_keys > 128 && 16 * (size_t)(d + 16) * 2 <= 4 * (size_t)kSplitWaveElems * 2) {
+    if (n_seq <= 0 || max_rows <= 0) return true;
+    const size_t shs = crossq_split_lds_bytes();
+    dim3 g(n_seq, H, (max_rows + 15) / 16);
+    const float scale = 1.0f / sqrtf((float)dh);
+    auto go = [&](auto nv_c) {
+      constexpr int NV = decltype(nv_c)::value;
+      static bool set = false;
+      if (!set) {
+        (void)hipFuncSetAttribute((const void*)k_crossq_attention_split<NV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shs);
+        set = true;
+      }
+      k_crossq_attention_split<NV><<<g, 256, shs, s>>>(desc, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V, ln.x, ln.g,
+                                                       ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
+    };
+    if (d == 512) go(std::integral_constant<int, 2>{});
+    else go(std::integral_constant<int, 4>{});
+    return true;
+  }
   const size_t sh = crossq_lds_bytes(max_keys, mt, d);
   if (sh > 160 * 1024) return false;
   if (n_seq <= 0 || max_rows <= 0) return true;

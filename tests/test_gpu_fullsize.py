@@ -162,6 +162,47 @@ def test_rows_of_the_wide_model_do_not_depend_on_the_gemm_kernel_the_row_count_s
         ctx.close()
 
 
+@pytest.mark.parametrize("name,src_lens", [("base", [300, 130, 512, 257, 40, 384, 129, 200]),
+                                           ("big", [512, 500, 129, 512, 300, 512, 40, 260])])
+def test_long_source_rows_do_not_depend_on_how_the_cross_attention_splits_the_keys(name, src_lens):
+    """Sources of more than 128 tokens, bit-exact.  One row tile per workgroup (a sequence alone, or few rows of
+    each): the four waves of the cross-attention kernel split the keys in super-blocks of 128; several row tiles
+    per workgroup (40 rows of each of 8 sequences): every wave walks all keys with four accumulators; the
+    projection and attention as two launches: the generic attention kernel.  All three sum a row's keys in the
+    order the key index fixes, so the logits of sequence 0 agree whatever the launch is; sources of 40, 129, 130
+    tokens leave waves without keys, 512 fills all four."""
+    dims = model_dims(name)
+    w = init_weights(dims, 977)
+    B = len(src_lens)
+    ctx = ad.Context(ad.make_config(dims, max_batch=B, max_src=512, max_len=16, k_max=40, dtype="bf16", special=SPECIAL,
+                                    debug_logits=True), w)
+    try:
+        V = dims["vocab"]
+        rng = np.random.default_rng(977)
+        srcs = [rng.integers(5, V, size=n).astype(np.int32) for n in src_lens]
+        blocks = [[int(t) for t in rng.integers(5, V, size=40)] for _ in range(B)]
+        got = {}
+        for fuse in (1, 0):
+            ctx.set_option(ad.AD_OPT_FUSE_CROSSQ, fuse)
+            for tag, ns, rows in (("8x40", B, 40), ("8x7", B, 7), ("1x40", 1, 40), ("1x1", 1, 1)):
+                ctx.encode(ad.AD_VERIFIER, srcs[:ns])
+                ctx.verify([b[:rows] for b in blocks[:ns]])
+                got[(tag, fuse)] = ctx.debug_logits().view(np.uint32)[:rows * ns].copy()
+        ref = got[("1x40", 1)]
+        assert ref.shape[0] == 40
+        for fuse in (1, 0):
+            assert np.array_equal(got[("1x40", fuse)], ref), fuse
+            assert np.array_equal(got[("8x40", fuse)][:40], ref), fuse
+            assert np.array_equal(got[("8x7", fuse)][:7], ref[:7]), fuse
+            assert np.array_equal(got[("1x1", fuse)], ref[:1]), fuse
+        # every sequence of the batch, not only the first: one launch style against the other
+        assert np.array_equal(got[("8x40", 1)], got[("8x40", 0)])
+        assert np.array_equal(got[("8x7", 1)], got[("8x7", 0)])
+    finally:
+        ctx.set_option(ad.AD_OPT_FUSE_CROSSQ, 1)
+        ctx.close()
+
+
 def _ctx_pair(name, seed, **cap):
     """Two contexts over the same weights: one keeps the logits (its output projection stores
     them), the other runs the shipped epilogue that never writes them."""
