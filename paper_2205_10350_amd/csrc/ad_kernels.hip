@@ -163,8 +163,10 @@ __device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld
 // scalar registers when a wave starts (kernel-argument preload); what the prologue needs first, the sizes that decide
 // the workgroup's place and the pointers of the first loads, comes first, the epilogue's description last.)
 // NW waves per workgroup (4, 8 or 16): a wave stages MT*16/NW rows and owns every NW-th run of SP strips.
+// (Register budget: two waves per SIMD; four for the 16-wave workgroups and for the 8-wave, 32-row, K = 512
+// variant, which then fits a CU twice: forward at 1152 rows 451 -> 446 us.)
 template <int MT, int AMAX, int SP, bool ONE, int LNMODE = -1, int EM = -1, int NW = 4>
-__global__ __launch_bounds__(64 * NW, NW == 16 ? 4 : 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+__global__ __launch_bounds__(64 * NW, NW == 16 || (NW == 8 && ONE && MT == 2 && SP == 1) ? 4 : 2) void k_gemm_bf16_astat(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                             int M, int N, int K, int strips_per_wg, int groups,
                                                             int chunks, const float* __restrict__ ln_x,
                                                             const float* __restrict__ ln_g, const float* __restrict__ ln_b,
@@ -685,7 +687,7 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
       // 1152 rows: QKV with the LayerNorm 12.4 -> 9.6 us, attention output projections 7.0 -> 5.5 us, FFN2
       // 12.9 -> 11.0 us; forward at 576 / 720 / 864 / 1008 / 1152 rows 372 / 411 / 425 / 453 / 517 ->
       // 362 / 393 / 401 / 417 / 458 us, at 432 rows 321 -> 350 us the other way; FFN1's 128 strips would need
-      // two rounds and gained nothing in any shape tried; K = 1024: drafter forward of the wide model at 626
+      // two rounds and gained nothing in any shape tried, in one round of two 8-wave workgroups per CU either; K = 1024: drafter forward of the wide model at 626
       // rows 983 -> 1073 us, so those shapes keep the rules below)
       if (M >= 520 && e.mode != EPI_ARGMAX && e.mode != EPI_COUNT) {
         const int n_strips = N / 16, chunks2 = (M + 31) / 32;
@@ -1045,6 +1047,8 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   // (measured forward times, base model, 16 / 32 / 64 rows per workgroup; batch x rows:
   //  1 x 25: 237 / 248 / 247 us, 1 x 64: 243 / 254 / 271, 8 x 36: 288 / 298 / 306, 12 x 36: 354 / 332 / 342,
   //  16 x 36: 434 / 409 / 418, 24 x 36: 477 / 455 / 431, 32 x 36: 535 / 514 / 487)
+  // (Where the tiles of a 64-row chunk do not fit in LDS, 512-token sources of the wide model, the projection and the
+  // attention stay two launches: 32-row chunks would fit and measured slower, drafter forward at 626 rows 957 -> 1051 us.)
   const int chunk = n_seq * H * ((max_rows + 15) / 16) <= 256 ? 16 : (n_seq * H * ((max_rows + 31) / 32) <= 256 ? 32 : 64);
   const int mt = (std::min(max_rows, chunk) + 15) / 16;
   // one row tile per workgroup and more than 128 keys: the waves split the keys
