@@ -51,6 +51,11 @@ def decoder_stream_params(dims):
     return NL * (6 * d * d + 2 * d * F) + d * V
 
 
+def _progress(what):
+    """One line per section on stderr: a long run shows that it is alive; stdout carries the JSON line alone."""
+    print(f"bench.py: {what}", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +118,7 @@ def main():
         ctx.close()
         return
 
+    _progress("batch 1")
     # ---------------- batch 1: the headline workload ------------------------------------------
     n_sent = cfg1["n_sent"]
     srcs, max_out = draw_sources(cfg1, V)
@@ -197,6 +203,7 @@ def main():
     verify_bs1 = {"rows": M1, "us": fwd_us, "algorithmic_MB": fwd_bytes / 1e6,
                   "hbm_frac": fwd_bytes / (fwd_us * 1e-6) / HBM_PEAK, "launches": n_launches}
 
+    _progress("batch 32")
     # ---------------- batch 32 ---------------------------------------------------------------------
     bs32 = None
     roofline_bs32 = None
@@ -244,6 +251,7 @@ def main():
                          "rows": M32, "us": fwd32_us, "algorithmic_flops": flops,
                          "achieved": flops / (fwd32_us * 1e-6) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
                          "frac": flops / (fwd32_us * 1e-6) / MFMA_BF16_PEAK, "traffic": None}
+    _progress("sweeps")
     # ---------------- verify forward against block size and batch size (roofline against rows) -------
     sweeps = None
     if not args.no_next:
@@ -267,6 +275,7 @@ def main():
                   "batch_size_block36": [point(bb, blk) for bb in (1, 2, 4, 8, 16, 32)]}
     ctx.close()
 
+    _progress("deep encoder")
     # ---------------- input-guided decoding, deep encoder + shallow decoder (workload 5) --------------
     deep = None
     if not args.no_next:
@@ -309,6 +318,7 @@ def main():
                 "vocab_kernel_hbm_frac": 2 * V * dims5["d_model"] / (v5_us * 1e-6) / HBM_PEAK}
         cx.close()
 
+    _progress("block drafting")
     # ---------------- draft-and-verify with the block drafter (workloads 3 and 4) ---------------------
     # The drafter forward runs and is timed inside every iteration; its output is replaced by a
     # positional draft with substitutions at the workload's rate (random weights draft nothing useful).
@@ -372,6 +382,7 @@ def main():
             cx.set_gadpp(1, 0.0)
             cx.close()
 
+    _progress("calibration")
     # ---------------- measured peaks of this machine (context for the nominal ones) -------------------
     a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
     b = torch.empty_like(a)
@@ -387,6 +398,7 @@ def main():
     mfma_tflops = max(ad.calibration_mfma() for _ in range(3))
     del a, b
 
+    _progress("cpu baseline")
     # ---------------- CPU oracle on this machine's host cores (bounded sample) ----------------------
     cpu = None
     if not args.no_cpu_baseline:
