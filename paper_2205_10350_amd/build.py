@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libad_mi355x.so")
-SOURCES = ["ad_hostlogic.cpp", "ad_api.cpp", "ad_kernels.hip"]
+SOURCES = ["ad_hostlogic.cpp", "ad_api.cpp", "ad_kernels.hip", "ad_attention_long.hip"]
 # -amdgpu-mfma-vgpr-form: MFMA results go to ordinary vector registers, not to the accumulation
 # registers and back through copies before every vector instruction that reads them (masks, maxima,
 # epilogues): 1-2 % of the forward, no spills.

@@ -407,13 +407,21 @@ template <> struct LdsRow<float> {
   static constexpr int kPerDword = 1;
 };
 
+// (the key-split paths, attn_split_keys / attn_split_tiles: per wave a [64][kSplitLd] value tile and a [16][kSplitLd]
+// probability tile)
+constexpr int kSplitLd = 128 + 16;                                   // row stride (elements): 32 bytes past a multiple of 64
+constexpr int kSplitWaveElems = (64 + 16) * kSplitLd;                // bf16 elements of a wave's two tiles
+constexpr int kSplitXchBytes = 4 * 16 * 4 + 4 * 64 * 16 + 4 * 4 * 64 * 16;   // attn_split_keys: maxima, denominators, partial outputs
+constexpr int kLongKeys = 256;   // key capacity from which the generic attention launch is the kernel that can split the keys
+constexpr int kSplitTilesBytes = 4 * kSplitWaveElems * 2 + 4 * 64 * 4;      // attn_split_tiles: the waves' tiles and the row maxima
 __host__ __device__ inline size_t attn_lds_bytes(int nk_cap, int dh, int esz, int waves) {
   const size_t row_dwords = (size_t)dh * esz / 4 + 1;
   const size_t scalar_path = 2 * (size_t)nk_cap * row_dwords * 4 + 64 * (size_t)dh * 4 + (size_t)waves * nk_cap * 4;
   // matrix-core path: transposed values [dh][keys + 16] and one 16-row probability tile per wave
   // (row stride = 32 bytes past a multiple of 64: the 16-byte fragment reads meet no bank twice)
   const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
-  const size_t mfma_path = ((size_t)dh + 16 * (size_t)waves) * ldv * 2;
+  size_t mfma_path = ((size_t)dh + 16 * (size_t)waves) * ldv * 2;
+  if (dh == 64 && esz == 2 && nk_cap >= kLongKeys && mfma_path < (size_t)kSplitTilesBytes) mfma_path = kSplitTilesBytes;
   return scalar_path > mfma_path ? scalar_path : mfma_path;
 }
 
@@ -447,7 +455,7 @@ __device__ __forceinline__ float row16_sum(float v) {
 // Every step treats a query row independently of the other rows of its tile and of how many
 // tiles or keys the call covers (keys a row does not see contribute exact zeros), so a row's
 // result does not depend on the shape of the block it is verified in.
-template <int DH, int NT>
+template <int DH, int NT, bool LONGK = false>
 __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb, bf16_t* __restrict__ out,
                                 const SeqDesc sd, int row_begin, int row_end, int h, int d, float scale,
                                 const bf16_t* Vt, bf16_t* Pw, int ldv, int nk_all,
@@ -553,12 +561,15 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
 #pragma unroll
       for (int i = 0; i < 4; ++i) mx[i] = row16_max(m[i]);
     }
-    // More than 128 keys (NT = 16), head width up to 64: the keys are taken in super-blocks of 128, super-block sb adds
-    // into accumulator sb % 4 (output sums and denominators alike, ascending inside an accumulator), and the four are
-    // combined as (a0 + a1) + (a2 + a3) at the end.  The order depends on the key index alone, so the kernel that gives
-    // the four accumulators to four waves (attn_split_keys) produces the same bits; with at most 128 keys there is one
-    // chain.  (Wider heads: one chain; no kernel splits their keys, and four accumulator sets would not fit the registers.)
-    constexpr int NA = NT == 16 && DH <= 64 ? 4 : 1;
+    // LONGK (the launches of configurations whose key capacity is kLongKeys or more; head width up to 64), more than
+    // 128 keys (NT = 16): the keys are taken in super-blocks of 128, super-block sb adds into accumulator sb % 4 (output
+    // sums and denominators alike, ascending inside an accumulator), and the four are combined as (a0 + a1) + (a2 + a3)
+    // at the end.  The order depends on the key index alone, so the kernels that give the four accumulators to four
+    // waves (attn_split_keys, attn_split_tiles) produce the same bits; with at most 128 keys there is one chain.
+    // Otherwise one chain for any key count: no kernel of such a configuration splits the keys, and the short-range
+    // kernels, the batch-1 path, stay as small as they were (the four accumulator sets alone cost their launches
+    // 0.3 us each, forward at 25 rows 186.6 -> 188.4 us, although that code never ran).
+    constexpr int NA = LONGK && NT == 16 && DH <= 64 ? 4 : 1;
     f32x4 O[NA][CT];
     float psum[NA][4];
 #pragma unroll
@@ -607,9 +618,13 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       }
       __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the next group and the wave's next rows
     };
-    for (int ch = 0; ch < max(nch, 1); ch += 2) {
-      group(std::integral_constant<int, 0>{}, ch);
-      if (ch + 1 < nch) group(std::integral_constant<int, 1>{}, ch + 1);
+    if constexpr (NA == 1) {
+      for (int ch = 0; ch < max(nch, 1); ++ch) group(std::integral_constant<int, 0>{}, ch);
+    } else {
+      for (int ch = 0; ch < max(nch, 1); ch += 2) {
+        group(std::integral_constant<int, 0>{}, ch);
+        if (ch + 1 < nch) group(std::integral_constant<int, 1>{}, ch + 1);
+      }
     }
     if constexpr (NA == 4) {
 #pragma unroll
@@ -786,9 +801,6 @@ __device__ __forceinline__ void attn_stage_values(const bf16_t* __restrict__ Vb,
 // touches either: no workgroup barrier), output product; then the four partial outputs and per-lane denominators
 // go through LDS and wave c combines and stores channel block c.
 // LDS per wave: values [64][kSplitLd] then probabilities [16][kSplitLd]; exchange area: see attn_split_lds_bytes.
-constexpr int kSplitLd = 128 + 16;                                   // row stride (elements): 32 bytes past a multiple of 64
-constexpr int kSplitWaveElems = (64 + 16) * kSplitLd;                // bf16 elements of a wave's two tiles
-constexpr int kSplitXchBytes = 4 * 16 * 4 + 4 * 64 * 16 + 4 * 4 * 64 * 16;   // maxima, denominators, partial outputs
 __host__ __device__ inline size_t attn_split_lds_bytes() { return 4 * (size_t)kSplitWaveElems * 2 + kSplitXchBytes; }
 // the key fragments of the eight tiles of super-block sb (indices clamped to the last key)
 __device__ __forceinline__ void split_request_keys(const bf16_t* __restrict__ Kb, const SeqDesc sd, int h, int d, int nk_all,
@@ -812,6 +824,32 @@ __device__ __forceinline__ void split_request_values(const bf16_t* __restrict__ 
     const int it = lane + 64 * b2, g = it & 7, t0 = 128 * sb + ((it >> 3) << 3);
 #pragma unroll
     for (int i = 0; i < 8; ++i) vraw[b2][i] = ldg16(vbase + (size_t)min(t0 + i, nk_all - 1) * d + g * 8);
+  }
+}
+// the raw values of super-block sb into the wave's tile Vw[c][t] = V[128 sb + t][c]: 8 x 8 transposes in registers,
+// 16-byte stores; keys past the last one as zeros
+__device__ __forceinline__ void split_stage_values(const uint4 (&vraw)[2][8], bf16_t* Vw, int sb, int nk_all) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int b2 = 0; b2 < 2; ++b2) {
+    const int it = lane + 64 * b2, g = it & 7, tl = (it >> 3) << 3, t0 = 128 * sb + tl;
+    unsigned in[8][4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool there = t0 + i < nk_all;
+      in[i][0] = there ? vraw[b2][i].x : 0u; in[i][1] = there ? vraw[b2][i].y : 0u;
+      in[i][2] = there ? vraw[b2][i].z : 0u; in[i][3] = there ? vraw[b2][i].w : 0u;
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      unsigned o[4];
+#pragma unroll
+      for (int pr = 0; pr < 4; ++pr) {
+        const unsigned lo = in[2 * pr][c >> 1], hi = in[2 * pr + 1][c >> 1];
+        o[pr] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+      }
+      *(uint4*)(Vw + (size_t)(g * 8 + c) * kSplitLd + tl) = uint4{o[0], o[1], o[2], o[3]};
+    }
   }
 }
 // kf0, vraw: the key fragments and raw values of the wave's first super-block (sb = wave), requested by the caller
@@ -898,28 +936,7 @@ __device__ __forceinline__ void attn_split_keys(const uint4 (&qf)[2], const uint
           psum[i] += pv;
           Pw[(4 * kq + i) * LD + r + 16 * j] = f2bf(pv);
         }
-      // values: 8 x 8 transposes in registers, 16-byte stores; keys past the last one as zeros
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        const int it = lane + 64 * b2, g = it & 7, tl = (it >> 3) << 3, t0 = 128 * sb + tl;
-        unsigned in[8][4];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const bool there = t0 + i < nk_all;
-          in[i][0] = there ? vraw[b2][i].x : 0u; in[i][1] = there ? vraw[b2][i].y : 0u;
-          in[i][2] = there ? vraw[b2][i].z : 0u; in[i][3] = there ? vraw[b2][i].w : 0u;
-        }
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          unsigned o[4];
-#pragma unroll
-          for (int pr = 0; pr < 4; ++pr) {
-            const unsigned lo = in[2 * pr][c >> 1], hi = in[2 * pr + 1][c >> 1];
-            o[pr] = (c & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-          }
-          *(uint4*)(Vw + (size_t)(g * 8 + c) * LD + tl) = uint4{o[0], o[1], o[2], o[3]};
-        }
-      }
+      split_stage_values(vraw, Vw, sb, nk_all);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) {
@@ -952,7 +969,144 @@ __device__ __forceinline__ void attn_split_keys(const uint4 (&qf)[2], const uint
     if (row < row_end) Store<bf16_t>::store(out + (size_t)(sd.q_row0 + row) * d + h * DH + 16 * wave + r, o[i] / l[i]);
   }
 }
-template <int DH>
+// Up to four 16-row tiles (one per wave in the other kernels) against 129..512 keys, head width 64, four waves: the split
+// of attn_split_keys for every row tile of the chunk.  Wave w owns super-block w: its key fragments are fetched once
+// and multiply the queries of all tiles; the row maxima of all tiles cross LDS behind one barrier; then, tile by tile,
+// exponentials, probabilities (the wave's own LDS tile), output product against the wave's own transposed values.
+// Behind a second barrier the partial outputs and denominators go through LDS (over the tiles, which nobody reads any
+// more) and wave c combines and stores channel block c of every tile.  Keys and values cross from memory once per
+// workgroup instead of once (values) and twice (keys) per wave.  Same bits as attn_tiles_mfma<64, 16>.
+__device__ __forceinline__ void attn_split_tiles(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
+                                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
+                                                 int row_begin, int row_end, int h, int d, float scale, int nk_all,
+                                                 bf16_t* lds) {
+  constexpr int DH = 64, CT = 4, LD = kSplitLd;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, kq = lane >> 4;
+  const int nt = (row_end - row_begin + 15) >> 4;     // 1..4 row tiles
+  bf16_t* Vw = lds + wave * kSplitWaveElems;          // [64][LD]
+  bf16_t* Pw = Vw + 64 * LD;                          // [16][LD]
+  float* xmax = (float*)(lds + 4 * kSplitWaveElems);  // [4 waves][64 rows]
+  f32x4* xout = (f32x4*)lds;                          // [(wave * 4 + tile) * 4 + channel block][64 lanes], over the tiles
+  f32x4* xsum = xout + 4 * 4 * 4 * 64;                // [wave * 4 + tile][64 lanes]
+  const int n_sb = (nk_all + 127) >> 7;
+  const bool mine = wave < n_sb;
+  uint4 kf[8][2];
+  split_request_keys(Kb, sd, h, d, nk_all, wave, kf);
+  uint4 qf[4][2];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = min(row_begin + 16 * min(t, nt - 1) + r, row_end - 1);
+    const bf16_t* qp = q + (size_t)(sd.q_row0 + row) * d + h * DH + kq * 8;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) qf[t][s2] = ldg16(qp + 32 * s2);
+  }
+  f32x4 S[4][8];
+  float m[4][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m[t][i] = -INFINITY;
+    if (mine && t < nt) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        S[t][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+          S[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qf[t][s2]), __builtin_bit_cast(bf16x8, kf[j][s2]), S[t][j], 0, 0, 0);
+        const int key = 128 * wave + 16 * j + r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int nkr = sd.causal ? sd.nk_base + row_begin + 16 * t + 4 * kq + i + 1 : sd.nk_base;
+          S[t][j][i] = key < nkr ? S[t][j][i] * scale : -INFINITY;
+          m[t][i] = fmaxf(m[t][i], S[t][j][i]);
+        }
+      }
+    }
+  }
+  uint4 vraw[2][8];
+  split_request_values(Vb, sd, h, d, nk_all, wave, vraw);
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) m[t][i] = row16_max(m[t][i]);
+  if (r == 0) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) xmax[wave * 64 + 16 * t + 4 * kq + i] = m[t][i];
+  }
+  __syncthreads();
+  f32x4 O[4][CT];
+  f32x4 psum[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    psum[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < CT; ++c) O[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  if (mine) {
+    split_stage_values(vraw, Vw, wave, nk_all);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (t < nt) {
+        float mx[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = 16 * t + 4 * kq + i;
+          mx[i] = fmaxf(fmaxf(xmax[row], xmax[64 + row]), fmaxf(xmax[128 + row], xmax[192 + row]));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float pv = __builtin_amdgcn_exp2f((S[t][j][i] - mx[i]) * 1.44269504088896340736f);
+            psum[t][i] += pv;
+            Pw[(4 * kq + i) * LD + r + 16 * j] = f2bf(pv);
+          }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+          const uint4 pa = *(const uint4*)(Pw + r * LD + 32 * kb + 8 * kq);
+          uint4 vb[CT];
+#pragma unroll
+          for (int c = 0; c < CT; ++c) vb[c] = *(const uint4*)(Vw + (16 * c + r) * LD + 32 * kb + 8 * kq);
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+            O[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa), __builtin_bit_cast(bf16x8, vb[c]), O[t][c], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();   // the probability tile is reused by the next row tile
+      }
+    }
+  }
+  __syncthreads();   // every wave is done with its tiles: the exchange area lies over them
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    if (t < nt) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) xout[((wave * 4 + t) * 4 + c) * 64 + lane] = O[t][c];
+      xsum[(wave * 4 + t) * 64 + lane] = psum[t];
+    }
+  }
+  __syncthreads();
+  // wave c: channel block c of every tile
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    if (t < nt) {
+      const f32x4 o = (xout[((0 * 4 + t) * 4 + wave) * 64 + lane] + xout[((1 * 4 + t) * 4 + wave) * 64 + lane]) +
+                      (xout[((2 * 4 + t) * 4 + wave) * 64 + lane] + xout[((3 * 4 + t) * 4 + wave) * 64 + lane]);
+      const f32x4 sm = (xsum[(0 * 4 + t) * 64 + lane] + xsum[(1 * 4 + t) * 64 + lane]) +
+                       (xsum[(2 * 4 + t) * 64 + lane] + xsum[(3 * 4 + t) * 64 + lane]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float l = row16_sum(sm[i]);
+        const int row = row_begin + 16 * t + 4 * kq + i;
+        if (row < row_end) Store<bf16_t>::store(out + (size_t)(sd.q_row0 + row) * d + h * DH + 16 * wave + r, o[i] / l);
+      }
+    }
+  }
+}
+template <int DH, bool LONGK = false>
 __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ Kb,
                                 const bf16_t* __restrict__ Vb, bf16_t* __restrict__ out, const SeqDesc sd,
                                 int row_begin, int row_end, int h, int d, float scale, unsigned* lds, int nk_all) {
@@ -974,17 +1128,17 @@ __device__ __forceinline__ void attn_block_mfma(const bf16_t* __restrict__ q, co
   __syncthreads();
   if (nkp <= 64) attn_tiles_mfma<DH, 4>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   else if (nkp <= 128) attn_tiles_mfma<DH, 8>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else attn_tiles_mfma<DH, 16>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else attn_tiles_mfma<DH, 16, LONGK>(q, Kb, out, sd, row_begin, row_end, h, d, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
   __syncthreads();   // LDS is free for the next call
 }
 
-template <typename T, int DH>
+template <typename T, int DH, bool LONGK = false>
 __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __restrict__ Kb, const T* __restrict__ Vb,
                            T* __restrict__ out, const SeqDesc sd, int row_begin, int row_end, int h, int d,
                            float scale, unsigned* lds, int nk_cap) {
   if constexpr (sizeof(T) == 2 && DH % 32 == 0) {
     const int nk_need = sd.causal ? sd.nk_base + row_end : sd.nk_base;
-    attn_block_mfma<DH>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
+    attn_block_mfma<DH, LONGK>(q, Kb, Vb, out, sd, row_begin, row_end, h, d, scale, lds, nk_need);
     return;
   }
   constexpr int RD = DH * (int)sizeof(T) / 4;   // dwords per key row
@@ -1106,5 +1260,282 @@ __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __r
   }
   __syncthreads();
 }
+
+// ------------------------------------------------- operand staging through LayerNorm (GEMM and cross-attention kernels)
+// A tile rows [row0, row0 + n_rows) of a workgroup from fp32 rows through LayerNorm (width
+// 256 * NV, the 16-byte rule of ln_load4 / ln_stats4), RB rows in flight at a time.
+// after_first_loads(): called once, when the wave's first batch of row loads has been issued:
+// whatever the caller wants in flight behind them.  Loads return in issue order, so what is
+// needed first (the rows: everything waits for the tile) is requested first.
+struct NoOp { __device__ __forceinline__ void operator()() const {} };
+template <int NV, int RB, typename F = NoOp>
+__device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld, int row0, int n_rows, int m0, int M,
+                                               int lane, bool store_y, const F& after_first_loads = F{}) {
+  constexpr int K = 256 * NV;
+  float4 gv[NV], bv[NV];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    gv[j] = *(const float4*)(ln.g + 4 * lane + 256 * j);
+    bv[j] = *(const float4*)(ln.b + 4 * lane + 256 * j);
+  }
+  for (int i0 = 0; i0 < n_rows; i0 += RB) {
+    float4 xv[RB][NV];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+      if (i0 + i < n_rows) ln_load4<NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
+    if (i0 == 0) after_first_loads();
+    // statistics of all rows of the batch first (independent reduction chains the scheduler can
+    // interleave), then the values, then, in the workgroups that keep them, the fp32 rows
+    float mean[RB], rstd[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) ln_stats4<NV>(xv[i0 + i < n_rows ? i : 0], K, mean[i], rstd[i]);
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+      if (i0 + i >= n_rows) break;
+      const int row = row0 + i0 + i;
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int c = 4 * lane + 256 * j;
+        const float4 o = float4{ln_value(xv[i][j].x, mean[i], rstd[i], gv[j].x, bv[j].x), ln_value(xv[i][j].y, mean[i], rstd[i], gv[j].y, bv[j].y),
+                                ln_value(xv[i][j].z, mean[i], rstd[i], gv[j].z, bv[j].z), ln_value(xv[i][j].w, mean[i], rstd[i], gv[j].w, bv[j].w)};
+        const unsigned lo = (unsigned)f2bf(o.x) | ((unsigned)f2bf(o.y) << 16), hi = (unsigned)f2bf(o.z) | ((unsigned)f2bf(o.w) << 16);
+        *(uint2*)(At + row * ld + c) = uint2{lo, hi};
+        xv[i][j] = o;
+      }
+    }
+    if (store_y) {
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        const int m = m0 + row0 + i0 + i;
+        if (i0 + i < n_rows && m < M) {
+#pragma unroll
+          for (int j = 0; j < NV; ++j) *(float4*)(ln.y + (size_t)m * K + 4 * lane + 256 * j) = xv[i][j];
+        }
+      }
+    }
+  }
+}
+
+
+// ------------------------------------------------- cross-attention with its query projection (kernels; launched from
+// ad_kernels.hip, and from ad_attention_long.hip for configurations with long sources)
+constexpr int kCrossqQld = 64 + 16;   // query tile row stride (elements): 32 bytes past a multiple of 64
+inline size_t crossq_lds_bytes(int nk_cap, int mt, int d) {
+  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
+  return (64 * ldv + ((size_t)64 * ldv > (size_t)mt * 16 * (d + 16) ? (size_t)64 * ldv : (size_t)mt * 16 * (d + 16)) + 64 * (size_t)kCrossqQld) * 2;
+}
+// The query projection of k_crossq_attention for MT row tiles: stage the chunk's rows in LDS (through
+// the pending LayerNorm, or as they are), multiply by the wave's strip `b` of the query matrix,
+// leave the queries (bias added, rounded) in the LDS tile Qt.  (A function with the arrays as
+// reference parameters, not a lambda that captures them: captured arrays end up in scratch memory.)
+template <int NV, int MT>
+__device__ __forceinline__ void crossq_stage(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, int m0, int m_end,
+                                             bool keep_rows) {
+  constexpr int K = 256 * NV, ld = K + 16, per_wave = MT * 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (ln.x) {
+    astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, keep_rows);
+  } else {
+    uint4 av[per_wave][K / 512];
+#pragma unroll
+    for (int i = 0; i < per_wave; ++i)
+#pragma unroll
+      for (int j = 0; j < K / 512; ++j)
+        av[i][j] = *(const uint4*)(A + (size_t)min(m0 + wave * per_wave + i, m_end - 1) * K + j * 512 + lane * 8);
+#pragma unroll
+    for (int i = 0; i < per_wave; ++i)
+#pragma unroll
+      for (int j = 0; j < K / 512; ++j) *(uint4*)(At + (wave * per_wave + i) * ld + j * 512 + lane * 8) = av[i][j];
+  }
+  __syncthreads();
+}
+template <int NV, int MT>
+__device__ __forceinline__ void crossq_multiply(const bf16_t* At, bf16_t* Qt, const uint4 (&b)[8 * NV], bool has_bias, float bn) {
+  constexpr int K = 256 * NV, KS = K / 32, ld = K + 16, QLD = kCrossqQld;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const bf16_t* a_lane = At + r * ld + kq * 8;
+  f32x4 acc[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int u = 0; u < KS; ++u) {
+    uint4 af[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) af[t] = *(const uint4*)(a_lane + t * 16 * ld + 32 * u);
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, b[u]), acc[t], 0, 0, 0);
+  }
+  // this lane: rows 16 t + 4 kq + i of the chunk, column 16 wave + r of the head
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float v = acc[t][i];
+      if (has_bias) v += bn;
+      Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
+    }
+}
+template <int NV, int MT>
+__device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, bf16_t* Qt,
+                                               const uint4 (&b)[8 * NV], bool has_bias, float bn, int m0, int m_end,
+                                               bool keep_rows) {
+  crossq_stage<NV, MT>(ln, A, At, m0, m_end, keep_rows);
+  crossq_multiply<NV, MT>(At, Qt, b, has_bias, bn);
+}
+// LONGK: the configuration's source capacity is kLongKeys or more (the summation order beyond 128 keys, attn_tiles_mfma)
+template <int NV, bool SMALL, bool LONGK = false>
+__global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
+                                                          const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
+                                                          const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
+                                                          const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+                                                          float* __restrict__ ln_y, const bf16_t* __restrict__ A,
+                                                          const float* __restrict__ bias, bf16_t* __restrict__ out) {
+  LnA ln;
+  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
+  constexpr int K = 256 * NV, KS = K / 32, DH = 64, ld = K + 16, QLD = kCrossqQld, G = DH / 8;
+  extern __shared__ uint4 cq_lds[];
+  const SeqDesc sd = desc[blockIdx.x];
+  const int row_begin = blockIdx.z * chunk_rows;
+  if (row_begin >= sd.nq) return;
+  const int row_end = min(sd.nq, row_begin + chunk_rows);
+  const int h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int mt = (row_end - row_begin + 15) >> 4;
+  const int m0 = sd.q_row0 + row_begin, m_end = sd.q_row0 + row_end;   // packed rows of the chunk
+  const int n0 = h * DH + wave * 16;
+  const int nk_all = sd.causal ? sd.nk_base + row_end : sd.nk_base;
+  const int nkp = (nk_all + 31) & ~31, ldv = nkp + 16;
+  bf16_t* Vt = (bf16_t*)cq_lds;          // [DH][ldv]
+  bf16_t* Pall = Vt + DH * ldv;          // [4 waves][16][ldv]
+  bf16_t* At = Pall;                     // [16 * mt][K + 16]
+  bf16_t* Qt = Pall + max(64 * ldv, mt * 16 * ld);   // [64][QLD]
+  // the wave's strip of the query matrix
+  uint4 b[KS];
+  {
+    const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
+#pragma unroll
+    for (int u = 0; u < KS; ++u) b[u] = *(const uint4*)(wp + u * 512);
+  }
+  const float bn = bias ? bias[n0 + r] : 0.f;
+  uint4 kf_pre[4][DH / 32];
+  attn_preload_k<DH>(Kb, sd, row_begin, row_end, h, K, nk_all, kf_pre);
+  // up to 128 keys: the values (piece i = 8 channels of one key; addresses clamped, never under a
+  // branch of their own) wait in registers until the row tile is staged
+  const bool v_small = SMALL || nkp <= 128;
+  uint4 vreg[4];
+  if (v_small) {
+    const bf16_t* vg = Vb + (size_t)sd.kv_row0 * K + h * DH;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int i = min((int)threadIdx.x + 256 * it, nkp * G - 1);
+      const int g = i / nkp, t = min(i - g * nkp, nk_all - 1);
+      vreg[it] = *(const uint4*)(vg + (size_t)t * K + g * 8);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
+  if (SMALL || mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else if (mt == 2) crossq_project<NV, 2>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else if (mt == 3) crossq_project<NV, 3>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else crossq_project<NV, 4>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  // values into LDS, transposed (keys nk_all .. nkp - 1 as zeros)
+  if (v_small) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int i = threadIdx.x + 256 * it;
+      if (i < nkp * G) {
+        const int g = i / nkp, t = i - g * nkp;
+        const uint4 v = t < nk_all ? vreg[it] : uint4{0u, 0u, 0u, 0u};
+        bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
+        dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
+        dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
+        dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
+        dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
+      }
+    }
+  } else {
+    attn_stage_values<DH>(Vb, sd, h, K, Vt, ldv, nkp, nk_all);
+  }
+  __syncthreads();   // queries and values are in LDS; the row tile is no longer needed
+  // the rest is attn_block_mfma with the query fragments read from the LDS tile
+  const int n_tiles = mt;
+  uint4 qf_pre[DH / 32];
+  {
+    const int row = min(min(wave, n_tiles - 1) * 16 + r, row_end - row_begin - 1);
+#pragma unroll
+    for (int s2 = 0; s2 < DH / 32; ++s2) qf_pre[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
+  }
+  const int nt_all = (nk_all + 15) >> 4;
+  const bool coop = !SMALL && row_end - row_begin <= 16 && nt_all > 8;
+  float* Sbuf = coop ? (float*)(Pall + 16 * ldv) : nullptr;
+  if (coop) {
+    attn_coop_scores_q<DH>(qf_pre, Kb, sd, h, K, nk_all, nt_all, Sbuf, nkp);
+    __syncthreads();
+  }
+  bf16_t* Pw = Pall + wave * 16 * ldv;
+  const bf16_t* qnone = nullptr;   // every wave has at most one tile: its fragments are qf_pre
+  if (SMALL || nkp <= 64) attn_tiles_mfma<DH, 4>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else if (nkp <= 128) attn_tiles_mfma<DH, 8>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+  else attn_tiles_mfma<DH, 16, LONGK>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
+}
+// The same for one row tile per workgroup against many keys (long sources): after the projection the four waves
+// split the keys (attn_split_keys: wave w owns the 128-key super-blocks w, w + 4, ...), instead of one wave walking
+// all of them behind a workgroup-wide staging of the values.  LDS: [4 waves: values, probabilities | row tile (until
+// the queries are there)][exchange area][queries].
+template <int NV>
+__global__ __launch_bounds__(256) void k_crossq_attention_split(const SeqDesc* __restrict__ desc, float scale,
+                                                                const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
+                                                                const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
+                                                                const float* __restrict__ ln_g, const float* __restrict__ ln_b,
+                                                                float* __restrict__ ln_y, const bf16_t* __restrict__ A,
+                                                                const float* __restrict__ bias, bf16_t* __restrict__ out) {
+  LnA ln;
+  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
+  constexpr int K = 256 * NV, KS = K / 32, DH = 64, QLD = kCrossqQld;
+  extern __shared__ uint4 cqs_lds[];
+  const int h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, kq = lane >> 4;
+  const int n0 = h * DH + wave * 16;
+  // the wave's strip of the query matrix first: its address depends on the head alone, not on the
+  // sequence's descriptor, which is a trip to memory of its own
+  uint4 b[KS];
+  {
+    const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
+#pragma unroll
+    for (int u = 0; u < KS; ++u) b[u] = *(const uint4*)(wp + u * 512);
+  }
+  const float bn = bias ? bias[n0 + r] : 0.f;
+  __builtin_amdgcn_sched_barrier(0);
+  const SeqDesc sd = desc[blockIdx.x];
+  const int row_begin = blockIdx.z * 16;
+  if (row_begin >= sd.nq) return;
+  const int row_end = min(sd.nq, row_begin + 16);
+  const int m0 = sd.q_row0 + row_begin, m_end = sd.q_row0 + row_end;
+  bf16_t* lds_waves = (bf16_t*)cqs_lds;
+  bf16_t* At = lds_waves;                                          // [16][K + 16]
+  float* xch = (float*)(lds_waves + 4 * kSplitWaveElems);
+  bf16_t* Qt = (bf16_t*)((char*)xch + kSplitXchBytes);             // [16][QLD]
+  const int nk_all = sd.causal ? sd.nk_base + row_end : sd.nk_base;
+  // the wave's first keys are requested once the rows are staged (the staging's registers are free
+  // again), its first values once the product has used up the weights
+  crossq_stage<NV, 1>(ln, A, At, m0, m_end, h == 0);
+  uint4 kf0[8][2], vraw0[2][8];
+  split_request_keys(Kb, sd, h, K, nk_all, wave, kf0);
+  crossq_multiply<NV, 1>(At, Qt, b, bias != nullptr, bn);
+  split_request_values(Vb, sd, h, K, nk_all, wave, vraw0);
+  __syncthreads();   // the queries are in LDS; the row tile is no longer needed
+  uint4 qf[2];
+  {
+    const int row = min(r, row_end - row_begin - 1);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) qf[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
+  }
+  attn_split_keys(qf, kf0, vraw0, Kb, Vb, out, sd, row_begin, row_end, h, K, scale, nk_all, lds_waves, xch);
+}
+inline size_t crossq_split_lds_bytes() { return attn_split_lds_bytes() + 16 * (size_t)kCrossqQld * 2; }
 
 }  // namespace ad

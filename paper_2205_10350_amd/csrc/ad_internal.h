@@ -88,6 +88,12 @@ int launch_gemm(int dtype, const void* A, const void* W, int M, int N, int K, co
 // one attention problem per descriptor (n_seq of them, at most max_rows query rows each)
 void launch_attention(int dtype, const void* q, const void* K, const void* V, void* out, const SeqDesc* desc,
                       int n_seq, int max_rows, int H, int dh, int max_keys, hipStream_t s);
+// the same launch for long key ranges (ad_attention_long.hip; bf16, head width 64, grid and LDS bytes as launch_attention computes them)
+void launch_attention_long(const void* q, const void* K, const void* V, void* out, const SeqDesc* desc, dim3 grid, int d,
+                           float scale, int max_keys, size_t lds_bytes, hipStream_t s);
+bool launch_crossq_attention_long(const LnA& ln, const void* A, const void* W, const float* bias, const void* K, const void* V,
+                                  void* out, const SeqDesc* desc, int n_seq, int max_rows, int H, int chunk, int max_keys,
+                                  hipStream_t s);
 // Cross-attention of a decoder layer with its query projection (and the pending LayerNorm of the
 // rows, `ln`, or the rows `A` as they are) in one launch; false = shape not covered (nothing
 // launched: use launch_gemm + launch_attention).

@@ -105,60 +105,6 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
 // Accumulation order per output element as in every other kernel: k ascending, 32 at a time,
 // one accumulator.
 // EPI_ARGMAX: one (value, column) partial per (row, workgroup) instead of one per strip.
-// A tile rows [row0, row0 + n_rows) of a workgroup from fp32 rows through LayerNorm (width
-// 256 * NV, the 16-byte rule of ln_load4 / ln_stats4), RB rows in flight at a time.
-// after_first_loads(): called once, when the wave's first batch of row loads has been issued:
-// whatever the caller wants in flight behind them.  Loads return in issue order, so what is
-// needed first (the rows: everything waits for the tile) is requested first.
-struct NoOp { __device__ __forceinline__ void operator()() const {} };
-template <int NV, int RB, typename F = NoOp>
-__device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld, int row0, int n_rows, int m0, int M,
-                                               int lane, bool store_y, const F& after_first_loads = F{}) {
-  constexpr int K = 256 * NV;
-  float4 gv[NV], bv[NV];
-#pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    gv[j] = *(const float4*)(ln.g + 4 * lane + 256 * j);
-    bv[j] = *(const float4*)(ln.b + 4 * lane + 256 * j);
-  }
-  for (int i0 = 0; i0 < n_rows; i0 += RB) {
-    float4 xv[RB][NV];
-#pragma unroll
-    for (int i = 0; i < RB; ++i)
-      if (i0 + i < n_rows) ln_load4<NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
-    if (i0 == 0) after_first_loads();
-    // statistics of all rows of the batch first (independent reduction chains the scheduler can
-    // interleave), then the values, then, in the workgroups that keep them, the fp32 rows
-    float mean[RB], rstd[RB];
-#pragma unroll
-    for (int i = 0; i < RB; ++i) ln_stats4<NV>(xv[i0 + i < n_rows ? i : 0], K, mean[i], rstd[i]);
-#pragma unroll
-    for (int i = 0; i < RB; ++i) {
-      if (i0 + i >= n_rows) break;
-      const int row = row0 + i0 + i;
-#pragma unroll
-      for (int j = 0; j < NV; ++j) {
-        const int c = 4 * lane + 256 * j;
-        const float4 o = float4{ln_value(xv[i][j].x, mean[i], rstd[i], gv[j].x, bv[j].x), ln_value(xv[i][j].y, mean[i], rstd[i], gv[j].y, bv[j].y),
-                                ln_value(xv[i][j].z, mean[i], rstd[i], gv[j].z, bv[j].z), ln_value(xv[i][j].w, mean[i], rstd[i], gv[j].w, bv[j].w)};
-        const unsigned lo = (unsigned)f2bf(o.x) | ((unsigned)f2bf(o.y) << 16), hi = (unsigned)f2bf(o.z) | ((unsigned)f2bf(o.w) << 16);
-        *(uint2*)(At + row * ld + c) = uint2{lo, hi};
-        xv[i][j] = o;
-      }
-    }
-    if (store_y) {
-#pragma unroll
-      for (int i = 0; i < RB; ++i) {
-        const int m = m0 + row0 + i0 + i;
-        if (i0 + i < n_rows && m < M) {
-#pragma unroll
-          for (int j = 0; j < NV; ++j) *(float4*)(ln.y + (size_t)m * K + 4 * lane + 256 * j) = xv[i][j];
-        }
-      }
-    }
-  }
-}
-
 // (Argument order, here and in the other kernels of a forward: the first 64 bytes of a kernel's arguments are in
 // scalar registers when a wave starts (kernel-argument preload); what the prologue needs first, the sizes that decide
 // the workgroup's place and the pointers of the first loads, comes first, the epilogue's description last.)
@@ -793,6 +739,12 @@ static void attention_dispatch(const void* q, const void* K, const void* V, void
     k_attention<T, DH><<<g, 256, sh, s>>>((const T*)q, (const T*)K, (const T*)V, (T*)out, desc, H * dh, scale, \
                                           max_keys);                                                           \
   } while (0)
+  if constexpr (sizeof(T) == 2) {
+    if (dh == 64 && max_keys >= kLongKeys) {   // long key ranges: a kernel in a code object of its own
+      launch_attention_long(q, K, V, out, desc, g, H * dh, scale, max_keys, sh, s);
+      return;
+    }
+  }
   switch (dh) {
     case 16: AD_ATT(16); break;
     case 32: AD_ATT(32); break;
@@ -820,223 +772,6 @@ void launch_attention(int dtype, const void* q, const void* K, const void* V, vo
 // tiles, the values when they are few) is requested at the very start, next to the weights, so
 // the kernel waits for memory once.  One launch and one trip through memory less per decoder layer.
 // LDS: [values, transposed][probability tiles | row tile (until the queries are there)][queries].
-constexpr int kCrossqQld = 64 + 16;   // query tile row stride (elements): 32 bytes past a multiple of 64
-static size_t crossq_lds_bytes(int nk_cap, int mt, int d) {
-  const size_t ldv = (size_t)((nk_cap + 31) & ~31) + 16;
-  return (64 * ldv + std::max((size_t)64 * ldv, (size_t)mt * 16 * (d + 16)) + 64 * (size_t)kCrossqQld) * 2;
-}
-// The query projection of k_crossq_attention for MT row tiles: stage the chunk's rows in LDS (through
-// the pending LayerNorm, or as they are), multiply by the wave's strip `b` of the query matrix,
-// leave the queries (bias added, rounded) in the LDS tile Qt.  (A function with the arrays as
-// reference parameters, not a lambda that captures them: captured arrays end up in scratch memory.)
-template <int NV, int MT>
-__device__ __forceinline__ void crossq_stage(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, int m0, int m_end,
-                                             bool keep_rows) {
-  constexpr int K = 256 * NV, ld = K + 16, per_wave = MT * 4;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (ln.x) {
-    astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, keep_rows);
-  } else {
-    uint4 av[per_wave][K / 512];
-#pragma unroll
-    for (int i = 0; i < per_wave; ++i)
-#pragma unroll
-      for (int j = 0; j < K / 512; ++j)
-        av[i][j] = *(const uint4*)(A + (size_t)min(m0 + wave * per_wave + i, m_end - 1) * K + j * 512 + lane * 8);
-#pragma unroll
-    for (int i = 0; i < per_wave; ++i)
-#pragma unroll
-      for (int j = 0; j < K / 512; ++j) *(uint4*)(At + (wave * per_wave + i) * ld + j * 512 + lane * 8) = av[i][j];
-  }
-  __syncthreads();
-}
-template <int NV, int MT>
-__device__ __forceinline__ void crossq_multiply(const bf16_t* At, bf16_t* Qt, const uint4 (&b)[8 * NV], bool has_bias, float bn) {
-  constexpr int K = 256 * NV, KS = K / 32, ld = K + 16, QLD = kCrossqQld;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, kq = lane >> 4;
-  const bf16_t* a_lane = At + r * ld + kq * 8;
-  f32x4 acc[MT];
-#pragma unroll
-  for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int u = 0; u < KS; ++u) {
-    uint4 af[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) af[t] = *(const uint4*)(a_lane + t * 16 * ld + 32 * u);
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[t]), __builtin_bit_cast(bf16x8, b[u]), acc[t], 0, 0, 0);
-  }
-  // this lane: rows 16 t + 4 kq + i of the chunk, column 16 wave + r of the head
-#pragma unroll
-  for (int t = 0; t < MT; ++t)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float v = acc[t][i];
-      if (has_bias) v += bn;
-      Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
-    }
-}
-template <int NV, int MT>
-__device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, bf16_t* Qt,
-                                               const uint4 (&b)[8 * NV], bool has_bias, float bn, int m0, int m_end,
-                                               bool keep_rows) {
-  crossq_stage<NV, MT>(ln, A, At, m0, m_end, keep_rows);
-  crossq_multiply<NV, MT>(At, Qt, b, has_bias, bn);
-}
-template <int NV, bool SMALL>
-__global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
-                                                          const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
-                                                          const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
-                                                          const float* __restrict__ ln_g, const float* __restrict__ ln_b,
-                                                          float* __restrict__ ln_y, const bf16_t* __restrict__ A,
-                                                          const float* __restrict__ bias, bf16_t* __restrict__ out) {
-  LnA ln;
-  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
-  constexpr int K = 256 * NV, KS = K / 32, DH = 64, ld = K + 16, QLD = kCrossqQld, G = DH / 8;
-  extern __shared__ uint4 cq_lds[];
-  const SeqDesc sd = desc[blockIdx.x];
-  const int row_begin = blockIdx.z * chunk_rows;
-  if (row_begin >= sd.nq) return;
-  const int row_end = min(sd.nq, row_begin + chunk_rows);
-  const int h = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, kq = lane >> 4;
-  const int mt = (row_end - row_begin + 15) >> 4;
-  const int m0 = sd.q_row0 + row_begin, m_end = sd.q_row0 + row_end;   // packed rows of the chunk
-  const int n0 = h * DH + wave * 16;
-  const int nk_all = sd.causal ? sd.nk_base + row_end : sd.nk_base;
-  const int nkp = (nk_all + 31) & ~31, ldv = nkp + 16;
-  bf16_t* Vt = (bf16_t*)cq_lds;          // [DH][ldv]
-  bf16_t* Pall = Vt + DH * ldv;          // [4 waves][16][ldv]
-  bf16_t* At = Pall;                     // [16 * mt][K + 16]
-  bf16_t* Qt = Pall + max(64 * ldv, mt * 16 * ld);   // [64][QLD]
-  // the wave's strip of the query matrix
-  uint4 b[KS];
-  {
-    const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
-#pragma unroll
-    for (int u = 0; u < KS; ++u) b[u] = *(const uint4*)(wp + u * 512);
-  }
-  const float bn = bias ? bias[n0 + r] : 0.f;
-  uint4 kf_pre[4][DH / 32];
-  attn_preload_k<DH>(Kb, sd, row_begin, row_end, h, K, nk_all, kf_pre);
-  // up to 128 keys: the values (piece i = 8 channels of one key; addresses clamped, never under a
-  // branch of their own) wait in registers until the row tile is staged
-  const bool v_small = SMALL || nkp <= 128;
-  uint4 vreg[4];
-  if (v_small) {
-    const bf16_t* vg = Vb + (size_t)sd.kv_row0 * K + h * DH;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int i = min((int)threadIdx.x + 256 * it, nkp * G - 1);
-      const int g = i / nkp, t = min(i - g * nkp, nk_all - 1);
-      vreg[it] = *(const uint4*)(vg + (size_t)t * K + g * 8);
-    }
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
-  if (SMALL || mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  else if (mt == 2) crossq_project<NV, 2>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  else if (mt == 3) crossq_project<NV, 3>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  else crossq_project<NV, 4>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  // values into LDS, transposed (keys nk_all .. nkp - 1 as zeros)
-  if (v_small) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int i = threadIdx.x + 256 * it;
-      if (i < nkp * G) {
-        const int g = i / nkp, t = i - g * nkp;
-        const uint4 v = t < nk_all ? vreg[it] : uint4{0u, 0u, 0u, 0u};
-        bf16_t* dst = Vt + (size_t)(g * 8) * ldv + t;
-        dst[0] = (bf16_t)(v.x & 0xffffu); dst[ldv] = (bf16_t)(v.x >> 16);
-        dst[2 * ldv] = (bf16_t)(v.y & 0xffffu); dst[3 * ldv] = (bf16_t)(v.y >> 16);
-        dst[4 * ldv] = (bf16_t)(v.z & 0xffffu); dst[5 * ldv] = (bf16_t)(v.z >> 16);
-        dst[6 * ldv] = (bf16_t)(v.w & 0xffffu); dst[7 * ldv] = (bf16_t)(v.w >> 16);
-      }
-    }
-  } else {
-    attn_stage_values<DH>(Vb, sd, h, K, Vt, ldv, nkp, nk_all);
-  }
-  __syncthreads();   // queries and values are in LDS; the row tile is no longer needed
-  // the rest is attn_block_mfma with the query fragments read from the LDS tile
-  const int n_tiles = mt;
-  uint4 qf_pre[DH / 32];
-  {
-    const int row = min(min(wave, n_tiles - 1) * 16 + r, row_end - row_begin - 1);
-#pragma unroll
-    for (int s2 = 0; s2 < DH / 32; ++s2) qf_pre[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
-  }
-  const int nt_all = (nk_all + 15) >> 4;
-  const bool coop = !SMALL && row_end - row_begin <= 16 && nt_all > 8;
-  float* Sbuf = coop ? (float*)(Pall + 16 * ldv) : nullptr;
-  if (coop) {
-    attn_coop_scores_q<DH>(qf_pre, Kb, sd, h, K, nk_all, nt_all, Sbuf, nkp);
-    __syncthreads();
-  }
-  bf16_t* Pw = Pall + wave * 16 * ldv;
-  const bf16_t* qnone = nullptr;   // every wave has at most one tile: its fragments are qf_pre
-  if (SMALL || nkp <= 64) attn_tiles_mfma<DH, 4>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else if (nkp <= 128) attn_tiles_mfma<DH, 8>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-  else attn_tiles_mfma<DH, 16>(qnone, Kb, out, sd, row_begin, row_end, h, K, scale, Vt, Pw, ldv, nk_all, qf_pre, kf_pre, Sbuf, nkp);
-}
-// The same for one row tile per workgroup against many keys (long sources): after the projection the four waves
-// split the keys (attn_split_keys: wave w owns the 128-key super-blocks w, w + 4, ...), instead of one wave walking
-// all of them behind a workgroup-wide staging of the values.  LDS: [4 waves: values, probabilities | row tile (until
-// the queries are there)][exchange area][queries].
-template <int NV>
-__global__ __launch_bounds__(256) void k_crossq_attention_split(const SeqDesc* __restrict__ desc, float scale,
-                                                                const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
-                                                                const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
-                                                                const float* __restrict__ ln_g, const float* __restrict__ ln_b,
-                                                                float* __restrict__ ln_y, const bf16_t* __restrict__ A,
-                                                                const float* __restrict__ bias, bf16_t* __restrict__ out) {
-  LnA ln;
-  ln.x = ln_x; ln.g = ln_g; ln.b = ln_b; ln.y = ln_y;
-  constexpr int K = 256 * NV, KS = K / 32, DH = 64, QLD = kCrossqQld;
-  extern __shared__ uint4 cqs_lds[];
-  const int h = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, kq = lane >> 4;
-  const int n0 = h * DH + wave * 16;
-  // the wave's strip of the query matrix first: its address depends on the head alone, not on the
-  // sequence's descriptor, which is a trip to memory of its own
-  uint4 b[KS];
-  {
-    const bf16_t* wp = W + (size_t)n0 * K + lane * 8;
-#pragma unroll
-    for (int u = 0; u < KS; ++u) b[u] = *(const uint4*)(wp + u * 512);
-  }
-  const float bn = bias ? bias[n0 + r] : 0.f;
-  __builtin_amdgcn_sched_barrier(0);
-  const SeqDesc sd = desc[blockIdx.x];
-  const int row_begin = blockIdx.z * 16;
-  if (row_begin >= sd.nq) return;
-  const int row_end = min(sd.nq, row_begin + 16);
-  const int m0 = sd.q_row0 + row_begin, m_end = sd.q_row0 + row_end;
-  bf16_t* lds_waves = (bf16_t*)cqs_lds;
-  bf16_t* At = lds_waves;                                          // [16][K + 16]
-  float* xch = (float*)(lds_waves + 4 * kSplitWaveElems);
-  bf16_t* Qt = (bf16_t*)((char*)xch + kSplitXchBytes);             // [16][QLD]
-  const int nk_all = sd.causal ? sd.nk_base + row_end : sd.nk_base;
-  // the wave's first keys are requested once the rows are staged (the staging's registers are free
-  // again), its first values once the product has used up the weights
-  crossq_stage<NV, 1>(ln, A, At, m0, m_end, h == 0);
-  uint4 kf0[8][2], vraw0[2][8];
-  split_request_keys(Kb, sd, h, K, nk_all, wave, kf0);
-  crossq_multiply<NV, 1>(At, Qt, b, bias != nullptr, bn);
-  split_request_values(Vb, sd, h, K, nk_all, wave, vraw0);
-  __syncthreads();   // the queries are in LDS; the row tile is no longer needed
-  uint4 qf[2];
-  {
-    const int row = min(r, row_end - row_begin - 1);
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) qf[s2] = *(const uint4*)(Qt + row * QLD + kq * 8 + 32 * s2);
-  }
-  attn_split_keys(qf, kf0, vraw0, Kb, Vb, out, sd, row_begin, row_end, h, K, scale, nk_all, lds_waves, xch);
-}
-static size_t crossq_split_lds_bytes() { return attn_split_lds_bytes() + 16 * (size_t)kCrossqQld * 2; }
 bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void* W, const float* bias, const void* K,
                              const void* V, void* out, const SeqDesc* desc, int n_seq, int max_rows, int H, int dh,
                              int max_keys, hipStream_t s) {
@@ -1051,26 +786,10 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   // attention stay two launches: 32-row chunks would fit and measured slower, drafter forward at 626 rows 957 -> 1051 us.)
   const int chunk = n_seq * H * ((max_rows + 15) / 16) <= 256 ? 16 : (n_seq * H * ((max_rows + 31) / 32) <= 256 ? 32 : 64);
   const int mt = (std::min(max_rows, chunk) + 15) / 16;
-  // one row tile per workgroup and more than 128 keys: the waves split the keys
-  if (mt == 1 && max_keys > 128 && 16 * (size_t)(d + 16) * 2 <= 4 * (size_t)kSplitWaveElems * 2) {
-    if (n_seq <= 0 || max_rows <= 0) return true;
-    const size_t shs = crossq_split_lds_bytes();
-    dim3 g(n_seq, H, (max_rows + 15) / 16);
-    const float scale = 1.0f / sqrtf((float)dh);
-    auto go = [&](auto nv_c) {
-      constexpr int NV = decltype(nv_c)::value;
-      static bool set = false;
-      if (!set) {
-        (void)hipFuncSetAttribute((const void*)k_crossq_attention_split<NV>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shs);
-        set = true;
-      }
-      k_crossq_attention_split<NV><<<g, 256, shs, s>>>(desc, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V, ln.x, ln.g,
-                                                       ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
-    };
-    if (d == 512) go(std::integral_constant<int, 2>{});
-    else go(std::integral_constant<int, 4>{});
-    return true;
-  }
+  // a long source capacity: the kernels of the other code object (the summation order beyond 128 keys; with one row
+  // tile per workgroup the waves split the keys)
+  if (max_keys >= kLongKeys)
+    return launch_crossq_attention_long(ln, A, W, bias, K, V, out, desc, n_seq, max_rows, H, chunk, max_keys, s);
   const size_t sh = crossq_lds_bytes(max_keys, mt, d);
   if (sh > 160 * 1024) return false;
   if (n_seq <= 0 || max_rows <= 0) return true;
