@@ -193,6 +193,9 @@ struct ad_ctx {
   // shape of the forward being launched: attention problems and the most query rows in one
   int fw_nseq = 0, fw_max_rows = 0;
   int last_nseq = 0, last_max_rows = 0;
+  // the keys the longest self-attention problem of the current / last verify forward sees (prefix + block, from the host's
+  // mirror of the lengths); 0: unknown, the cache capacity bounds them
+  int fw_self_keys = 0, last_self_keys = 0;
   // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
   const LnW* ln_pending = nullptr;
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
@@ -310,8 +313,10 @@ static void self_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, voi
   e.mode = EPI_QKV; e.d = d; e.bias = a.bqkv; e.out0 = c->at<void>(p.q); e.out1 = Kl; e.out2 = Vl; e.row_dst = t.row_dst;
   gemm_rows(c, a.wqkv, M, 3 * d, e);
   if (head_rows > 0) { c->fw_nseq = head_nseq; c->fw_max_rows = head_max_rows; M = head_rows; }
+  // (a bound of at most 64 keys selects the compact attention kernel; it is part of the call shape's graph key)
+  const int key_bound = c->fw_self_keys > 0 && c->fw_self_keys <= 64 ? 64 : max_keys;
   launch_attention(c->cfg.dtype, c->at<void>(p.q), Kl, Vl, c->at<void>(p.att), t.self_desc, c->fw_nseq, c->fw_max_rows,
-                   H, d / H, max_keys, c->stream);
+                   H, d / H, key_bound, c->stream);
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
 
@@ -678,7 +683,7 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
       e.out1 = c->at<void>(p.tk); e.out2 = c->at<void>(p.tv); e.row_dst = t.row_dst;
       gemm_rows(c, L.self.wqkv, M, 3 * d, e);
       launch_attention(cf.dtype, c->at<void>(p.q), c->at<void>(p.tk), c->at<void>(p.tv), c->at<void>(p.att),
-                       t.self_desc, B, c->fw_max_rows, cf.n_heads, d / cf.n_heads, S, c->stream);
+                       t.self_desc, B, c->fw_max_rows, cf.n_heads, d / cf.n_heads, c->fw_max_rows <= 64 ? 64 : S, c->stream);
       gemm_resid_ln(c, c->at<void>(p.att), L.self.wo, L.self.bo, M, d, d, L.ln1);
       ffn_block(c, L.ffn, L.ln2, M);
     }
@@ -834,7 +839,11 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
   v.part_stride = p.n_strips;
   c->fw_nseq = B;
   c->fw_max_rows = max_rows;
-  c->last_nseq = B; c->last_max_rows = max_rows;
+  int self_keys = 0;
+  for (int b = 0; b < B; ++b)
+    if (k[b] > 0) self_keys = std::max(self_keys, c->h_len[b] + (int)k[b]);
+  c->fw_self_keys = self_keys;
+  c->last_nseq = B; c->last_max_rows = max_rows; c->last_self_keys = self_keys;
   // The result lands in host memory the device writes directly, as ONE 8-byte word per sequence that
   // carries the call's ticket, and the host watches for the ticket instead of waiting for the
   // stream to drain (the end of the kernel, its completion signal and the runtime's wake-up are off
@@ -855,7 +864,7 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
   const bool gadpp = c->gadpp_beta > 1;
   bool launched = false;
   if (mapped && !static_scratch) {
-    const unsigned long long key = shape_key(M, max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0));
+    const unsigned long long key = shape_key(M, max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0) | (self_keys <= 64 ? 8 : 0));
     unsigned tau_bits;
     memcpy(&tau_bits, &c->gadpp_tau, 4);
     const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;
@@ -966,6 +975,7 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     int rows = M;
     c->fw_nseq = 2 * live;
     c->fw_max_rows = max_rows;
+    c->fw_self_keys = 0;
     for (int l = 0; l < cf.dec_layers; ++l) {
       const DecLayerW& L = w.dec[l];
       if (l + 1 == cf.dec_layers) {
@@ -1225,7 +1235,7 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   if (reps < 1 || !forward_us || !vocab_kernel_us) return fail(c, AD_EINVAL, "bad argument");
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
   double tot = 0, voc = 0;
-  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
+  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows; c->fw_self_keys = c->last_self_keys;
   verify_forward(c, c->last_M);   // warm
   // the whole forward, reps times back to back between two events
   HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
@@ -1268,7 +1278,7 @@ int ad_time_output_projection(ad_ctx* c, const void* w_copies, size_t copy_strid
   const size_t need = (size_t)c->cfg.vocab * c->cfg.d_model * (c->cfg.dtype == AD_BF16 ? 2 : 4);
   if (copy_stride_bytes < need || copy_stride_bytes % 16) return fail(c, AD_EINVAL, "copy stride smaller than the matrix or not a multiple of 16");
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
-  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows;
+  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows; c->fw_self_keys = c->last_self_keys;
   verify_forward(c, c->last_M);   // the rows (and the pending LayerNorm) the projection works on
   const ModelW& w = c->w[AD_VERIFIER];
   auto copy = [&](int r) { return (const char*)w_copies + (size_t)(r % n_copies) * copy_stride_bytes; };

@@ -268,6 +268,44 @@ def test_rows_do_not_depend_on_the_row_regime_of_the_gemm_kernels():
         rig.close()
 
 
+def test_rows_do_not_depend_on_the_attention_kernel_the_key_bound_selects():
+    """Base model, bit-exact.  A verify call whose longest prefix + block stays within 64 keys runs the compact
+    self-attention kernel, any other the generic one, and the bound is part of the call shape a graph is kept for.
+    One sequence is verified 8 rows at a time along its own greedy output (every block is accepted whole, so the
+    prefix grows by 8 per call and passes 64 keys at the ninth call; the call shape stays the same throughout: the early
+    calls are replayed from a graph built with the compact kernel, the late ones must not be).  Every call's logits must
+    equal those of the same rows (a) with graphs off and (b) verified beside a second sequence whose 70-row block forces
+    the generic kernel in every call."""
+    rig = Rig("base", "bf16", 91, B=2, max_src=40, max_len=96, k_max=72)
+    try:
+        V = rig.dims["vocab"]
+        rng = np.random.default_rng(91)
+        srcs = _sources(rig.dims, 91, [23, 31])
+        g = rig.ctx.decode_greedy(srcs[:1], max_out=[88])[0][0]
+        assert len(g) == 88
+        other = [int(t) for t in rng.integers(5, V, size=70)]
+
+        def run(graphs, beside):
+            rig.ctx.set_option(ad.AD_OPT_GRAPHS, graphs)
+            rig.ctx.encode(ad.AD_VERIFIER, srcs if beside else srcs[:1])
+            out = []
+            for i in range(0, 88, 8):
+                n, _ = rig.ctx.verify([g[i:i + 8]] + ([other] if beside else []))
+                assert n[0] == 8, (i, n)
+                out.append(rig.ctx.debug_logits().view(np.uint32)[:8].copy())
+            return out
+
+        a = run(1, False)
+        b = run(0, False)
+        c = run(1, True)
+        for i in range(len(a)):
+            assert np.array_equal(a[i], b[i]), ("graphs on / off", i)
+            assert np.array_equal(a[i], c[i]), ("compact / generic kernel", i)
+    finally:
+        rig.ctx.set_option(ad.AD_OPT_GRAPHS, 1)
+        rig.close()
+
+
 def test_ragged_batch_rollback_and_inactive_sequences():
     rig = Rig("tiny", "fp32", 9, B=4, k_max=12)
     try:
