@@ -77,10 +77,10 @@ bool launch_crossq_attention_long(const LnA& ln, const void* A, const void* W, c
     constexpr int NV = decltype(nv_c)::value;
     static size_t set_for = 0;
     if (sh > set_for) {
-      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, 0, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       set_for = sh;
     }
-    k_crossq_attention<NV, false, true><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
+    k_crossq_attention<NV, 0, true><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
                                                            ln.x, ln.g, ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
   };
   if (d == 512) go(std::integral_constant<int, 2>{});

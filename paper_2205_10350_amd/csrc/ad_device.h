@@ -1385,7 +1385,8 @@ __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __re
   crossq_multiply<NV, MT>(At, Qt, b, has_bias, bn);
 }
 // LONGK: the configuration's source capacity is kLongKeys or more (the summation order beyond 128 keys, attn_tiles_mfma)
-template <int NV, bool SMALL, bool LONGK = false>
+// SMALL: what the launch bounds promise: 1 = one row tile per workgroup and at most 64 keys, 2 = at most 64 keys, 0 = nothing
+template <int NV, int SMALL, bool LONGK = false>
 __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
                                                           const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
                                                           const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
@@ -1437,7 +1438,7 @@ __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restr
   }
   __builtin_amdgcn_sched_barrier(0);
   // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
-  if (SMALL || mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  if (SMALL == 1 || mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   else if (mt == 2) crossq_project<NV, 2>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   else if (mt == 3) crossq_project<NV, 3>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   else crossq_project<NV, 4>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);

@@ -839,12 +839,12 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   if (n_seq <= 0 || max_rows <= 0) return true;
   dim3 g(n_seq, H, (max_rows + chunk - 1) / chunk);
   const float scale = 1.0f / sqrtf((float)dh);
-  // one row tile per workgroup and at most 64 keys (the bounds the caller gives promise both): a
-  // variant that holds that one path only (a quarter of the code)
-  const bool small = mt == 1 && max_keys <= 64;
+  // at most 64 keys (the bound the caller gives promises it): variants that hold that path only, a sixth of the code with
+  // one row tile per workgroup, less than half with several
+  const int small = max_keys <= 64 ? (mt == 1 ? 1 : 2) : 0;
   auto go = [&](auto nv_c, auto small_c) {
     constexpr int NV = decltype(nv_c)::value;
-    constexpr bool SMALL = decltype(small_c)::value;
+    constexpr int SMALL = decltype(small_c)::value;
     static size_t set_for = 0;
     if (sh > set_for) {
       (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, SMALL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
@@ -853,10 +853,12 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
     k_crossq_attention<NV, SMALL><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
                                                      ln.x, ln.g, ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
   };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
   using I4 = std::integral_constant<int, 4>;
-  if (d == 512) { if (small) go(I2{}, std::true_type{}); else go(I2{}, std::false_type{}); }
-  else { if (small) go(I4{}, std::true_type{}); else go(I4{}, std::false_type{}); }
+  if (d == 512) { if (small == 1) go(I2{}, I1{}); else if (small == 2) go(I2{}, I2{}); else go(I2{}, I0{}); }
+  else { if (small == 1) go(I4{}, I1{}); else if (small == 2) go(I4{}, I2{}); else go(I4{}, I0{}); }
   return true;
 }
 
