@@ -196,6 +196,8 @@ struct ad_ctx {
   // the keys the longest self-attention problem of the current / last verify forward sees (prefix + block, from the host's
   // mirror of the lengths); 0: unknown, the cache capacity bounds them
   int fw_self_keys = 0, last_self_keys = 0;
+  // the same for the cross-attention: the longest source of the batch the forward runs on
+  int fw_cross_keys = 0, last_cross_keys = 0;
   // LayerNorm deferred into the next GEMM's operand staging: s -> (x, xa) with these parameters
   const LnW* ln_pending = nullptr;
   const LnW* ln_vocab = nullptr;  // the one the last verify forward's output projection applied (timing)
@@ -329,9 +331,12 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
   if (c->ln_pending) {
     la.x = c->at<float>(p.s); la.g = c->ln_pending->g; la.b = c->ln_pending->b; la.y = c->at<float>(p.x);
   }
+  // (only a bound of at most 64 keys replaces the capacity: it selects the compact kernels, whose results for such key
+  // counts are those of every other kernel; a bound between the classes of longer ranges could change the summation order)
+  const int key_bound = c->fw_cross_keys > 0 && c->fw_cross_keys <= 64 ? 64 : c->cfg.max_src;
   if (c->fuse_crossq &&
       launch_crossq_attention(c->cfg.dtype, la, c->at<void>(p.xa), a.wqkv, a.bqkv, Km, Vm,
-                              c->at<void>(p.att), t.cross_desc, c->fw_nseq, c->fw_max_rows, H, d / H, c->cfg.max_src,
+                              c->at<void>(p.att), t.cross_desc, c->fw_nseq, c->fw_max_rows, H, d / H, key_bound,
                               c->stream)) {
     c->ln_pending = nullptr;
   } else {
@@ -339,7 +344,7 @@ static void cross_attn_block(ad_ctx* c, const AttnW& a, const LnW& ln, int M, co
     e.mode = EPI_STORE; e.bias = a.bqkv; e.out0 = c->at<void>(p.q);
     gemm_rows(c, a.wqkv, M, d, e);
     launch_attention(c->cfg.dtype, c->at<void>(p.q), Km, Vm, c->at<void>(p.att), t.cross_desc, c->fw_nseq,
-                     c->fw_max_rows, H, d / H, c->cfg.max_src, c->stream);
+                     c->fw_max_rows, H, d / H, key_bound, c->stream);
   }
   gemm_resid_ln(c, c->at<void>(p.att), a.wo, a.bo, M, d, d, ln);
 }
@@ -843,7 +848,9 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
   for (int b = 0; b < B; ++b)
     if (k[b] > 0) self_keys = std::max(self_keys, c->h_len[b] + (int)k[b]);
   c->fw_self_keys = self_keys;
-  c->last_nseq = B; c->last_max_rows = max_rows; c->last_self_keys = self_keys;
+  const int cross_keys = *std::max_element(c->h_src_len[AD_VERIFIER].begin(), c->h_src_len[AD_VERIFIER].begin() + B);
+  c->fw_cross_keys = cross_keys;
+  c->last_nseq = B; c->last_max_rows = max_rows; c->last_self_keys = self_keys; c->last_cross_keys = cross_keys;
   // The result lands in host memory the device writes directly, as ONE 8-byte word per sequence that
   // carries the call's ticket, and the host watches for the ticket instead of waiting for the
   // stream to drain (the end of the kernel, its completion signal and the runtime's wake-up are off
@@ -864,7 +871,7 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
   const bool gadpp = c->gadpp_beta > 1;
   bool launched = false;
   if (mapped && !static_scratch) {
-    const unsigned long long key = shape_key(M, max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0) | (self_keys <= 64 ? 8 : 0));
+    const unsigned long long key = shape_key(M, max_rows, B, (gadpp ? 1 : 0) | (watch ? 2 : 0) | (c->fuse_crossq ? 4 : 0) | (self_keys <= 64 ? 8 : 0) | (cross_keys <= 64 ? 16 : 0));
     unsigned tau_bits;
     memcpy(&tau_bits, &c->gadpp_tau, 4);
     const unsigned long long more = gadpp ? ((unsigned long long)c->gadpp_beta << 32) | tau_bits : 0;
@@ -976,6 +983,7 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     c->fw_nseq = 2 * live;
     c->fw_max_rows = max_rows;
     c->fw_self_keys = 0;
+    c->fw_cross_keys = *std::max_element(c->h_src_len[AD_DRAFTER].begin(), c->h_src_len[AD_DRAFTER].begin() + B);
     for (int l = 0; l < cf.dec_layers; ++l) {
       const DecLayerW& L = w.dec[l];
       if (l + 1 == cf.dec_layers) {
@@ -1235,7 +1243,7 @@ int ad_time_verify_forward(ad_ctx* c, int reps, double* forward_us, double* voca
   if (reps < 1 || !forward_us || !vocab_kernel_us) return fail(c, AD_EINVAL, "bad argument");
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
   double tot = 0, voc = 0;
-  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows; c->fw_self_keys = c->last_self_keys;
+  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows; c->fw_self_keys = c->last_self_keys; c->fw_cross_keys = c->last_cross_keys;
   verify_forward(c, c->last_M);   // warm
   // the whole forward, reps times back to back between two events
   HIP_TRY(c, hipEventRecord(c->ev0, c->stream));
@@ -1278,7 +1286,7 @@ int ad_time_output_projection(ad_ctx* c, const void* w_copies, size_t copy_strid
   const size_t need = (size_t)c->cfg.vocab * c->cfg.d_model * (c->cfg.dtype == AD_BF16 ? 2 : 4);
   if (copy_stride_bytes < need || copy_stride_bytes % 16) return fail(c, AD_EINVAL, "copy stride smaller than the matrix or not a multiple of 16");
   if (c->last_M < 1) return fail(c, AD_ESTATE, "the last forward was not an ad_verify");
-  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows; c->fw_self_keys = c->last_self_keys;
+  c->fw_nseq = c->last_nseq; c->fw_max_rows = c->last_max_rows; c->fw_self_keys = c->last_self_keys; c->fw_cross_keys = c->last_cross_keys;
   verify_forward(c, c->last_M);   // the rows (and the pending LayerNorm) the projection works on
   const ModelW& w = c->w[AD_VERIFIER];
   auto copy = [&](int r) { return (const char*)w_copies + (size_t)(r % n_copies) * copy_stride_bytes; };

@@ -306,6 +306,27 @@ def test_rows_do_not_depend_on_the_attention_kernel_the_key_bound_selects():
         rig.close()
 
 
+def test_rows_do_not_depend_on_the_cross_attention_kernel_the_source_bound_selects():
+    """Base model with a source capacity of 80, bit-exact: a batch whose longest source has at most 64 tokens runs the
+    compact cross-attention kernels, any other the generic ones; the logits of sequence 0 (a 30-token source, blocks of
+    1, 20 and 40 rows) must be the same alone and beside a 75-token source."""
+    rig = Rig("base", "bf16", 93, B=2, max_src=80, max_len=48, k_max=40)
+    try:
+        V = rig.dims["vocab"]
+        rng = np.random.default_rng(93)
+        srcs = _sources(rig.dims, 93, [30, 75])
+        block = [int(t) for t in rng.integers(5, V, size=40)]
+        for rows in (1, 20, 40):
+            rig.ctx.encode(ad.AD_VERIFIER, srcs[:1])
+            rig.ctx.verify([block[:rows]])
+            alone = rig.ctx.debug_logits().view(np.uint32)[:rows].copy()
+            rig.ctx.encode(ad.AD_VERIFIER, srcs)
+            rig.ctx.verify([block[:rows], block[:3]])
+            assert np.array_equal(rig.ctx.debug_logits().view(np.uint32)[:rows], alone), rows
+    finally:
+        rig.close()
+
+
 def test_ragged_batch_rollback_and_inactive_sequences():
     rig = Rig("tiny", "fp32", 9, B=4, k_max=12)
     try:
