@@ -959,9 +959,12 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     return AD_OK;
   }
   VerifyTables t = tables(c);
-  int max_rows = k;
+  int max_rows = k, self_keys = 0;
   for (int b = 0; b < B; ++b)
-    if (!c->h_finished[b]) max_rows = std::max(max_rows, c->h_len[b] + 1);
+    if (!c->h_finished[b]) {
+      max_rows = std::max(max_rows, c->h_len[b] + 1);
+      self_keys = std::max(self_keys, c->h_len[b] + 1 + k);   // every row of a sequence sees its prefix and the k masks
+    }
   const int Mv = live * k;
   int32_t* h = c->pin + c->pl.d_copy;
   unsigned long long* slots = (unsigned long long*)(c->pin + c->pl.d_slots);   // [B, k_max]
@@ -982,7 +985,7 @@ int ad_draft_nat(ad_ctx* c, int k, int32_t* draft_out) {
     int rows = M;
     c->fw_nseq = 2 * live;
     c->fw_max_rows = max_rows;
-    c->fw_self_keys = 0;
+    c->fw_self_keys = self_keys;
     c->fw_cross_keys = *std::max_element(c->h_src_len[AD_DRAFTER].begin(), c->h_src_len[AD_DRAFTER].begin() + B);
     for (int l = 0; l < cf.dec_layers; ++l) {
       const DecLayerW& L = w.dec[l];
