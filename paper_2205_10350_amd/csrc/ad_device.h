@@ -644,8 +644,10 @@ __device__ __forceinline__ void attn_tiles_mfma(const bf16_t* __restrict__ q, co
       }
     }
   };
+  // (Every caller hands a chunk of at most 64 rows to a workgroup of four waves: a wave has at most one tile, the one
+  // whose operands were requested ahead.  A loop over further tiles, with its own copy of the tile body, was never
+  // entered, and the attention kernels ran slower for carrying it.)
   if (wave < n_tiles) tile(std::true_type{}, wave);
-  for (int rt = wave + waves; rt < n_tiles; rt += waves) tile(std::false_type{}, rt);
 }
 // Query fragments and the first four key tiles of the wave's first 16-row tile (what
 // attn_tiles_mfma takes as qf_pre / kf_pre): same addresses, same clamping.
