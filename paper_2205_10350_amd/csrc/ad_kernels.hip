@@ -453,7 +453,41 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
   }
   using I3 = std::integral_constant<int, 3>;
   const bool count = e.mode == EPI_COUNT;
+  // a variant with the pending LayerNorm (1) or its absence (0) and, for the layer GEMMs, the epilogue as constants
+  auto fixed_variant = [&](auto amax_c, auto ln_c, auto em_c, auto one_c) {
+    constexpr int AMAX = decltype(amax_c)::value, LNM = decltype(ln_c)::value, EMV = decltype(em_c)::value;
+    constexpr bool ONE = decltype(one_c)::value;
+    static size_t set_fixed = 0;
+    if (lds > set_fixed) {
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, AMAX, SP, ONE, LNM, EMV, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      set_fixed = lds;
+    }
+    k_gemm_bf16_astat<MT, AMAX, SP, ONE, LNM, EMV, NW><<<grid, 64 * NW, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln.x, ln.g, ln.b, ln.y, e);
+  };
   if constexpr (NW != 4) {   // the wide workgroups serve the layer GEMMs only
+    // (the combinations that occur with the pending LayerNorm and the epilogue as compile-time constants, as for the
+    // few-row kernels below: forward at 1152 rows 432.6 -> 425.6 us, at 720 rows 370.5 -> 366.5 us)
+    auto wide = [&](auto one_c, auto ln_c, auto em_c) {
+      constexpr bool ONE = decltype(one_c)::value;
+      constexpr int LNM = decltype(ln_c)::value, EMV = decltype(em_c)::value;
+      static size_t set_wide = 0;
+      if (lds > set_wide) {
+        (void)hipFuncSetAttribute((const void*)k_gemm_bf16_astat<MT, 0, SP, ONE, LNM, EMV, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        set_wide = lds;
+      }
+      k_gemm_bf16_astat<MT, 0, SP, ONE, LNM, EMV, NW><<<grid, 64 * NW, lds, s>>>(A, W, M, N, K, per_wg, gx, chunks, ln.x, ln.g, ln.b, ln.y, e);
+    };
+    using L0 = std::integral_constant<int, 0>;
+    using L1 = std::integral_constant<int, 1>;
+    using EQKV = std::integral_constant<int, EPI_QKV>;
+    using ERES = std::integral_constant<int, EPI_RESID>;
+    if constexpr (NW == 16) {
+      if (K == 512 && ln.x && e.mode == EPI_QKV) { wide(std::true_type{}, L1{}, EQKV{}); return gx; }
+      if (K == 512 && !ln.x && e.mode == EPI_QKV) { wide(std::true_type{}, L0{}, EQKV{}); return gx; }
+    } else {
+      if (K == 512 && !ln.x && e.mode == EPI_RESID) { wide(std::true_type{}, L0{}, ERES{}); return gx; }
+      if (K == 2048 && !ln.x && e.mode == EPI_RESID) { wide(std::false_type{}, L0{}, ERES{}); return gx; }
+    }
     if (K == 512) go(I0{}, std::true_type{});
     else go(I0{}, std::false_type{});
     return gx;
@@ -461,6 +495,12 @@ static int launch_astat(const bf16_t* A, const bf16_t* W, int M, int N, int K, c
   if (K == 512) {
     if (amax) go(I1{}, std::true_type{});
     else if (count) go(I3{}, std::true_type{});
+    else if constexpr (MT == 1 && SP == 2 && NW == 4) {
+      // FFN1 at many rows (forward at 1152 rows 424.6 -> 412.6 us; the same for the 32-row variant at 720 rows, for FFN2
+      // at 192..384 rows and for the many-row output projection measured no gain and was not kept)
+      if (ln.x && e.mode == EPI_RELU) fixed_variant(I0{}, std::integral_constant<int, 1>{}, std::integral_constant<int, EPI_RELU>{}, std::true_type{});
+      else go(I0{}, std::true_type{});
+    }
     else if constexpr (MT == 1 && SP == 1 && NW == 4) {
       // the layer GEMMs of the few-row regime: the pending LayerNorm (or none) and the epilogue mode as
       // compile-time constants, a kernel per combination that occurs (run-time branches around loads in
