@@ -1330,12 +1330,13 @@ inline size_t crossq_lds_bytes(int nk_cap, int mt, int d) {
 // the pending LayerNorm, or as they are), multiply by the wave's strip `b` of the query matrix,
 // leave the queries (bias added, rounded) in the LDS tile Qt.  (A function with the arrays as
 // reference parameters, not a lambda that captures them: captured arrays end up in scratch memory.)
-template <int NV, int MT>
+// (LNMODE 1: the caller knows at compile time that a LayerNorm is pending; -1: ln.x decides)
+template <int NV, int MT, int LNMODE = -1>
 __device__ __forceinline__ void crossq_stage(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, int m0, int m_end,
                                              bool keep_rows) {
   constexpr int K = 256 * NV, ld = K + 16, per_wave = MT * 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (ln.x) {
+  if (LNMODE == 1 || ln.x) {
     astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, keep_rows);
   } else {
     uint4 av[per_wave][K / 512];
@@ -1379,16 +1380,16 @@ __device__ __forceinline__ void crossq_multiply(const bf16_t* At, bf16_t* Qt, co
       Qt[(t * 16 + 4 * kq + i) * QLD + wave * 16 + r] = f2bf(v);
     }
 }
-template <int NV, int MT>
+template <int NV, int MT, int LNMODE = -1>
 __device__ __forceinline__ void crossq_project(const LnA& ln, const bf16_t* __restrict__ A, bf16_t* At, bf16_t* Qt,
                                                const uint4 (&b)[8 * NV], bool has_bias, float bn, int m0, int m_end,
                                                bool keep_rows) {
-  crossq_stage<NV, MT>(ln, A, At, m0, m_end, keep_rows);
+  crossq_stage<NV, MT, LNMODE>(ln, A, At, m0, m_end, keep_rows);
   crossq_multiply<NV, MT>(At, Qt, b, has_bias, bn);
 }
 // LONGK: the configuration's source capacity is kLongKeys or more (the summation order beyond 128 keys, attn_tiles_mfma)
 // SMALL: what the launch bounds promise: 1 = one row tile per workgroup and at most 64 keys, 2 = at most 64 keys, 0 = nothing
-template <int NV, int SMALL, bool LONGK = false>
+template <int NV, int SMALL, bool LONGK = false, int LNMODE = -1>
 __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restrict__ desc, int chunk_rows, float scale,
                                                           const bf16_t* __restrict__ W, const bf16_t* __restrict__ Kb,
                                                           const bf16_t* __restrict__ Vb, const float* __restrict__ ln_x,
@@ -1440,10 +1441,10 @@ __global__ __launch_bounds__(256) void k_crossq_attention(const SeqDesc* __restr
   }
   __builtin_amdgcn_sched_barrier(0);
   // the number of row tiles as a constant (staging and product fully unrolled, as in the GEMM kernel)
-  if (SMALL == 1 || mt == 1) crossq_project<NV, 1>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  else if (mt == 2) crossq_project<NV, 2>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  else if (mt == 3) crossq_project<NV, 3>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
-  else crossq_project<NV, 4>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  if (SMALL == 1 || mt == 1) crossq_project<NV, 1, LNMODE>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else if (mt == 2) crossq_project<NV, 2, LNMODE>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else if (mt == 3) crossq_project<NV, 3, LNMODE>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
+  else crossq_project<NV, 4, LNMODE>(ln, A, At, Qt, b, bias != nullptr, bn, m0, m_end, h == 0);
   // values into LDS, transposed (keys nk_all .. nkp - 1 as zeros)
   if (v_small) {
 #pragma unroll

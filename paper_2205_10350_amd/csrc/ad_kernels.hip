@@ -882,23 +882,33 @@ bool launch_crossq_attention(int dtype, const LnA& ln, const void* A, const void
   // at most 64 keys (the bound the caller gives promises it): variants that hold that path only, a sixth of the code with
   // one row tile per workgroup, less than half with several
   const int small = max_keys <= 64 ? (mt == 1 ? 1 : 2) : 0;
-  auto go = [&](auto nv_c, auto small_c) {
+  auto go = [&](auto nv_c, auto small_c, auto ln_c) {
     constexpr int NV = decltype(nv_c)::value;
     constexpr int SMALL = decltype(small_c)::value;
+    constexpr int LNM = decltype(ln_c)::value;
     static size_t set_for = 0;
     if (sh > set_for) {
-      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, SMALL>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+      (void)hipFuncSetAttribute((const void*)k_crossq_attention<NV, SMALL, false, LNM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       set_for = sh;
     }
-    k_crossq_attention<NV, SMALL><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
-                                                     ln.x, ln.g, ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
+    k_crossq_attention<NV, SMALL, false, LNM><<<g, 256, sh, s>>>(desc, chunk, scale, (const bf16_t*)W, (const bf16_t*)K, (const bf16_t*)V,
+                                                                 ln.x, ln.g, ln.b, ln.y, (const bf16_t*)A, bias, (bf16_t*)out);
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
   using I4 = std::integral_constant<int, 4>;
-  if (d == 512) { if (small == 1) go(I2{}, I1{}); else if (small == 2) go(I2{}, I2{}); else go(I2{}, I0{}); }
-  else { if (small == 1) go(I4{}, I1{}); else if (small == 2) go(I4{}, I2{}); else go(I4{}, I0{}); }
+  using LX = std::integral_constant<int, -1>;
+  // (in a decoder layer a LayerNorm is always pending here: the compact variants hold that staging path alone)
+  if (d == 512) {
+    if (small == 1) { if (ln.x) go(I2{}, I1{}, I1{}); else go(I2{}, I1{}, LX{}); }
+    else if (small == 2) { if (ln.x) go(I2{}, I2{}, I1{}); else go(I2{}, I2{}, LX{}); }
+    else go(I2{}, I0{}, LX{});
+  } else {
+    if (small == 1) { if (ln.x) go(I4{}, I1{}, I1{}); else go(I4{}, I1{}, LX{}); }
+    else if (small == 2) { if (ln.x) go(I4{}, I2{}, I1{}); else go(I4{}, I2{}, LX{}); }
+    else go(I4{}, I0{}, LX{});
+  }
   return true;
 }
 
