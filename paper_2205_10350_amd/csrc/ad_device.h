@@ -1264,54 +1264,65 @@ __device__ __forceinline__ void attn_block(const T* __restrict__ q, const T* __r
 }
 
 // ------------------------------------------------- operand staging through LayerNorm (GEMM and cross-attention kernels)
-// A tile rows [row0, row0 + n_rows) of a workgroup from fp32 rows through LayerNorm (width
-// 256 * NV, the 16-byte rule of ln_load4 / ln_stats4), RB rows in flight at a time.
+// A tile rows [row0, row0 + NR) of a workgroup from fp32 rows through LayerNorm (width
+// 256 * NV, the 16-byte rule of ln_load4 / ln_stats4), in rounds of RB rows.
 // after_first_loads(): called once, when the wave's first batch of row loads has been issued:
 // whatever the caller wants in flight behind them.  Loads return in issue order, so what is
 // needed first (the rows: everything waits for the tile) is requested first.
 struct NoOp { __device__ __forceinline__ void operator()() const {} };
-template <int NV, int RB, typename F = NoOp>
-__device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld, int row0, int n_rows, int m0, int M,
+template <int NV, int RB, int NR, typename F = NoOp>
+__device__ __forceinline__ void astat_stage_ln(const LnA& ln, bf16_t* At, int ld, int row0, int m0, int M,
                                                int lane, bool store_y, const F& after_first_loads = F{}) {
-  constexpr int K = 256 * NV;
+  constexpr int K = 256 * NV, ROUNDS = (NR + RB - 1) / RB;
+  constexpr bool PIPE = ROUNDS > 1 && NV == 2;   // (the 1024-wide rows of four in a second register set would spill)
   float4 gv[NV], bv[NV];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     gv[j] = *(const float4*)(ln.g + 4 * lane + 256 * j);
     bv[j] = *(const float4*)(ln.b + 4 * lane + 256 * j);
   }
-  for (int i0 = 0; i0 < n_rows; i0 += RB) {
-    float4 xv[RB][NV];
+  // NR rows in rounds of RB; with PIPE a round's rows are requested before the round before it is worked on (two
+  // register sets), so that a wave with several rounds waits for memory once
+  float4 xv[PIPE ? 2 : 1][RB][NV];
+  auto request = [&](int rd) {
 #pragma unroll
     for (int i = 0; i < RB; ++i)
-      if (i0 + i < n_rows) ln_load4<NV>(ln.x + (size_t)min(m0 + row0 + i0 + i, M - 1) * K, lane, xv[i]);
-    if (i0 == 0) after_first_loads();
-    // statistics of all rows of the batch first (independent reduction chains the scheduler can
+      if (rd * RB + i < NR) ln_load4<NV>(ln.x + (size_t)min(m0 + row0 + rd * RB + i, M - 1) * K, lane, xv[PIPE ? rd & 1 : 0][i]);
+  };
+  request(0);
+  after_first_loads();
+#pragma unroll
+  for (int rd = 0; rd < ROUNDS; ++rd) {
+    const int i0 = rd * RB;
+    float4 (&xr)[RB][NV] = xv[PIPE ? rd & 1 : 0];
+    if (PIPE && rd + 1 < ROUNDS) request(rd + 1);
+    if (!PIPE && rd > 0) request(rd);
+    // statistics of all rows of the round first (independent reduction chains the scheduler can
     // interleave), then the values, then, in the workgroups that keep them, the fp32 rows
     float mean[RB], rstd[RB];
 #pragma unroll
-    for (int i = 0; i < RB; ++i) ln_stats4<NV>(xv[i0 + i < n_rows ? i : 0], K, mean[i], rstd[i]);
+    for (int i = 0; i < RB; ++i) ln_stats4<NV>(xr[i0 + i < NR ? i : 0], K, mean[i], rstd[i]);
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
-      if (i0 + i >= n_rows) break;
+      if (i0 + i >= NR) break;
       const int row = row0 + i0 + i;
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
         const int c = 4 * lane + 256 * j;
-        const float4 o = float4{ln_value(xv[i][j].x, mean[i], rstd[i], gv[j].x, bv[j].x), ln_value(xv[i][j].y, mean[i], rstd[i], gv[j].y, bv[j].y),
-                                ln_value(xv[i][j].z, mean[i], rstd[i], gv[j].z, bv[j].z), ln_value(xv[i][j].w, mean[i], rstd[i], gv[j].w, bv[j].w)};
+        const float4 o = float4{ln_value(xr[i][j].x, mean[i], rstd[i], gv[j].x, bv[j].x), ln_value(xr[i][j].y, mean[i], rstd[i], gv[j].y, bv[j].y),
+                                ln_value(xr[i][j].z, mean[i], rstd[i], gv[j].z, bv[j].z), ln_value(xr[i][j].w, mean[i], rstd[i], gv[j].w, bv[j].w)};
         const unsigned lo = (unsigned)f2bf(o.x) | ((unsigned)f2bf(o.y) << 16), hi = (unsigned)f2bf(o.z) | ((unsigned)f2bf(o.w) << 16);
         *(uint2*)(At + row * ld + c) = uint2{lo, hi};
-        xv[i][j] = o;
+        xr[i][j] = o;
       }
     }
     if (store_y) {
 #pragma unroll
       for (int i = 0; i < RB; ++i) {
         const int m = m0 + row0 + i0 + i;
-        if (i0 + i < n_rows && m < M) {
+        if (i0 + i < NR && m < M) {
 #pragma unroll
-          for (int j = 0; j < NV; ++j) *(float4*)(ln.y + (size_t)m * K + 4 * lane + 256 * j) = xv[i][j];
+          for (int j = 0; j < NV; ++j) *(float4*)(ln.y + (size_t)m * K + 4 * lane + 256 * j) = xr[i][j];
         }
       }
     }
@@ -1337,7 +1348,7 @@ __device__ __forceinline__ void crossq_stage(const LnA& ln, const bf16_t* __rest
   constexpr int K = 256 * NV, ld = K + 16, per_wave = MT * 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (LNMODE == 1 || ln.x) {
-    astat_stage_ln<NV, (NV == 2 ? 8 : 4)>(ln, At, ld, wave * per_wave, per_wave, m0, m_end, lane, keep_rows);
+    astat_stage_ln<NV, (NV == 2 && per_wave <= 8 ? 8 : 4), per_wave>(ln, At, ld, wave * per_wave, m0, m_end, lane, keep_rows);
   } else {
     uint4 av[per_wave][K / 512];
 #pragma unroll

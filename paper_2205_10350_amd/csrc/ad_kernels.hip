@@ -171,11 +171,7 @@ __global__ __launch_bounds__(64 * NW, NW == 16 || (NW == 8 && ONE && MT == 2 && 
 #pragma unroll
       for (int j = 0; j < SP; ++j) b[j][u] = *(const uint4*)(w[j] + u * 512);
   };
-  // (The widest variants have no registers for the rows' staging values on top of the addresses
-  // this order keeps alive: they request the weights first, as the loop order has it.)
-  constexpr bool ROWS_FIRST = !(SP == 2 && MT >= 2);
-  if constexpr (!ROWS_FIRST) prefetch0();
-  auto behind_rows = [&]() { if constexpr (ROWS_FIRST) prefetch0(); };
+  auto behind_rows = [&]() { prefetch0(); };
   // stage the rows (past M: the last valid row, computed and never stored)
   // (LNMODE 0 / 1: the caller knows at compile time that no LayerNorm / a LayerNorm is pending)
   const bool has_ln = LNMODE < 0 ? ln.x != nullptr : LNMODE == 1;
@@ -184,8 +180,8 @@ __global__ __launch_bounds__(64 * NW, NW == 16 || (NW == 8 && ONE && MT == 2 && 
     // kernel; the workgroups of strip group 0 also store the fp32 rows
     // (the output projection is the last consumer of its rows: nobody needs them in fp32)
     const bool keep_y = group == 0 && AMAX == 0;
-    if (ONE || K == 512) astat_stage_ln<2, (SP == 1 && RPW >= 8 ? 8 : RPW >= 4 ? 4 : RPW)>(ln, At, ld, wave * RPW, RPW, m0, M, lane, keep_y, behind_rows);
-    else astat_stage_ln<4, (RPW >= 4 ? 4 : RPW)>(ln, At, ld, wave * RPW, RPW, m0, M, lane, keep_y, behind_rows);
+    if (ONE || K == 512) astat_stage_ln<2, (SP == 1 && RPW >= 8 ? 8 : RPW >= 4 ? 4 : RPW), RPW>(ln, At, ld, wave * RPW, m0, M, lane, keep_y, behind_rows);
+    else astat_stage_ln<4, (RPW >= 4 ? 4 : RPW), RPW>(ln, At, ld, wave * RPW, m0, M, lane, keep_y, behind_rows);
   } else if (MT == 1 && NW == 4 && !ONE && halves == 4) {
     // few rows of K = 2048: every slice's loads before the weights
     uint4 av[4][4];
