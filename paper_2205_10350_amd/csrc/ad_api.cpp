@@ -120,6 +120,7 @@ static Plan make_plan(const ad_config& c, bool with_drafter) {
 // never lies where another call's words are watched.
 struct PinLayout {
   size_t k, draft, result, o_hat;     // ad_verify: k[B], draft[B, k_max] in; result[B, 2], o_hat[mv_cap] out
+  size_t rows;                        // ad_verify: the packed rows, (sequence << 14 | index)[mv_cap] then the fed token (or -1: the pending one)[mv_cap]
   size_t v_ticket, v_slots;           // ad_verify: the call's ticket (in), one 8-byte result word per sequence (out)
   size_t d_ticket, d_slots;           // ad_draft_nat: ticket (in), one 8-byte (ticket, token) word per drafted token (out)
   size_t d_copy;                      // ad_draft_nat without the watch: draft_out[B, k_max]
@@ -133,6 +134,7 @@ static PinLayout make_pin_layout(const ad_config& c, const Plan& p) {
   size_t off = 0;
   auto take = [&](size_t ints) { size_t o = off; off = (off + ints + 3) & ~(size_t)3; return o; };   // 16-byte steps
   l.k = take(B); l.draft = take(B * c.k_max); l.result = take(2 * B); l.o_hat = take(p.mv_cap);
+  l.rows = take(2 * p.mv_cap);
   l.v_ticket = take(4); l.v_slots = take(2 * B);
   l.d_ticket = take(4); l.d_slots = take(2 * B * c.k_max);
   l.d_copy = take(B * c.k_max);
@@ -736,6 +738,8 @@ int ad_encode(ad_ctx* c, int model, const int32_t* src, const int32_t* src_len, 
 struct VerifyLaunch {
   const int* k_src;
   const int* draft_src;
+  const int* rows_src;               // the packed row list (device view of the staging buffer), null: the kernel finds the rows from k
+  int rows_stride;
   int* result_dst;
   const int* ticket_in;              // device view, null: no ticket
   unsigned long long* ticket_out;    // device view
@@ -757,7 +761,7 @@ static void verify_launches(ad_ctx* c, const VerifyLaunch& v) {
                          c->at<int>(p.pending), c->at<int>(p.finished), c->at<int>(p.out), v.result_dst, v.ticket_in,
                          v.ticket_out, c->fw_max_rows, v.M, c->stream, gp);
   };
-  launch_assemble_embed_verify(cf.dtype, v.k_src, v.draft_src, km, c->at<int>(p.len), c->at<int>(p.pending),
+  launch_assemble_embed_verify(cf.dtype, v.k_src, v.draft_src, v.rows_src, v.rows_stride, km, c->at<int>(p.len), c->at<int>(p.pending),
                                c->at<int>(p.src_len[0]), v.B, p.l_cap, cf.max_src, t, v.M, c->w[AD_VERIFIER].emb,
                                c->at<float>(p.pe), cf.d_model, sqrtf((float)cf.d_model), c->at<float>(p.x),
                                c->at<void>(p.xa), c->stream);
@@ -829,6 +833,20 @@ static int verify_call(ad_ctx* c, const int32_t* draft, const int32_t* k, int32_
   v.M = M; v.B = B;
   if (mapped) {
     v.k_src = c->pin_dev + pl.k; v.draft_src = c->pin_dev + pl.draft; v.result_dst = c->pin_dev + pl.result;
+    // with several sequences also the list of packed rows, so that the row's workgroup needs one trip over the bus
+    // (its own entry) instead of two (the counts, then its token)
+    if (B > 1) {
+      int32_t* rows = h + pl.rows;
+      const size_t cap = p.mv_cap;
+      int m = 0;
+      for (int b = 0; b < B; ++b)
+        for (int i = 0; i < k[b]; ++i, ++m) {
+          rows[m] = (b << 14) | i;
+          rows[cap + m] = i == 0 ? -1 : draft[(size_t)b * km + i - 1];
+        }
+      v.rows_src = c->pin_dev + pl.rows;
+      v.rows_stride = (int)cap;
+    }
   } else {
     HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.k_dev), h + pl.k, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->at<int>(p.draft_dev), h + pl.draft, (size_t)B * km * 4, hipMemcpyHostToDevice, c->stream));

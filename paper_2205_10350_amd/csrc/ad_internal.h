@@ -128,7 +128,7 @@ struct VerifyTables {
   SeqDesc *self_desc, *cross_desc;                          // [B]
 };
 // those tables and the embedding of the M rows (x, xa) in one launch
-void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int k_max, const int* len,
+void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, const int* rows, int rows_stride, int k_max, const int* len,
                                   const int* pending, const int* src_len, int B, int l_cap, int s_max, VerifyTables t,
                                   int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,
                                   hipStream_t s);

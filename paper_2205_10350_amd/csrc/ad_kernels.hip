@@ -1061,13 +1061,54 @@ void launch_argmax_draft(const float* pv, const int* pi, int M, int stride, int 
 
 
 // ------------------------------------------------------------------------------------- row assembly
+// Packed row m of a batch whose sequences contribute n[0..B) rows: its sequence and its index there.  The counts may
+// live in host memory, where every read is a trip over the bus: the threads read them side by side (one trip per 128
+// sequences) into LDS and thread 0 scans them there.  The result is in where[0..1] for the whole workgroup.
+__device__ __forceinline__ void locate_packed_row(const int* __restrict__ n, int B, int m, int* chunk, int* where) {
+  int acc = 0, bb = 0, ii = 0;
+  for (int base = 0; base < B; base += (int)blockDim.x) {
+    const int b = base + (int)threadIdx.x;
+    chunk[threadIdx.x] = b < B ? n[b] : 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int here = min((int)blockDim.x, B - base);
+      for (int j = 0; j < here; ++j) {
+        const int nb = chunk[j];
+        if (m >= acc && m < acc + nb) { bb = base + j; ii = m - acc; }
+        acc += nb;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { where[0] = bb; where[1] = ii; }
+  __syncthreads();
+}
+// row_start[0..B] = running sums of the counts, read the same way
+__device__ __forceinline__ void packed_row_starts(const int* __restrict__ n, int B, int* chunk, int* __restrict__ row_start) {
+  int acc = 0;
+  for (int base = 0; base < B; base += (int)blockDim.x) {
+    const int b = base + (int)threadIdx.x;
+    chunk[threadIdx.x] = b < B ? n[b] : 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int here = min((int)blockDim.x, B - base);
+      for (int j = 0; j < here; ++j) { row_start[base + j] = acc; acc += chunk[j]; }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) row_start[B] = acc;
+  __syncthreads();
+}
 // Verify call: sequence b feeds (pending_b, draft_b[0..k_b-2]) at positions len_b .. len_b+k_b-1
 // (Section 3.2, the verifier equation conditions row i on the accepted prefix and the first
 // i-1 drafted tokens).  The row tables and the embedding of the rows in one launch: workgroup 0
-// writes the tables the later kernels read; workgroup m + 1 finds row m's (sequence, block index)
-// by the same scan and embeds it.
+// writes the per-sequence tables the later kernels read; workgroup m + 1 finds row m's (sequence, block
+// index) by the same scan, writes the row's table entries and embeds it.  (k and the draft live in host memory:
+// a workgroup makes two trips over the bus, one for the counts and one for its token; a workgroup 0 that walked
+// the sequences one after the other made two trips per sequence, 10-40 us per call at 32 sequences.)
 template <typename T>
 __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __restrict__ k, const int* __restrict__ draft,
+                                                               const int* __restrict__ rows, int rows_stride,
                                                                const int* __restrict__ len,
                                                                const int* __restrict__ pending, const T* __restrict__ emb,
                                                                const float* __restrict__ pe, float* __restrict__ x,
@@ -1076,24 +1117,30 @@ __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __rest
                                                                const int* __restrict__ src_len, VerifyTables t) {
   // k lives in host memory (a trip over the bus); with one sequence it is the row count M
   __shared__ int where[2];
+  __shared__ int chunk[128];
   if (blockIdx.x != 0) {
     const int m = blockIdx.x - 1;
-    if (B > 1) {
-      if (threadIdx.x == 0) {
-        int acc = 0, bb = 0, ii = 0;
-        for (int b = 0; b < B; ++b) {
-          const int kb = k[b];
-          if (m >= acc && m < acc + kb) { bb = b; ii = m - acc; }
-          acc += kb;
-        }
-        where[0] = bb; where[1] = ii;
-      }
-      __syncthreads();
+    // rows (host memory, written by the caller of several sequences): row m's (sequence << 14 | index) and, behind
+    // them, the token it feeds (-1: the sequence's pending token); both requested at once
+    int b, i, tok;
+    if (rows) {
+      const int w = rows[m], fed = rows[rows_stride + m];
+      b = w >> 14; i = w & 0x3fff;
+      tok = fed < 0 ? pending[b] : fed;
+    } else {
+      if (B > 1) locate_packed_row(k, B, m, chunk, where);
+      b = B > 1 ? where[0] : 0; i = B > 1 ? where[1] : m;
+      tok = i == 0 ? pending[b] : draft[b * k_max + i - 1];
     }
-    const int b = B > 1 ? where[0] : 0, i = B > 1 ? where[1] : m;
-    const int tok = i == 0 ? pending[b] : draft[b * k_max + i - 1];
+    const int L = len[b];
+    if (threadIdx.x == 0) {
+      t.row_tok[m] = tok;
+      t.row_pos[m] = L + i;
+      t.row_seq[m] = b;
+      t.row_dst[m] = b * l_cap + L + i;
+    }
     const T* e = emb + (size_t)tok * d;
-    const float* p = pe + (size_t)(len[b] + i) * d;
+    const float* p = pe + (size_t)(L + i) * d;
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
       const float v = embed_value(Store<T>::load(e + c), sqrt_d, p[c]);
       x[(size_t)m * d + c] = v;
@@ -1101,41 +1148,31 @@ __global__ __launch_bounds__(128) void k_assemble_embed_verify(const int* __rest
     }
     return;
   }
-  // workgroup 0: the tables
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += B > 1 ? k[b] : M; }
-    t.row_start[B] = acc;
+  // workgroup 0: the per-sequence tables
+  if (B > 1) packed_row_starts(k, B, chunk, t.row_start);
+  else {
+    if (threadIdx.x == 0) { t.row_start[0] = 0; t.row_start[1] = M; }
+    __syncthreads();
   }
-  __syncthreads();
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
     SeqDesc s;
-    s.q_row0 = t.row_start[b]; s.nq = B > 1 ? k[b] : M; s.kv_row0 = b * l_cap; s.nk_base = len[b]; s.causal = 1;
+    s.q_row0 = t.row_start[b]; s.nq = t.row_start[b + 1] - t.row_start[b]; s.kv_row0 = b * l_cap; s.nk_base = len[b]; s.causal = 1;
     s.pad0 = s.pad1 = s.pad2 = 0;
     t.self_desc[b] = s;
     s.kv_row0 = b * s_max; s.nk_base = src_len[b]; s.causal = 0;
     t.cross_desc[b] = s;
   }
-  for (int b = 0; b < B; ++b) {
-    const int r0 = t.row_start[b], kb = B > 1 ? k[b] : M, L = len[b];
-    for (int i = threadIdx.x; i < kb; i += blockDim.x) {
-      t.row_tok[r0 + i] = i == 0 ? pending[b] : draft[b * k_max + i - 1];
-      t.row_pos[r0 + i] = L + i;
-      t.row_seq[r0 + i] = b;
-      t.row_dst[r0 + i] = b * l_cap + L + i;
-    }
-  }
 }
-void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int k_max, const int* len,
+void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, const int* rows, int rows_stride, int k_max, const int* len,
                                   const int* pending, const int* src_len, int B, int l_cap, int s_max, VerifyTables t,
                                   int M, const void* emb, const float* pe, int d, float sqrt_d, float* x, void* xa,
                                   hipStream_t s) {
   if (M <= 0) return;
   if (dtype == AD_BF16)
-    k_assemble_embed_verify<bf16_t><<<M + 1, 128, 0, s>>>(k, draft, len, pending, (const bf16_t*)emb, pe, x, (bf16_t*)xa, k_max,
+    k_assemble_embed_verify<bf16_t><<<M + 1, 128, 0, s>>>(k, draft, rows, rows_stride, len, pending, (const bf16_t*)emb, pe, x, (bf16_t*)xa, k_max,
                                                       B, d, sqrt_d, M, l_cap, s_max, src_len, t);
   else
-    k_assemble_embed_verify<float><<<M + 1, 128, 0, s>>>(k, draft, len, pending, (const float*)emb, pe, x, (float*)xa, k_max, B,
+    k_assemble_embed_verify<float><<<M + 1, 128, 0, s>>>(k, draft, rows, rows_stride, len, pending, (const float*)emb, pe, x, (float*)xa, k_max, B,
                                                      d, sqrt_d, M, l_cap, s_max, src_len, t);
 }
 
@@ -1143,9 +1180,9 @@ void launch_assemble_embed_verify(int dtype, const int* k, const int* draft, int
 // sentence's own rows (keys live in the packed temporary buffers, row_dst = identity); the
 // cross_desc slot describes where the memory keys/values of each sentence go.
 // The encoder's tables, the embedding of its rows and the per-call device state in one launch
-// (src, src_len, max_out may live in host memory): workgroup 0 writes the tables, keeps the
+// (src, src_len, max_out may live in host memory): workgroup 0 writes the per-sequence tables, keeps the
 // source lengths and, for the verifier (len != null), the output limits and the start state of a
-// decode; workgroup m + 1 embeds row m.
+// decode; workgroup m + 1 writes row m's table entries and embeds it.
 template <typename T>
 __global__ __launch_bounds__(128) void k_assemble_embed_encoder(const int* __restrict__ src, int max_src,
                                                                 const int* __restrict__ src_len,
@@ -1157,20 +1194,20 @@ __global__ __launch_bounds__(128) void k_assemble_embed_encoder(const int* __res
                                                                 const float* __restrict__ pe, int d, float sqrt_d,
                                                                 float* __restrict__ x, T* __restrict__ xa) {
   __shared__ int where[2];
+  __shared__ int chunk[128];
   if (blockIdx.x != 0) {
     const int m = blockIdx.x - 1;
-    if (threadIdx.x == 0) {
-      int acc = 0, bb = 0, ii = 0;
-      for (int b = 0; b < B; ++b) {
-        const int n = src_len[b];
-        if (m >= acc && m < acc + n) { bb = b; ii = m - acc; }
-        acc += n;
-      }
-      where[0] = bb; where[1] = ii;
-    }
-    __syncthreads();
+    locate_packed_row(src_len, B, m, chunk, where);
     const int b = where[0], i = where[1];
-    const T* e = emb + (size_t)src[b * max_src + i] * d;
+    const int tok = src[b * max_src + i];
+    if (threadIdx.x == 0) {
+      t.row_tok[m] = tok;
+      t.row_pos[m] = i;
+      t.row_seq[m] = b;
+      t.row_dst[m] = m;                   // own keys/values: packed temporaries
+      t.row_dst2[m] = b * s_max + i;      // where this row's memory key/value goes
+    }
+    const T* e = emb + (size_t)tok * d;
     const float* p = pe + (size_t)i * d;
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
       const float v = embed_value(Store<T>::load(e + c), sqrt_d, p[c]);
@@ -1179,30 +1216,15 @@ __global__ __launch_bounds__(128) void k_assemble_embed_encoder(const int* __res
     }
     return;
   }
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    for (int b = 0; b < B; ++b) { t.row_start[b] = acc; acc += src_len[b]; }
-    t.row_start[B] = acc;
-  }
-  __syncthreads();
+  packed_row_starts(src_len, B, chunk, t.row_start);
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    const int n = src_len[b];
+    const int n = t.row_start[b + 1] - t.row_start[b];
     SeqDesc s;
     s.q_row0 = t.row_start[b]; s.nq = n; s.kv_row0 = t.row_start[b]; s.nk_base = n; s.causal = 0;
     s.pad0 = s.pad1 = s.pad2 = 0;
     t.self_desc[b] = s;
     src_len_out[b] = n;
     if (len) { max_out[b] = max_out_in[b]; len[b] = 0; pending[b] = bos; finished[b] = 0; }
-  }
-  for (int b = 0; b < B; ++b) {
-    const int r0 = t.row_start[b], n = src_len[b];
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      t.row_tok[r0 + i] = src[b * max_src + i];
-      t.row_pos[r0 + i] = i;
-      t.row_seq[r0 + i] = b;
-      t.row_dst[r0 + i] = r0 + i;            // own keys/values: packed temporaries
-      t.row_dst2[r0 + i] = b * s_max + i;    // where this row's memory key/value goes
-    }
   }
 }
 void launch_assemble_embed_encoder(int dtype, const int* src, int max_src, const int* src_len, const int* max_out_in,
@@ -1364,20 +1386,21 @@ __global__ __launch_bounds__(1024) void k_argmax_accept(const int* __restrict__ 
                                                        int* __restrict__ out, int* __restrict__ result,
                                                        unsigned long long* __restrict__ ticket_out, GadppIn gp) {
   const int b = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int kb = gridDim.x == 1 ? M : k[b];   // k is in host memory; a lone sequence owns all M rows
+  // what the end of the kernel needs and nothing here depends on is requested first (k, the draft and the ticket
+  // sit in host memory, one trip over the bus for all of them: the draft as all of the sequence's slots, so that
+  // its request does not wait for k)
+  const int my_draft = (int)threadIdx.x < k_max ? draft[b * k_max + threadIdx.x] : 0;
+  const int ticket = threadIdx.x == 0 && ticket_out ? *ticket_in : 0;
+  const int kb = gridDim.x == 1 ? M : k[b];   // a lone sequence owns all M rows
   if (kb == 0) {
     if (threadIdx.x == 0) {
-      if (ticket_out) __hip_atomic_store(ticket_out + b, (unsigned long long)*ticket_in << 46, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      if (ticket_out) __hip_atomic_store(ticket_out + b, (unsigned long long)ticket << 46, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       else { result[2 * b] = 0; result[2 * b + 1] = 0; }
     }
     return;
   }
   const int r0 = row_start[b];
-  // what the end of the kernel needs and nothing here depends on: requested now (the draft and
-  // the ticket sit in host memory, one trip over the bus each)
   __shared__ int s_first, s_eos;
-  const int my_draft = (int)threadIdx.x < kb ? draft[b * k_max + threadIdx.x] : 0;
-  const int ticket = threadIdx.x == 0 && ticket_out ? *ticket_in : 0;
   const int L = len[b], lim = max_out[b];
   if (threadIdx.x == 0) { s_first = kb; s_eos = kb; }
   for (int i = wave; i < kb; i += (int)(blockDim.x >> 6)) {
